@@ -1,0 +1,176 @@
+"""Input generators (see package docstring).  Inputs only; no search arithmetic."""
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def _gen(seed: int, device) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    return g
+
+
+def _normalize(x: torch.Tensor) -> torch.Tensor:
+    return x / x.norm(dim=-1, keepdim=True).clamp_min(1e-30)
+
+
+@dataclass
+class Datastore:
+    """A synthetic vector datastore.
+
+    rows       [n, d] in `dtype`; input order when `assign` is set, cluster-major
+               (list c = rows offsets[c]:offsets[c+1]) when `offsets` is set
+    centroids  [nlist, d] float32
+    """
+    rows: torch.Tensor
+    centroids: torch.Tensor
+    dtype: str
+    assign: Optional[torch.Tensor] = None
+    offsets: Optional[torch.Tensor] = None
+    centres: Optional[torch.Tensor] = None      # mixture centres the rows were drawn around
+    component: Optional[torch.Tensor] = None    # mixture component of each row (kmeans route)
+
+    @property
+    def n(self):
+        return self.rows.shape[0]
+
+    @property
+    def d(self):
+        return self.rows.shape[1]
+
+    @property
+    def nlist(self):
+        return self.centroids.shape[0]
+
+
+def mixture_rows(n, d, n_comp, sigma, seed, device="cpu", chunk=1 << 18):
+    """n unit-norm rows: normalize(centre_c + sigma * N(0, I)), c uniform over n_comp
+    centres drawn from N(0, I).  Returns (rows fp32, component int64, centres fp32)."""
+    g = _gen(seed, device)
+    centres = torch.randn(n_comp, d, generator=g, device=device)
+    comp = torch.randint(0, n_comp, (n,), generator=g, device=device)
+    rows = torch.empty(n, d, device=device)
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        noise = torch.randn(e - s, d, generator=g, device=device)
+        rows[s:e] = _normalize(centres[comp[s:e]] + sigma * noise)
+    return rows, comp, centres
+
+
+def _nearest(rows, centroids, chunk=1 << 16):
+    """Index of the L2-nearest centroid of each row (input preparation only)."""
+    out = torch.empty(rows.shape[0], dtype=torch.int64, device=rows.device)
+    c2 = (centroids * centroids).sum(1)
+    for s in range(0, rows.shape[0], chunk):
+        r = rows[s:s + chunk].float()
+        dist = c2[None, :] - 2.0 * (r @ centroids.T)
+        out[s:s + chunk] = dist.argmin(1)
+    return out
+
+
+def kmeans_datastore(n, d, n_comp, sigma, nlist, iters, seed, sample=None, dtype="f32",
+                     device="cpu"):
+    """Mixture rows, centroids from `iters` Lloyd iterations (on a seeded sample of
+    `sample` rows when given; initial centroids = nlist seeded random sample rows),
+    and each row's nearest-centroid assignment."""
+    rows, comp, centres = mixture_rows(n, d, n_comp, sigma, seed, device)
+    g = _gen(seed + 1, device)
+    if sample is not None and sample < n:
+        pick = torch.randperm(n, generator=g, device=device)[:sample]
+        train = rows[pick]
+    else:
+        train = rows
+    init = torch.randperm(train.shape[0], generator=g, device=device)[:nlist]
+    cent = train[init].clone()
+    for _ in range(iters):
+        a = _nearest(train, cent)
+        sums = torch.zeros_like(cent).index_add_(0, a, train)
+        cnt = torch.zeros(nlist, device=device).index_add_(0, a, torch.ones_like(a, dtype=torch.float32))
+        keep = cnt > 0
+        cent[keep] = sums[keep] / cnt[keep, None]
+    assign = _nearest(rows, cent).to(torch.int32)
+    rows = rows.to(TORCH_DTYPE[dtype])
+    return Datastore(rows=rows, centroids=cent.contiguous(), dtype=dtype, assign=assign,
+                     centres=centres, component=comp)
+
+
+def zipf_sizes(n, nlist, exponent, seed, min_rows=1):
+    """nlist list sizes summing to n with size of rank r proportional to r^-exponent,
+    rank order randomly permuted over the clusters.  exponent 0 gives near-uniform sizes."""
+    g = _gen(seed, "cpu")
+    w = torch.arange(1, nlist + 1, dtype=torch.float64) ** (-float(exponent))
+    sizes = torch.floor(w / w.sum() * (n - min_rows * nlist)).to(torch.int64) + min_rows
+    sizes[0] += n - int(sizes.sum())
+    return sizes[torch.randperm(nlist, generator=g)]
+
+
+def cluster_major_datastore(sizes, d, sigma, seed, dtype="f16", device="cpu", out=None,
+                            chunk=1 << 18):
+    """Rows generated directly in cluster-major order: list c has sizes[c] rows
+    normalize(centre_c + sigma * N(0, I)), rounded to `dtype`; the centroid of list c is
+    the mean of its stored rows (zero for an empty list).  `out` may be a preallocated
+    (for example pinned-host) [n, d] tensor that receives the rows chunk by chunk."""
+    sizes = sizes.to(torch.int64).cpu()
+    nlist = sizes.shape[0]
+    n = int(sizes.sum())
+    offsets = torch.zeros(nlist + 1, dtype=torch.int64)
+    offsets[1:] = torch.cumsum(sizes, 0)
+    g = _gen(seed, device)
+    centres = torch.randn(nlist, d, generator=g, device=device)
+    tdt = TORCH_DTYPE[dtype]
+    rows = out if out is not None else torch.empty(n, d, dtype=tdt, device=device)
+    assert rows.shape == (n, d) and rows.dtype == tdt
+    sums = torch.zeros(nlist, d, dtype=torch.float32, device=device)
+    off_dev = offsets.to(device)
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        pos = torch.arange(s, e, device=device)
+        cl = torch.searchsorted(off_dev, pos, right=True) - 1
+        noise = torch.randn(e - s, d, generator=g, device=device)
+        block = _normalize(centres[cl] + sigma * noise).to(tdt)
+        sums.index_add_(0, cl, block.float())
+        rows[s:e].copy_(block)
+    cent = sums / sizes.to(device).clamp_min(1).float()[:, None]
+    return Datastore(rows=rows, centroids=cent.contiguous(), dtype=dtype, offsets=offsets,
+                     centres=centres)
+
+
+def query_pairs(anchor_rows, nq, alpha, seed, anchor_noise=0.1):
+    """(q_in, q_out), both [nq, d] float32 unit vectors on the anchors' device.
+
+    q_in  = normalize(anchor + anchor_noise * g),  anchor = a seeded random row,
+    q_out = normalize(q_in + alpha * g'),          g, g' ~ N(0, I/d)  (unit expected norm).
+    """
+    device = anchor_rows.device
+    d = anchor_rows.shape[1]
+    g = _gen(seed, device)
+    pick = torch.randint(0, anchor_rows.shape[0], (nq,), generator=g, device=device)
+    base = anchor_rows[pick].float()
+    scale = d ** -0.5
+    q_in = _normalize(base + anchor_noise * scale * torch.randn(nq, d, generator=g, device=device))
+    q_out = _normalize(q_in + alpha * scale * torch.randn(nq, d, generator=g, device=device))
+    return q_in.contiguous(), q_out.contiguous()
+
+
+# ---- the named workloads ------------------------------------------------------
+
+def config1_tiny(seed=20969, device="cpu", dtype="f32"):
+    """20,000 x 128 rows from a 64-component mixture (sigma 0.3), nlist 64 from 10 Lloyd
+    iterations, 16 query pairs with alpha 0.2.  Searched with inner product, nprobe 8, k 10."""
+    ds = kmeans_datastore(20000, 128, 64, 0.3, 64, 10, seed, dtype=dtype, device=device)
+    q_in, q_out = query_pairs(ds.rows, 16, 0.2, seed + 2)
+    return ds, q_in, q_out
+
+
+def config2_single_query(seed=20970, device="cpu", n=1_000_000, d=768, nlist=1024, nq=256,
+                         dtype="f32"):
+    """1,000,000 x 768 fp32 rows from a 1024-component mixture, nlist 1024 from k-means on a
+    100k sample, nq query pairs with alpha 0.3.  Searched with nprobe 32, k 10, batch 1.
+    `n`, `d`, `nlist` can be scaled down for tests; the sample stays one tenth of n."""
+    ds = kmeans_datastore(n, d, nlist, 0.3, nlist, 10, seed, sample=max(nlist, n // 10),
+                          dtype=dtype, device=device)
+    q_in, q_out = query_pairs(ds.rows, nq, 0.3, seed + 2)
+    return ds, q_in, q_out
