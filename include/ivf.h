@@ -1,0 +1,202 @@
+/*
+ * libivf -- IVF-Flat nearest-neighbour search with lookahead prefetch for one
+ * MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ or torch types.
+ *
+ * The operations are those of TeleRAG (arxiv 2502.20969):
+ *   - IVF search (App. B): coarse scoring of the query against all centroids,
+ *     selection of the nprobe nearest clusters, a scan of the rows of those
+ *     clusters, and the k nearest rows.
+ *   - Lookahead retrieval (Sec. 4.1 steps 1-4, Sec. 4.3 "Prefetching target"):
+ *     clusters ranked by q_in are copied host->device under a byte budget while
+ *     other work runs; q_out is then searched over the resident clusters
+ *     (C_overlap) on the GPU and over the others (C_miss) on the host, and the
+ *     two partial results are merged.
+ *
+ * Conventions
+ *   - Every function returns 0 (IVF_OK) or a negative ivf_status; nothing
+ *     throws or aborts across this boundary.  ivf_strerror() names a status;
+ *     ivf_last_error() gives a longer message for the calling thread.
+ *   - "host" pointers are ordinary process memory unless "pinned" is said;
+ *     "device" pointers are HIP device memory on the current device.
+ *   - An index is used by one host thread at a time.  The library never frees
+ *     or keeps caller memory unless a function says the index adopts it.
+ *   - Metric (App. B, the distance d): IVF_IP ranks by inner product, larger is
+ *     nearer, reported distances are the raw inner products (descending).
+ *     IVF_L2 ranks by squared Euclidean distance, smaller is nearer, reported
+ *     distances are the squared distances (ascending).  The coarse and the fine
+ *     stage use the same metric.
+ *   - Order: equal scores are ordered by smaller cluster index (coarse stage)
+ *     or smaller vector id (fine stage), so results are deterministic.
+ *   - nprobe larger than nlist is clamped to nlist.  When fewer than k rows
+ *     were scanned the tail is padded with id -1 and distance -INF (IP) or
+ *     +INF (L2).
+ *   - Arithmetic: coarse scores are accumulated in fp64.  The list scan
+ *     accumulates in fp32 over rows stored as fp32 / fp16 / bf16 with the fp32
+ *     query; the k + slack best rows are then re-scored in fp64 and ordered by
+ *     that score, and the fp64 value rounded to fp32 is what is returned.
+ */
+#ifndef IVF_H
+#define IVF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ivf_index ivf_index; /* opaque */
+
+enum ivf_status {
+    IVF_OK = 0,
+    IVF_EINVAL = -1, /* bad argument: NULL, size < 1, unknown enum, assignment out of range */
+    IVF_ENOMEM = -2, /* host or device allocation failed; the index is unchanged */
+    IVF_EHIP = -3,   /* a HIP call failed; ivf_last_error() holds its text */
+    IVF_ESTATE = -4, /* call not valid for this index (e.g. prefetch on a device-resident index) */
+    IVF_ELIMIT = -5  /* a size is above what this build supports (k, d, n) */
+};
+
+enum ivf_metric { IVF_IP = 0, IVF_L2 = 1 };
+enum ivf_dtype { IVF_F32 = 0, IVF_F16 = 1, IVF_BF16 = 2 }; /* storage type of list rows */
+enum ivf_placement {
+    IVF_PLACE_DEVICE = 0, /* every list resident in HBM */
+    IVF_PLACE_HOST = 1    /* lists in pinned host memory + a device prefetch buffer
+                             (Sec. "Implementation Details": pinned region, fixed GPU buffer) */
+};
+
+#define IVF_PREFETCH_RESET 1u /* drop all residency before planning (each request starts cold) */
+
+#define IVF_MAX_K 112 /* largest k of ivf_search / ivf_search_device */
+
+typedef struct ivf_prefetch_stats {
+    int32_t n_ranked;   /* clusters considered (sum over queries of min(nprobe, nlist)) */
+    int32_t n_taken;    /* clusters whose copy was enqueued by this call */
+    int32_t n_skipped;  /* clusters that did not fit the remaining budget or buffer */
+    int32_t n_resident; /* clusters considered that were already resident */
+    uint64_t bytes;     /* payload bytes enqueued by this call */
+    uint64_t buffer_used; /* bytes of the device buffer in use after this call */
+} ivf_prefetch_stats;
+
+typedef struct ivf_search_stats {
+    int32_t n_probed;      /* sum over queries of clusters selected */
+    int32_t n_overlap;     /* of those, scanned on the GPU */
+    int32_t n_miss;        /* of those, scanned on the host */
+    float hit_rate;        /* mean over queries of |C_overlap| / |C_out| (Table 1 caption) */
+    uint64_t bytes_gpu;    /* list bytes the GPU scan covered: sum n_c*d*elem over C_overlap */
+    uint64_t bytes_host;   /* list bytes the host scan covered */
+    float ms_total;        /* wall time of the call */
+    float ms_probe;        /* until the selected clusters were known to the host (host placement) */
+    float ms_host_scan;    /* host scan of C_miss */
+} ivf_search_stats;
+
+typedef struct ivf_profile {
+    uint64_t calls;        /* searches measured since ivf_profile_reset() */
+    double ms_coarse;      /* summed HIP-event time of the coarse-scoring kernel */
+    double ms_select;      /* ... of the top-nprobe selection kernel */
+    double ms_scan;        /* ... of the list-scan kernel */
+    double ms_merge;       /* ... of the merge / re-score kernel */
+    uint64_t scan_bytes;   /* summed list bytes the scan kernels covered */
+    uint64_t scan_rows;    /* summed rows the scan kernels covered */
+} ivf_profile;
+
+/*
+ * Builds cluster-major lists from rows in input order (one-time; the a0 step:
+ * the contiguous cluster-major region of Sec. "Implementation Details").
+ *   vectors    host, n x d row-major in `dtype`
+ *   centroids  host, nlist x d float32, copied to the device
+ *   assign     host, n entries in [0, nlist): the list of each row
+ *   ids        host, n entries >= 0, or NULL for ids 0..n-1
+ *   device_buffer_bytes  size of the prefetch buffer (IVF_PLACE_HOST only)
+ *   compute_stream, copy_stream  hipStream_t values, or NULL for streams the
+ *              library creates; kernels run on the first, prefetch copies on
+ *              the second; both must be of default priority
+ * Rows keep their input order inside a list.  The library owns all storage it
+ * creates (device lists, or a pinned host region for IVF_PLACE_HOST).
+ */
+int ivf_build_layout(const void* vectors, int64_t n, int32_t d, int dtype,
+                     const float* centroids, int32_t nlist, const int32_t* assign,
+                     const int64_t* ids, int metric, int placement,
+                     size_t device_buffer_bytes, void* compute_stream, void* copy_stream,
+                     ivf_index** out);
+
+/*
+ * Adopts rows that are already cluster-major, without copying them.
+ *   lists      IVF_PLACE_DEVICE: device pointer; IVF_PLACE_HOST: pinned host pointer
+ *              (allocated with hipHostMalloc, e.g. a torch pinned tensor).  Owned by the
+ *              caller and must outlive the index.
+ *   offsets    host, nlist + 1 entries: list c = rows offsets[c] .. offsets[c+1]
+ *   ids        host, n entries >= 0, or NULL for ids = row position
+ */
+int ivf_adopt_layout(void* lists, const int64_t* offsets, const int64_t* ids, int64_t n,
+                     int32_t d, int dtype, const float* centroids, int32_t nlist, int metric,
+                     int placement, size_t device_buffer_bytes, void* compute_stream,
+                     void* copy_stream, ivf_index** out);
+
+void ivf_free(ivf_index* index);
+
+/*
+ * Lookahead step 1 (Sec. 4.1 "Predict & prefetch", Sec. 4.3 "Prefetching target").
+ * For each of the nq queries q_in (host, nq x d float32): ranks all clusters, walks the
+ * nprobe nearest in order and enqueues on copy_stream the copy of every cluster that is
+ * not resident and fits both the remaining budget (budget_bytes / nq per query) and the
+ * remaining device buffer; a cluster that does not fit is skipped whole and the walk goes
+ * on.  A cluster's size is n_c * d * element size.  Returns once the copies are enqueued;
+ * the next ivf_search waits for them on the device.  IVF_PLACE_HOST only.
+ */
+int ivf_prefetch(ivf_index* index, const float* q_in, int32_t nq, int32_t nprobe,
+                 size_t budget_bytes, uint32_t flags, ivf_prefetch_stats* stats /* or NULL */);
+
+/* Blocks the host until all enqueued prefetch copies have finished; *ms (or NULL) receives
+ * the HIP-event time from the first to the last copy of the most recent ivf_prefetch. */
+int ivf_prefetch_wait(ivf_index* index, float* ms);
+
+/*
+ * IVF search (App. B; with host placement: Sec. 4.1 steps 2-4).
+ *   q_out  host, nq x d float32      ids    host, nq x k, nearest first
+ *   dists  host, nq x k float32
+ * On return the outputs are complete.  With IVF_PLACE_HOST the clusters selected for
+ * q_out that are resident are scanned on the GPU while the others are scanned by host
+ * threads; the result equals a search with every list resident.
+ */
+int ivf_search(ivf_index* index, const float* q_out, int32_t nq, int32_t nprobe, int32_t k,
+               int64_t* ids, float* dists, ivf_search_stats* stats /* or NULL */);
+
+/*
+ * The same search with device-resident queries and outputs (all device pointers), enqueued
+ * on compute_stream without waiting: outputs are complete once that stream has reached
+ * this point.  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
+ * ivf_reserve() or an earlier search has sized the workspace for, else the call sizes it
+ * itself, which synchronises the device.
+ */
+int ivf_search_device(ivf_index* index, const float* q_dev, int32_t nq, int32_t nprobe,
+                      int32_t k, int64_t* ids_dev, float* dists_dev);
+
+/* Sizes the workspace for searches up to (nq, nprobe, k) so that later calls allocate nothing. */
+int ivf_reserve(ivf_index* index, int32_t nq, int32_t nprobe, int32_t k);
+
+/* Stage-level entry points, used by the parity tests. */
+/* coarse scores of App. B's first step: scores (host, nq x nlist fp64), raw metric values */
+int ivf_coarse_scores(ivf_index* index, const float* q, int32_t nq, double* scores);
+/* the nprobe nearest clusters, nearest first: clusters (host, nq x min(nprobe, nlist)) */
+int ivf_probe(ivf_index* index, const float* q, int32_t nq, int32_t nprobe, int32_t* clusters);
+/* resident clusters in ascending order; *n in: capacity of clusters, out: count */
+int ivf_resident(ivf_index* index, int32_t* clusters, int32_t* n);
+/* layout as built: offsets (host, nlist + 1) and/or ids (host, n); either may be NULL */
+int ivf_get_layout(ivf_index* index, int64_t* offsets, int64_t* ids);
+
+/* Kernel timing with HIP events on compute_stream around each kernel of every search while
+ * enabled (adds event records to the stream; leave off when timing throughput). */
+int ivf_profile_enable(ivf_index* index, int on);
+int ivf_profile_read(ivf_index* index, ivf_profile* out); /* synchronises compute_stream */
+int ivf_profile_reset(ivf_index* index);
+
+/* Number of host threads used for the scan of C_miss (default: hardware threads, at most 64). */
+int ivf_set_host_threads(ivf_index* index, int32_t n);
+
+const char* ivf_strerror(int status);
+const char* ivf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVF_H */

@@ -1,0 +1,267 @@
+"""ctypes binding of libivf.so: same names as include/ivf.h, argument marshalling only.
+
+Host arguments are numpy arrays (or CPU torch tensors); device arguments are torch CUDA
+tensors.  Nothing here computes: every step of the search runs in the HIP library, and the
+module raises at import of the library if it has not been built.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libivf.so")
+
+IVF_IP, IVF_L2 = 0, 1
+IVF_F32, IVF_F16, IVF_BF16 = 0, 1, 2
+IVF_PLACE_DEVICE, IVF_PLACE_HOST = 0, 1
+IVF_PREFETCH_RESET = 1
+IVF_MAX_K = 112
+DTYPE_CODE = {"f32": IVF_F32, "f16": IVF_F16, "bf16": IVF_BF16}
+
+EXPORTS = [
+    "ivf_build_layout", "ivf_adopt_layout", "ivf_free", "ivf_prefetch", "ivf_prefetch_wait",
+    "ivf_search", "ivf_search_device", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
+    "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
+    "ivf_profile_reset", "ivf_set_host_threads", "ivf_strerror", "ivf_last_error",
+]
+
+
+class PrefetchStats(C.Structure):
+    _fields_ = [("n_ranked", C.c_int32), ("n_taken", C.c_int32), ("n_skipped", C.c_int32),
+                ("n_resident", C.c_int32), ("bytes", C.c_uint64), ("buffer_used", C.c_uint64)]
+
+
+class SearchStats(C.Structure):
+    _fields_ = [("n_probed", C.c_int32), ("n_overlap", C.c_int32), ("n_miss", C.c_int32),
+                ("hit_rate", C.c_float), ("bytes_gpu", C.c_uint64), ("bytes_host", C.c_uint64),
+                ("ms_total", C.c_float), ("ms_probe", C.c_float), ("ms_host_scan", C.c_float)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("calls", C.c_uint64), ("ms_coarse", C.c_double), ("ms_select", C.c_double),
+                ("ms_scan", C.c_double), ("ms_merge", C.c_double), ("scan_bytes", C.c_uint64),
+                ("scan_rows", C.c_uint64)]
+
+
+class IvfError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"libivf status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Loads libivf.so; fails loudly when it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz, u32, ci = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_uint32, C.c_int
+    L.ivf_build_layout.argtypes = [vp, i64, i32, ci, vp, i32, vp, vp, ci, ci, sz, vp, vp, C.POINTER(vp)]
+    L.ivf_adopt_layout.argtypes = [vp, vp, vp, i64, i32, ci, vp, i32, ci, ci, sz, vp, vp, C.POINTER(vp)]
+    L.ivf_free.argtypes = [vp]
+    L.ivf_free.restype = None
+    L.ivf_prefetch.argtypes = [vp, vp, i32, i32, sz, u32, C.POINTER(PrefetchStats)]
+    L.ivf_prefetch_wait.argtypes = [vp, C.POINTER(C.c_float)]
+    L.ivf_search.argtypes = [vp, vp, i32, i32, i32, vp, vp, C.POINTER(SearchStats)]
+    L.ivf_search_device.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    L.ivf_reserve.argtypes = [vp, i32, i32, i32]
+    L.ivf_coarse_scores.argtypes = [vp, vp, i32, vp]
+    L.ivf_probe.argtypes = [vp, vp, i32, i32, vp]
+    L.ivf_resident.argtypes = [vp, vp, C.POINTER(i32)]
+    L.ivf_get_layout.argtypes = [vp, vp, vp]
+    L.ivf_profile_enable.argtypes = [vp, ci]
+    L.ivf_profile_read.argtypes = [vp, C.POINTER(Profile)]
+    L.ivf_profile_reset.argtypes = [vp]
+    L.ivf_set_host_threads.argtypes = [vp, i32]
+    L.ivf_strerror.argtypes = [ci]
+    L.ivf_strerror.restype = C.c_char_p
+    L.ivf_last_error.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("ivf_free", "ivf_strerror", "ivf_last_error"):
+            getattr(L, name).restype = ci
+    _lib = L
+    return L
+
+
+def _check(status):
+    if status != 0:
+        L = load()
+        raise IvfError(status, f"{L.ivf_strerror(status).decode()} ({L.ivf_last_error().decode()})")
+
+
+def _host(a, dtype):
+    """numpy view of a host array in the dtype the ABI wants (no arithmetic, copies only if needed)."""
+    if a is None:
+        return None
+    if hasattr(a, "detach"):          # torch CPU tensor
+        assert a.device.type == "cpu", "expected a host array"
+        import torch
+        if a.dtype == torch.bfloat16:
+            a = a.contiguous().view(torch.int16)
+        a = a.detach().contiguous().numpy()
+    if dtype is None:
+        return np.ascontiguousarray(a)
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    if hasattr(a, "data_ptr"):
+        return C.c_void_p(a.data_ptr())
+    return C.c_void_p(a.ctypes.data)
+
+
+def _stream(s):
+    return None if s is None else C.c_void_p(s.cuda_stream)
+
+
+def _rows_host(vectors, dtype):
+    code = DTYPE_CODE[dtype]
+    if code == IVF_F32:
+        return _host(vectors, np.float32)
+    a = _host(vectors, None)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype == np.int16:
+        a = a.view(np.uint16)
+    assert a.dtype == np.uint16 and a.flags["C_CONTIGUOUS"]
+    return a
+
+
+class Index:
+    """Owner of one ivf_index handle."""
+
+    def __init__(self, handle, d, nlist, n, keep=()):
+        self._h = handle
+        self.d, self.nlist, self.n = d, nlist, n
+        self._keep = keep      # arrays the index adopted and that must outlive it
+
+    def close(self):
+        if self._h is not None:
+            load().ivf_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- lookahead -------------------------------------------------------------------------
+    def ivf_prefetch(self, q_in, nprobe, budget_bytes, flags=0):
+        q = _host(q_in, np.float32).reshape(-1, self.d)
+        st = PrefetchStats()
+        _check(load().ivf_prefetch(self._h, _ptr(q), q.shape[0], nprobe, int(budget_bytes), flags, C.byref(st)))
+        return st
+
+    def ivf_prefetch_wait(self):
+        ms = C.c_float(0)
+        _check(load().ivf_prefetch_wait(self._h, C.byref(ms)))
+        return ms.value
+
+    # -- search ------------------------------------------------------------------------------
+    def ivf_search(self, q_out, nprobe, k, with_stats=False):
+        q = _host(q_out, np.float32).reshape(-1, self.d)
+        nq = q.shape[0]
+        ids = np.empty((nq, k), dtype=np.int64)
+        dists = np.empty((nq, k), dtype=np.float32)
+        st = SearchStats()
+        _check(load().ivf_search(self._h, _ptr(q), nq, nprobe, k, _ptr(ids), _ptr(dists), C.byref(st)
+                                 if with_stats else None))
+        return (ids, dists, st) if with_stats else (ids, dists)
+
+    def ivf_search_device(self, q_dev, nprobe, k, ids_dev, dists_dev):
+        """q_dev [nq, d] float32, ids_dev [nq, k] int64, dists_dev [nq, k] float32: CUDA tensors."""
+        assert q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda
+        assert q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()
+        nq = q_dev.numel() // self.d
+        assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
+        _check(load().ivf_search_device(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
+
+    def ivf_reserve(self, nq, nprobe, k):
+        _check(load().ivf_reserve(self._h, nq, nprobe, k))
+
+    # -- stages ------------------------------------------------------------------------------
+    def ivf_coarse_scores(self, q):
+        q = _host(q, np.float32).reshape(-1, self.d)
+        out = np.empty((q.shape[0], self.nlist), dtype=np.float64)
+        _check(load().ivf_coarse_scores(self._h, _ptr(q), q.shape[0], _ptr(out)))
+        return out
+
+    def ivf_probe(self, q, nprobe):
+        q = _host(q, np.float32).reshape(-1, self.d)
+        out = np.empty((q.shape[0], min(nprobe, self.nlist)), dtype=np.int32)
+        _check(load().ivf_probe(self._h, _ptr(q), q.shape[0], nprobe, _ptr(out)))
+        return out
+
+    def ivf_resident(self):
+        n = C.c_int32(self.nlist)
+        out = np.empty(self.nlist, dtype=np.int32)
+        _check(load().ivf_resident(self._h, _ptr(out), C.byref(n)))
+        return out[:n.value].copy()
+
+    def ivf_get_layout(self):
+        off = np.empty(self.nlist + 1, dtype=np.int64)
+        ids = np.empty(self.n, dtype=np.int64)
+        _check(load().ivf_get_layout(self._h, _ptr(off), _ptr(ids)))
+        return off, ids
+
+    # -- profiling ---------------------------------------------------------------------------
+    def ivf_profile_enable(self, on=True):
+        _check(load().ivf_profile_enable(self._h, 1 if on else 0))
+
+    def ivf_profile_read(self):
+        p = Profile()
+        _check(load().ivf_profile_read(self._h, C.byref(p)))
+        return p
+
+    def ivf_profile_reset(self):
+        _check(load().ivf_profile_reset(self._h))
+
+    def ivf_set_host_threads(self, n):
+        _check(load().ivf_set_host_threads(self._h, n))
+
+
+def ivf_build_layout(vectors, dtype, centroids, assign, ids=None, metric=IVF_IP,
+                     placement=IVF_PLACE_DEVICE, device_buffer_bytes=0, compute_stream=None,
+                     copy_stream=None):
+    rows = _rows_host(vectors, dtype)
+    cent = _host(centroids, np.float32)
+    asg = _host(assign, np.int32)
+    idv = _host(ids, np.int64)
+    n, d = rows.shape
+    nlist = cent.shape[0]
+    assert cent.shape[1] == d and asg.shape[0] == n
+    h = C.c_void_p()
+    _check(load().ivf_build_layout(_ptr(rows), n, d, DTYPE_CODE[dtype], _ptr(cent), nlist, _ptr(asg),
+                                   _ptr(idv), metric, placement, int(device_buffer_bytes),
+                                   _stream(compute_stream), _stream(copy_stream), C.byref(h)))
+    return Index(h, d, nlist, n)
+
+
+def ivf_adopt_layout(lists, dtype, offsets, centroids, ids=None, metric=IVF_IP,
+                     placement=IVF_PLACE_DEVICE, device_buffer_bytes=0, compute_stream=None,
+                     copy_stream=None):
+    """lists: torch tensor [n, d], on the GPU (device placement) or pinned on the host."""
+    assert lists.is_contiguous()
+    if placement == IVF_PLACE_DEVICE:
+        assert lists.is_cuda
+    else:
+        assert (not lists.is_cuda) and lists.is_pinned()
+    n, d = lists.shape
+    cent = _host(centroids, np.float32)
+    off = _host(offsets, np.int64)
+    idv = _host(ids, np.int64)
+    nlist = cent.shape[0]
+    h = C.c_void_p()
+    _check(load().ivf_adopt_layout(_ptr(lists), _ptr(off), _ptr(idv), n, d, DTYPE_CODE[dtype], _ptr(cent),
+                                   nlist, metric, placement, int(device_buffer_bytes),
+                                   _stream(compute_stream), _stream(copy_stream), C.byref(h)))
+    return Index(h, d, nlist, n, keep=(lists,))

@@ -1,0 +1,734 @@
+// C-ABI of libivf (include/ivf.h): index construction, lookahead prefetch planning and copies,
+// and the search drivers that enqueue the kernels of ivf_kernels.hip.
+#include "../../include/ivf.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "host_scan.h"
+#include "ivf_internal.h"
+
+namespace ivf {
+uint32_t select_sort_pad(int nlist, int nprobe);
+}
+using namespace ivf;
+
+// ---- errors -----------------------------------------------------------------------------------
+static thread_local std::string g_last_error;
+
+static int fail(int status, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return status;
+}
+
+#define HIP_TRY(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(e_ == hipErrorOutOfMemory ? IVF_ENOMEM : IVF_EHIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                             \
+    } while (0)
+
+extern "C" const char* ivf_strerror(int status) {
+    switch (status) {
+    case IVF_OK: return "ok";
+    case IVF_EINVAL: return "invalid argument";
+    case IVF_ENOMEM: return "out of memory";
+    case IVF_EHIP: return "HIP call failed";
+    case IVF_ESTATE: return "call not valid for this index";
+    case IVF_ELIMIT: return "size above what this build supports";
+    default: return "unknown status";
+    }
+}
+
+extern "C" const char* ivf_last_error(void) { return g_last_error.c_str(); }
+
+// ---- the index ----------------------------------------------------------------------------------
+namespace {
+
+constexpr int kMaxD = 4096;             // coarse kernel stages 4 queries x d floats in 64 KB of LDS
+constexpr int kProfileRing = 2048;      // searches whose events are kept before a drain
+
+struct Workspace {
+    int nq = 0, nprobe = 0, k = 0, kprime = 0, grid = 0;
+    uint32_t pad = 0;
+    float* d_q = nullptr;
+    double* d_scores = nullptr;
+    int32_t* d_probe = nullptr;
+    SlotTables slots{nullptr, nullptr, nullptr, nullptr};
+    uint64_t* d_sort_keys = nullptr;
+    uint32_t* d_sort_idx = nullptr;
+    float* d_part_key = nullptr;
+    uint32_t* d_part_row = nullptr;
+    int64_t* d_out_ids = nullptr;
+    float* d_out_dists = nullptr;
+    // pinned host staging
+    float* h_q = nullptr;
+    int32_t* h_probe = nullptr;
+    int64_t* h_out_ids = nullptr;
+    float* h_out_dists = nullptr;
+    HostCand* h_cand = nullptr;
+    int32_t* h_cand_count = nullptr;
+    double* h_scores = nullptr;   // only for ivf_coarse_scores (allocated on demand)
+    size_t h_scores_len = 0;
+};
+
+struct ProfSet { hipEvent_t e[5]; };
+
+}  // namespace
+
+struct ivf_index {
+    int64_t n = 0;
+    int d = 0, dtype = 0, nlist = 0, metric = 0, placement = 0;
+    size_t row_bytes = 0;
+    int device = 0, n_cu = 256;
+    hipStream_t compute = nullptr, copy = nullptr;
+    bool own_compute = false, own_copy = false;
+
+    float* d_centroids = nullptr;
+    int64_t* d_off = nullptr;
+    int64_t* d_ids = nullptr;
+    int64_t* d_res_off = nullptr;
+    void* d_buf = nullptr;          // device lists (device placement) or the prefetch buffer
+    size_t buf_bytes = 0;
+    bool own_buf = false;
+
+    std::vector<int64_t> h_off;
+    std::vector<int64_t> h_ids;     // empty when id = row position
+    void* h_lists = nullptr;        // pinned host lists (host placement)
+    bool own_h_lists = false;
+    std::vector<int64_t> h_res_off; // host mirror of d_res_off
+    int64_t* h_res_stage = nullptr; // pinned copy used as the source of the table upload
+    size_t buf_used = 0;
+    hipEvent_t ev_pf_begin = nullptr, ev_pf_done = nullptr, ev_probe = nullptr;
+    bool pf_recorded = false;
+
+    std::vector<uint64_t> rows_desc_prefix;   // prefix sums of list sizes, largest first
+    ScanShape shape{0, 0, 0, 4};
+    Workspace ws;
+    std::unique_ptr<ThreadPool> pool;
+
+    bool profiling = false;
+    std::vector<ProfSet> prof_sets;
+    size_t prof_used = 0;
+    ivf_profile prof{};
+    unsigned long long* d_prof_rows = nullptr;
+};
+
+namespace {
+
+void free_workspace(Workspace& w) {
+    hipFree(w.d_q); hipFree(w.d_scores); hipFree(w.d_probe);
+    hipFree(w.slots.base); hipFree(w.slots.grow); hipFree(w.slots.nrows); hipFree(w.slots.tprefix);
+    hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part_key); hipFree(w.d_part_row);
+    hipFree(w.d_out_ids); hipFree(w.d_out_dists);
+    hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
+    hipHostFree(w.h_cand); hipHostFree(w.h_cand_count); hipHostFree(w.h_scores);
+    w = Workspace{};
+}
+
+// number of scan workgroups for a search of `nprobe` clusters: enough to give every wavefront
+// one task in the worst case, at most four workgroups per compute unit
+int scan_grid_for(const ivf_index* ix, int nprobe) {
+    uint64_t rows = ix->rows_desc_prefix[std::min<size_t>(nprobe, ix->rows_desc_prefix.size() - 1)];
+    uint64_t tasks = rows / ix->shape.rows_per_task + (uint64_t)nprobe;
+    uint64_t g = (tasks + 3) / 4;
+    uint64_t cap = (uint64_t)ix->n_cu * 4;
+    if (g > cap) g = cap;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
+    Workspace& w = ix->ws;
+    const int kprime = kprime_for(k);
+    const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
+    const int grid_cap = ix->n_cu * 4;
+    if (nq <= w.nq && nprobe <= w.nprobe && k <= w.k && pad <= w.pad) return IVF_OK;
+    const int nq2 = std::max(nq, w.nq), np2 = std::max(nprobe, w.nprobe), k2 = std::max(k, w.k);
+    const uint32_t pad2 = std::max(pad, w.pad);
+    const int kp2 = std::max(kprime, w.kprime);
+    HIP_TRY(hipDeviceSynchronize());
+    free_workspace(w);
+    const size_t nqz = nq2, npz = np2;
+    HIP_TRY(hipMalloc(&w.d_q, nqz * ix->d * sizeof(float)));
+    HIP_TRY(hipMalloc(&w.d_scores, nqz * ix->nlist * sizeof(double)));
+    HIP_TRY(hipMalloc(&w.d_probe, nqz * npz * sizeof(int32_t)));
+    HIP_TRY(hipMalloc(&w.slots.base, nqz * npz * sizeof(int64_t)));
+    HIP_TRY(hipMalloc(&w.slots.grow, nqz * npz * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.slots.nrows, nqz * npz * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.slots.tprefix, nqz * (npz + 1) * sizeof(uint32_t)));
+    if (pad2 > (uint32_t)kSortLdsCap) {
+        HIP_TRY(hipMalloc(&w.d_sort_keys, nqz * pad2 * sizeof(uint64_t)));
+        HIP_TRY(hipMalloc(&w.d_sort_idx, nqz * pad2 * sizeof(uint32_t)));
+    }
+    HIP_TRY(hipMalloc(&w.d_part_key, nqz * grid_cap * kp2 * sizeof(float)));
+    HIP_TRY(hipMalloc(&w.d_part_row, nqz * grid_cap * kp2 * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_out_ids, nqz * k2 * sizeof(int64_t)));
+    HIP_TRY(hipMalloc(&w.d_out_dists, nqz * k2 * sizeof(float)));
+    HIP_TRY(hipHostMalloc(&w.h_q, nqz * ix->d * sizeof(float)));
+    HIP_TRY(hipHostMalloc(&w.h_probe, nqz * npz * sizeof(int32_t)));
+    HIP_TRY(hipHostMalloc(&w.h_out_ids, nqz * k2 * sizeof(int64_t)));
+    HIP_TRY(hipHostMalloc(&w.h_out_dists, nqz * k2 * sizeof(float)));
+    HIP_TRY(hipHostMalloc(&w.h_cand, nqz * kp2 * sizeof(HostCand)));
+    HIP_TRY(hipHostMalloc(&w.h_cand_count, nqz * sizeof(int32_t)));
+    memset(w.h_cand_count, 0, nqz * sizeof(int32_t));
+    w.nq = nq2; w.nprobe = np2; w.k = k2; w.kprime = kp2; w.pad = pad2; w.grid = grid_cap;
+    return IVF_OK;
+}
+
+int check_query_args(const ivf_index* ix, const void* q, int32_t nq, int32_t nprobe) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (!q) return fail(IVF_EINVAL, "query pointer is NULL");
+    if (nq < 1) return fail(IVF_EINVAL, "nq must be at least 1 (got %d)", nq);
+    if (nprobe < 1) return fail(IVF_EINVAL, "nprobe must be at least 1 (got %d)", nprobe);
+    return IVF_OK;
+}
+
+// ---- profiling events ---------------------------------------------------------------------
+int drain_profile(ivf_index* ix) {
+    if (ix->prof_used == 0) return IVF_OK;
+    HIP_TRY(hipStreamSynchronize(ix->compute));
+    for (size_t i = 0; i < ix->prof_used; ++i) {
+        float ms[4];
+        for (int j = 0; j < 4; ++j) HIP_TRY(hipEventElapsedTime(&ms[j], ix->prof_sets[i].e[j], ix->prof_sets[i].e[j + 1]));
+        ix->prof.ms_coarse += ms[0]; ix->prof.ms_select += ms[1];
+        ix->prof.ms_scan += ms[2]; ix->prof.ms_merge += ms[3];
+        ix->prof.calls += 1;
+    }
+    ix->prof_used = 0;
+    unsigned long long rows = 0;
+    HIP_TRY(hipMemcpy(&rows, ix->d_prof_rows, sizeof rows, hipMemcpyDeviceToHost));
+    ix->prof.scan_rows = rows;
+    ix->prof.scan_bytes = rows * ix->row_bytes;
+    return IVF_OK;
+}
+
+int prof_mark(ivf_index* ix, int which) {
+    if (!ix->profiling) return IVF_OK;
+    if (which == 0 && ix->prof_used == ix->prof_sets.size()) {
+        int rc = drain_profile(ix);
+        if (rc) return rc;
+    }
+    HIP_TRY(hipEventRecord(ix->prof_sets[ix->prof_used].e[which], ix->compute));
+    if (which == 4) ix->prof_used += 1;
+    return IVF_OK;
+}
+
+// ---- kernel sequences ---------------------------------------------------------------------
+// coarse scoring + selection for nq queries already in d_q (device); leaves the probe lists
+// and slot tables in the workspace
+int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe) {
+    Workspace& w = ix->ws;
+    int rc;
+    if ((rc = prof_mark(ix, 0))) return rc;
+    CoarseArgs ca{ix->d_centroids, q_dev, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
+    HIP_TRY(launch_coarse(ca, ix->compute));
+    if ((rc = prof_mark(ix, 1))) return rc;
+    SelectArgs sa{};
+    sa.scores = w.d_scores; sa.probe = w.d_probe; sa.off = ix->d_off; sa.res_off = ix->d_res_off;
+    sa.slots = w.slots; sa.sort_keys = w.d_sort_keys; sa.sort_idx = w.d_sort_idx;
+    sa.nlist = ix->nlist; sa.nprobe = nprobe; sa.nq = nq; sa.metric = ix->metric;
+    sa.rows_per_task = ix->shape.rows_per_task;
+    sa.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
+    HIP_TRY(launch_select(sa, ix->compute));
+    if ((rc = prof_mark(ix, 2))) return rc;
+    return IVF_OK;
+}
+
+int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kprime, int grid) {
+    Workspace& w = ix->ws;
+    ScanArgs sc{};
+    sc.buf = ix->d_buf; sc.q = q_dev; sc.ids = ix->d_ids; sc.slots = w.slots;
+    sc.part_key = w.d_part_key; sc.part_row = w.d_part_row;
+    sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
+    sc.kprime = kprime; sc.grid = grid; sc.shape = ix->shape;
+    HIP_TRY(launch_scan(sc, ix->compute));
+    return prof_mark(ix, 3);
+}
+
+int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, int grid,
+                  bool with_host, int64_t* out_ids, float* out_dists) {
+    Workspace& w = ix->ws;
+    MergeArgs ma{};
+    ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.slots = w.slots;
+    ma.part_key = w.d_part_key; ma.part_row = w.d_part_row;
+    ma.host_cand = with_host ? w.h_cand : nullptr;
+    ma.host_count = with_host ? w.h_cand_count : nullptr;
+    ma.out_ids = out_ids; ma.out_dists = out_dists;
+    ma.d = ix->d; ma.dtype = ix->dtype; ma.metric = ix->metric; ma.nprobe = nprobe; ma.nq = nq;
+    ma.k = k; ma.kprime = kprime; ma.nparts = grid;
+    ma.identity = ix->placement == IVF_PLACE_DEVICE;
+    HIP_TRY(launch_merge(ma, ix->compute));
+    return prof_mark(ix, 4);
+}
+
+// ---- construction helpers --------------------------------------------------------------------
+int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* centroids, int32_t nlist,
+                int metric, int placement, void* compute_stream, void* copy_stream) {
+    ix->n = n; ix->d = d; ix->dtype = dtype; ix->nlist = nlist; ix->metric = metric;
+    ix->placement = placement;
+    ix->row_bytes = (size_t)d * (dtype == IVF_F32 ? 4 : 2);
+    HIP_TRY(hipGetDevice(&ix->device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, ix->device));
+    ix->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (compute_stream) ix->compute = (hipStream_t)compute_stream;
+    else { HIP_TRY(hipStreamCreateWithFlags(&ix->compute, hipStreamNonBlocking)); ix->own_compute = true; }
+    if (copy_stream) ix->copy = (hipStream_t)copy_stream;
+    else { HIP_TRY(hipStreamCreateWithFlags(&ix->copy, hipStreamNonBlocking)); ix->own_copy = true; }
+    HIP_TRY(hipEventCreate(&ix->ev_pf_begin));
+    HIP_TRY(hipEventCreate(&ix->ev_pf_done));
+    HIP_TRY(hipEventCreateWithFlags(&ix->ev_probe, hipEventDisableTiming));
+    HIP_TRY(hipMalloc(&ix->d_centroids, (size_t)nlist * d * sizeof(float)));
+    HIP_TRY(hipMemcpy(ix->d_centroids, centroids, (size_t)nlist * d * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(hipMalloc(&ix->d_off, (size_t)(nlist + 1) * sizeof(int64_t)));
+    HIP_TRY(hipMalloc(&ix->d_res_off, (size_t)nlist * sizeof(int64_t)));
+    HIP_TRY(hipMalloc(&ix->d_prof_rows, sizeof(unsigned long long)));
+    HIP_TRY(hipMemset(ix->d_prof_rows, 0, sizeof(unsigned long long)));
+    HIP_TRY(hipDeviceSynchronize());
+    ix->shape = pick_scan_shape(d, dtype);
+    return IVF_OK;
+}
+
+// after h_off / h_ids are set: uploads them and initialises residency
+int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
+    const int nlist = ix->nlist;
+    HIP_TRY(hipMemcpy(ix->d_off, ix->h_off.data(), (size_t)(nlist + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    if (!ix->h_ids.empty()) {
+        HIP_TRY(hipMalloc(&ix->d_ids, (size_t)ix->n * sizeof(int64_t)));
+        HIP_TRY(hipMemcpy(ix->d_ids, ix->h_ids.data(), (size_t)ix->n * sizeof(int64_t), hipMemcpyHostToDevice));
+    }
+    ix->h_res_off.assign(nlist, -1);
+    if (ix->placement == IVF_PLACE_DEVICE) {
+        for (int c = 0; c < nlist; ++c) ix->h_res_off[c] = ix->h_off[c];
+    } else {
+        ix->buf_bytes = device_buffer_bytes;
+        if (device_buffer_bytes > 0) HIP_TRY(hipMalloc(&ix->d_buf, device_buffer_bytes));
+        ix->own_buf = true;
+        HIP_TRY(hipHostMalloc(&ix->h_res_stage, (size_t)nlist * sizeof(int64_t)));
+        unsigned hw = std::thread::hardware_concurrency();
+        int nt = hw == 0 ? 8 : (int)std::min(hw, 64u);
+        ix->pool.reset(new ThreadPool(nt));
+    }
+    HIP_TRY(hipMemcpy(ix->d_res_off, ix->h_res_off.data(), (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice));
+    std::vector<uint64_t> sizes(nlist);
+    for (int c = 0; c < nlist; ++c) sizes[c] = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]);
+    std::sort(sizes.begin(), sizes.end(), std::greater<uint64_t>());
+    ix->rows_desc_prefix.assign(nlist + 1, 0);
+    for (int c = 0; c < nlist; ++c) ix->rows_desc_prefix[c + 1] = ix->rows_desc_prefix[c] + sizes[c];
+    return IVF_OK;
+}
+
+int check_build_args(const void* data, int64_t n, int32_t d, int dtype, const float* centroids,
+                     int32_t nlist, int metric, int placement, ivf_index** out) {
+    if (!data && n > 0) return fail(IVF_EINVAL, "vector data pointer is NULL");
+    if (!centroids || !out) return fail(IVF_EINVAL, "centroids or out is NULL");
+    if (n < 0 || d < 1 || nlist < 1) return fail(IVF_EINVAL, "need n >= 0, d >= 1, nlist >= 1");
+    if (dtype < IVF_F32 || dtype > IVF_BF16) return fail(IVF_EINVAL, "unknown dtype %d", dtype);
+    if (metric != IVF_IP && metric != IVF_L2) return fail(IVF_EINVAL, "unknown metric %d", metric);
+    if (placement != IVF_PLACE_DEVICE && placement != IVF_PLACE_HOST)
+        return fail(IVF_EINVAL, "unknown placement %d", placement);
+    if (d > kMaxD) return fail(IVF_ELIMIT, "d = %d is above the supported %d", d, kMaxD);
+    if (n >= 0xFFFFFFFFll) return fail(IVF_ELIMIT, "n = %lld does not fit 32-bit row numbers", (long long)n);
+    if (placement == IVF_PLACE_HOST &&
+        !(__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma") && __builtin_cpu_supports("f16c")))
+        return fail(IVF_ESTATE, "host placement needs a CPU with AVX2, FMA and F16C");
+    return IVF_OK;
+}
+
+}  // namespace
+
+extern "C" void ivf_free(ivf_index* ix) {
+    if (!ix) return;
+    hipDeviceSynchronize();
+    free_workspace(ix->ws);
+    for (auto& s : ix->prof_sets) for (auto& e : s.e) hipEventDestroy(e);
+    hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_res_off);
+    hipFree(ix->d_prof_rows);
+    if (ix->own_buf) hipFree(ix->d_buf);
+    if (ix->own_h_lists) hipHostFree(ix->h_lists);
+    hipHostFree(ix->h_res_stage);
+    if (ix->ev_pf_begin) hipEventDestroy(ix->ev_pf_begin);
+    if (ix->ev_pf_done) hipEventDestroy(ix->ev_pf_done);
+    if (ix->ev_probe) hipEventDestroy(ix->ev_probe);
+    if (ix->own_compute) hipStreamDestroy(ix->compute);
+    if (ix->own_copy) hipStreamDestroy(ix->copy);
+    delete ix;
+}
+
+extern "C" int ivf_build_layout(const void* vectors, int64_t n, int32_t d, int dtype,
+                                const float* centroids, int32_t nlist, const int32_t* assign,
+                                const int64_t* ids, int metric, int placement,
+                                size_t device_buffer_bytes, void* compute_stream, void* copy_stream,
+                                ivf_index** out) {
+    int rc = check_build_args(vectors, n, d, dtype, centroids, nlist, metric, placement, out);
+    if (rc) return rc;
+    if (!assign && n > 0) return fail(IVF_EINVAL, "assign is NULL");
+    // stable grouping by cluster: pos[i] = position of input row i in cluster-major order
+    std::vector<int64_t> off(nlist + 1, 0);
+    for (int64_t i = 0; i < n; ++i) {
+        if (assign[i] < 0 || assign[i] >= nlist)
+            return fail(IVF_EINVAL, "assign[%lld] = %d is outside [0, %d)", (long long)i, assign[i], nlist);
+        off[assign[i] + 1] += 1;
+    }
+    for (int c = 0; c < nlist; ++c) off[c + 1] += off[c];
+    std::vector<int64_t> pos(n), cursor(off.begin(), off.end() - 1);
+    for (int64_t i = 0; i < n; ++i) pos[i] = cursor[assign[i]]++;
+
+    ivf_index* ix = new (std::nothrow) ivf_index();
+    if (!ix) return fail(IVF_ENOMEM, "host allocation failed");
+    rc = init_common(ix, n, d, dtype, centroids, nlist, metric, placement, compute_stream, copy_stream);
+    if (rc) { ivf_free(ix); return rc; }
+    ix->h_off = off;
+    ix->h_ids.resize(n);
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t id = ids ? ids[i] : i;
+        if (id < 0) { ivf_free(ix); return fail(IVF_EINVAL, "ids[%lld] is negative", (long long)i); }
+        ix->h_ids[pos[i]] = id;
+    }
+    const size_t rb = ix->row_bytes;
+    auto body = [&]() -> int {
+        if (placement == IVF_PLACE_DEVICE) {
+            ix->buf_bytes = (size_t)n * rb;
+            ix->own_buf = true;
+            if (n > 0) HIP_TRY(hipMalloc(&ix->d_buf, ix->buf_bytes));
+            // upload input rows in chunks and scatter them to their cluster-major positions
+            const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(n, (int64_t)((256u << 20) / rb)));
+            void* d_stage = nullptr; int64_t* d_pos = nullptr;
+            if (n > 0) {
+                HIP_TRY(hipMalloc(&d_stage, (size_t)chunk * rb));
+                HIP_TRY(hipMalloc(&d_pos, (size_t)chunk * sizeof(int64_t)));
+            }
+            int status = IVF_OK;
+            for (int64_t i0 = 0; i0 < n && status == IVF_OK; i0 += chunk) {
+                int64_t cnt = std::min(chunk, n - i0);
+                hipError_t e = hipMemcpy(d_stage, (const char*)vectors + (size_t)i0 * rb, (size_t)cnt * rb, hipMemcpyHostToDevice);
+                if (e == hipSuccess) e = hipMemcpy(d_pos, pos.data() + i0, (size_t)cnt * sizeof(int64_t), hipMemcpyHostToDevice);
+                if (e == hipSuccess) e = launch_scatter_rows(d_stage, ix->d_buf, d_pos, cnt, rb, ix->compute);
+                if (e == hipSuccess) e = hipStreamSynchronize(ix->compute);
+                if (e != hipSuccess) status = fail(IVF_EHIP, "layout upload: %s", hipGetErrorString(e));
+            }
+            hipFree(d_stage); hipFree(d_pos);
+            if (status) return status;
+        } else {
+            if (n > 0) HIP_TRY(hipHostMalloc(&ix->h_lists, (size_t)n * rb));
+            ix->own_h_lists = true;
+            for (int64_t i = 0; i < n; ++i)
+                memcpy((char*)ix->h_lists + (size_t)pos[i] * rb, (const char*)vectors + (size_t)i * rb, rb);
+        }
+        return finish_tables(ix, device_buffer_bytes);
+    };
+    rc = body();
+    if (rc) { ivf_free(ix); return rc; }
+    *out = ix;
+    return IVF_OK;
+}
+
+extern "C" int ivf_adopt_layout(void* lists, const int64_t* offsets, const int64_t* ids, int64_t n,
+                                int32_t d, int dtype, const float* centroids, int32_t nlist,
+                                int metric, int placement, size_t device_buffer_bytes,
+                                void* compute_stream, void* copy_stream, ivf_index** out) {
+    int rc = check_build_args(lists, n, d, dtype, centroids, nlist, metric, placement, out);
+    if (rc) return rc;
+    if (!offsets) return fail(IVF_EINVAL, "offsets is NULL");
+    if (offsets[0] != 0 || offsets[nlist] != n) return fail(IVF_EINVAL, "offsets must run from 0 to n");
+    for (int c = 0; c < nlist; ++c)
+        if (offsets[c + 1] < offsets[c]) return fail(IVF_EINVAL, "offsets decrease at cluster %d", c);
+    ivf_index* ix = new (std::nothrow) ivf_index();
+    if (!ix) return fail(IVF_ENOMEM, "host allocation failed");
+    rc = init_common(ix, n, d, dtype, centroids, nlist, metric, placement, compute_stream, copy_stream);
+    if (rc) { ivf_free(ix); return rc; }
+    ix->h_off.assign(offsets, offsets + nlist + 1);
+    if (ids) {
+        for (int64_t i = 0; i < n; ++i)
+            if (ids[i] < 0) { ivf_free(ix); return fail(IVF_EINVAL, "ids[%lld] is negative", (long long)i); }
+        ix->h_ids.assign(ids, ids + n);
+    }
+    if (placement == IVF_PLACE_DEVICE) {
+        ix->d_buf = lists; ix->buf_bytes = (size_t)n * ix->row_bytes; ix->own_buf = false;
+    } else {
+        ix->h_lists = lists; ix->own_h_lists = false;
+    }
+    rc = finish_tables(ix, device_buffer_bytes);
+    if (rc) { ivf_free(ix); return rc; }
+    *out = ix;
+    return IVF_OK;
+}
+
+extern "C" int ivf_reserve(ivf_index* ix, int32_t nq, int32_t nprobe, int32_t k) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (nq < 1 || nprobe < 1 || k < 1) return fail(IVF_EINVAL, "nq, nprobe and k must be at least 1");
+    if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
+    return ensure_workspace(ix, nq, std::min(nprobe, ix->nlist), k);
+}
+
+// ---- search -------------------------------------------------------------------------------------
+extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, int32_t nprobe,
+                                 int32_t k, int64_t* ids_dev, float* dists_dev) {
+    int rc = check_query_args(ix, q_dev, nq, nprobe);
+    if (rc) return rc;
+    if (!ids_dev || !dists_dev) return fail(IVF_EINVAL, "output pointer is NULL");
+    if (k < 1) return fail(IVF_EINVAL, "k must be at least 1 (got %d)", k);
+    if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
+    if (ix->placement != IVF_PLACE_DEVICE)
+        return fail(IVF_ESTATE, "ivf_search_device needs a device-resident index");
+    nprobe = std::min(nprobe, ix->nlist);
+    if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
+    const int kprime = kprime_for(k);
+    const int grid = scan_grid_for(ix, nprobe);
+    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe))) return rc;
+    if ((rc = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return rc;
+    return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+}
+
+static double now_ms() {
+    using namespace std::chrono;
+    return duration<double, std::milli>(steady_clock::now().time_since_epoch()).count();
+}
+
+extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t nprobe, int32_t k,
+                          int64_t* ids, float* dists, ivf_search_stats* stats) {
+    int rc = check_query_args(ix, q_out, nq, nprobe);
+    if (rc) return rc;
+    if (!ids || !dists) return fail(IVF_EINVAL, "output pointer is NULL");
+    if (k < 1) return fail(IVF_EINVAL, "k must be at least 1 (got %d)", k);
+    if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
+    const double t0 = now_ms();
+    nprobe = std::min(nprobe, ix->nlist);
+    if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
+    Workspace& w = ix->ws;
+    const int kprime = kprime_for(k);
+    const int grid = scan_grid_for(ix, nprobe);
+    const bool hybrid = ix->placement == IVF_PLACE_HOST;
+    ivf_search_stats st{};
+
+    memcpy(w.h_q, q_out, (size_t)nq * ix->d * sizeof(float));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    if (hybrid && ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->compute, ix->ev_pf_done, 0));
+    if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe))) return rc;
+    const bool want_probe = hybrid || stats;
+    if (want_probe) {
+        HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
+        HIP_TRY(hipEventRecord(ix->ev_probe, ix->compute));
+    }
+    if ((rc = enqueue_scan(ix, w.d_q, nq, nprobe, kprime, grid))) return rc;
+
+    if (want_probe) {
+        HIP_TRY(hipEventSynchronize(ix->ev_probe));
+        st.ms_probe = (float)(now_ms() - t0);
+        double hit_sum = 0.0;
+        std::vector<int32_t> miss;
+        const double ts = now_ms();
+        for (int qi = 0; qi < nq; ++qi) {
+            miss.clear();
+            int overlap = 0;
+            for (int i = 0; i < nprobe; ++i) {
+                int32_t c = w.h_probe[(size_t)qi * nprobe + i];
+                uint64_t bytes = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * ix->row_bytes;
+                if (ix->h_res_off[c] >= 0) { ++overlap; st.bytes_gpu += bytes; }
+                else { miss.push_back(c); st.bytes_host += bytes; }
+            }
+            st.n_probed += nprobe; st.n_overlap += overlap; st.n_miss += (int)miss.size();
+            hit_sum += (double)overlap / (double)nprobe;
+            if (hybrid) {
+                HostScanArgs ha{ix->h_lists, ix->h_off.data(), ix->h_ids.empty() ? nullptr : ix->h_ids.data(),
+                                ix->d, ix->dtype, ix->metric, q_out + (size_t)qi * ix->d,
+                                miss.data(), (int)miss.size(), kprime};
+                w.h_cand_count[qi] = host_scan_query(ha, *ix->pool, w.h_cand + (size_t)qi * kprime, nullptr);
+            }
+        }
+        st.ms_host_scan = (float)(now_ms() - ts);
+        st.hit_rate = (float)(hit_sum / nq);
+    }
+    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.d_out_ids, w.d_out_dists))) return rc;
+    HIP_TRY(hipMemcpyAsync(w.h_out_ids, w.d_out_ids, (size_t)nq * k * sizeof(int64_t), hipMemcpyDeviceToHost, ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.h_out_dists, w.d_out_dists, (size_t)nq * k * sizeof(float), hipMemcpyDeviceToHost, ix->compute));
+    HIP_TRY(hipStreamSynchronize(ix->compute));
+    memcpy(ids, w.h_out_ids, (size_t)nq * k * sizeof(int64_t));
+    memcpy(dists, w.h_out_dists, (size_t)nq * k * sizeof(float));
+    st.ms_total = (float)(now_ms() - t0);
+    if (stats) *stats = st;
+    return IVF_OK;
+}
+
+// ---- lookahead prefetch --------------------------------------------------------------------------
+extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_t nprobe,
+                            size_t budget_bytes, uint32_t flags, ivf_prefetch_stats* stats) {
+    int rc = check_query_args(ix, q_in, nq, nprobe);
+    if (rc) return rc;
+    if (ix->placement != IVF_PLACE_HOST) return fail(IVF_ESTATE, "ivf_prefetch needs a host-placed index");
+    if (flags & ~IVF_PREFETCH_RESET) return fail(IVF_EINVAL, "unknown prefetch flags 0x%x", flags);
+    nprobe = std::min(nprobe, ix->nlist);
+    if ((rc = ensure_workspace(ix, nq, nprobe, 1))) return rc;
+    Workspace& w = ix->ws;
+    // rank the clusters by q_in on the GPU
+    memcpy(w.h_q, q_in, (size_t)nq * ix->d * sizeof(float));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    const bool was_profiling = ix->profiling;
+    ix->profiling = false;
+    rc = enqueue_probe(ix, w.d_q, nq, nprobe);
+    ix->profiling = was_profiling;
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
+    HIP_TRY(hipStreamSynchronize(ix->compute));
+
+    if (flags & IVF_PREFETCH_RESET) {
+        std::fill(ix->h_res_off.begin(), ix->h_res_off.end(), (int64_t)-1);
+        ix->buf_used = 0;
+    }
+    ivf_prefetch_stats st{};
+    HIP_TRY(hipEventRecord(ix->ev_pf_begin, ix->copy));
+    const size_t per_query = budget_bytes / (size_t)nq;
+    const size_t rb = ix->row_bytes;
+    for (int qi = 0; qi < nq; ++qi) {
+        size_t remaining = per_query;
+        for (int i = 0; i < nprobe; ++i) {
+            const int32_t c = w.h_probe[(size_t)qi * nprobe + i];
+            st.n_ranked += 1;
+            if (ix->h_res_off[c] >= 0) { st.n_resident += 1; continue; }
+            const size_t bytes = (size_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
+            if (bytes <= remaining && bytes <= ix->buf_bytes - ix->buf_used) {
+                if (bytes > 0)
+                    HIP_TRY(hipMemcpyAsync((char*)ix->d_buf + ix->buf_used,
+                                           (const char*)ix->h_lists + (size_t)ix->h_off[c] * rb, bytes,
+                                           hipMemcpyHostToDevice, ix->copy));
+                ix->h_res_off[c] = (int64_t)(ix->buf_used / rb);
+                ix->buf_used += bytes;
+                remaining -= bytes;
+                st.bytes += bytes;
+                st.n_taken += 1;
+            } else {
+                st.n_skipped += 1;
+            }
+        }
+    }
+    // the residency table follows the data on the same stream
+    memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)ix->nlist * sizeof(int64_t));
+    HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)ix->nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->copy));
+    HIP_TRY(hipEventRecord(ix->ev_pf_done, ix->copy));
+    ix->pf_recorded = true;
+    st.buffer_used = ix->buf_used;
+    if (stats) *stats = st;
+    return IVF_OK;
+}
+
+extern "C" int ivf_prefetch_wait(ivf_index* ix, float* ms) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (ix->placement != IVF_PLACE_HOST) return fail(IVF_ESTATE, "not a host-placed index");
+    if (ms) *ms = 0.f;
+    if (!ix->pf_recorded) return IVF_OK;
+    HIP_TRY(hipEventSynchronize(ix->ev_pf_done));
+    if (ms) HIP_TRY(hipEventElapsedTime(ms, ix->ev_pf_begin, ix->ev_pf_done));
+    return IVF_OK;
+}
+
+// ---- stage-level entry points ----------------------------------------------------------------------
+extern "C" int ivf_coarse_scores(ivf_index* ix, const float* q, int32_t nq, double* scores) {
+    int rc = check_query_args(ix, q, nq, 1);
+    if (rc) return rc;
+    if (!scores) return fail(IVF_EINVAL, "scores is NULL");
+    if ((rc = ensure_workspace(ix, nq, 1, 1))) return rc;
+    Workspace& w = ix->ws;
+    memcpy(w.h_q, q, (size_t)nq * ix->d * sizeof(float));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    CoarseArgs ca{ix->d_centroids, w.d_q, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
+    HIP_TRY(launch_coarse(ca, ix->compute));
+    HIP_TRY(hipStreamSynchronize(ix->compute));
+    HIP_TRY(hipMemcpy(scores, w.d_scores, (size_t)nq * ix->nlist * sizeof(double), hipMemcpyDeviceToHost));
+    return IVF_OK;
+}
+
+extern "C" int ivf_probe(ivf_index* ix, const float* q, int32_t nq, int32_t nprobe, int32_t* clusters) {
+    int rc = check_query_args(ix, q, nq, nprobe);
+    if (rc) return rc;
+    if (!clusters) return fail(IVF_EINVAL, "clusters is NULL");
+    nprobe = std::min(nprobe, ix->nlist);
+    if ((rc = ensure_workspace(ix, nq, nprobe, 1))) return rc;
+    Workspace& w = ix->ws;
+    memcpy(w.h_q, q, (size_t)nq * ix->d * sizeof(float));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    const bool was_profiling = ix->profiling;
+    ix->profiling = false;
+    rc = enqueue_probe(ix, w.d_q, nq, nprobe);
+    ix->profiling = was_profiling;
+    if (rc) return rc;
+    HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
+    HIP_TRY(hipStreamSynchronize(ix->compute));
+    memcpy(clusters, w.h_probe, (size_t)nq * nprobe * sizeof(int32_t));
+    return IVF_OK;
+}
+
+extern "C" int ivf_resident(ivf_index* ix, int32_t* clusters, int32_t* n) {
+    if (!ix || !n) return fail(IVF_EINVAL, "index or n is NULL");
+    int32_t cap = *n, cnt = 0;
+    for (int c = 0; c < ix->nlist; ++c) {
+        if (ix->h_res_off[c] < 0) continue;
+        if (clusters && cnt < cap) clusters[cnt] = c;
+        ++cnt;
+    }
+    *n = cnt;
+    return IVF_OK;
+}
+
+extern "C" int ivf_get_layout(ivf_index* ix, int64_t* offsets, int64_t* ids) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (offsets) memcpy(offsets, ix->h_off.data(), (size_t)(ix->nlist + 1) * sizeof(int64_t));
+    if (ids) {
+        if (ix->h_ids.empty()) for (int64_t i = 0; i < ix->n; ++i) ids[i] = i;
+        else memcpy(ids, ix->h_ids.data(), (size_t)ix->n * sizeof(int64_t));
+    }
+    return IVF_OK;
+}
+
+// ---- profiling ------------------------------------------------------------------------------------
+extern "C" int ivf_profile_enable(ivf_index* ix, int on) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (on && ix->prof_sets.empty()) {
+        ix->prof_sets.resize(kProfileRing);
+        for (auto& s : ix->prof_sets) for (auto& e : s.e) HIP_TRY(hipEventCreate(&e));
+    }
+    if (!on) { int rc = drain_profile(ix); if (rc) return rc; }
+    ix->profiling = on != 0;
+    return IVF_OK;
+}
+
+extern "C" int ivf_profile_read(ivf_index* ix, ivf_profile* out) {
+    if (!ix || !out) return fail(IVF_EINVAL, "index or out is NULL");
+    int rc = drain_profile(ix);
+    if (rc) return rc;
+    *out = ix->prof;
+    return IVF_OK;
+}
+
+extern "C" int ivf_profile_reset(ivf_index* ix) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    int rc = drain_profile(ix);
+    if (rc) return rc;
+    ix->prof = ivf_profile{};
+    HIP_TRY(hipMemset(ix->d_prof_rows, 0, sizeof(unsigned long long)));
+    HIP_TRY(hipDeviceSynchronize());
+    return IVF_OK;
+}
+
+extern "C" int ivf_set_host_threads(ivf_index* ix, int32_t n) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (n < 1 || n > 256) return fail(IVF_EINVAL, "thread count must be in [1, 256]");
+    if (ix->placement != IVF_PLACE_HOST) return fail(IVF_ESTATE, "not a host-placed index");
+    ix->pool.reset(new ThreadPool(n));
+    return IVF_OK;
+}

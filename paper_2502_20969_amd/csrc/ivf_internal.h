@@ -1,0 +1,90 @@
+// Internal declarations shared by the host side (ivf_api.hip, host_scan.cpp) and the
+// kernel launchers (ivf_kernels.hip).  Not part of the public boundary (include/ivf.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ivf_host_types.h"
+
+namespace ivf {
+
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;   // empty slot of a candidate list
+constexpr int kMaxKPrime = 128;            // candidates kept per list: k + slack <= 128
+constexpr int kScanThreads = 256;          // scan workgroup: 4 wavefronts
+constexpr int kSelectThreads = 1024;       // select / merge workgroup: 16 wavefronts
+constexpr int kSortLdsCap = 2048;          // select: pairs sorted in LDS up to this many
+constexpr int kScanLdsSlots = 2048;        // scan: slot table kept in LDS up to this nprobe
+
+// candidates re-scored in fp64 per query: the requested k plus a margin that absorbs the
+// rounding of the fp32 scan
+inline int kprime_for(int k) {
+    int slack = k / 8 > 8 ? k / 8 : 8;
+    int kp = k + slack;
+    return kp > kMaxKPrime ? kMaxKPrime : kp;
+}
+
+// How one scan kernel variant walks rows: a task is `rows_per_task` consecutive rows of a list.
+struct ScanShape {
+    int lanes_per_row;   // 16, 32 or 64; 0 selects the any-d fallback kernel
+    int segments;        // 16-byte loads per lane per row
+    int unroll;          // row groups in flight per wavefront
+    int rows_per_task;
+};
+ScanShape pick_scan_shape(int d, int dtype);
+
+struct SlotTables {          // written by the select kernel, read by scan and merge; per query
+    int64_t* base;           // [nq x nprobe]   row offset of the list in the device buffer, -1 = not resident
+    uint32_t* grow;          // [nq x nprobe]   global row of the list's first row
+    uint32_t* nrows;         // [nq x nprobe]   rows in the list
+    uint32_t* tprefix;       // [nq x (nprobe+1)] exclusive prefix of tasks over resident slots
+};
+
+struct CoarseArgs {
+    const float* centroids; const float* q; double* scores;
+    int nlist, d, nq, metric;
+};
+hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s);
+
+struct SelectArgs {
+    const double* scores;    // [nq x nlist]
+    int32_t* probe;          // [nq x nprobe] out, nearest first
+    const int64_t* off;      // [nlist+1]
+    const int64_t* res_off;  // [nlist] row offset in the device buffer or -1
+    SlotTables slots;
+    uint64_t* sort_keys;     // global scratch [nq x pad] when the sort does not fit LDS
+    uint32_t* sort_idx;
+    unsigned long long* rows_counter;  // nullable: receives the rows of all resident selected lists
+    int nlist, nprobe, nq, metric, rows_per_task;
+};
+hipError_t launch_select(const SelectArgs& a, hipStream_t s);
+
+struct ScanArgs {
+    const void* buf;         // device buffer holding resident lists, row-major
+    const float* q;          // [nq x d]
+    const int64_t* ids;      // [n] global row -> id, or nullptr (id = global row)
+    SlotTables slots;
+    float* part_key;         // [nq x grid x kprime] out, larger = nearer
+    uint32_t* part_row;      // [nq x grid x kprime] out, global row or kNoRow
+    int d, dtype, metric, nprobe, nq, kprime, grid;
+    ScanShape shape;
+};
+hipError_t launch_scan(const ScanArgs& a, hipStream_t s);
+
+struct MergeArgs {
+    const void* buf; const float* q; const int64_t* ids;
+    SlotTables slots;
+    const float* part_key; const uint32_t* part_row;
+    const HostCand* host_cand;   // [nq x kprime] device-visible, or nullptr
+    const int32_t* host_count;   // [nq] valid entries in host_cand
+    int64_t* out_ids; float* out_dists;   // [nq x k]
+    int d, dtype, metric, nprobe, nq, k, kprime, nparts;
+    int identity;            // 1: buffer row == global row (device placement)
+};
+hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+
+// scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
+hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,
+                               size_t row_bytes, hipStream_t s);
+
+}  // namespace ivf

@@ -1,0 +1,99 @@
+"""GPU parity of lookahead retrieval (Sec. 4.1 steps 1-4, Sec. 4.3 'Prefetching target'): prefetch
+plan, residency, overlap/miss split and the hybrid GPU + host search, against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2502_20969_amd as P
+import workloads as W
+from parity import check_topk, stored
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def streams():
+    assert torch.cuda.is_available()
+    return torch.cuda.Stream(), torch.cuda.Stream()
+
+
+def _problem(seed, n, d, nlist, dtype):
+    sizes = W.zipf_sizes(n, nlist, 1.1, seed)
+    ds = W.cluster_major_datastore(sizes, d, 0.4, seed + 1, dtype=dtype)
+    q_in, q_out = W.query_pairs(ds.rows.float(), 6, 0.3, seed + 2)
+    return ds, q_in.numpy(), q_out.numpy()
+
+
+@pytest.mark.parametrize("dtype,metric", [("f16", "ip"), ("f32", "l2"), ("bf16", "ip")])
+def test_prefetch_plan_and_hybrid_search(streams, dtype, metric):
+    pm, om = {"ip": (P.IVF_IP, O.IP), "l2": (P.IVF_L2, O.L2)}[metric]
+    n, d, nlist, L, k = 30000, 256, 48, 12, 10
+    ds, q_in, q_out = _problem(50, n, d, nlist, dtype)
+    off = ds.offsets.numpy()
+    cent = ds.centroids.numpy()
+    lists_pinned = ds.rows.pin_memory()
+    st, odt = stored(ds.rows.float().numpy(), dtype)
+    esz = 4 if dtype == "f32" else 2
+    cap = int(n * d * esz // 3)
+    index = P.ivf_adopt_layout(lists_pinned, dtype, off, cent, metric=pm, placement=P.IVF_PLACE_HOST,
+                               device_buffer_bytes=cap, compute_stream=streams[0], copy_stream=streams[1])
+    sizes = np.diff(off) * d * esz
+    total_exempt = 0
+    for b in range(q_in.shape[0]):
+        for budget in (0, int(sizes[sizes > 0].min()), int(sizes.sum() // 10), 1 << 40):
+            res = O.Residency(nlist, cap)
+            chosen, skipped, nbytes = O.prefetch(cent, off, odt, q_in[b], L, budget, res, om)
+            ps = index.ivf_prefetch(q_in[b], L, budget, flags=P.IVF_PREFETCH_RESET)
+            assert ps.n_taken == len(chosen) and ps.n_skipped == skipped and ps.bytes == nbytes
+            assert ps.buffer_used == res.used.value
+            assert list(index.ivf_resident()) == list(res.clusters())
+            # search right away: the copies are certainly still in flight
+            gi, gd, ss = index.ivf_search(q_out[b], L, k, with_stats=True)
+            ov, ms = O.split(cent, q_out[b], L, res.flags, om)
+            assert ss.n_overlap == len(ov) and ss.n_miss == len(ms) and ss.n_probed == len(ov) + len(ms)
+            _, _, hr = O.hybrid(st, odt, off, None, cent, q_out[b], L, k, res.flags, om)
+            assert abs(ss.hit_rate - hr) < 1e-6
+            assert ss.bytes_gpu == sizes[ov].sum() and ss.bytes_host == sizes[ms].sum()
+            total_exempt += check_topk(gi[0], gd[0], st, odt, off, None, cent, q_out[b], L, k, om)
+    assert total_exempt == 0
+    # incremental prefetch (no reset): resident clusters are not copied again
+    res = O.Residency(nlist, cap)
+    index.ivf_prefetch(q_in[0], L, 1 << 40, flags=P.IVF_PREFETCH_RESET)
+    O.prefetch(cent, off, odt, q_in[0], L, 1 << 40, res, om)
+    ps = index.ivf_prefetch(q_out[0], L, 1 << 40)
+    chosen, skipped, nbytes = O.prefetch(cent, off, odt, q_out[0], L, 1 << 40, res, om)
+    assert ps.n_taken == len(chosen) and ps.bytes == nbytes and ps.n_skipped == skipped
+    assert list(index.ivf_resident()) == list(res.clusters())
+    ms = index.ivf_prefetch_wait()
+    assert ms >= 0.0
+    gi, gd = index.ivf_search(q_out[0], L, k)
+    check_topk(gi[0], gd[0], st, odt, off, None, cent, q_out[0], L, k, om)
+    index.close()
+
+
+def test_built_host_index_with_ids_and_batches(streams):
+    """ivf_build_layout with host placement, caller ids, a buffer smaller than one cluster
+    (nothing can be prefetched: the whole search runs on the host) and a batch of queries."""
+    rng = np.random.default_rng(12)
+    n, d, nlist = 8000, 96, 10
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    assign = rng.integers(0, nlist, n).astype(np.int32)
+    rows = (cent[assign] + 0.6 * rng.standard_normal((n, d))).astype(np.float32)
+    ids = rng.permutation(n).astype(np.int64) + 5
+    off, perm = O.build_layout(assign, nlist)
+    q = rng.standard_normal((4, d)).astype(np.float32)
+    for cap in (64, n * d * 4):
+        index = P.ivf_build_layout(rows, "f32", cent, assign, ids=ids, placement=P.IVF_PLACE_HOST,
+                                   device_buffer_bytes=cap, compute_stream=streams[0], copy_stream=streams[1])
+        ps = index.ivf_prefetch(q, 5, 1 << 40, flags=P.IVF_PREFETCH_RESET)
+        if cap == 64:
+            assert ps.n_taken == 0 and len(index.ivf_resident()) == 0
+        gi, gd, ss = index.ivf_search(q, 5, 10, with_stats=True)
+        if cap == 64:
+            assert ss.n_overlap == 0 and ss.hit_rate == 0.0
+        else:
+            assert ss.n_miss == 0 and ss.hit_rate == 1.0       # q_out == q_in, unbounded budget
+        for b in range(4):
+            assert check_topk(gi[b], gd[b], rows[perm], O.F32, off, ids[perm], cent, q[b], 5, 10, O.IP) == 0
+        index.close()
