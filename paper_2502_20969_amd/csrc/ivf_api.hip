@@ -17,9 +17,6 @@
 #include "host_scan.h"
 #include "ivf_internal.h"
 
-namespace ivf {
-uint32_t select_sort_pad(int nlist, int nprobe);
-}
 using namespace ivf;
 
 // ---- errors -----------------------------------------------------------------------------------
@@ -72,6 +69,7 @@ struct Workspace {
     SlotTables slots{nullptr, nullptr, nullptr, nullptr};
     uint64_t* d_sort_keys = nullptr;
     uint32_t* d_sort_idx = nullptr;
+    WgDesc* d_desc = nullptr;
     float* d_part_key = nullptr;
     uint32_t* d_part_row = nullptr;
     int64_t* d_out_ids = nullptr;
@@ -118,6 +116,7 @@ struct ivf_index {
     bool pf_recorded = false;
 
     std::vector<uint64_t> rows_desc_prefix;   // prefix sums of list sizes, largest first
+    int resident_grid[2] = {0, 0};            // scan workgroups resident at once, for kprime <= 64 / > 64
     ScanShape shape{0, 0, 0, 4};
     Workspace ws;
     std::unique_ptr<ThreadPool> pool;
@@ -133,21 +132,26 @@ namespace {
 
 void free_workspace(Workspace& w) {
     hipFree(w.d_q); hipFree(w.d_scores); hipFree(w.d_probe);
-    hipFree(w.slots.base); hipFree(w.slots.grow); hipFree(w.slots.nrows); hipFree(w.slots.tprefix);
+    hipFree(w.slots.base); hipFree(w.slots.grow); hipFree(w.slots.nrows); hipFree(w.slots.rprefix);
     hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part_key); hipFree(w.d_part_row);
+    hipFree(w.d_desc);
     hipFree(w.d_out_ids); hipFree(w.d_out_dists);
     hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
     hipHostFree(w.h_cand); hipHostFree(w.h_cand_count); hipHostFree(w.h_scores);
     w = Workspace{};
 }
 
-// number of scan workgroups for a search of `nprobe` clusters: enough to give every wavefront
-// one task in the worst case, at most four workgroups per compute unit
-int scan_grid_for(const ivf_index* ix, int nprobe) {
+// Number of scan workgroups for a search of `nprobe` clusters with `kprime` candidates: all of
+// them must be resident at once (the rows are split evenly and statically), and there is no
+// point in more wavefronts than the largest possible scan has batches.
+int scan_grid_for(ivf_index* ix, int nprobe, int kprime) {
+    const int cls = kprime > 64 ? 1 : 0;
+    if (ix->resident_grid[cls] == 0)
+        ix->resident_grid[cls] = scan_resident_grid(ix->shape, ix->dtype, ix->metric, cls ? 128 : 64, ix->d, ix->n_cu);
     uint64_t rows = ix->rows_desc_prefix[std::min<size_t>(nprobe, ix->rows_desc_prefix.size() - 1)];
-    uint64_t tasks = rows / ix->shape.rows_per_task + (uint64_t)nprobe;
-    uint64_t g = (tasks + 3) / 4;
-    uint64_t cap = (uint64_t)ix->n_cu * 4;
+    uint64_t batches = rows / ix->shape.rows_per_batch + (uint64_t)nprobe;
+    uint64_t g = (batches + kScanWaves - 1) / kScanWaves;
+    uint64_t cap = (uint64_t)ix->resident_grid[cls];
     if (g > cap) g = cap;
     if (g < 1) g = 1;
     return (int)g;
@@ -157,7 +161,7 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     Workspace& w = ix->ws;
     const int kprime = kprime_for(k);
     const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
-    const int grid_cap = ix->n_cu * 4;
+    const int grid_cap = ix->n_cu * 2;
     if (nq <= w.nq && nprobe <= w.nprobe && k <= w.k && pad <= w.pad) return IVF_OK;
     const int nq2 = std::max(nq, w.nq), np2 = std::max(nprobe, w.nprobe), k2 = std::max(k, w.k);
     const uint32_t pad2 = std::max(pad, w.pad);
@@ -171,7 +175,8 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     HIP_TRY(hipMalloc(&w.slots.base, nqz * npz * sizeof(int64_t)));
     HIP_TRY(hipMalloc(&w.slots.grow, nqz * npz * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&w.slots.nrows, nqz * npz * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&w.slots.tprefix, nqz * (npz + 1) * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.slots.rprefix, nqz * (npz + 1) * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_desc, nqz * grid_cap * sizeof(WgDesc)));
     if (pad2 > (uint32_t)kSortLdsCap) {
         HIP_TRY(hipMalloc(&w.d_sort_keys, nqz * pad2 * sizeof(uint64_t)));
         HIP_TRY(hipMalloc(&w.d_sort_idx, nqz * pad2 * sizeof(uint32_t)));
@@ -232,7 +237,7 @@ int prof_mark(ivf_index* ix, int which) {
 // ---- kernel sequences ---------------------------------------------------------------------
 // coarse scoring + selection for nq queries already in d_q (device); leaves the probe lists
 // and slot tables in the workspace
-int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe) {
+int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid) {
     Workspace& w = ix->ws;
     int rc;
     if ((rc = prof_mark(ix, 0))) return rc;
@@ -243,7 +248,8 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe) {
     sa.scores = w.d_scores; sa.probe = w.d_probe; sa.off = ix->d_off; sa.res_off = ix->d_res_off;
     sa.slots = w.slots; sa.sort_keys = w.d_sort_keys; sa.sort_idx = w.d_sort_idx;
     sa.nlist = ix->nlist; sa.nprobe = nprobe; sa.nq = nq; sa.metric = ix->metric;
-    sa.rows_per_task = ix->shape.rows_per_task;
+    sa.grid = grid;
+    sa.desc = w.d_desc;
     sa.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
     HIP_TRY(launch_select(sa, ix->compute));
     if ((rc = prof_mark(ix, 2))) return rc;
@@ -255,6 +261,7 @@ int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kpri
     ScanArgs sc{};
     sc.buf = ix->d_buf; sc.q = q_dev; sc.ids = ix->d_ids; sc.slots = w.slots;
     sc.part_key = w.d_part_key; sc.part_row = w.d_part_row;
+    sc.desc = w.d_desc;
     sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
     sc.kprime = kprime; sc.grid = grid; sc.shape = ix->shape;
     HIP_TRY(launch_scan(sc, ix->compute));
@@ -490,8 +497,8 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     nprobe = std::min(nprobe, ix->nlist);
     if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
     const int kprime = kprime_for(k);
-    const int grid = scan_grid_for(ix, nprobe);
-    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe))) return rc;
+    const int grid = scan_grid_for(ix, nprobe, kprime);
+    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe, grid))) return rc;
     if ((rc = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return rc;
     return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
 }
@@ -513,14 +520,14 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
     if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
     Workspace& w = ix->ws;
     const int kprime = kprime_for(k);
-    const int grid = scan_grid_for(ix, nprobe);
+    const int grid = scan_grid_for(ix, nprobe, kprime);
     const bool hybrid = ix->placement == IVF_PLACE_HOST;
     ivf_search_stats st{};
 
     memcpy(w.h_q, q_out, (size_t)nq * ix->d * sizeof(float));
     HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
     if (hybrid && ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->compute, ix->ev_pf_done, 0));
-    if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe))) return rc;
+    if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe, grid))) return rc;
     const bool want_probe = hybrid || stats;
     if (want_probe) {
         HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
@@ -581,7 +588,7 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
-    rc = enqueue_probe(ix, w.d_q, nq, nprobe);
+    rc = enqueue_probe(ix, w.d_q, nq, nprobe, 1);
     ix->profiling = was_profiling;
     if (rc) return rc;
     HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
@@ -664,7 +671,7 @@ extern "C" int ivf_probe(ivf_index* ix, const float* q, int32_t nq, int32_t npro
     HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
-    rc = enqueue_probe(ix, w.d_q, nq, nprobe);
+    rc = enqueue_probe(ix, w.d_q, nq, nprobe, 1);
     ix->profiling = was_profiling;
     if (rc) return rc;
     HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));

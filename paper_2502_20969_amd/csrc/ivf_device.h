@@ -8,6 +8,14 @@ namespace dev {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
+// Development aid (off in the product build): timestamps of kernel phases, 10 ns ticks.
+#ifdef IVF_TRACE
+__device__ unsigned long long g_trace[64];
+#define IVF_TRACE_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) g_trace[i] = wall_clock64(); } while (0)
+#else
+#define IVF_TRACE_MARK(i) do { } while (0)
+#endif
+
 // ---- cross-lane sums ----------------------------------------------------------------------
 // DPP controls (GFX9): quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E,
 // row_half_mirror = 0x141, row_mirror = 0x140.  Applied in this order to a value each lane
@@ -27,6 +35,32 @@ __device__ __forceinline__ float group_sum(float v) {
     if (LANES >= 32) v += __shfl_xor(v, 16);
     if (LANES >= 64) v += __shfl_xor(v, 32);
     return v;
+}
+
+// Same sum, but only the LAST lane of each group is guaranteed to hold it (cheaper: the two
+// widest steps are DPP row broadcasts, row_bcast:15 = 0x142 into rows 1 and 3 and
+// row_bcast:31 = 0x143 into rows 2 and 3, instead of LDS permutes).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move_rows(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+template <int LANES>
+__device__ __forceinline__ float group_total_last_lane(float v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    if (LANES >= 32) v += dpp_move_rows<0x142, 0xA>(v);
+    if (LANES >= 64) v += dpp_move_rows<0x143, 0xC>(v);
+    return v;
+}
+
+// 16-byte streaming load: the rows of a list are read once, so they should not displace
+// the query, the tables or the centroids from the caches.
+typedef unsigned int u4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+    u4_t t = __builtin_nontemporal_load((const u4_t*)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
 }
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -99,24 +133,83 @@ __device__ __forceinline__ uint64_t ordered(double f) {
 }
 
 // ---- block-wide radix select -----------------------------------------------------------------
-// Finds, among n keys (key_at(i), smaller = better), the split that keeps the `want` smallest.
-// On return every thread holds: `mask` (the high bits decided), `prefix` (their value for the
-// boundary group), `need` (how many keys of the boundary group, (key & mask) == prefix, are
-// kept) and `group` (size of that group).  Keys with (key & mask) < prefix are all kept.
-// need == group unless the boundary group is a set of fully equal keys.
-// hist: 256 words of LDS; sh: 4 words of LDS.  Must be called by all threads of the block.
+// Adds 1 to hist[digit] for every active lane; lanes of a wavefront that share a digit are
+// combined into one LDS atomic for the first two distinct digits (keys that agree in their
+// high bits would otherwise all hit the same counter one after the other).
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t digit, bool active) {
+#pragma unroll 1
+    for (int round = 0; round < 2; ++round) {
+        uint64_t act = __ballot(active);
+        if (!act) return;
+        int first = __ffsll((long long)act) - 1;
+        uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, first);
+        uint64_t same = __ballot(active && digit == d0);
+        if (lane_id() == first) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        active = active && digit != d0;
+    }
+    if (active) atomicAdd(&hist[digit], 1u);
+}
+
+// Finds, among the valid keys key_at(i), i < n (smaller = better; the all-ones key marks an
+// invalid entry and is ignored), the split that keeps the `want` smallest; want must not exceed
+// the number of valid keys.  On return every thread holds: `mask` (the high bits decided),
+// `prefix` (their value for the boundary group), `need` (how many keys of the boundary group,
+// (key & mask) == prefix, are kept) and `group` (size of that group).  Keys with
+// (key & mask) < prefix are all kept.  need == group unless the boundary group is a set of
+// fully equal keys.  Digits above the highest bit in which the keys differ are skipped.
+// hist: 256 words of LDS; sh: 8 words of LDS.  Must be called by all threads of the block.
 template <typename KeyT, typename KeyAt>
 __device__ void block_radix_select(KeyAt key_at, uint32_t n, uint32_t want, uint32_t* hist,
                                    uint32_t* sh, KeyT& mask, KeyT& prefix, uint32_t& need,
                                    uint32_t& group) {
     const int tid = threadIdx.x, nt = blockDim.x;
-    mask = 0; prefix = 0; need = want; group = n;
-    for (int shift = (int)sizeof(KeyT) * 8 - 8; shift >= 0; shift -= 8) {
+    constexpr KeyT kInvalid = ~(KeyT)0;
+    // bits in which the valid keys differ, and how many valid keys there are
+    KeyT all_or = 0, all_and = kInvalid;
+    uint32_t cnt = 0;
+    for (uint32_t i = tid; i < n; i += nt) {
+        KeyT k = key_at(i);
+        if (k != kInvalid) { all_or |= k; all_and &= k; ++cnt; }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        all_or |= __shfl_xor(all_or, m);
+        all_and &= __shfl_xor(all_and, m);
+        cnt += __shfl_xor(cnt, m);
+    }
+    KeyT* sk = (KeyT*)hist;                 // scratch use of hist before the first pass
+    const int nw = nt >> 6;
+    if ((tid & 63) == 0) { sk[2 * (tid >> 6)] = all_or; sk[2 * (tid >> 6) + 1] = all_and; }
+    if ((tid & 63) == 0) sh[7] = 0;
+    __syncthreads();
+    if ((tid & 63) == 0) atomicAdd(&sh[7], cnt);
+    all_or = 0; all_and = kInvalid;
+    for (int w = 0; w < nw; ++w) { all_or |= sk[2 * w]; all_and &= sk[2 * w + 1]; }
+    __syncthreads();
+    const uint32_t n_valid = sh[7];
+    const KeyT diff = all_or ^ all_and;
+    mask = 0; prefix = 0; need = want; group = n_valid;
+    int top_shift = (int)sizeof(KeyT) * 8 - 8;
+    if (n_valid > 0) {
+        // highest differing bit decides the first digit; everything above it is common
+        int hb = diff == 0 ? -1 : (int)(sizeof(KeyT) * 8 - 1 - (sizeof(KeyT) == 8 ? __clzll((long long)diff) : __clz((int)diff)));
+        int first_shift = hb < 0 ? -8 : (hb / 8) * 8;
+        for (int sft = top_shift; sft > first_shift; sft -= 8) {
+            mask |= (KeyT)255 << sft;
+        }
+        prefix = all_and & mask;
+        top_shift = first_shift;
+    }
+    __syncthreads();
+    for (int shift = top_shift; shift >= 0; shift -= 8) {
+        if (need == group) break;
         for (int i = tid; i < 256; i += nt) hist[i] = 0;
         __syncthreads();
-        for (uint32_t i = tid; i < n; i += nt) {
-            KeyT k = key_at(i);
-            if ((k & mask) == prefix) atomicAdd(&hist[(uint32_t)(k >> shift) & 255u], 1u);
+        for (uint32_t i0 = 0; i0 < n; i0 += nt) {
+            uint32_t i = i0 + tid;
+            KeyT k = i < n ? key_at(i) : kInvalid;
+            bool act = k != kInvalid && (k & mask) == prefix;
+            hist_add(hist, (uint32_t)(k >> shift) & 255u, act);
         }
         __syncthreads();
         if (tid < 64) {
@@ -147,7 +240,6 @@ __device__ void block_radix_select(KeyAt key_at, uint32_t n, uint32_t want, uint
         need = sh[1];
         group = sh[2];
         __syncthreads();
-        if (need == group) break;
     }
 }
 
@@ -175,55 +267,159 @@ __device__ inline void block_bitonic_sort(uint64_t* keys, uint32_t* idx, uint32_
     }
 }
 
-// ---- wavefront-resident sorted candidate list ---------------------------------------------------
-// The 64*KL best (key, row) pairs seen by a wavefront, best first: entry e lives in register
-// e / 64 of lane e % 64.  Larger key is better; equal keys are ordered by smaller id.
-// `thr` is the key of entry kprime-1: a candidate below it cannot enter the first kprime.
+// ---- sorting networks over the 64 lanes of a wavefront --------------------------------------------
+// A candidate type C holds one element per lane in a few registers; an order O decides which of
+// two candidates comes first.  Two instances: row candidates of the list scan (RowCand /
+// RowOrder) and cluster candidates of the coarse selection (ClusterCand / ClusterOrder).
+
+// Row candidate: larger key first, equal keys by smaller id (id = ids[row], or the row itself
+// when ids is null).  The empty candidate (key -inf, row kNoRow) comes last.
+struct RowCand { float k; uint32_t r; };
+__device__ __forceinline__ RowCand empty_row_cand() { return RowCand{-INFINITY, kNoRow}; }
+struct RowOrder {
+    const int64_t* ids;
+    __device__ __forceinline__ int64_t id_of(uint32_t r) const {
+        if (r == kNoRow) return INT64_MAX;
+        return ids ? ids[r] : (int64_t)r;
+    }
+    // sets a_first / b_first (both false for identical candidates)
+    __device__ __forceinline__ void compare(const RowCand& a, const RowCand& b, bool& a_first, bool& b_first) const {
+        a_first = a.k > b.k; b_first = b.k > a.k;
+        if (a.k == b.k && a.r != b.r) {          // equal keys: rare
+            int64_t ia = id_of(a.r), ib = id_of(b.r);
+            a_first = ia < ib; b_first = ib < ia;
+        }
+    }
+};
+// Cluster candidate: smaller 64-bit key first, equal keys by smaller cluster index.
+struct ClusterCand { uint64_t k; uint32_t i; };
+struct ClusterOrder {
+    __device__ __forceinline__ void compare(const ClusterCand& a, const ClusterCand& b, bool& a_first, bool& b_first) const {
+        a_first = a.k < b.k || (a.k == b.k && a.i < b.i);
+        b_first = b.k < a.k || (a.k == b.k && b.i < a.i);
+    }
+};
+
+template <int STRIDE>
+__device__ __forceinline__ uint32_t xor_lane_u32(uint32_t v) {
+    if (STRIDE == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
+    if (STRIDE == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
+    return (uint32_t)__shfl_xor((int)v, STRIDE);
+}
+template <int STRIDE>
+__device__ __forceinline__ RowCand xor_lane(const RowCand& c) {
+    return RowCand{__uint_as_float(xor_lane_u32<STRIDE>(__float_as_uint(c.k))), xor_lane_u32<STRIDE>(c.r)};
+}
+template <int STRIDE>
+__device__ __forceinline__ ClusterCand xor_lane(const ClusterCand& c) {
+    uint32_t lo = xor_lane_u32<STRIDE>((uint32_t)c.k), hi = xor_lane_u32<STRIDE>((uint32_t)(c.k >> 32));
+    return ClusterCand{((uint64_t)hi << 32) | lo, xor_lane_u32<STRIDE>(c.i)};
+}
+__device__ __forceinline__ RowCand from_lane(const RowCand& c, int src) {
+    return RowCand{__shfl(c.k, src), (uint32_t)__shfl((int)c.r, src)};
+}
+__device__ __forceinline__ ClusterCand from_lane(const ClusterCand& c, int src) {
+    uint32_t lo = (uint32_t)__shfl((int)(uint32_t)c.k, src), hi = (uint32_t)__shfl((int)(uint32_t)(c.k >> 32), src);
+    return ClusterCand{((uint64_t)hi << 32) | lo, (uint32_t)__shfl((int)c.i, src)};
+}
+
+// One compare-exchange step between lane and lane ^ STRIDE.  keep_first: this lane keeps the
+// candidate that comes first (else the one that comes last).
+template <int STRIDE, typename C, typename O>
+__device__ __forceinline__ void cmp_exchange(C& c, bool keep_first, const O& order) {
+    C p = xor_lane<STRIDE>(c);
+    bool mine_first, partner_first;
+    order.compare(c, p, mine_first, partner_first);
+    if (keep_first ? partner_first : mine_first) c = p;
+}
+
+// Sorts a bitonic sequence of 64 lane-held candidates into first-to-last order.
+template <typename C, typename O>
+__device__ __forceinline__ void bitonic_merge64(C& c, const O& order) {
+    const int lane = lane_id();
+    cmp_exchange<32>(c, (lane & 32) == 0, order);
+    cmp_exchange<16>(c, (lane & 16) == 0, order);
+    cmp_exchange<8>(c, (lane & 8) == 0, order);
+    cmp_exchange<4>(c, (lane & 4) == 0, order);
+    cmp_exchange<2>(c, (lane & 2) == 0, order);
+    cmp_exchange<1>(c, (lane & 1) == 0, order);
+}
+
+// Sorts 64 lane-held candidates first-to-last (bitonic sorting network over the lanes).
+template <typename C, typename O>
+__device__ __forceinline__ void bitonic_sort64(C& c, const O& order) {
+    const int lane = lane_id();
+#define IVF_STAGE(SIZE, STRIDE) cmp_exchange<STRIDE>(c, ((lane & STRIDE) == 0) == ((lane & SIZE) == 0), order);
+    IVF_STAGE(2, 1)
+    IVF_STAGE(4, 2) IVF_STAGE(4, 1)
+    IVF_STAGE(8, 4) IVF_STAGE(8, 2) IVF_STAGE(8, 1)
+    IVF_STAGE(16, 8) IVF_STAGE(16, 4) IVF_STAGE(16, 2) IVF_STAGE(16, 1)
+    IVF_STAGE(32, 16) IVF_STAGE(32, 8) IVF_STAGE(32, 4) IVF_STAGE(32, 2) IVF_STAGE(32, 1)
+    IVF_STAGE(64, 32) IVF_STAGE(64, 16) IVF_STAGE(64, 8) IVF_STAGE(64, 4) IVF_STAGE(64, 2) IVF_STAGE(64, 1)
+#undef IVF_STAGE
+}
+
+// a <- the first 64 of (a u p), sorted; a and p sorted.
+template <typename C, typename O>
+__device__ __forceinline__ void merge_best64(C& a, const C& p, const O& order) {
+    C rev = from_lane(p, 63 - lane_id());
+    bool a_first, r_first;
+    order.compare(a, rev, a_first, r_first);
+    if (r_first) a = rev;
+    bitonic_merge64(a, order);
+}
+
+// ---- wavefront-resident top-k ------------------------------------------------------------------
+// The 64*KL best row candidates seen by a wavefront, best first: entry e lives in register
+// e / 64 of lane e % 64.  New candidates wait in a 64-entry pending buffer (one per lane) and
+// are folded in by a sort + bitonic merge when it fills up or on flush().
+// `thr` is the key of entry kprime-1 of the sorted part: a key below it cannot matter.
 template <int KL>
-struct TopList {
-    float key[KL];
-    uint32_t row[KL];
+struct WaveTopK {
+    RowCand top[KL];
+    RowCand pend;
+    int pcount;
     float thr;
 
     __device__ __forceinline__ void init() {
 #pragma unroll
-        for (int j = 0; j < KL; ++j) { key[j] = -INFINITY; row[j] = kNoRow; }
+        for (int j = 0; j < KL; ++j) top[j] = empty_row_cand();
+        pend = empty_row_cand(); pcount = 0;
         thr = -INFINITY;
     }
 
-    __device__ static __forceinline__ int64_t id_of(uint32_t r, const int64_t* ids) {
-        if (r == kNoRow) return INT64_MAX;
-        return ids ? ids[r] : (int64_t)r;
-    }
-
-    // Called by the whole wavefront with a uniform candidate.
-    __device__ __forceinline__ void insert(float ckey, uint32_t crow, const int64_t* ids, int kprime) {
-        const int lane = lane_id();
-        int pos = 0;
-#pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            bool before = key[j] > ckey;
-            if (key[j] == ckey) before = id_of(row[j], ids) < id_of(crow, ids);
-            pos += __popcll(__ballot(before));
-        }
-        if (pos >= 64 * KL) return;
-#pragma unroll
-        for (int j = KL - 1; j >= 0; --j) {
-            float uk = __shfl_up(key[j], 1);
-            uint32_t ur = __shfl_up(row[j], 1);
-            if (j > 0) {
-                float ck = read_lane(key[j - 1], 63);
-                uint32_t cr = read_lane(row[j - 1], 63);
-                if (lane == 0) { uk = ck; ur = cr; }
-            }
-            int e = j * 64 + lane;
-            if (e == pos) { key[j] = ckey; row[j] = crow; }
-            else if (e > pos) { key[j] = uk; row[j] = ur; }
+    // Folds a sorted run of 64 candidates (one per lane) into the list.
+    __device__ __forceinline__ void merge_run(const RowCand& run, const RowOrder& order, int kprime) {
+        if (KL == 1) {
+            merge_best64(top[0], run, order);
+        } else {
+            // the best 128 of (L0, L1, P) are L0 plus the best 64 of (L1 u P)
+            merge_best64(top[KL - 1], run, order);
+            RowCand rev = from_lane(top[KL - 1], 63 - lane_id());
+            bool a_first, r_first;
+            order.compare(top[0], rev, a_first, r_first);
+            if (r_first) { RowCand t = top[0]; top[0] = rev; rev = t; }
+            bitonic_merge64(top[0], order);
+            bitonic_merge64(rev, order);
+            top[KL - 1] = rev;
         }
         const int last = kprime - 1;
 #pragma unroll
         for (int j = 0; j < KL; ++j)
-            if ((last >> 6) == j) thr = read_lane(key[j], last & 63);
+            if ((last >> 6) == j) thr = read_lane(top[j].k, last & 63);
+    }
+
+    __device__ __forceinline__ void flush(const RowOrder& order, int kprime) {
+        if (pcount == 0) return;
+        bitonic_sort64(pend, order);
+        merge_run(pend, order, kprime);
+        pend = empty_row_cand(); pcount = 0;
+    }
+
+    // Called by the whole wavefront with a uniform candidate.
+    __device__ __forceinline__ void push(float ckey, uint32_t crow, const RowOrder& order, int kprime) {
+        if (lane_id() == pcount) pend = RowCand{ckey, crow};
+        if (++pcount == 64) flush(order, kprime);
     }
 };
 

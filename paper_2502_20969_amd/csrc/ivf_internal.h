@@ -1,5 +1,5 @@
-// Internal declarations shared by the host side (ivf_api.hip, host_scan.cpp) and the
-// kernel launchers (ivf_kernels.hip).  Not part of the public boundary (include/ivf.h).
+// Internal declarations shared by the host side (ivf_api.hip) and the kernel launchers
+// (ivf_kernels.hip).  Not part of the public boundary (include/ivf.h).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stddef.h>
@@ -11,10 +11,11 @@ namespace ivf {
 
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;   // empty slot of a candidate list
 constexpr int kMaxKPrime = 128;            // candidates kept per list: k + slack <= 128
-constexpr int kScanThreads = 256;          // scan workgroup: 4 wavefronts
+constexpr int kScanWaves = 12;             // scan workgroup: 12 wavefronts, one workgroup per compute unit
+constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kSelectThreads = 1024;       // select / merge workgroup: 16 wavefronts
 constexpr int kSortLdsCap = 2048;          // select: pairs sorted in LDS up to this many
-constexpr int kScanLdsSlots = 2048;        // scan: slot table kept in LDS up to this nprobe
+constexpr int kPrefixLdsCap = 8192;        // select: row-prefix table kept in LDS up to this nprobe
 
 // candidates re-scored in fp64 per query: the requested k plus a margin that absorbs the
 // rounding of the fp32 scan
@@ -24,20 +25,33 @@ inline int kprime_for(int k) {
     return kp > kMaxKPrime ? kMaxKPrime : kp;
 }
 
-// How one scan kernel variant walks rows: a task is `rows_per_task` consecutive rows of a list.
+// How one scan kernel variant walks rows: a batch is up to `rows_per_batch` consecutive rows
+// of one list; two batches are in flight per wavefront.
 struct ScanShape {
     int lanes_per_row;   // 16, 32 or 64; 0 selects the any-d fallback kernel
     int segments;        // 16-byte loads per lane per row
-    int unroll;          // row groups in flight per wavefront
-    int rows_per_task;
+    int unroll;          // row groups per batch
+    int rows_per_batch;
 };
 ScanShape pick_scan_shape(int d, int dtype);
 
-struct SlotTables {          // written by the select kernel, read by scan and merge; per query
+// Per query and selected cluster ("slot", nearest first), written by the select kernel.
+struct SlotTables {
     int64_t* base;           // [nq x nprobe]   row offset of the list in the device buffer, -1 = not resident
     uint32_t* grow;          // [nq x nprobe]   global row of the list's first row
     uint32_t* nrows;         // [nq x nprobe]   rows in the list
-    uint32_t* tprefix;       // [nq x (nprobe+1)] exclusive prefix of tasks over resident slots
+    uint32_t* rprefix;       // [nq x (nprobe+1)] exclusive prefix of rows over the resident slots
+};
+
+// The share of one scan workgroup: rows [r_begin, r_end) of the query's concatenated resident
+// rows, and the slot that holds r_begin with its table entries inlined.
+struct WgDesc {
+    uint32_t r_begin, r_end;
+    uint32_t slot;
+    uint32_t slot_rbegin;    // rprefix[slot]
+    uint32_t slot_rend;      // rprefix[slot + 1]
+    uint32_t slot_grow;
+    int64_t slot_base;
 };
 
 struct CoarseArgs {
@@ -52,10 +66,11 @@ struct SelectArgs {
     const int64_t* off;      // [nlist+1]
     const int64_t* res_off;  // [nlist] row offset in the device buffer or -1
     SlotTables slots;
+    WgDesc* desc;            // [nq x grid] out
     uint64_t* sort_keys;     // global scratch [nq x pad] when the sort does not fit LDS
     uint32_t* sort_idx;
     unsigned long long* rows_counter;  // nullable: receives the rows of all resident selected lists
-    int nlist, nprobe, nq, metric, rows_per_task;
+    int nlist, nprobe, nq, metric, grid;
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t s);
 
@@ -64,17 +79,20 @@ struct ScanArgs {
     const float* q;          // [nq x d]
     const int64_t* ids;      // [n] global row -> id, or nullptr (id = global row)
     SlotTables slots;
-    float* part_key;         // [nq x grid x kprime] out, larger = nearer
-    uint32_t* part_row;      // [nq x grid x kprime] out, global row or kNoRow
+    const WgDesc* desc;      // [nq x grid]
+    float* part_key;         // [nq x grid x kprime] out: workgroup lists, larger = nearer
+    uint32_t* part_row;      //                          global row or kNoRow
     int d, dtype, metric, nprobe, nq, kprime, grid;
     ScanShape shape;
 };
 hipError_t launch_scan(const ScanArgs& a, hipStream_t s);
+// workgroups of the scan kernel for (shape, dtype, metric, kprime) that are resident at once
+int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime, int d, int n_cu);
 
 struct MergeArgs {
     const void* buf; const float* q; const int64_t* ids;
     SlotTables slots;
-    const float* part_key; const uint32_t* part_row;
+    const float* part_key; const uint32_t* part_row;     // [nq x nparts x kprime]
     const HostCand* host_cand;   // [nq x kprime] device-visible, or nullptr
     const int32_t* host_count;   // [nq] valid entries in host_cand
     int64_t* out_ids; float* out_dists;   // [nq x k]
@@ -86,5 +104,7 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
 hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,
                                size_t row_bytes, hipStream_t s);
+
+uint32_t select_sort_pad(int nlist, int nprobe);
 
 }  // namespace ivf

@@ -7,16 +7,21 @@
 namespace ivf {
 using namespace dev;
 
+__device__ __forceinline__ int wave_id() {
+    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform: kept in an SGPR
+}
+
 // =============================================================================================
 // Coarse scoring (App. B, first step): scores[q][j] = d(x_q, c_j) for every centroid, in fp64.
 // One wavefront per centroid row; the queries are staged in LDS and widened on use.
 // HBM-bound on the nlist*d*4 bytes of the centroid matrix.
 // =============================================================================================
 constexpr int kCoarseQT = 4;   // queries sharing one pass over a centroid row
+constexpr int kSelectWaveSortMax = 4096;   // select: register sorting path up to this many clusters
 
 __global__ __launch_bounds__(256) void coarse_kernel(CoarseArgs a) {
     extern __shared__ float qd[];    // [kCoarseQT][d]
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int lane = lane_id(), wave = wave_id();
     const int q0 = blockIdx.y * kCoarseQT;
     const int nqt = min(kCoarseQT, a.nq - q0);
     for (int i = threadIdx.x; i < kCoarseQT * a.d; i += blockDim.x) {
@@ -71,44 +76,33 @@ hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s) {
 
 // =============================================================================================
 // Top-nprobe selection (App. B: the L nearest centroids), ordered nearest first with ties by
-// smaller cluster index, plus the slot tables the scan walks.  One workgroup per query.
+// smaller cluster index, plus the tables the scan walks: per selected cluster ("slot") its
+// placement and rows, and per scan workgroup its share of the rows.  One workgroup per query.
 // =============================================================================================
 __device__ __forceinline__ uint64_t coarse_key(double score, int metric) {
     uint64_t o = ordered(score);
     return metric == 0 ? ~o : o;       // ascending key = nearest first
 }
 
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, uint32_t pad, int in_lds) {
-    extern __shared__ unsigned char smem_raw[];
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t sh[8];
-    __shared__ uint32_t scan_buf[kSelectThreads / 64 + 1];
+// Fills keys/idx (LDS or global, `pad` entries) with the nprobe best (key, index) pairs sorted
+// ascending.  Inlined once per memory kind so that LDS accesses compile to LDS instructions.
+__device__ __forceinline__ void select_sorted(const SelectArgs& a, const double* sc, uint64_t* keys,
+                                              uint32_t* idx, uint32_t pad, uint32_t* hist, uint32_t* sh) {
     const int tid = threadIdx.x, nt = blockDim.x;
-    const int qi = blockIdx.x;
-    const double* sc = a.scores + (size_t)qi * a.nlist;
-    uint64_t* keys; uint32_t* idx;
-    if (in_lds) {
-        keys = (uint64_t*)smem_raw;
-        idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
-    } else {
-        keys = a.sort_keys + (size_t)qi * pad;
-        idx = a.sort_idx + (size_t)qi * pad;
-    }
     const uint32_t nlist = a.nlist, nprobe = a.nprobe;
-
     if (nlist <= pad) {
-        // small index: sort every centroid
+        // every centroid fits the sort: no selection pass needed
         for (uint32_t i = tid; i < pad; i += nt) {
             keys[i] = i < nlist ? coarse_key(sc[i], a.metric) : ~0ull;
             idx[i] = i < nlist ? i : 0xFFFFFFFFu;
         }
         __syncthreads();
     } else {
-        // large index: radix-select the nprobe best, then sort only those
+        // radix-select the nprobe best, then sort only those
         uint64_t mask, prefix; uint32_t need, group;
         auto key_at = [&](uint32_t i) { return coarse_key(sc[i], a.metric); };
         block_radix_select<uint64_t>(key_at, nlist, nprobe, hist, sh, mask, prefix, need, group);
-        if (tid == 0) { sh[4] = 0; sh[5] = 0; }
+        if (tid == 0) sh[4] = 0;
         for (uint32_t i = tid; i < pad; i += nt) { keys[i] = ~0ull; idx[i] = 0xFFFFFFFFu; }
         __syncthreads();
         const bool take_group = need == group;
@@ -142,19 +136,73 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
         }
     }
     block_bitonic_sort(keys, idx, pad);
+}
 
-    // slot tables: per selected cluster its placement and its share of the scan tasks
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, uint32_t pad, int in_lds,
+                                                                int prefix_in_lds) {
+    extern __shared__ unsigned char smem_raw[];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh[8];
+    __shared__ uint32_t scan_buf[kSelectThreads / 64 + 1];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int qi = blockIdx.x;
+    const double* sc = a.scores + (size_t)qi * a.nlist;
+    const uint32_t nprobe = a.nprobe;
+    const size_t sort_bytes = in_lds ? (size_t)pad * 12 : 0;
+    IVF_TRACE_MARK(10);
+    uint32_t* idx;
+    if (in_lds && nprobe <= 64 && a.nlist <= kSelectWaveSortMax) {
+        // Few clusters wanted from a small index: every wavefront sorts chunks of 64 scores in
+        // registers and keeps its best 64; wavefront 0 merges the wavefronts' runs.
+        uint64_t* keys = (uint64_t*)smem_raw;
+        idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
+        const int lane = lane_id(), wave = wave_id(), nw = nt >> 6;
+        const ClusterOrder order;
+        ClusterCand best{~0ull, 0xFFFFFFFFu};
+        for (int c0 = wave * 64; c0 < a.nlist; c0 += nw * 64) {
+            int i = c0 + lane;
+            ClusterCand c = i < a.nlist ? ClusterCand{coarse_key(sc[i], a.metric), (uint32_t)i} : ClusterCand{~0ull, 0xFFFFFFFFu};
+            bitonic_sort64(c, order);
+            merge_best64(best, c, order);
+        }
+        // runs of wavefronts 1.. go through LDS (reusing hist is too small: use the sort area)
+        uint64_t* r_key = (uint64_t*)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4 + 8);
+        r_key = (uint64_t*)(((uintptr_t)r_key + 7) & ~(uintptr_t)7);
+        uint32_t* r_idx = (uint32_t*)(r_key + (size_t)(nw - 1) * 64);
+        if (wave > 0) { r_key[(wave - 1) * 64 + lane] = best.k; r_idx[(wave - 1) * 64 + lane] = best.i; }
+        __syncthreads();
+        if (wave == 0) {
+            for (int w = 0; w < nw - 1; ++w) {
+                ClusterCand run{r_key[w * 64 + lane], r_idx[w * 64 + lane]};
+                merge_best64(best, run, order);
+            }
+            if (lane < (int)pad) { keys[lane] = best.k; idx[lane] = best.i; }
+        }
+        __syncthreads();
+    } else if (in_lds) {
+        uint64_t* keys = (uint64_t*)smem_raw;
+        idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
+        select_sorted(a, sc, keys, idx, pad, hist, sh);
+    } else {
+        uint64_t* keys = a.sort_keys + (size_t)qi * pad;
+        idx = a.sort_idx + (size_t)qi * pad;
+        select_sorted(a, sc, keys, idx, pad, hist, sh);
+    }
+
+    IVF_TRACE_MARK(11);
+    // slot tables: per selected cluster its placement and its rows
     const int64_t* off = a.off;
     int64_t* s_base = a.slots.base + (size_t)qi * nprobe;
     uint32_t* s_grow = a.slots.grow + (size_t)qi * nprobe;
     uint32_t* s_n = a.slots.nrows + (size_t)qi * nprobe;
-    uint32_t* s_tp = a.slots.tprefix + (size_t)qi * (nprobe + 1);
+    uint32_t* s_rp = a.slots.rprefix + (size_t)qi * (nprobe + 1);
+    uint32_t* l_rp = (uint32_t*)(smem_raw + sort_bytes);     // LDS copy of the row prefix
     uint32_t carry = 0;
     for (uint32_t base = 0; base < nprobe; base += nt) {
         uint32_t i = base + tid;
-        uint32_t tasks = 0;
+        uint32_t rows = 0;
         if (i < nprobe) {
-            uint32_t c = idx[i];
+            uint32_t c = in_lds ? ((uint32_t*)(smem_raw + sizeof(uint64_t) * pad))[i] : idx[i];
             a.probe[(size_t)qi * nprobe + i] = (int32_t)c;
             int64_t lo = off[c];
             uint32_t n = (uint32_t)(off[c + 1] - lo);
@@ -162,11 +210,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
             s_base[i] = ro;
             s_grow[i] = (uint32_t)lo;
             s_n[i] = n;
-            tasks = ro >= 0 ? (n + a.rows_per_task - 1) / a.rows_per_task : 0;
-            if (a.rows_counter && ro >= 0) atomicAdd(a.rows_counter, (unsigned long long)n);
+            rows = ro >= 0 ? n : 0;
         }
-        // block-wide exclusive scan of `tasks`
-        uint32_t incl = tasks;
+        // block-wide exclusive scan of `rows`
+        uint32_t incl = rows;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             uint32_t up = __shfl_up(incl, o);
@@ -178,43 +225,80 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
         for (int w = 0; w < (tid >> 6); ++w) wave_off += scan_buf[w];
         uint32_t total = 0;
         for (int w = 0; w < nt / 64; ++w) total += scan_buf[w];
-        if (i < nprobe) s_tp[i] = carry + wave_off + incl - tasks;
+        if (i < nprobe) {
+            uint32_t ex = carry + wave_off + incl - rows;
+            s_rp[i] = ex;
+            if (prefix_in_lds) l_rp[i] = ex;
+        }
         carry += total;
         __syncthreads();
     }
-    if (tid == 0) s_tp[nprobe] = carry;
+    if (tid == 0) {
+        s_rp[nprobe] = carry;
+        if (prefix_in_lds) l_rp[nprobe] = carry;
+        if (a.rows_counter) atomicAdd(a.rows_counter, (unsigned long long)carry);
+    }
+    __syncthreads();
+
+    IVF_TRACE_MARK(12);
+    // workgroup shares: rows split evenly, each share starting inside some slot
+    const uint32_t R = carry;
+    const uint32_t per = R / (uint32_t)a.grid, extra = R % (uint32_t)a.grid;
+    const uint32_t* rp = prefix_in_lds ? l_rp : s_rp;
+    for (int b = tid; b < a.grid; b += nt) {
+        WgDesc ds;
+        ds.r_begin = per * (uint32_t)b + min((uint32_t)b, extra);        // the first `extra` shares get one more row
+        ds.r_end = per * (uint32_t)(b + 1) + min((uint32_t)(b + 1), extra);
+        uint32_t slot = 0;
+        if (ds.r_begin < ds.r_end) {
+            uint32_t lo = 0, hi = nprobe;        // invariant: rp[lo] <= r_begin < rp[hi]
+            while (hi - lo > 1) {
+                uint32_t mid = (lo + hi) >> 1;
+                if (rp[mid] <= ds.r_begin) lo = mid; else hi = mid;
+            }
+            slot = lo;
+        }
+        ds.slot = slot;
+        ds.slot_rbegin = rp[slot];
+        ds.slot_rend = rp[slot + 1];
+        ds.slot_grow = s_grow[slot];
+        ds.slot_base = s_base[slot];
+        a.desc[(size_t)qi * a.grid + b] = ds;
+    }
+    IVF_TRACE_MARK(13);
 }
 
 static uint32_t next_pow2(uint32_t v) { uint32_t p = 1; while (p < v) p <<= 1; return p; }
 
 // power-of-two length of the select kernel's sort array for (nlist, nprobe)
 uint32_t select_sort_pad(int nlist, int nprobe) {
-    uint32_t full = next_pow2((uint32_t)nlist);
-    return full <= (uint32_t)kSortLdsCap ? full : next_pow2((uint32_t)nprobe);
+    uint32_t full = next_pow2((uint32_t)nlist), part = next_pow2((uint32_t)nprobe);
+    return part < full ? part : full;     // sort only the selected clusters when that is fewer
 }
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t s) {
     uint32_t pad = select_sort_pad(a.nlist, a.nprobe);
     int in_lds = pad <= (uint32_t)kSortLdsCap;
-    size_t lds = in_lds ? (size_t)pad * 12 : 0;
-    hipLaunchKernelGGL(select_kernel, dim3(a.nq), dim3(kSelectThreads), lds, s, a, pad, in_lds);
+    int prefix_in_lds = a.nprobe <= kPrefixLdsCap;
+    // a workgroup with one wavefront per SIMD issues fastest when there is little work per thread
+    const int threads = a.nlist <= 4096 && a.grid <= 1024 ? 256 : kSelectThreads;
+    size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
+    if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64 - 1) * 64 * 12;
+    hipLaunchKernelGGL(select_kernel, dim3(a.nq), dim3(threads), lds, s, a, pad, in_lds, prefix_in_lds);
     return hipGetLastError();
 }
 
 // =============================================================================================
 // List scan (App. B, second step): d(x, y) for every row y of every selected, resident list,
-// reduced in the kernel to the kprime best rows per workgroup.  HBM-bound: each row is read
-// once with 16-byte loads; nothing but kprime pairs per workgroup is written.
+// reduced in the kernel to the kprime best rows per group of workgroups.  HBM-bound: each row
+// is read once with 16-byte streaming loads; only candidate lists are written.
 //
-// A row is covered by LPR lanes with SEG 16-byte loads each; a wavefront instruction covers
-// 64/LPR rows; U such row groups are in flight per wavefront.  A task is U*64/LPR consecutive
-// rows of one list.  The tasks of a query are split evenly over the grid; the four wavefronts
-// of a workgroup take the tasks of its share in turn.
+// A row is covered by LPR lanes with SEG 16-byte loads each, so one wavefront instruction
+// covers 64/LPR rows; a batch is U such row groups; each wavefront keeps two batches in
+// flight (the next one is requested before the current one is reduced).  The resident rows of
+// a query's clusters form one sequence that is split evenly over the workgroups and, inside a
+// workgroup, over its four wavefronts.
 // =============================================================================================
-struct SlotView {
-    const int64_t* base; const uint32_t* grow; const uint32_t* nrows; const uint32_t* tp;
-};
-
 template <int U>
 __device__ __forceinline__ float pick(const float (&a)[U], int u) {
     float r = a[0];
@@ -223,86 +307,146 @@ __device__ __forceinline__ float pick(const float (&a)[U], int u) {
     return r;
 }
 
-// first slot whose task range contains t (tp is non-decreasing, tp[0] = 0, t < tp[nprobe])
-__device__ __forceinline__ int find_slot(const uint32_t* tp, int nprobe, uint32_t t) {
-    int lo = 0, hi = nprobe;      // invariant: tp[lo] <= t < tp[hi]
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (tp[mid] <= t) lo = mid; else hi = mid;
+// Position of a wavefront in the row sequence of its query.
+struct Cursor {
+    uint32_t r, r_end;           // next row and end of this wavefront's range
+    uint32_t slot, s_rb, s_re;   // current slot and its row range
+    uint32_t s_grow;
+    int64_t s_base;
+};
+
+struct Batch {
+    const unsigned char* rows;   // first row of the batch in the device buffer
+    uint32_t nr;                 // rows in the batch (0: none left)
+    uint32_t grow;               // global row of the first row
+};
+
+__device__ __forceinline__ Batch next_batch(Cursor& c, const ScanArgs& p, int qi, int rows_per_batch,
+                                            size_t row_bytes) {
+    Batch b{nullptr, 0, 0};
+    if (c.r >= c.r_end) return b;
+    while (c.r >= c.s_re) {      // step to the slot that holds row r (skips empty / absent lists)
+        c.slot += 1;
+        const size_t o = (size_t)qi * p.nprobe + c.slot;
+        c.s_rb = c.s_re;
+        c.s_re = p.slots.rprefix[o + qi + 1];
+        c.s_grow = p.slots.grow[o];
+        c.s_base = p.slots.base[o];
     }
-    return lo;
+    const uint32_t in_slot = c.r - c.s_rb;
+    b.nr = min((uint32_t)rows_per_batch, min(c.r_end, c.s_re) - c.r);
+    b.rows = (const unsigned char*)p.buf + ((size_t)c.s_base + in_slot) * row_bytes;
+    b.grow = c.s_grow + in_slot;
+    c.r += b.nr;
+    return b;
 }
 
+// LDS of the scan epilogue: a pool of loose candidates (one 64-entry chunk per wavefront at
+// most) and one sorted list of kprime entries per wavefront.
+struct ScanLds {
+    float* pool_key; uint32_t* pool_row;    // [kScanWaves * 64]
+    float* list_key; uint32_t* list_row;    // [kScanWaves * kprime]
+    uint32_t* ctl;                          // [0] pool count, [1] bit mask of wavefronts with a list
+};
+__host__ __device__ inline size_t scan_epilogue_bytes(int kprime) {
+    return (size_t)kScanWaves * 64 * 8 + (size_t)kScanWaves * kprime * 8 + 16;
+}
+__device__ __forceinline__ ScanLds scan_lds(unsigned char* smem, int kprime) {
+    ScanLds l;
+    l.pool_key = (float*)smem;
+    l.pool_row = (uint32_t*)(l.pool_key + kScanWaves * 64);
+    l.list_key = (float*)(l.pool_row + kScanWaves * 64);
+    l.list_row = (uint32_t*)(l.list_key + kScanWaves * kprime);
+    l.ctl = l.list_row + kScanWaves * kprime;
+    return l;
+}
+
+// Workgroup epilogue.  Every wavefront puts its loose (pending) candidates into the pool and,
+// when it has one, its sorted list into its list slot.  The pool is sorted in chunks of 64 by
+// as many wavefronts as there are chunks; wavefront 0 then merges all sorted runs into the
+// workgroup's list and writes it out.
 template <int KL>
-__device__ __forceinline__ void finish_workgroup(TopList<KL>& top, const ScanArgs& p, float* m_key,
-                                                 uint32_t* m_row, int qi) {
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+__device__ __forceinline__ void finish_workgroup(WaveTopK<KL>& top, const ScanArgs& p, const ScanLds& l, int qi) {
+    const int lane = lane_id(), wave = wave_id();
     const int kp = p.kprime;
-    if (wave > 0) {
+    const RowOrder order{p.ids};
+    // ctl was zeroed at kernel start (before a barrier every wavefront has passed)
+    if (top.pcount > 0) {
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&l.ctl[0], (uint32_t)top.pcount);
+        base = read_lane(base, 0);
+        if (lane < top.pcount) { l.pool_key[base + lane] = top.pend.k; l.pool_row[base + lane] = top.pend.r; }
+    }
+    const bool has_list = read_lane(top.top[0].r, 0) != kNoRow;
+    if (has_list) {
 #pragma unroll
         for (int j = 0; j < KL; ++j) {
             int e = j * 64 + lane;
-            if (e < kp) { m_key[(wave - 1) * kp + e] = top.key[j]; m_row[(wave - 1) * kp + e] = top.row[j]; }
+            if (e < kp) { l.list_key[wave * kp + e] = top.top[j].k; l.list_row[wave * kp + e] = top.top[j].r; }
         }
+        if (lane == 0) atomicOr(&l.ctl[1], 1u << wave);
     }
     __syncthreads();
-    if (wave == 0) {
-        for (int w = 0; w < 3; ++w) {
-            for (int i = 0; i < kp; ++i) {
-                float ck = m_key[w * kp + i];
-                uint32_t cr = m_row[w * kp + i];
-                if (cr == kNoRow || ck < top.thr) break;     // lists are sorted: nothing further can enter
-                top.insert(ck, cr, p.ids, kp);
-            }
-        }
-        size_t o = ((size_t)qi * p.grid + blockIdx.x) * kp;
+    const uint32_t pool = l.ctl[0];
+    const int nchunks = (int)((pool + 63) / 64);
+    if (wave < nchunks) {
+        uint32_t e = wave * 64 + lane;
+        RowCand c = e < pool ? RowCand{l.pool_key[e], l.pool_row[e]} : empty_row_cand();
+        bitonic_sort64(c, order);
+        l.pool_key[e] = c.k; l.pool_row[e] = c.r;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const uint32_t lists = l.ctl[1];
+    top.init();
+    for (int w = 0; w < kScanWaves; ++w) {
+        if (!((lists >> w) & 1u)) continue;
 #pragma unroll
         for (int j = 0; j < KL; ++j) {
             int e = j * 64 + lane;
-            if (e < kp) { p.part_key[o + e] = top.key[j]; p.part_row[o + e] = top.row[j]; }
+            RowCand run = e < kp ? RowCand{l.list_key[w * kp + e], l.list_row[w * kp + e]} : empty_row_cand();
+            if (read_lane(run.r, 0) != kNoRow && read_lane(run.k, 0) >= top.thr) top.merge_run(run, order, kp);
         }
     }
-}
-
-// loads the slot table of query qi into LDS when it fits, else points at global memory
-__device__ __forceinline__ SlotView stage_slots(const ScanArgs& p, int qi, unsigned char* smem, int in_lds) {
-    const int np = p.nprobe;
-    SlotView g{p.slots.base + (size_t)qi * np, p.slots.grow + (size_t)qi * np,
-               p.slots.nrows + (size_t)qi * np, p.slots.tprefix + (size_t)qi * (np + 1)};
-    if (!in_lds) return g;
-    int64_t* l_base = (int64_t*)smem;
-    uint32_t* l_grow = (uint32_t*)(smem + 8 * (size_t)np);
-    uint32_t* l_n = l_grow + np;
-    uint32_t* l_tp = l_n + np;
-    for (int i = threadIdx.x; i < np; i += blockDim.x) {
-        l_base[i] = g.base[i]; l_grow[i] = g.grow[i]; l_n[i] = g.nrows[i]; l_tp[i] = g.tp[i];
+    for (int c = 0; c < nchunks; ++c) {
+        RowCand run{l.pool_key[c * 64 + lane], l.pool_row[c * 64 + lane]};
+        if (read_lane(run.k, 0) >= top.thr) top.merge_run(run, order, kp);
     }
-    if (threadIdx.x == 0) l_tp[np] = g.tp[np];
-    __syncthreads();
-    return SlotView{l_base, l_grow, l_n, l_tp};
+    size_t o = ((size_t)qi * p.grid + blockIdx.x) * kp;
+#pragma unroll
+    for (int j = 0; j < KL; ++j) {
+        int e = j * 64 + lane;
+        if (e < kp) { p.part_key[o + e] = top.top[j].k; p.part_row[o + e] = top.top[j].r; }
+    }
 }
 
-__host__ __device__ inline size_t scan_lds_bytes(int nprobe, int kprime, int in_lds, int d_floats) {
-    size_t table = in_lds ? (size_t)nprobe * 20 + 8 : 0;
-    table = (table + 7) & ~(size_t)7;
-    return table + (size_t)3 * kprime * 8 + (size_t)d_floats * 4;
+__device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi) {
+    const WgDesc ds = p.desc[(size_t)qi * p.grid + blockIdx.x];
+    const int wave = wave_id();
+    const uint32_t cnt = ds.r_end - ds.r_begin;
+    Cursor c;
+    c.r = ds.r_begin + (uint32_t)((uint64_t)cnt * wave / kScanWaves);
+    c.r_end = ds.r_begin + (uint32_t)((uint64_t)cnt * (wave + 1) / kScanWaves);
+    c.slot = ds.slot; c.s_rb = ds.slot_rbegin; c.s_re = ds.slot_rend;
+    c.s_grow = ds.slot_grow; c.s_base = ds.slot_base;
+    return c;
 }
 
 template <typename T, int LPR, int SEG, int U, int METRIC, int KL>
-__global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p, int in_lds) {
+__global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     constexpr int EPL = T::kPerLoad;
     constexpr int RPI = 64 / LPR;
-    constexpr int RPT = U * RPI;
+    constexpr int RPB = U * RPI;
     extern __shared__ unsigned char smem[];
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int lane = lane_id();
     const int sub = lane % LPR, rsel = lane / LPR;
     const int qi = blockIdx.y;
-    const int np = p.nprobe;
-    SlotView sv = stage_slots(p, qi, smem, in_lds);
-    size_t table = in_lds ? (size_t)np * 20 + 8 : 0;
-    table = (table + 7) & ~(size_t)7;
-    float* m_key = (float*)(smem + table);
-    uint32_t* m_row = (uint32_t*)(m_key + 3 * p.kprime);
+    IVF_TRACE_MARK(30);
+    const ScanLds lds = scan_lds(smem, p.kprime);
+    if (threadIdx.x < 2) lds.ctl[threadIdx.x] = 0;
+    const size_t row_bytes = (size_t)p.d * T::kBytes;
+
+    Cursor cur = start_cursor(p, qi);
 
     // this lane's slice of the query
     float qv[SEG][EPL];
@@ -314,34 +458,24 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p, int in_l
         for (int e = 0; e < EPL; ++e) qv[sg][e] = col + e < p.d ? q[col + e] : 0.f;
     }
 
-    TopList<KL> top;
+    WaveTopK<KL> top;
     top.init();
+    const RowOrder order{p.ids};
 
-    const uint32_t total = sv.tp[np];
-    const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
-    const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
-    const size_t row_bytes = (size_t)p.d * T::kBytes;
-    uint32_t t = t_begin + wave;
-    int slot = t < t_end ? find_slot(sv.tp, np, t) : 0;
-    for (; t < t_end; t += 4) {
-        while (t >= sv.tp[slot + 1]) ++slot;
-        const uint32_t n = sv.nrows[slot];
-        const uint32_t r0 = (t - sv.tp[slot]) * RPT;
-        const uint32_t nr = min((uint32_t)RPT, n - r0);
-        const unsigned char* rows = (const unsigned char*)p.buf + ((size_t)sv.base[slot] + r0) * row_bytes;
-
-        uint4 v[U][SEG];
+    auto issue = [&](const Batch& b, uint4 (&v)[U][SEG]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            uint32_t r = min((uint32_t)(u * RPI + rsel), nr - 1);   // rows past the end re-read the last one
-            const unsigned char* rp = rows + (size_t)r * row_bytes;
+            uint32_t r = min((uint32_t)(u * RPI + rsel), b.nr - 1);   // rows past the end re-read the last one
+            const unsigned char* rp = b.rows + (size_t)r * row_bytes;
 #pragma unroll
             for (int sg = 0; sg < SEG; ++sg) {
                 int col = (sg * LPR + sub) * EPL;
-                if (col < p.d) v[u][sg] = *(const uint4*)(rp + (size_t)col * T::kBytes);
+                if (col < p.d) v[u][sg] = load_stream16(rp + (size_t)col * T::kBytes);
                 else v[u][sg] = make_uint4(0, 0, 0, 0);
             }
         }
+    };
+    auto consume = [&](const Batch& b, const uint4 (&v)[U][SEG]) {
         float acc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -356,13 +490,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p, int in_l
                     else { float df = qv[sg][e] - x[e]; s = fmaf(df, df, s); }
                 }
             }
-            s = group_sum<LPR>(s);
+            s = group_total_last_lane<LPR>(s);
             acc[u] = METRIC == 0 ? s : -s;        // key: larger is nearer
         }
         // almost every row fails the threshold: one ballot decides whether to look closer
         bool any = false;
+        const bool leader = sub == LPR - 1;
 #pragma unroll
-        for (int u = 0; u < U; ++u) any |= (uint32_t)(u * RPI + rsel) < nr && acc[u] >= top.thr;
+        for (int u = 0; u < U; ++u) any |= leader && (uint32_t)(u * RPI + rsel) < b.nr && acc[u] >= top.thr;
         if (__ballot(any)) {
 #pragma unroll 1
             for (int u = 0; u < U; ++u) {
@@ -370,197 +505,370 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p, int in_l
 #pragma unroll 1
                 for (int j = 0; j < RPI; ++j) {
                     uint32_t r = u * RPI + j;
-                    if (r >= nr) break;
-                    float ck = read_lane(au, j * LPR);
-                    if (ck >= top.thr) top.insert(ck, sv.grow[slot] + r0 + r, p.ids, p.kprime);
+                    if (r >= b.nr) break;
+                    float ck = read_lane(au, j * LPR + LPR - 1);
+                    if (ck >= top.thr) top.push(ck, b.grow + r, order, p.kprime);
                 }
             }
         }
+    };
+
+    IVF_TRACE_MARK(31);
+    uint4 va[U][SEG], vb[U][SEG];
+    Batch ba = next_batch(cur, p, qi, RPB, row_bytes);
+    if (ba.nr) issue(ba, va);
+    while (ba.nr) {
+        Batch bb = next_batch(cur, p, qi, RPB, row_bytes);
+        if (bb.nr) issue(bb, vb);
+        consume(ba, va);
+        if (!bb.nr) break;
+        ba = next_batch(cur, p, qi, RPB, row_bytes);
+        if (ba.nr) issue(ba, va);
+        consume(bb, vb);
     }
-    finish_workgroup<KL>(top, p, m_key, m_row, qi);
+    IVF_TRACE_MARK(32);
+    __syncthreads();          // orders the zeroing of lds.ctl before its use
+    IVF_TRACE_MARK(33);
+    finish_workgroup<KL>(top, p, lds, qi);
+    IVF_TRACE_MARK(34);
 }
 
-// Fallback for any d and any row alignment: element-wise loads, query in LDS, 4 rows per task.
+// Fallback for any d and any row alignment: element-wise loads, query in LDS, 4 rows per batch.
 template <int METRIC, int KL>
-__global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p, int in_lds) {
-    constexpr int RPT = 4;
+__global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) {
     extern __shared__ unsigned char smem[];
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int lane = lane_id();
     const int qi = blockIdx.y;
-    const int np = p.nprobe;
-    SlotView sv = stage_slots(p, qi, smem, in_lds);
-    size_t table = in_lds ? (size_t)np * 20 + 8 : 0;
-    table = (table + 7) & ~(size_t)7;
-    float* m_key = (float*)(smem + table);
-    uint32_t* m_row = (uint32_t*)(m_key + 3 * p.kprime);
-    float* ql = (float*)(m_row + 3 * p.kprime);
+    const ScanLds lds = scan_lds(smem, p.kprime);
+    if (threadIdx.x < 2) lds.ctl[threadIdx.x] = 0;
+    float* ql = (float*)(smem + scan_epilogue_bytes(p.kprime));
     for (int i = threadIdx.x; i < p.d; i += blockDim.x) ql[i] = p.q[(size_t)qi * p.d + i];
     __syncthreads();
-
-    TopList<KL> top;
+    const int esz = p.dtype == 0 ? 4 : 2;
+    const size_t row_bytes = (size_t)p.d * esz;
+    Cursor cur = start_cursor(p, qi);
+    WaveTopK<KL> top;
     top.init();
-    const uint32_t total = sv.tp[np];
-    const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
-    const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
-    uint32_t t = t_begin + wave;
-    int slot = t < t_end ? find_slot(sv.tp, np, t) : 0;
-    for (; t < t_end; t += 4) {
-        while (t >= sv.tp[slot + 1]) ++slot;
-        const uint32_t n = sv.nrows[slot];
-        const uint32_t r0 = (t - sv.tp[slot]) * RPT;
-        const uint32_t nr = min((uint32_t)RPT, n - r0);
-        for (uint32_t r = 0; r < nr; ++r) {
-            size_t e0 = ((size_t)sv.base[slot] + r0 + r) * p.d;
+    const RowOrder order{p.ids};
+    for (Batch b = next_batch(cur, p, qi, 4, row_bytes); b.nr; b = next_batch(cur, p, qi, 4, row_bytes)) {
+        for (uint32_t r = 0; r < b.nr; ++r) {
+            const unsigned char* rp = b.rows + (size_t)r * row_bytes;
             float s = 0.f;
             for (int c = lane; c < p.d; c += 64) {
                 float x;
-                if (p.dtype == 0) x = ((const float*)p.buf)[e0 + c];
+                if (p.dtype == 0) x = ((const float*)rp)[c];
                 else {
-                    uint16_t b = ((const uint16_t*)p.buf)[e0 + c];
-                    x = p.dtype == 1 ? (float)__builtin_bit_cast(_Float16, b) : __uint_as_float((uint32_t)b << 16);
+                    uint16_t h = ((const uint16_t*)rp)[c];
+                    x = p.dtype == 1 ? (float)__builtin_bit_cast(_Float16, h) : __uint_as_float((uint32_t)h << 16);
                 }
                 if (METRIC == 0) s = fmaf(ql[c], x, s);
                 else { float df = ql[c] - x; s = fmaf(df, df, s); }
             }
-            s = group_sum<64>(s);
-            float ck = read_lane(METRIC == 0 ? s : -s, 0);
-            if (ck >= top.thr) top.insert(ck, sv.grow[slot] + r0 + r, p.ids, p.kprime);
+            s = group_total_last_lane<64>(s);
+            float ck = read_lane(METRIC == 0 ? s : -s, 63);
+            if (ck >= top.thr) top.push(ck, b.grow + r, order, p.kprime);
         }
     }
-    finish_workgroup<KL>(top, p, m_key, m_row, qi);
+    finish_workgroup<KL>(top, p, lds, qi);
 }
 
 // ---- shape selection ---------------------------------------------------------------------
-// (lanes per row, 16-byte segments per lane, row groups in flight), keyed by the number of
-// 16-byte chunks in a row.  About 24 KB of loads are in flight per wavefront.
+// (lanes per row, 16-byte segments per lane, row groups per batch), keyed by the number of
+// 16-byte chunks in a row.  Two batches of about 12 KB are in flight per wavefront.
+struct ShapeOpt { int lpr, seg, u; };
+static const ShapeOpt kShapes[] = {{16, 1, 8}, {32, 1, 8}, {64, 1, 8}, {32, 3, 4}, {64, 2, 4},
+                                   {64, 3, 4}, {64, 4, 3}, {64, 8, 1}};
+
 ScanShape pick_scan_shape(int d, int dtype) {
     const int esz = dtype == 0 ? 4 : 2;
     const size_t row_bytes = (size_t)d * esz;
     if (row_bytes % 16 != 0) return ScanShape{0, 0, 0, 4};
     const int chunks = (int)(row_bytes / 16);
-    struct Opt { int lpr, seg, u; };
-    static const Opt opts[] = {{16, 1, 16}, {32, 1, 16}, {64, 1, 16}, {32, 3, 8}, {64, 2, 8},
-                               {64, 3, 8},  {64, 4, 6},  {64, 8, 3}};
     int best = -1, best_waste = 1 << 30;
-    for (int i = 0; i < (int)(sizeof(opts) / sizeof(opts[0])); ++i) {
-        int cap = opts[i].lpr * opts[i].seg;
+    for (int i = 0; i < (int)(sizeof(kShapes) / sizeof(kShapes[0])); ++i) {
+        int cap = kShapes[i].lpr * kShapes[i].seg;
         if (cap < chunks) continue;
         int waste = cap - chunks;
         if (waste < best_waste) { best = i; best_waste = waste; }
     }
     if (best < 0) return ScanShape{0, 0, 0, 4};
-    return ScanShape{opts[best].lpr, opts[best].seg, opts[best].u, opts[best].u * (64 / opts[best].lpr)};
+    return ScanShape{kShapes[best].lpr, kShapes[best].seg, kShapes[best].u,
+                     kShapes[best].u * (64 / kShapes[best].lpr)};
 }
 
+typedef void (*ScanFn)(ScanArgs);
+
 template <typename T, int LPR, int SEG, int U>
-static void launch_scan_shape(const ScanArgs& a, dim3 grid, size_t lds, int in_lds, hipStream_t s) {
-    const bool big = a.kprime > 64;
-    if (a.metric == 0) {
-        if (big) hipLaunchKernelGGL((scan_kernel<T, LPR, SEG, U, 0, 2>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-        else hipLaunchKernelGGL((scan_kernel<T, LPR, SEG, U, 0, 1>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-    } else {
-        if (big) hipLaunchKernelGGL((scan_kernel<T, LPR, SEG, U, 1, 2>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-        else hipLaunchKernelGGL((scan_kernel<T, LPR, SEG, U, 1, 1>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-    }
+static ScanFn scan_fn_shape(int metric, bool big) {
+    if (metric == 0) return big ? (ScanFn)scan_kernel<T, LPR, SEG, U, 0, 2> : (ScanFn)scan_kernel<T, LPR, SEG, U, 0, 1>;
+    return big ? (ScanFn)scan_kernel<T, LPR, SEG, U, 1, 2> : (ScanFn)scan_kernel<T, LPR, SEG, U, 1, 1>;
 }
 
 template <typename T>
-static bool launch_scan_dtype(const ScanArgs& a, dim3 grid, size_t lds, int in_lds, hipStream_t s) {
-    const int l = a.shape.lanes_per_row, g = a.shape.segments;
-#define IVF_SHAPE(L, G, UU) if (l == L && g == G) { launch_scan_shape<T, L, G, UU>(a, grid, lds, in_lds, s); return true; }
-    IVF_SHAPE(16, 1, 16) IVF_SHAPE(32, 1, 16) IVF_SHAPE(64, 1, 16) IVF_SHAPE(32, 3, 8)
-    IVF_SHAPE(64, 2, 8) IVF_SHAPE(64, 3, 8) IVF_SHAPE(64, 4, 6) IVF_SHAPE(64, 8, 3)
+static ScanFn scan_fn_dtype(const ScanShape& sh, int metric, bool big) {
+    const int l = sh.lanes_per_row, g = sh.segments;
+#define IVF_SHAPE(L, G, UU) if (l == L && g == G) return scan_fn_shape<T, L, G, UU>(metric, big);
+    IVF_SHAPE(16, 1, 8) IVF_SHAPE(32, 1, 8) IVF_SHAPE(64, 1, 8) IVF_SHAPE(32, 3, 4)
+    IVF_SHAPE(64, 2, 4) IVF_SHAPE(64, 3, 4) IVF_SHAPE(64, 4, 3) IVF_SHAPE(64, 8, 1)
 #undef IVF_SHAPE
-    return false;
+    return nullptr;
+}
+
+static ScanFn scan_fn(const ScanShape& sh, int dtype, int metric, int kprime) {
+    const bool big = kprime > 64;
+    if (sh.lanes_per_row == 0) {
+        if (metric == 0) return big ? (ScanFn)scan_generic_kernel<0, 2> : (ScanFn)scan_generic_kernel<0, 1>;
+        return big ? (ScanFn)scan_generic_kernel<1, 2> : (ScanFn)scan_generic_kernel<1, 1>;
+    }
+    if (dtype == 0) return scan_fn_dtype<F32>(sh, metric, big);
+    if (dtype == 1) return scan_fn_dtype<F16>(sh, metric, big);
+    return scan_fn_dtype<BF16>(sh, metric, big);
+}
+
+static size_t scan_lds_bytes(const ScanShape& sh, int kprime, int d) {
+    return scan_epilogue_bytes(kprime) + (sh.lanes_per_row == 0 ? (size_t)d * 4 : 0);
+}
+
+int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime, int d, int n_cu) {
+    ScanFn fn = scan_fn(shape, dtype, metric, kprime);
+    if (!fn) return n_cu;
+    int per_cu = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, kScanThreads,
+                                                                scan_lds_bytes(shape, kprime, d));
+    if (e != hipSuccess || per_cu < 1) per_cu = 1;
+    if (per_cu > 2) per_cu = 2;
+    return per_cu * n_cu;
 }
 
 hipError_t launch_scan(const ScanArgs& a, hipStream_t s) {
-    const int in_lds = a.nprobe <= kScanLdsSlots;
+    ScanFn fn = scan_fn(a.shape, a.dtype, a.metric, a.kprime);
+    if (!fn) return hipErrorInvalidValue;
     dim3 grid(a.grid, a.nq);
-    const bool generic = a.shape.lanes_per_row == 0;
-    size_t lds = scan_lds_bytes(a.nprobe, a.kprime, in_lds, generic ? a.d : 0);
-    if (generic) {
-        const bool big = a.kprime > 64;
-        if (a.metric == 0) {
-            if (big) hipLaunchKernelGGL((scan_generic_kernel<0, 2>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-            else hipLaunchKernelGGL((scan_generic_kernel<0, 1>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-        } else {
-            if (big) hipLaunchKernelGGL((scan_generic_kernel<1, 2>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-            else hipLaunchKernelGGL((scan_generic_kernel<1, 1>), grid, dim3(kScanThreads), lds, s, a, in_lds);
-        }
-        return hipGetLastError();
-    }
-    bool ok = false;
-    if (a.dtype == 0) ok = launch_scan_dtype<F32>(a, grid, lds, in_lds, s);
-    else if (a.dtype == 1) ok = launch_scan_dtype<F16>(a, grid, lds, in_lds, s);
-    else ok = launch_scan_dtype<BF16>(a, grid, lds, in_lds, s);
-    if (!ok) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.kprime, a.d), s, a);
     return hipGetLastError();
 }
 
 // =============================================================================================
 // Merge (App. B: "this involves sorting"; Sec. 4.1 step 4: results of the GPU and the host part
-// are merged on the GPU).  One workgroup per query: picks the kprime best fp32 candidates of all
-// workgroup lists, re-scores them in fp64 from the stored rows, adds the host's candidates
-// (already fp64), orders everything by (score, id) and writes the k nearest.
+// are merged on the GPU).  One workgroup per query: finds the kprime best fp32 candidates of
+// all workgroup lists, re-scores those rows in fp64 from the stored rows, adds the host's
+// candidates (already fp64), orders everything by (score, id) and writes the k nearest.
 // =============================================================================================
-__global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a) {
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t sh[8];
-    __shared__ uint32_t c_row[kMaxKPrime];
-    __shared__ double f_key[2 * kMaxKPrime];
-    __shared__ int64_t f_id[2 * kMaxKPrime];
+constexpr int kMergeCandCap = 4096;    // loose candidates the fast path can hold in LDS
+constexpr int kMergeFastWaves = 8;
+
+struct MergeLds {
+    uint32_t hist[256];
+    uint32_t sh[8];
+    uint32_t c_row[kMaxKPrime];
+    double f_key[2 * kMaxKPrime];
+    int64_t f_id[2 * kMaxKPrime];
+    unsigned long long best;
+};
+
+// Fast path (kprime <= 64).  Every list is sorted, so with T0 = the kprime-th best list head,
+// only entries >= T0 of lists whose head is >= T0 can be among the kprime best: a few hundred
+// at most.  Those are gathered, sorted in chunks of 64 and merged.  Returns false (uniformly)
+// when equal keys make the gathered set overflow its buffer.
+__device__ __forceinline__ bool gather_fast(const MergeArgs& a, const float* pk, const uint32_t* pr,
+                                            MergeLds& L, float* cand_key, uint32_t* cand_row,
+                                            uint32_t* qlist) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id(), nw = nt >> 6;
+    const int kp = a.kprime, np = a.nparts;
+    const RowOrder order{a.ids};
+    // 1. T0 from the list heads
+    WaveTopK<1> ht;
+    ht.init();
+    for (int c0 = wave * 64; c0 < np; c0 += nw * 64) {
+        int l = c0 + lane;
+        RowCand h = l < np ? RowCand{pk[(size_t)l * kp], pr[(size_t)l * kp]} : empty_row_cand();
+        if (h.r == kNoRow) h.k = -INFINITY;
+        bitonic_sort64(h, order);
+        if (read_lane(h.r, 0) != kNoRow && read_lane(h.k, 0) >= ht.thr) ht.merge_run(h, order, kp);
+    }
+    float* run_key = cand_key;               // the candidate buffer is free until step 2
+    uint32_t* run_row = cand_row;
+    if (wave > 0) { run_key[(wave - 1) * 64 + lane] = ht.top[0].k; run_row[(wave - 1) * 64 + lane] = ht.top[0].r; }
+    if (tid == 0) { L.sh[4] = 0; L.sh[5] = 0; }
+    __syncthreads();
+    if (wave == 0) {
+        for (int w = 0; w < nw - 1; ++w) {
+            RowCand run{run_key[w * 64 + lane], run_row[w * 64 + lane]};
+            if (read_lane(run.r, 0) != kNoRow && read_lane(run.k, 0) >= ht.thr) ht.merge_run(run, order, kp);
+        }
+        if (lane == 0) L.sh[6] = __float_as_uint(ht.thr);
+    }
+    __syncthreads();
+    const float t0 = __uint_as_float(L.sh[6]);
+    // 2. lists whose head reaches T0, then their entries that reach T0
+    for (int l = tid; l < np; l += nt) {
+        if (pr[(size_t)l * kp] != kNoRow && pk[(size_t)l * kp] >= t0) {
+            uint32_t p = atomicAdd(&L.sh[5], 1u);
+            if (p < 1024) qlist[p] = l;
+        }
+    }
+    __syncthreads();
+    const uint32_t nql = L.sh[5];
+    if (nql > 1024) return false;
+    for (uint32_t i = wave; i < nql; i += nw) {
+        const size_t o = (size_t)qlist[i] * kp;
+        float k = lane < kp ? pk[o + lane] : -INFINITY;
+        uint32_t r = lane < kp ? pr[o + lane] : kNoRow;
+        bool ok = r != kNoRow && k >= t0;
+        uint64_t b = __ballot(ok);
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&L.sh[4], (uint32_t)__popcll(b));
+        base = read_lane(base, 0);
+        uint32_t p = base + __popcll(b & ((1ull << lane) - 1ull));
+        if (ok && p < (uint32_t)kMergeCandCap) { cand_key[p] = k; cand_row[p] = r; }
+    }
+    __syncthreads();
+    const uint32_t cnt = L.sh[4];
+    if (cnt > (uint32_t)kMergeCandCap) return false;
+    // 3. sort the gathered candidates in chunks of 64, merge the chunks
+    const int nchunks = (int)((cnt + 63) / 64);
+    for (int c = wave; c < nchunks; c += nw) {
+        uint32_t e = c * 64 + lane;
+        RowCand x = e < cnt ? RowCand{cand_key[e], cand_row[e]} : empty_row_cand();
+        bitonic_sort64(x, order);
+        cand_key[e] = x.k; cand_row[e] = x.r;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        WaveTopK<1> ft;
+        ft.init();
+        for (int c = 0; c < nchunks; ++c) {
+            RowCand run{cand_key[c * 64 + lane], cand_row[c * 64 + lane]};
+            if (read_lane(run.k, 0) >= ft.thr) ft.merge_run(run, order, kp);
+        }
+        bool ok = lane < kp && ft.top[0].r != kNoRow;
+        if (ok) L.c_row[lane] = ft.top[0].r;          // valid entries form a prefix
+        uint32_t m = (uint32_t)__popcll(__ballot(ok));
+        if (lane == 0) L.sh[4] = m;
+    }
+    __syncthreads();
+    return true;
+}
+
+// General path: radix select over all entries of all lists.
+__device__ __forceinline__ void gather_radix(const MergeArgs& a, const float* pk, const uint32_t* pr, MergeLds& L) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
+    const uint32_t n = (uint32_t)a.nparts * a.kprime, kp = a.kprime;
+    // ascending radix key = best first; all ones = empty entry
+    auto key_at = [&](uint32_t i) { return pr[i] == kNoRow ? 0xFFFFFFFFu : ~ordered(pk[i]); };
+    uint32_t my_valid = 0;
+    for (uint32_t i = tid; i < n; i += nt) my_valid += key_at(i) != 0xFFFFFFFFu;
+    if (tid == 0) { L.sh[4] = 0; L.sh[5] = 0; }
+    __syncthreads();
+#pragma unroll
+    for (int m2 = 32; m2 >= 1; m2 >>= 1) my_valid += __shfl_xor(my_valid, m2);
+    if (lane == 0) atomicAdd(&L.sh[5], my_valid);
+    __syncthreads();
+    const uint32_t n_valid = L.sh[5];
+    if (n_valid <= kp) {
+        for (uint32_t i = tid; i < n; i += nt)
+            if (key_at(i) != 0xFFFFFFFFu) { uint32_t p = atomicAdd(&L.sh[4], 1u); L.c_row[p] = pr[i]; }
+        __syncthreads();
+        return;
+    }
+    uint32_t mask, prefix, need, group;
+    block_radix_select<uint32_t>(key_at, n, kp, L.hist, L.sh, mask, prefix, need, group);
+    const bool take_group = need == group;
+    for (uint32_t i = tid; i < n; i += nt) {
+        uint32_t k = key_at(i);
+        uint32_t hi = k & mask;
+        if (k != 0xFFFFFFFFu && (hi < prefix || (take_group && hi == prefix))) {
+            uint32_t p = atomicAdd(&L.sh[4], 1u);
+            L.c_row[p] = pr[i];
+        }
+    }
+    __syncthreads();
+    if (!take_group) {
+        // boundary group of bit-identical fp32 keys: keep the `need` smallest ids, one at a time
+        long long last = -1;
+        for (uint32_t it = 0; it < need; ++it) {
+            if (tid == 0) L.best = ~0ull;
+            __syncthreads();
+            for (uint32_t i = tid; i < n; i += nt) {
+                uint32_t k = key_at(i);
+                if (k != 0xFFFFFFFFu && (k & mask) == prefix) {
+                    long long id = a.ids ? a.ids[pr[i]] : (long long)pr[i];
+                    if (id > last) atomicMin(&L.best, (unsigned long long)id);
+                }
+            }
+            __syncthreads();
+            unsigned long long b = L.best;
+            if (b == ~0ull) break;
+            last = (long long)b;
+            for (uint32_t i = tid; i < n; i += nt) {
+                uint32_t k = key_at(i);
+                if (k != 0xFFFFFFFFu && (k & mask) == prefix) {
+                    long long id = a.ids ? a.ids[pr[i]] : (long long)pr[i];
+                    if (id == last) { uint32_t p = atomicAdd(&L.sh[4], 1u); if (p < kMaxKPrime) L.c_row[p] = pr[i]; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+}
+
+// fp64 score of one stored row against q, by one wavefront; rows of whole 16-byte chunks are
+// read with up to four 16-byte loads per lane in flight.
+template <typename T>
+__device__ __forceinline__ double rescore_chunks(const unsigned char* row, const float* q, int d, int metric) {
+    constexpr int EPL = T::kPerLoad;
+    const int lane = lane_id();
+    const int chunks = d / EPL;
+    double acc = 0.0;
+    for (int c0 = lane; c0 < chunks; c0 += 256) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 64;
+            v[u] = c < chunks ? *(const uint4*)(row + (size_t)c * 16) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 64;
+            if (c < chunks) {
+                float x[EPL];
+                Unpack<T>::run(v[u], x);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    double qv = (double)q[c * EPL + e], y = (double)x[e];
+                    if (metric == 0) acc = fma(qv, y, acc);
+                    else { double df = qv - y; acc = fma(df, df, acc); }
+                }
+            }
+        }
+    }
+    return wave_sum(acc);
+}
+
+__global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int fast) {
+    extern __shared__ unsigned char m_dyn[];
+    __shared__ MergeLds L;
     const int tid = threadIdx.x, nt = blockDim.x;
-    const int lane = lane_id(), wave = tid >> 6;
+    const int lane = lane_id(), wave = wave_id();
     const int qi = blockIdx.x;
     const uint32_t n = (uint32_t)a.nparts * a.kprime;
     const float* pk = a.part_key + (size_t)qi * n;
     const uint32_t* pr = a.part_row + (size_t)qi * n;
     const uint32_t kp = a.kprime;
 
-    // 1. the kprime best fp32 keys (ascending radix key = best first)
-    uint32_t mask, prefix, need, group;
-    auto key_at = [&](uint32_t i) { return ~ordered(pk[i]); };
-    block_radix_select<uint32_t>(key_at, n, kp, hist, sh, mask, prefix, need, group);
-    if (tid == 0) sh[4] = 0;
-    __syncthreads();
-    const bool take_group = need == group;
-    for (uint32_t i = tid; i < n; i += nt) {
-        uint32_t hi = key_at(i) & mask;
-        if ((hi < prefix || (take_group && hi == prefix)) && pr[i] != kNoRow) {
-            uint32_t p = atomicAdd(&sh[4], 1u);
-            c_row[p] = pr[i];
-        }
+    IVF_TRACE_MARK(20);
+    // 1. the kprime best fp32 candidates
+    bool done = false;
+    if (fast) {
+        float* cand_key = (float*)m_dyn;
+        uint32_t* cand_row = (uint32_t*)(cand_key + kMergeCandCap);
+        uint32_t* qlist = cand_row + kMergeCandCap;
+        done = gather_fast(a, pk, pr, L, cand_key, cand_row, qlist);
     }
-    __syncthreads();
-    if (!take_group) {
-        // boundary group of bit-identical fp32 keys: keep the `need` smallest ids, one at a time
-        __shared__ unsigned long long best;
-        long long last = -1;
-        for (uint32_t it = 0; it < need; ++it) {
-            if (tid == 0) best = ~0ull;
-            __syncthreads();
-            for (uint32_t i = tid; i < n; i += nt) {
-                if ((key_at(i) & mask) == prefix && pr[i] != kNoRow) {
-                    long long id = a.ids ? a.ids[pr[i]] : (long long)pr[i];
-                    if (id > last) atomicMin(&best, ((unsigned long long)id << 0));
-                }
-            }
-            __syncthreads();
-            unsigned long long b = best;
-            if (b == ~0ull) break;
-            last = (long long)b;
-            for (uint32_t i = tid; i < n; i += nt) {
-                if ((key_at(i) & mask) == prefix && pr[i] != kNoRow) {
-                    long long id = a.ids ? a.ids[pr[i]] : (long long)pr[i];
-                    if (id == last) { uint32_t p = atomicAdd(&sh[4], 1u); if (p < kMaxKPrime) c_row[p] = pr[i]; }
-                }
-            }
-            __syncthreads();
-        }
-    }
-    __syncthreads();
-    const uint32_t m = min(sh[4], (uint32_t)kMaxKPrime);
+    if (!done) gather_radix(a, pk, pr, L);
+    const uint32_t m = min(L.sh[4], (uint32_t)kMaxKPrime);
+    IVF_TRACE_MARK(23);
 
     // 2. fp64 re-score, one wavefront per candidate
     const float* q = a.q + (size_t)qi * a.d;
@@ -568,32 +876,45 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a) {
     const int64_t* s_base = a.slots.base + (size_t)qi * np;
     const uint32_t* s_grow = a.slots.grow + (size_t)qi * np;
     const uint32_t* s_n = a.slots.nrows + (size_t)qi * np;
+    const size_t row_bytes = (size_t)a.d * (a.dtype == 0 ? 4 : 2);
     for (uint32_t c = wave; c < m; c += nt / 64) {
-        const uint32_t row = c_row[c];
+        const uint32_t row = L.c_row[c];
+        const int64_t id = a.ids ? a.ids[row] : (int64_t)row;
         size_t brow = row;
+        bool found_row = true;
         if (!a.identity) {
             // find the slot whose global row range holds `row`
-            long long found = -1;
+            int found = -1;
             for (int s0 = 0; s0 < np && found < 0; s0 += 64) {
                 int s = s0 + lane;
                 bool hit = s < np && row >= s_grow[s] && row - s_grow[s] < s_n[s];
                 uint64_t b = __ballot(hit);
                 if (b) found = s0 + __ffsll((long long)b) - 1;
             }
-            brow = (size_t)(s_base[found] + (int64_t)(row - s_grow[found]));
+            found_row = found >= 0;
+            if (found_row) brow = (size_t)(s_base[found] + (int64_t)(row - s_grow[found]));
         }
         double acc = 0.0;
-        const size_t e0 = brow * (size_t)a.d;
-        for (int t = lane; t < a.d; t += 64) {
-            double x = (double)q[t];
-            double y = widen(a.buf, a.dtype, e0 + t);
-            if (a.metric == 0) acc = fma(x, y, acc);
-            else { double df = x - y; acc = fma(df, df, acc); }
+        if (found_row) {
+            const unsigned char* rp = (const unsigned char*)a.buf + brow * row_bytes;
+            if (row_bytes % 16 == 0) {
+                if (a.dtype == 0) acc = rescore_chunks<F32>(rp, q, a.d, a.metric);
+                else if (a.dtype == 1) acc = rescore_chunks<F16>(rp, q, a.d, a.metric);
+                else acc = rescore_chunks<BF16>(rp, q, a.d, a.metric);
+            } else {
+                const size_t e0 = brow * (size_t)a.d;
+                for (int t = lane; t < a.d; t += 64) {
+                    double x = (double)q[t];
+                    double y = widen(a.buf, a.dtype, e0 + t);
+                    if (a.metric == 0) acc = fma(x, y, acc);
+                    else { double df = x - y; acc = fma(df, df, acc); }
+                }
+                acc = wave_sum(acc);
+            }
         }
-        acc = wave_sum(acc);
         if (lane == 0) {
-            f_key[c] = a.metric == 0 ? acc : -acc;
-            f_id[c] = a.ids ? a.ids[row] : (int64_t)row;
+            L.f_key[c] = !found_row ? -INFINITY : (a.metric == 0 ? acc : -acc);
+            L.f_id[c] = id;
         }
     }
     // 3. host candidates
@@ -601,19 +922,20 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a) {
     if (a.host_cand) {
         nh = min((uint32_t)a.host_count[qi], kp);
         for (uint32_t i = tid; i < nh; i += nt) {
-            f_key[m + i] = a.host_cand[(size_t)qi * kp + i].key;
-            f_id[m + i] = a.host_cand[(size_t)qi * kp + i].id;
+            L.f_key[m + i] = a.host_cand[(size_t)qi * kp + i].key;
+            L.f_id[m + i] = a.host_cand[(size_t)qi * kp + i].id;
         }
     }
     __syncthreads();
+    IVF_TRACE_MARK(24);
     // 4. rank by counting; nearest first, ties by smaller id
     const uint32_t tot = m + nh;
     const int k = a.k;
     if ((uint32_t)tid < tot) {
-        double mk = f_key[tid]; int64_t mi = f_id[tid];
+        double mk = L.f_key[tid]; int64_t mi = L.f_id[tid];
         uint32_t rank = 0;
         for (uint32_t j = 0; j < tot; ++j) {
-            double ok = f_key[j]; int64_t oi = f_id[j];
+            double ok = L.f_key[j]; int64_t oi = L.f_id[j];
             rank += (ok > mk) || (ok == mk && oi < mi);
         }
         if (rank < (uint32_t)k) {
@@ -625,10 +947,15 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a) {
         a.out_ids[(size_t)qi * k + i] = -1;
         a.out_dists[(size_t)qi * k + i] = a.metric == 0 ? -INFINITY : INFINITY;
     }
+    IVF_TRACE_MARK(25);
 }
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL(merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
+    const size_t n = (size_t)a.nparts * a.kprime;
+    const int fast = a.kprime <= 64;
+    const int threads = fast ? kMergeFastWaves * 64 : (n <= 8192 ? 256 : kSelectThreads);
+    const size_t lds = fast ? (size_t)kMergeCandCap * 8 + 1024 * 4 : 0;
+    hipLaunchKernelGGL(merge_kernel, dim3(a.nq), dim3(threads), lds, s, a, fast);
     return hipGetLastError();
 }
 
@@ -661,5 +988,11 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, i
                        (const unsigned char*)src, (unsigned char*)dst, pos, n, row_bytes);
     return hipGetLastError();
 }
+
+#ifdef IVF_TRACE
+extern "C" int ivf_debug_trace(unsigned long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dev::g_trace), sizeof(unsigned long long) * 64);
+}
+#endif
 
 }  // namespace ivf
