@@ -48,7 +48,7 @@ def time_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, k, steps, warmu
     for i in range(steps):
         j = (warmup + i) % nq
         index.ivf_search_device(q_dev[j], nprobe, k, ids_dev[j], dists_dev[j])
-    stream.synchronize()
+    index.ivf_synchronize()
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--n", type=int, default=1_000_000, help="rows of the datastore (default: the named config)")
     ap.add_argument("--nprobe", type=int, default=32)
     ap.add_argument("--k", type=int, default=10)
+    ap.add_argument("--depth", type=int, default=4,
+                    help="independent searches kept in flight (ivf_set_pipeline_depth); 1 = strictly one after another")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
@@ -117,17 +119,25 @@ def main():
     q_dev = q_out.contiguous()
     ids_dev = torch.empty(nq, args.k, dtype=torch.int64, device="cuda")
     dists_dev = torch.empty(nq, args.k, dtype=torch.float32, device="cuda")
+    index.ivf_set_pipeline_depth(args.depth)
     index.ivf_reserve(1, 1024, args.k)
     torch.cuda.synchronize()
 
     dt = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, args.steps, args.warmup)
+    # kernel durations are taken with one search at a time, so that no other kernel shares the GPU
+    index.ivf_set_pipeline_depth(1)
+    index.ivf_reserve(1, 1024, args.k)
+    dt1 = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, args.steps, args.warmup)
     prof = profile_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, min(args.steps, 2048))
 
     sweep = []
     if not args.no_sweep:
         for nprobe in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024):
             steps = max(64, min(args.steps, int(200000 / max(nprobe, 8))))
+            index.ivf_set_pipeline_depth(args.depth)
+            index.ivf_reserve(1, 1024, args.k)
             t = time_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, args.k, steps, 32)
+            index.ivf_set_pipeline_depth(1)
             pr = profile_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, args.k, min(steps, 512))
             sweep.append({"nprobe": nprobe, "qps": round(steps / t, 1), "us_scan": round(pr["us_scan"], 2),
                           "scan_gbs": round(pr["scan_gbs"], 1), "frac": round(pr["scan_gbs"] / HBM_PEAK_GBS, 4),
@@ -141,7 +151,8 @@ def main():
         "config": {"workload": f"configs[1] single-query retrieval: {args.n} x 768 fp32, 1024-component mixture, "
                                f"nlist 1024 (k-means on a tenth of the rows), nprobe {args.nprobe}, k {args.k}, "
                                f"batch 1, inner product, {nq} distinct queries cycled",
-                   "entry_point": "ivf_search_device", "seed": 20970},
+                   "entry_point": "ivf_search_device", "searches_in_flight": args.depth, "seed": 20970},
+        "one_at_a_time": {"value": round(args.steps / dt1, 1), "ms_per_step": dt1 / args.steps * 1e3},
         "roofline": {"bound": "hbm", "achieved": round(prof["scan_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(prof["scan_gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
                      "kernel": "scan_kernel", "us_per_launch": round(prof["us_scan"], 2),
@@ -156,9 +167,10 @@ def main():
         # the timed outputs of those queries must equal the oracle's
         torch.cuda.synchronize()
         index.ivf_profile_enable(False)
+        index.ivf_set_pipeline_depth(args.depth)
         for j in range(nq):
             index.ivf_search_device(q_dev[j], args.nprobe, args.k, ids_dev[j], dists_dev[j])
-        stream.synchronize()
+        index.ivf_synchronize()
         got = ids_dev.cpu().numpy()
         bad = sum(int(not np.array_equal(got[j], results[j][0])) for j in range(len(results)))
         out["parity_sample"] = {"queries": len(results), "id_mismatches": bad}

@@ -164,7 +164,7 @@ int ivf_search(ivf_index* index, const float* q_out, int32_t nq, int32_t nprobe,
 /*
  * The same search with device-resident queries and outputs (all device pointers), enqueued
  * on compute_stream without waiting: outputs are complete once that stream has reached
- * this point.  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
+ * this point (with a pipeline depth above 1: see ivf_set_pipeline_depth).  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
  * ivf_reserve() or an earlier search has sized the workspace for, else the call sizes it
  * itself, which synchronises the device.
  */
@@ -173,6 +173,18 @@ int ivf_search_device(ivf_index* index, const float* q_dev, int32_t nq, int32_t 
 
 /* Sizes the workspace for searches up to (nq, nprobe, k) so that later calls allocate nothing. */
 int ivf_reserve(ivf_index* index, int32_t nq, int32_t nprobe, int32_t k);
+
+/*
+ * Overlap of independent searches (batch-1 serving: one query's coarse scoring, selection and
+ * merge run on a few compute units while another query's scan streams its lists).  With depth
+ * n > 1, successive ivf_search_device calls rotate over n internal streams (the first is
+ * compute_stream), each with its own workspace; inputs must be complete when the call is made,
+ * and outputs are complete after ivf_synchronize().  Depth 1 (the default) keeps everything on
+ * compute_stream.  Changing the depth synchronises the device.  IVF_PLACE_DEVICE only.
+ */
+int ivf_set_pipeline_depth(ivf_index* index, int32_t depth);
+/* Blocks the host until every search enqueued by ivf_search_device has finished. */
+int ivf_synchronize(ivf_index* index);
 
 /* Stage-level entry points, used by the parity tests. */
 /* coarse scores of App. B's first step: scores (host, nq x nlist fp64), raw metric values */

@@ -23,7 +23,8 @@ EXPORTS = [
     "ivf_build_layout", "ivf_adopt_layout", "ivf_free", "ivf_prefetch", "ivf_prefetch_wait",
     "ivf_search", "ivf_search_device", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
-    "ivf_profile_reset", "ivf_set_host_threads", "ivf_strerror", "ivf_last_error",
+    "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
+    "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -79,6 +80,8 @@ def load():
     L.ivf_profile_read.argtypes = [vp, C.POINTER(Profile)]
     L.ivf_profile_reset.argtypes = [vp]
     L.ivf_set_host_threads.argtypes = [vp, i32]
+    L.ivf_set_pipeline_depth.argtypes = [vp, i32]
+    L.ivf_synchronize.argtypes = [vp]
     L.ivf_strerror.argtypes = [ci]
     L.ivf_strerror.restype = C.c_char_p
     L.ivf_last_error.restype = C.c_char_p
@@ -227,6 +230,12 @@ class Index:
 
     def ivf_set_host_threads(self, n):
         _check(load().ivf_set_host_threads(self._h, n))
+
+    def ivf_set_pipeline_depth(self, depth):
+        _check(load().ivf_set_pipeline_depth(self._h, depth))
+
+    def ivf_synchronize(self):
+        _check(load().ivf_synchronize(self._h))
 
 
 def ivf_build_layout(vectors, dtype, centroids, assign, ids=None, metric=IVF_IP,

@@ -118,7 +118,13 @@ struct ivf_index {
     std::vector<uint64_t> rows_desc_prefix;   // prefix sums of list sizes, largest first
     int resident_grid[2] = {0, 0};            // scan workgroups resident at once, for kprime <= 64 / > 64
     ScanShape shape{0, 0, 0, 4};
-    Workspace ws;
+    // Searches through ivf_search_device rotate over `lanes` (stream + workspace each) so that
+    // independent queries overlap; lane 0 runs on compute_stream.  cs / cw: lane in use.
+    struct Lane { hipStream_t stream = nullptr; bool own = false; Workspace ws; };
+    std::vector<Lane> lanes;
+    size_t next_lane = 0;
+    hipStream_t cs = nullptr;
+    Workspace* cw = nullptr;
     std::unique_ptr<ThreadPool> pool;
 
     bool profiling = false;
@@ -157,8 +163,20 @@ int scan_grid_for(ivf_index* ix, int nprobe, int kprime) {
     return (int)g;
 }
 
+void use_lane(ivf_index* ix, size_t i) {
+    ix->cs = ix->lanes[i].stream;
+    ix->cw = &ix->lanes[i].ws;
+}
+
+// waits on the host for every lane other than lane 0, then selects lane 0
+int settle_on_lane0(ivf_index* ix) {
+    for (size_t i = 1; i < ix->lanes.size(); ++i) HIP_TRY(hipStreamSynchronize(ix->lanes[i].stream));
+    use_lane(ix, 0);
+    return IVF_OK;
+}
+
 int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     const int kprime = kprime_for(k);
     const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
     const int grid_cap = ix->n_cu * 2;
@@ -207,7 +225,7 @@ int check_query_args(const ivf_index* ix, const void* q, int32_t nq, int32_t npr
 // ---- profiling events ---------------------------------------------------------------------
 int drain_profile(ivf_index* ix) {
     if (ix->prof_used == 0) return IVF_OK;
-    HIP_TRY(hipStreamSynchronize(ix->compute));
+    for (auto& l : ix->lanes) HIP_TRY(hipStreamSynchronize(l.stream));
     for (size_t i = 0; i < ix->prof_used; ++i) {
         float ms[4];
         for (int j = 0; j < 4; ++j) HIP_TRY(hipEventElapsedTime(&ms[j], ix->prof_sets[i].e[j], ix->prof_sets[i].e[j + 1]));
@@ -229,7 +247,7 @@ int prof_mark(ivf_index* ix, int which) {
         int rc = drain_profile(ix);
         if (rc) return rc;
     }
-    HIP_TRY(hipEventRecord(ix->prof_sets[ix->prof_used].e[which], ix->compute));
+    HIP_TRY(hipEventRecord(ix->prof_sets[ix->prof_used].e[which], ix->cs));
     if (which == 4) ix->prof_used += 1;
     return IVF_OK;
 }
@@ -238,11 +256,11 @@ int prof_mark(ivf_index* ix, int which) {
 // coarse scoring + selection for nq queries already in d_q (device); leaves the probe lists
 // and slot tables in the workspace
 int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid) {
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     int rc;
     if ((rc = prof_mark(ix, 0))) return rc;
     CoarseArgs ca{ix->d_centroids, q_dev, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
-    HIP_TRY(launch_coarse(ca, ix->compute));
+    HIP_TRY(launch_coarse(ca, ix->cs));
     if ((rc = prof_mark(ix, 1))) return rc;
     SelectArgs sa{};
     sa.scores = w.d_scores; sa.probe = w.d_probe; sa.off = ix->d_off; sa.res_off = ix->d_res_off;
@@ -251,26 +269,26 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
     sa.grid = grid;
     sa.desc = w.d_desc;
     sa.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
-    HIP_TRY(launch_select(sa, ix->compute));
+    HIP_TRY(launch_select(sa, ix->cs));
     if ((rc = prof_mark(ix, 2))) return rc;
     return IVF_OK;
 }
 
 int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kprime, int grid) {
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     ScanArgs sc{};
     sc.buf = ix->d_buf; sc.q = q_dev; sc.ids = ix->d_ids; sc.slots = w.slots;
     sc.part_key = w.d_part_key; sc.part_row = w.d_part_row;
     sc.desc = w.d_desc;
     sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
     sc.kprime = kprime; sc.grid = grid; sc.shape = ix->shape;
-    HIP_TRY(launch_scan(sc, ix->compute));
+    HIP_TRY(launch_scan(sc, ix->cs));
     return prof_mark(ix, 3);
 }
 
 int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, int grid,
                   bool with_host, int64_t* out_ids, float* out_dists) {
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     MergeArgs ma{};
     ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.slots = w.slots;
     ma.part_key = w.d_part_key; ma.part_row = w.d_part_row;
@@ -280,7 +298,7 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     ma.d = ix->d; ma.dtype = ix->dtype; ma.metric = ix->metric; ma.nprobe = nprobe; ma.nq = nq;
     ma.k = k; ma.kprime = kprime; ma.nparts = grid;
     ma.identity = ix->placement == IVF_PLACE_DEVICE;
-    HIP_TRY(launch_merge(ma, ix->compute));
+    HIP_TRY(launch_merge(ma, ix->cs));
     return prof_mark(ix, 4);
 }
 
@@ -296,6 +314,10 @@ int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* cen
     ix->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     if (compute_stream) ix->compute = (hipStream_t)compute_stream;
     else { HIP_TRY(hipStreamCreateWithFlags(&ix->compute, hipStreamNonBlocking)); ix->own_compute = true; }
+    ix->lanes.resize(1);
+    ix->lanes[0].stream = ix->compute;
+    ix->cs = ix->compute;
+    ix->cw = &ix->lanes[0].ws;
     if (copy_stream) ix->copy = (hipStream_t)copy_stream;
     else { HIP_TRY(hipStreamCreateWithFlags(&ix->copy, hipStreamNonBlocking)); ix->own_copy = true; }
     HIP_TRY(hipEventCreate(&ix->ev_pf_begin));
@@ -363,7 +385,7 @@ int check_build_args(const void* data, int64_t n, int32_t d, int dtype, const fl
 extern "C" void ivf_free(ivf_index* ix) {
     if (!ix) return;
     hipDeviceSynchronize();
-    free_workspace(ix->ws);
+    for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) hipStreamDestroy(l.stream); }
     for (auto& s : ix->prof_sets) for (auto& e : s.e) hipEventDestroy(e);
     hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_res_off);
     hipFree(ix->d_prof_rows);
@@ -426,8 +448,8 @@ extern "C" int ivf_build_layout(const void* vectors, int64_t n, int32_t d, int d
                 int64_t cnt = std::min(chunk, n - i0);
                 hipError_t e = hipMemcpy(d_stage, (const char*)vectors + (size_t)i0 * rb, (size_t)cnt * rb, hipMemcpyHostToDevice);
                 if (e == hipSuccess) e = hipMemcpy(d_pos, pos.data() + i0, (size_t)cnt * sizeof(int64_t), hipMemcpyHostToDevice);
-                if (e == hipSuccess) e = launch_scatter_rows(d_stage, ix->d_buf, d_pos, cnt, rb, ix->compute);
-                if (e == hipSuccess) e = hipStreamSynchronize(ix->compute);
+                if (e == hipSuccess) e = launch_scatter_rows(d_stage, ix->d_buf, d_pos, cnt, rb, ix->cs);
+                if (e == hipSuccess) e = hipStreamSynchronize(ix->cs);
                 if (e != hipSuccess) status = fail(IVF_EHIP, "layout upload: %s", hipGetErrorString(e));
             }
             hipFree(d_stage); hipFree(d_pos);
@@ -481,7 +503,41 @@ extern "C" int ivf_reserve(ivf_index* ix, int32_t nq, int32_t nprobe, int32_t k)
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
     if (nq < 1 || nprobe < 1 || k < 1) return fail(IVF_EINVAL, "nq, nprobe and k must be at least 1");
     if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
-    return ensure_workspace(ix, nq, std::min(nprobe, ix->nlist), k);
+    for (size_t i = 0; i < ix->lanes.size(); ++i) {
+        use_lane(ix, i);
+        int rc = ensure_workspace(ix, nq, std::min(nprobe, ix->nlist), k);
+        if (rc) { use_lane(ix, 0); return rc; }
+    }
+    use_lane(ix, 0);
+    return IVF_OK;
+}
+
+extern "C" int ivf_set_pipeline_depth(ivf_index* ix, int32_t depth) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (depth < 1 || depth > 8) return fail(IVF_EINVAL, "pipeline depth must be in [1, 8]");
+    if (ix->placement != IVF_PLACE_DEVICE) return fail(IVF_ESTATE, "pipelining needs a device-resident index");
+    HIP_TRY(hipDeviceSynchronize());
+    while ((int)ix->lanes.size() > depth) {
+        auto& l = ix->lanes.back();
+        free_workspace(l.ws);
+        if (l.own) hipStreamDestroy(l.stream);
+        ix->lanes.pop_back();
+    }
+    while ((int)ix->lanes.size() < depth) {
+        ivf_index::Lane l;
+        HIP_TRY(hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking));
+        l.own = true;
+        ix->lanes.push_back(l);
+    }
+    ix->next_lane = 0;
+    use_lane(ix, 0);
+    return IVF_OK;
+}
+
+extern "C" int ivf_synchronize(ivf_index* ix) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    for (auto& l : ix->lanes) HIP_TRY(hipStreamSynchronize(l.stream));
+    return IVF_OK;
 }
 
 // ---- search -------------------------------------------------------------------------------------
@@ -495,12 +551,20 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     if (ix->placement != IVF_PLACE_DEVICE)
         return fail(IVF_ESTATE, "ivf_search_device needs a device-resident index");
     nprobe = std::min(nprobe, ix->nlist);
-    if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
-    const int kprime = kprime_for(k);
-    const int grid = scan_grid_for(ix, nprobe, kprime);
-    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe, grid))) return rc;
-    if ((rc = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return rc;
-    return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+    use_lane(ix, ix->next_lane);
+    ix->next_lane = (ix->next_lane + 1) % ix->lanes.size();
+    auto body = [&]() -> int {
+        int r;
+        if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
+        const int kprime = kprime_for(k);
+        const int grid = scan_grid_for(ix, nprobe, kprime);
+        if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid))) return r;
+        if ((r = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return r;
+        return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+    };
+    rc = body();
+    use_lane(ix, 0);
+    return rc;
 }
 
 static double now_ms() {
@@ -517,21 +581,22 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
     if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
     const double t0 = now_ms();
     nprobe = std::min(nprobe, ix->nlist);
+    if ((rc = settle_on_lane0(ix))) return rc;
     if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     const int kprime = kprime_for(k);
     const int grid = scan_grid_for(ix, nprobe, kprime);
     const bool hybrid = ix->placement == IVF_PLACE_HOST;
     ivf_search_stats st{};
 
     memcpy(w.h_q, q_out, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
-    if (hybrid && ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->compute, ix->ev_pf_done, 0));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    if (hybrid && ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->cs, ix->ev_pf_done, 0));
     if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe, grid))) return rc;
     const bool want_probe = hybrid || stats;
     if (want_probe) {
-        HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
-        HIP_TRY(hipEventRecord(ix->ev_probe, ix->compute));
+        HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
+        HIP_TRY(hipEventRecord(ix->ev_probe, ix->cs));
     }
     if ((rc = enqueue_scan(ix, w.d_q, nq, nprobe, kprime, grid))) return rc;
 
@@ -563,9 +628,9 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
         st.hit_rate = (float)(hit_sum / nq);
     }
     if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.d_out_ids, w.d_out_dists))) return rc;
-    HIP_TRY(hipMemcpyAsync(w.h_out_ids, w.d_out_ids, (size_t)nq * k * sizeof(int64_t), hipMemcpyDeviceToHost, ix->compute));
-    HIP_TRY(hipMemcpyAsync(w.h_out_dists, w.d_out_dists, (size_t)nq * k * sizeof(float), hipMemcpyDeviceToHost, ix->compute));
-    HIP_TRY(hipStreamSynchronize(ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.h_out_ids, w.d_out_ids, (size_t)nq * k * sizeof(int64_t), hipMemcpyDeviceToHost, ix->cs));
+    HIP_TRY(hipMemcpyAsync(w.h_out_dists, w.d_out_dists, (size_t)nq * k * sizeof(float), hipMemcpyDeviceToHost, ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
     memcpy(ids, w.h_out_ids, (size_t)nq * k * sizeof(int64_t));
     memcpy(dists, w.h_out_dists, (size_t)nq * k * sizeof(float));
     st.ms_total = (float)(now_ms() - t0);
@@ -582,17 +647,17 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     if (flags & ~IVF_PREFETCH_RESET) return fail(IVF_EINVAL, "unknown prefetch flags 0x%x", flags);
     nprobe = std::min(nprobe, ix->nlist);
     if ((rc = ensure_workspace(ix, nq, nprobe, 1))) return rc;
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     // rank the clusters by q_in on the GPU
     memcpy(w.h_q, q_in, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
     rc = enqueue_probe(ix, w.d_q, nq, nprobe, 1);
     ix->profiling = was_profiling;
     if (rc) return rc;
-    HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
-    HIP_TRY(hipStreamSynchronize(ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
 
     if (flags & IVF_PREFETCH_RESET) {
         std::fill(ix->h_res_off.begin(), ix->h_res_off.end(), (int64_t)-1);
@@ -649,13 +714,14 @@ extern "C" int ivf_coarse_scores(ivf_index* ix, const float* q, int32_t nq, doub
     int rc = check_query_args(ix, q, nq, 1);
     if (rc) return rc;
     if (!scores) return fail(IVF_EINVAL, "scores is NULL");
+    if ((rc = settle_on_lane0(ix))) return rc;
     if ((rc = ensure_workspace(ix, nq, 1, 1))) return rc;
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     memcpy(w.h_q, q, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
     CoarseArgs ca{ix->d_centroids, w.d_q, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
-    HIP_TRY(launch_coarse(ca, ix->compute));
-    HIP_TRY(hipStreamSynchronize(ix->compute));
+    HIP_TRY(launch_coarse(ca, ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
     HIP_TRY(hipMemcpy(scores, w.d_scores, (size_t)nq * ix->nlist * sizeof(double), hipMemcpyDeviceToHost));
     return IVF_OK;
 }
@@ -665,17 +731,18 @@ extern "C" int ivf_probe(ivf_index* ix, const float* q, int32_t nq, int32_t npro
     if (rc) return rc;
     if (!clusters) return fail(IVF_EINVAL, "clusters is NULL");
     nprobe = std::min(nprobe, ix->nlist);
+    if ((rc = settle_on_lane0(ix))) return rc;
     if ((rc = ensure_workspace(ix, nq, nprobe, 1))) return rc;
-    Workspace& w = ix->ws;
+    Workspace& w = *ix->cw;
     memcpy(w.h_q, q, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
     rc = enqueue_probe(ix, w.d_q, nq, nprobe, 1);
     ix->profiling = was_profiling;
     if (rc) return rc;
-    HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->compute));
-    HIP_TRY(hipStreamSynchronize(ix->compute));
+    HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
     memcpy(clusters, w.h_probe, (size_t)nq * nprobe * sizeof(int32_t));
     return IVF_OK;
 }

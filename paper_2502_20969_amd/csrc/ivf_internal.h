@@ -11,7 +11,7 @@ namespace ivf {
 
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;   // empty slot of a candidate list
 constexpr int kMaxKPrime = 128;            // candidates kept per list: k + slack <= 128
-constexpr int kScanWaves = 12;             // scan workgroup: 12 wavefronts, one workgroup per compute unit
+constexpr int kScanWaves = 8;              // scan workgroup: 12 wavefronts, one workgroup per compute unit
 constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kSelectThreads = 1024;       // select / merge workgroup: 16 wavefronts
 constexpr int kSortLdsCap = 2048;          // select: pairs sorted in LDS up to this many

@@ -247,6 +247,19 @@ def test_search_device_and_adopt(streams):
     assert np.array_equal(ids_dev.cpu().numpy(), hi) and np.array_equal(d_dev.cpu().numpy(), hd)
     for b in range(12):
         assert check_topk(hi[b], hd[b], lists, O.F32, off, perm, cent, q[b], 8, 10, O.IP) == 0
+    # several searches in flight on the library's own streams give the same results
+    index.ivf_set_pipeline_depth(3)
+    ids2 = torch.zeros_like(ids_dev)
+    d2 = torch.zeros_like(d_dev)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for b in range(12):
+            index.ivf_search_device(q_dev[b], 8, 10, ids2[b], d2[b])
+    index.ivf_synchronize()
+    assert np.array_equal(ids2.cpu().numpy(), hi) and np.array_equal(d2.cpu().numpy(), hd)
+    hi2, hd2 = index.ivf_search(q, 8, 10)        # host entry point while lanes exist
+    assert np.array_equal(hi2, hi) and np.array_equal(hd2, hd)
+    index.ivf_set_pipeline_depth(1)
     # profiling counters: rows covered equal the rows of the selected lists
     index.ivf_profile_enable(True)
     index.ivf_profile_reset()
