@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--k", type=int, default=10)
     ap.add_argument("--depth", type=int, default=4,
                     help="independent searches kept in flight (ivf_set_pipeline_depth); 1 = strictly one after another")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (a kernel of known traffic for scaling rocprofv3 counters)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     args = ap.parse_args()
@@ -122,6 +124,13 @@ def main():
     index.ivf_set_pipeline_depth(args.depth)
     index.ivf_reserve(1, 1024, args.k)
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     dt = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, args.steps, args.warmup)
     # kernel durations are taken with one search at a time, so that no other kernel shares the GPU

@@ -85,7 +85,7 @@ struct Workspace {
     size_t h_scores_len = 0;
 };
 
-struct ProfSet { hipEvent_t e[5]; };
+struct ProfSet { hipEvent_t e[8]; };   // begin/end of the coarse, select, scan and merge kernels
 
 }  // namespace
 
@@ -228,7 +228,8 @@ int drain_profile(ivf_index* ix) {
     for (auto& l : ix->lanes) HIP_TRY(hipStreamSynchronize(l.stream));
     for (size_t i = 0; i < ix->prof_used; ++i) {
         float ms[4];
-        for (int j = 0; j < 4; ++j) HIP_TRY(hipEventElapsedTime(&ms[j], ix->prof_sets[i].e[j], ix->prof_sets[i].e[j + 1]));
+        for (int j = 0; j < 4; ++j)
+            HIP_TRY(hipEventElapsedTime(&ms[j], ix->prof_sets[i].e[2 * j], ix->prof_sets[i].e[2 * j + 1]));
         ix->prof.ms_coarse += ms[0]; ix->prof.ms_select += ms[1];
         ix->prof.ms_scan += ms[2]; ix->prof.ms_merge += ms[3];
         ix->prof.calls += 1;
@@ -241,14 +242,17 @@ int drain_profile(ivf_index* ix) {
     return IVF_OK;
 }
 
-int prof_mark(ivf_index* ix, int which) {
+// events for kernel `which` (0 coarse .. 3 merge) of the search being enqueued, or nulls
+int prof_events(ivf_index* ix, int which, hipEvent_t* e0, hipEvent_t* e1) {
+    *e0 = *e1 = nullptr;
     if (!ix->profiling) return IVF_OK;
     if (which == 0 && ix->prof_used == ix->prof_sets.size()) {
         int rc = drain_profile(ix);
         if (rc) return rc;
     }
-    HIP_TRY(hipEventRecord(ix->prof_sets[ix->prof_used].e[which], ix->cs));
-    if (which == 4) ix->prof_used += 1;
+    *e0 = ix->prof_sets[ix->prof_used].e[2 * which];
+    *e1 = ix->prof_sets[ix->prof_used].e[2 * which + 1];
+    if (which == 3) ix->prof_used += 1;
     return IVF_OK;
 }
 
@@ -258,10 +262,11 @@ int prof_mark(ivf_index* ix, int which) {
 int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid) {
     Workspace& w = *ix->cw;
     int rc;
-    if ((rc = prof_mark(ix, 0))) return rc;
+    hipEvent_t e0, e1;
+    if ((rc = prof_events(ix, 0, &e0, &e1))) return rc;
     CoarseArgs ca{ix->d_centroids, q_dev, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
-    HIP_TRY(launch_coarse(ca, ix->cs));
-    if ((rc = prof_mark(ix, 1))) return rc;
+    HIP_TRY(launch_coarse(ca, ix->cs, e0, e1));
+    if ((rc = prof_events(ix, 1, &e0, &e1))) return rc;
     SelectArgs sa{};
     sa.scores = w.d_scores; sa.probe = w.d_probe; sa.off = ix->d_off; sa.res_off = ix->d_res_off;
     sa.slots = w.slots; sa.sort_keys = w.d_sort_keys; sa.sort_idx = w.d_sort_idx;
@@ -269,8 +274,7 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
     sa.grid = grid;
     sa.desc = w.d_desc;
     sa.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
-    HIP_TRY(launch_select(sa, ix->cs));
-    if ((rc = prof_mark(ix, 2))) return rc;
+    HIP_TRY(launch_select(sa, ix->cs, e0, e1));
     return IVF_OK;
 }
 
@@ -282,8 +286,11 @@ int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kpri
     sc.desc = w.d_desc;
     sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
     sc.kprime = kprime; sc.grid = grid; sc.shape = ix->shape;
-    HIP_TRY(launch_scan(sc, ix->cs));
-    return prof_mark(ix, 3);
+    hipEvent_t e0, e1;
+    int rc = prof_events(ix, 2, &e0, &e1);
+    if (rc) return rc;
+    HIP_TRY(launch_scan(sc, ix->cs, e0, e1));
+    return IVF_OK;
 }
 
 int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, int grid,
@@ -298,8 +305,11 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     ma.d = ix->d; ma.dtype = ix->dtype; ma.metric = ix->metric; ma.nprobe = nprobe; ma.nq = nq;
     ma.k = k; ma.kprime = kprime; ma.nparts = grid;
     ma.identity = ix->placement == IVF_PLACE_DEVICE;
-    HIP_TRY(launch_merge(ma, ix->cs));
-    return prof_mark(ix, 4);
+    hipEvent_t e0, e1;
+    int rc = prof_events(ix, 3, &e0, &e1);
+    if (rc) return rc;
+    HIP_TRY(launch_merge(ma, ix->cs, e0, e1));
+    return IVF_OK;
 }
 
 // ---- construction helpers --------------------------------------------------------------------

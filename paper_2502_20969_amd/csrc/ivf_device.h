@@ -300,11 +300,30 @@ struct ClusterOrder {
     }
 };
 
+// Value held by lane (lane ^ STRIDE), with register-to-register moves only: DPP quad
+// permutes (1, 2), row shifts (4), a row rotate (8), and the 16- and 32-lane swaps of gfx950.
 template <int STRIDE>
 __device__ __forceinline__ uint32_t xor_lane_u32(uint32_t v) {
+    const int lane = lane_id();
     if (STRIDE == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
     if (STRIDE == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
-    return (uint32_t)__shfl_xor((int)v, STRIDE);
+    if (STRIDE == 4) {
+        int up = __builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0xF, true);   // row_shl:4 = lane + 4
+        int dn = __builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);   // row_shr:4 = lane - 4
+        return (uint32_t)((lane & 4) ? dn : up);
+    }
+    if (STRIDE == 8) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, true);  // row_ror:8
+    if (STRIDE == 16) {
+        auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);   // [0] = rows 0,0,2,2  [1] = rows 1,1,3,3
+        return (lane & 16) ? r[0] : r[1];
+    }
+    auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);       // [0] = low half twice, [1] = high half twice
+    return (lane & 32) ? r[0] : r[1];
+}
+// Value held by lane 63 - lane.
+__device__ __forceinline__ uint32_t mirror_lane_u32(uint32_t v) {
+    uint32_t m = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true);   // row_mirror = lane ^ 15
+    return xor_lane_u32<32>(xor_lane_u32<16>(m));
 }
 template <int STRIDE>
 __device__ __forceinline__ RowCand xor_lane(const RowCand& c) {
@@ -359,10 +378,18 @@ __device__ __forceinline__ void bitonic_sort64(C& c, const O& order) {
 #undef IVF_STAGE
 }
 
+__device__ __forceinline__ RowCand mirror(const RowCand& c) {
+    return RowCand{__uint_as_float(mirror_lane_u32(__float_as_uint(c.k))), mirror_lane_u32(c.r)};
+}
+__device__ __forceinline__ ClusterCand mirror(const ClusterCand& c) {
+    uint32_t lo = mirror_lane_u32((uint32_t)c.k), hi = mirror_lane_u32((uint32_t)(c.k >> 32));
+    return ClusterCand{((uint64_t)hi << 32) | lo, mirror_lane_u32(c.i)};
+}
+
 // a <- the first 64 of (a u p), sorted; a and p sorted.
 template <typename C, typename O>
 __device__ __forceinline__ void merge_best64(C& a, const C& p, const O& order) {
-    C rev = from_lane(p, 63 - lane_id());
+    C rev = mirror(p);
     bool a_first, r_first;
     order.compare(a, rev, a_first, r_first);
     if (r_first) a = rev;
@@ -395,7 +422,7 @@ struct WaveTopK {
         } else {
             // the best 128 of (L0, L1, P) are L0 plus the best 64 of (L1 u P)
             merge_best64(top[KL - 1], run, order);
-            RowCand rev = from_lane(top[KL - 1], 63 - lane_id());
+            RowCand rev = mirror(top[KL - 1]);
             bool a_first, r_first;
             order.compare(top[0], rev, a_first, r_first);
             if (r_first) { RowCand t = top[0]; top[0] = rev; rev = t; }
@@ -416,10 +443,11 @@ struct WaveTopK {
         pend = empty_row_cand(); pcount = 0;
     }
 
-    // Called by the whole wavefront with a uniform candidate.
-    __device__ __forceinline__ void push(float ckey, uint32_t crow, const RowOrder& order, int kprime) {
+    // Called by the whole wavefront with a uniform candidate; the caller flushes before the
+    // pending buffer (64 entries) can overflow.
+    __device__ __forceinline__ void push(float ckey, uint32_t crow) {
         if (lane_id() == pcount) pend = RowCand{ckey, crow};
-        if (++pcount == 64) flush(order, kprime);
+        ++pcount;
     }
 };
 

@@ -54,11 +54,12 @@ struct WgDesc {
     int64_t slot_base;
 };
 
+// Every launcher takes optional events that receive the kernel's own begin and end time.
 struct CoarseArgs {
     const float* centroids; const float* q; double* scores;
     int nlist, d, nq, metric;
 };
-hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s);
+hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
 struct SelectArgs {
     const double* scores;    // [nq x nlist]
@@ -72,7 +73,7 @@ struct SelectArgs {
     unsigned long long* rows_counter;  // nullable: receives the rows of all resident selected lists
     int nlist, nprobe, nq, metric, grid;
 };
-hipError_t launch_select(const SelectArgs& a, hipStream_t s);
+hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
 struct ScanArgs {
     const void* buf;         // device buffer holding resident lists, row-major
@@ -85,7 +86,7 @@ struct ScanArgs {
     int d, dtype, metric, nprobe, nq, kprime, grid;
     ScanShape shape;
 };
-hipError_t launch_scan(const ScanArgs& a, hipStream_t s);
+hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 // workgroups of the scan kernel for (shape, dtype, metric, kprime) that are resident at once
 int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime, int d, int n_cu);
 
@@ -99,7 +100,7 @@ struct MergeArgs {
     int d, dtype, metric, nprobe, nq, k, kprime, nparts;
     int identity;            // 1: buffer row == global row (device placement)
 };
-hipError_t launch_merge(const MergeArgs& a, hipStream_t s);
+hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
 hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,

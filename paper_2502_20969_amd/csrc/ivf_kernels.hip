@@ -3,6 +3,7 @@
 // The operations are those of TeleRAG (arxiv 2502.20969) App. B: coarse search over the
 // centroids, fine search over the rows of the selected clusters, k nearest by a sort.
 #include "ivf_device.h"
+#include <hip/hip_ext.h>
 
 namespace ivf {
 using namespace dev;
@@ -67,10 +68,10 @@ __global__ __launch_bounds__(256) void coarse_kernel(CoarseArgs a) {
     }
 }
 
-hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s) {
+hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     dim3 grid((a.nlist + 3) / 4, (a.nq + kCoarseQT - 1) / kCoarseQT);
     size_t lds = sizeof(float) * kCoarseQT * a.d;
-    hipLaunchKernelGGL(coarse_kernel, grid, dim3(256), lds, s, a);
+    hipExtLaunchKernelGGL(coarse_kernel, grid, dim3(256), lds, s, e0, e1, 0, a);
     return hipGetLastError();
 }
 
@@ -276,7 +277,7 @@ uint32_t select_sort_pad(int nlist, int nprobe) {
     return part < full ? part : full;     // sort only the selected clusters when that is fewer
 }
 
-hipError_t launch_select(const SelectArgs& a, hipStream_t s) {
+hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     uint32_t pad = select_sort_pad(a.nlist, a.nprobe);
     int in_lds = pad <= (uint32_t)kSortLdsCap;
     int prefix_in_lds = a.nprobe <= kPrefixLdsCap;
@@ -284,7 +285,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s) {
     const int threads = a.nlist <= 4096 && a.grid <= 1024 ? 256 : kSelectThreads;
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
     if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64 - 1) * 64 * 12;
-    hipLaunchKernelGGL(select_kernel, dim3(a.nq), dim3(threads), lds, s, a, pad, in_lds, prefix_in_lds);
+    hipExtLaunchKernelGGL(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, 0, a, pad, in_lds, prefix_in_lds);
     return hipGetLastError();
 }
 
@@ -299,14 +300,6 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s) {
 // a query's clusters form one sequence that is split evenly over the workgroups and, inside a
 // workgroup, over its four wavefronts.
 // =============================================================================================
-template <int U>
-__device__ __forceinline__ float pick(const float (&a)[U], int u) {
-    float r = a[0];
-#pragma unroll
-    for (int i = 1; i < U; ++i) r = (u == i) ? a[i] : r;
-    return r;
-}
-
 // Position of a wavefront in the row sequence of its query.
 struct Cursor {
     uint32_t r, r_end;           // next row and end of this wavefront's range
@@ -499,17 +492,16 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
 #pragma unroll
         for (int u = 0; u < U; ++u) any |= leader && (uint32_t)(u * RPI + rsel) < b.nr && acc[u] >= top.thr;
         if (__ballot(any)) {
-#pragma unroll 1
+#pragma unroll
             for (int u = 0; u < U; ++u) {
-                float au = pick<U>(acc, u);
-#pragma unroll 1
+#pragma unroll
                 for (int j = 0; j < RPI; ++j) {
-                    uint32_t r = u * RPI + j;
-                    if (r >= b.nr) break;
-                    float ck = read_lane(au, j * LPR + LPR - 1);
-                    if (ck >= top.thr) top.push(ck, b.grow + r, order, p.kprime);
+                    const uint32_t r = u * RPI + j;
+                    const float ck = read_lane(acc[u], j * LPR + LPR - 1);
+                    if (r < b.nr && ck >= top.thr) top.push(ck, b.grow + r);
                 }
             }
+            if (top.pcount > 64 - RPB) top.flush(order, p.kprime);   // room for a whole batch stays free
         }
     };
 
@@ -566,7 +558,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
             }
             s = group_total_last_lane<64>(s);
             float ck = read_lane(METRIC == 0 ? s : -s, 63);
-            if (ck >= top.thr) top.push(ck, b.grow + r, order, p.kprime);
+            if (ck >= top.thr) {
+                top.push(ck, b.grow + r);
+                if (top.pcount == 64) top.flush(order, p.kprime);
+            }
         }
     }
     finish_workgroup<KL>(top, p, lds, qi);
@@ -640,11 +635,11 @@ int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime
     return per_cu * n_cu;
 }
 
-hipError_t launch_scan(const ScanArgs& a, hipStream_t s) {
+hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     ScanFn fn = scan_fn(a.shape, a.dtype, a.metric, a.kprime);
     if (!fn) return hipErrorInvalidValue;
     dim3 grid(a.grid, a.nq);
-    hipLaunchKernelGGL(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.kprime, a.d), s, a);
+    hipExtLaunchKernelGGL(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.kprime, a.d), s, e0, e1, 0, a);
     return hipGetLastError();
 }
 
@@ -950,12 +945,12 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     IVF_TRACE_MARK(25);
 }
 
-hipError_t launch_merge(const MergeArgs& a, hipStream_t s) {
+hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     const size_t n = (size_t)a.nparts * a.kprime;
     const int fast = a.kprime <= 64;
     const int threads = fast ? kMergeFastWaves * 64 : (n <= 8192 ? 256 : kSelectThreads);
     const size_t lds = fast ? (size_t)kMergeCandCap * 8 + 1024 * 4 : 0;
-    hipLaunchKernelGGL(merge_kernel, dim3(a.nq), dim3(threads), lds, s, a, fast);
+    hipExtLaunchKernelGGL(merge_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, 0, a, fast);
     return hipGetLastError();
 }
 
