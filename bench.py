@@ -93,6 +93,114 @@ def cpu_baseline(rows_host, assign_host, cent_host, q_out, nprobe, k, budget_s=1
         (off, perm, lists, results)
 
 
+def run_lookahead(args):
+    """Benchmark configs[3]: lists in pinned host memory, an 8 GB device prefetch buffer,
+    ivf_prefetch(q_in) overlapped with a synthetic ~20 ms decode, then ivf_search(q_out) with the
+    resident clusters on the GPU and the others on the host.  One JSON line with a budget sweep."""
+    import numpy as np
+    import torch
+    import paper_2502_20969_amd as P
+    import workloads as W
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    scale, pinned = args.scale, None
+    while pinned is None:
+        # the datastore is scaled down (same d, rows per list and nprobe) when the host cannot pin it
+        n, d, nlist, nprobe, k = int(60_000_000 * scale), 768, max(64, int(16384 * scale)), 256, 10
+        print(f"[c4] allocating {n * d * 2 / 1e9:.1f} GB of pinned host memory", file=sys.stderr, flush=True)
+        try:
+            pinned = torch.empty((n, d), dtype=torch.float16, pin_memory=True)
+        except RuntimeError as e:
+            print(f"[c4] could not pin it ({str(e).splitlines()[0]}); halving the datastore", file=sys.stderr, flush=True)
+            scale /= 2
+            if scale < 0.01:
+                raise
+    nprobe = min(nprobe, nlist)
+    sizes = W.zipf_sizes(n, nlist, 0.1, 20972)
+    print(f"[c4] pinned after {time.time() - t0:.1f} s; generating rows on the GPU", file=sys.stderr, flush=True)
+    ds = W.cluster_major_datastore(sizes, d, 0.3, 20973, dtype="f16", device="cuda", out=pinned, chunk=1 << 20)
+    torch.cuda.synchronize()
+    print(f"[c4] datastore ready after {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    q_in, q_out = W.query_pairs(pinned, args.pairs, 0.3, 20974)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    cap = int(8e9 * min(1.0, scale * 4))
+    index = P.ivf_adopt_layout(pinned, "f16", ds.offsets, ds.centroids.cpu(), metric=P.IVF_IP,
+                               placement=P.IVF_PLACE_HOST, device_buffer_bytes=cap,
+                               compute_stream=compute, copy_stream=copy)
+    threads = min(16, len(os.sched_getaffinity(0)))
+    index.ivf_set_host_threads(threads)
+    index.ivf_reserve(1, nprobe, k)
+    setup_s = time.time() - t0
+
+    # synthetic decode: bf16 matmuls on torch's stream, count calibrated to about 20 ms
+    a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    def decode(reps):
+        for _ in range(reps):
+            torch.matmul(a, b)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    decode(4); torch.cuda.synchronize()
+    e0.record(); decode(16); e1.record(); torch.cuda.synchronize()
+    reps = max(1, int(round(20.0 / (e0.elapsed_time(e1) / 16))))
+    e0.record(); decode(reps); e1.record(); torch.cuda.synchronize()
+    decode_alone_ms = e0.elapsed_time(e1)
+
+    qi, qo = q_in.numpy(), q_out.numpy()
+    for j in range(args.pairs):          # untimed: first host touch of the lists these queries scan
+        index.ivf_prefetch(qi[j], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
+        index.ivf_search(qo[j], nprobe, k)
+    print(f"[c4] warm after {time.time() - t0:.1f} s; budget sweep", file=sys.stderr, flush=True)
+    rows = []
+    for budget_gb in (0.0, 0.25, 0.5, 1.28, 2.0, 8.0):
+        budget = int(budget_gb * 1e9 * min(1.0, scale * 4))
+        acc = {"hit": [], "ms_search": [], "ms_host": [], "ms_probe": [], "ms_copy": [], "bytes": [], "ms_prefetch_call": [],
+               "ms_decode": [], "gpu_bytes": [], "host_bytes": []}
+        for j in range(args.pairs):
+            t = time.perf_counter()
+            ps = index.ivf_prefetch(qi[j], nprobe, budget, flags=P.IVF_PREFETCH_RESET)
+            acc["ms_prefetch_call"].append((time.perf_counter() - t) * 1e3)
+            e0.record(); decode(reps); e1.record()                 # overlaps the copies
+            torch.cuda.synchronize()
+            acc["ms_decode"].append(e0.elapsed_time(e1))
+            acc["ms_copy"].append(index.ivf_prefetch_wait())
+            acc["bytes"].append(ps.bytes)
+            ids, dists, st = index.ivf_search(qo[j], nprobe, k, with_stats=True)
+            acc["hit"].append(st.hit_rate); acc["ms_search"].append(st.ms_total); acc["ms_host"].append(st.ms_host_scan)
+            acc["ms_probe"].append(st.ms_probe); acc["gpu_bytes"].append(st.bytes_gpu); acc["host_bytes"].append(st.bytes_host)
+        m = {k_: float(np.mean(v)) for k_, v in acc.items()}
+        copy_gbs = (m["bytes"] / 1e9) / (m["ms_copy"] / 1e3) if m["ms_copy"] > 0 else 0.0
+        rows.append({"budget_gb": budget / 1e9, "hit_rate": round(m["hit"], 4), "prefetched_gb": round(m["bytes"] / 1e9, 3),
+                     "copy_ms": round(m["ms_copy"], 2), "pcie_gbs": round(copy_gbs, 1),
+                     "prefetch_call_ms": round(m["ms_prefetch_call"], 3), "decode_ms": round(m["ms_decode"], 2),
+                     "search_ms": round(m["ms_search"], 3), "probe_ms": round(m["ms_probe"], 3),
+                     "host_scan_ms": round(m["ms_host"], 3), "gpu_scan_gb": round(m["gpu_bytes"] / 1e9, 3),
+                     "host_scan_gb": round(m["host_bytes"] / 1e9, 3),
+                     "host_scan_gbs": round((m["host_bytes"] / 1e9) / (m["ms_host"] / 1e3), 1) if m["ms_host"] > 0 else 0.0})
+    # sampled parity at this size: two hybrid searches against the oracle on the same pinned lists
+    parity = None
+    if not args.no_cpu:
+        import oracle as O
+        lists_np = pinned.numpy().view(np.uint16)
+        off_np, cent_np = ds.offsets.numpy(), ds.centroids.cpu().numpy()
+        bad = 0
+        for j in range(min(2, args.pairs)):
+            index.ivf_prefetch(qi[j], nprobe, int(1.28e9 * min(1.0, scale * 4)), flags=P.IVF_PREFETCH_RESET)
+            gi, gd = index.ivf_search(qo[j], nprobe, k)
+            oi, osc = O.search(lists_np, O.F16, off_np, None, cent_np, qo[j], nprobe, k, O.IP)
+            bad += int(not np.array_equal(gi[0], oi)) + int(not np.allclose(gd[0], osc, rtol=2e-3))
+        parity = {"queries": min(2, args.pairs), "mismatches": bad}
+    head = [r for r in rows if abs(r["budget_gb"] - 1.28 * min(1.0, scale * 4)) < 1e-6][0]
+    out = {"metric": "lookahead retrieval: hybrid IVF searches/sec with prefetch under a byte budget, 1 GPU",
+           "value": round(1e3 / head["search_ms"], 1), "unit": "queries/s", "n_gpus": 1, "steps": args.pairs, "warmup": 0,
+           "ms_per_step": head["search_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f16", "data": "synthetic",
+           "config": {"workload": f"configs[3] limited-GPU-memory lookahead: {n} x 768 fp16 in pinned host memory, nlist {nlist}, "
+                                  f"nprobe {nprobe}, k {k}, batch 1, device buffer {cap / 1e9:.1f} GB, scale {scale}",
+                      "host_threads": threads, "decode_alone_ms": round(decode_alone_ms, 2), "decode_matmuls": reps},
+           "budget_sweep": rows, "parity_sample": parity, "setup_s": round(setup_s, 1)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +215,10 @@ def main():
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic for scaling rocprofv3 counters)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--workload", default="c2", choices=["c2", "c4"],
+                    help="c2: single-query retrieval (the default bench line); c4: lookahead with host-resident lists")
+    ap.add_argument("--scale", type=float, default=1.0, help="c4: fraction of the 60M-row datastore to build")
+    ap.add_argument("--pairs", type=int, default=16, help="c4: (q_in, q_out) pairs per budget")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -115,6 +227,8 @@ def main():
     import numpy as np
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.workload == "c4":
+        return run_lookahead(args)
     torch.cuda.set_device(0)
     index, stream, rows_host, assign_host, cent_host, q_in, q_out, info = build_config2("cuda", args.n)
     nq = q_out.shape[0]
