@@ -186,6 +186,21 @@ int ivf_set_pipeline_depth(ivf_index* index, int32_t depth);
 /* Blocks the host until every search enqueued by ivf_search_device has finished. */
 int ivf_synchronize(ivf_index* index);
 
+/*
+ * How a call with several queries is executed (Sec. 4.2 "Batching").
+ *   0  automatic: batches of 4 or more queries on a device-resident fp16 / bf16 inner-product
+ *      index with d a multiple of 16 are searched list-major (each selected cluster is read
+ *      once per group of up to 32 queries that probe it, scores by MFMA); anything else query
+ *      by query
+ *   1  always query by query
+ *   2  list-major whenever the index allows it (from 2 queries on)
+ * The results are the same in every mode (the MFMA scores only filter rows; the ranking uses
+ * fp64 re-scores with the fp32 query).  A list-major call synchronises compute_stream before
+ * it returns, also through ivf_search_device.  With bytes_gpu of ivf_search_stats a
+ * list-major call reports the bytes of the union of the selected clusters.
+ */
+int ivf_set_batch_mode(ivf_index* index, int32_t mode);
+
 /* Stage-level entry points, used by the parity tests. */
 /* coarse scores of App. B's first step: scores (host, nq x nlist fp64), raw metric values */
 int ivf_coarse_scores(ivf_index* index, const float* q, int32_t nq, double* scores);

@@ -24,7 +24,7 @@ EXPORTS = [
     "ivf_search", "ivf_search_device", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
-    "ivf_strerror", "ivf_last_error",
+    "ivf_set_batch_mode", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -82,6 +82,7 @@ def load():
     L.ivf_set_host_threads.argtypes = [vp, i32]
     L.ivf_set_pipeline_depth.argtypes = [vp, i32]
     L.ivf_synchronize.argtypes = [vp]
+    L.ivf_set_batch_mode.argtypes = [vp, i32]
     L.ivf_strerror.argtypes = [ci]
     L.ivf_strerror.restype = C.c_char_p
     L.ivf_last_error.restype = C.c_char_p
@@ -236,6 +237,9 @@ class Index:
 
     def ivf_synchronize(self):
         _check(load().ivf_synchronize(self._h))
+
+    def ivf_set_batch_mode(self, mode):
+        _check(load().ivf_set_batch_mode(self._h, mode))
 
 
 def ivf_build_layout(vectors, dtype, centroids, assign, ids=None, metric=IVF_IP,

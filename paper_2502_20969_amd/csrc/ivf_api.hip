@@ -83,6 +83,15 @@ struct Workspace {
     int32_t* h_cand_count = nullptr;
     double* h_scores = nullptr;   // only for ivf_coarse_scores (allocated on demand)
     size_t h_scores_len = 0;
+    // batched (list-major) search
+    int b_nq = 0, b_nprobe = 0;
+    void* d_q_store = nullptr;
+    float* d_thr = nullptr;
+    uint32_t *d_list_count = nullptr, *d_cursor = nullptr, *d_qstart = nullptr, *d_tstart = nullptr, *d_qidx = nullptr;
+    BatchTask* d_tasks = nullptr;
+    uint32_t *d_cand_count = nullptr, *d_cand_row = nullptr;
+    uint64_t* d_cand_key = nullptr;
+    int32_t *d_overflow = nullptr, *h_overflow = nullptr;
 };
 
 struct ProfSet { hipEvent_t e[8]; };   // begin/end of the coarse, select, scan and merge kernels
@@ -117,6 +126,9 @@ struct ivf_index {
 
     std::vector<uint64_t> rows_desc_prefix;   // prefix sums of list sizes, largest first
     int resident_grid[2] = {0, 0};            // scan workgroups resident at once, for kprime <= 64 / > 64
+    int batched_grid = 0;                     // resident workgroups of the batched scan kernel
+    int batch_mode = 0;                       // 0 auto, 1 always query by query, 2 list-major when eligible
+    unsigned int* d_row_norm_max = nullptr;   // largest squared row norm (float bits); device placement, 2-byte rows
     ScanShape shape{0, 0, 0, 4};
     // Searches through ivf_search_device rotate over `lanes` (stream + workspace each) so that
     // independent queries overlap; lane 0 runs on compute_stream.  cs / cw: lane in use.
@@ -144,6 +156,9 @@ void free_workspace(Workspace& w) {
     hipFree(w.d_out_ids); hipFree(w.d_out_dists);
     hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
     hipHostFree(w.h_cand); hipHostFree(w.h_cand_count); hipHostFree(w.h_scores);
+    hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
+    hipFree(w.d_tstart); hipFree(w.d_qidx); hipFree(w.d_tasks); hipFree(w.d_cand_count); hipFree(w.d_cand_row);
+    hipFree(w.d_cand_key); hipFree(w.d_overflow); hipHostFree(w.h_overflow);
     w = Workspace{};
 }
 
@@ -259,7 +274,7 @@ int prof_events(ivf_index* ix, int which, hipEvent_t* e0, hipEvent_t* e1) {
 // ---- kernel sequences ---------------------------------------------------------------------
 // coarse scoring + selection for nq queries already in d_q (device); leaves the probe lists
 // and slot tables in the workspace
-int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid) {
+int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid, bool count_rows = true) {
     Workspace& w = *ix->cw;
     int rc;
     hipEvent_t e0, e1;
@@ -273,7 +288,7 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
     sa.nlist = ix->nlist; sa.nprobe = nprobe; sa.nq = nq; sa.metric = ix->metric;
     sa.grid = grid;
     sa.desc = w.d_desc;
-    sa.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
+    sa.rows_counter = ix->profiling && count_rows ? ix->d_prof_rows : nullptr;
     HIP_TRY(launch_select(sa, ix->cs, e0, e1));
     return IVF_OK;
 }
@@ -309,6 +324,72 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     int rc = prof_events(ix, 3, &e0, &e1);
     if (rc) return rc;
     HIP_TRY(launch_merge(ma, ix->cs, e0, e1));
+    return IVF_OK;
+}
+
+// ---- batched (list-major) search ----------------------------------------------------------------
+constexpr int kCandCap = 16384;          // candidates a query may collect in the batched scan
+constexpr int kSampleRows = 2048;        // rows of the nearest cluster scored for the threshold
+
+bool batched_eligible(const ivf_index* ix, int nq) {
+    if (ix->batch_mode == 1 || nq < 2) return false;
+    if (ix->placement != IVF_PLACE_DEVICE || ix->metric != IVF_IP || ix->dtype == IVF_F32) return false;
+    if (ix->d % 16 != 0 || !ix->d_row_norm_max) return false;
+    return ix->batch_mode == 2 || nq >= 4;
+}
+
+int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
+    Workspace& w = *ix->cw;
+    if (nq <= w.b_nq && nprobe <= w.b_nprobe) return IVF_OK;
+    const int nq2 = std::max(nq, w.b_nq), np2 = std::max(nprobe, w.b_nprobe);
+    HIP_TRY(hipDeviceSynchronize());
+    hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
+    hipFree(w.d_tstart); hipFree(w.d_qidx); hipFree(w.d_tasks); hipFree(w.d_cand_count); hipFree(w.d_cand_row);
+    hipFree(w.d_cand_key); hipFree(w.d_overflow); hipHostFree(w.h_overflow);
+    w.d_q_store = nullptr; w.d_thr = nullptr; w.d_list_count = w.d_cursor = w.d_qstart = w.d_tstart = w.d_qidx = nullptr;
+    w.d_tasks = nullptr; w.d_cand_count = w.d_cand_row = nullptr; w.d_cand_key = nullptr; w.d_overflow = w.h_overflow = nullptr;
+    w.b_nq = w.b_nprobe = 0;
+    const size_t nqz = nq2, nl = ix->nlist;
+    const uint64_t task_cap = batched_task_bound(ix->h_off.data(), ix->nlist, nq2, np2);
+    HIP_TRY(hipMalloc(&w.d_q_store, nqz * ix->d * 2));
+    HIP_TRY(hipMalloc(&w.d_thr, nqz * sizeof(float)));
+    HIP_TRY(hipMalloc(&w.d_list_count, nl * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_cursor, nl * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_qstart, (nl + 1) * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_tstart, (nl + 1) * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_qidx, nqz * np2 * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_tasks, task_cap * sizeof(BatchTask)));
+    HIP_TRY(hipMalloc(&w.d_cand_count, nqz * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_cand_row, nqz * kCandCap * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_cand_key, nqz * kCandCap * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&w.d_overflow, nqz * sizeof(int32_t)));
+    HIP_TRY(hipHostMalloc(&w.h_overflow, nqz * sizeof(int32_t)));
+    w.b_nq = nq2; w.b_nprobe = np2;
+    return IVF_OK;
+}
+
+// coarse + select for the batch, then the list-major scan and the final ranking into (out_ids,
+// out_dists) (device pointers); the overflow flags land in the workspace
+int enqueue_batched(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int64_t* out_ids, float* out_dists) {
+    Workspace& w = *ix->cw;
+    int rc;
+    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe, 1, false))) return rc;
+    if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->d, ix->n_cu);
+    BatchedArgs b{};
+    b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.q = q_dev; b.probe = w.d_probe;
+    b.q_store = w.d_q_store; b.thr = w.d_thr; b.row_norm_max_bits = ix->d_row_norm_max;
+    b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
+    b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
+    b.cand_key = w.d_cand_key; b.overflow = w.d_overflow; b.out_ids = out_ids; b.out_dists = out_dists;
+    b.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
+    b.nlist = ix->nlist; b.d = ix->d; b.dtype = ix->dtype; b.nq = nq; b.nprobe = nprobe; b.k = k;
+    b.kprime = kprime_for(k); b.cand_cap = kCandCap; b.sample_rows = kSampleRows;
+    hipEvent_t e0, e1, m0, m1;
+    if ((rc = prof_events(ix, 2, &e0, &e1))) return rc;
+    if ((rc = prof_events(ix, 3, &m0, &m1))) return rc;
+    HIP_TRY(launch_batched(b, ix->batched_grid, ix->cs, e0, e1));
+    if (m0) { HIP_TRY(hipEventRecord(m0, ix->cs)); HIP_TRY(hipEventRecord(m1, ix->cs)); }
+    HIP_TRY(hipMemcpyAsync(w.h_overflow, w.d_overflow, (size_t)nq * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
     return IVF_OK;
 }
 
@@ -365,6 +446,13 @@ int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
         ix->pool.reset(new ThreadPool(nt));
     }
     HIP_TRY(hipMemcpy(ix->d_res_off, ix->h_res_off.data(), (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice));
+    if (ix->placement == IVF_PLACE_DEVICE && ix->dtype != IVF_F32) {
+        HIP_TRY(hipMalloc(&ix->d_row_norm_max, sizeof(unsigned int)));
+        HIP_TRY(hipMemset(ix->d_row_norm_max, 0, sizeof(unsigned int)));
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(launch_row_norm_max(ix->d_buf, ix->dtype, ix->n, ix->d, ix->d_row_norm_max, ix->compute));
+        HIP_TRY(hipStreamSynchronize(ix->compute));
+    }
     std::vector<uint64_t> sizes(nlist);
     for (int c = 0; c < nlist; ++c) sizes[c] = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]);
     std::sort(sizes.begin(), sizes.end(), std::greater<uint64_t>());
@@ -398,7 +486,7 @@ extern "C" void ivf_free(ivf_index* ix) {
     for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) hipStreamDestroy(l.stream); }
     for (auto& s : ix->prof_sets) for (auto& e : s.e) hipEventDestroy(e);
     hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_res_off);
-    hipFree(ix->d_prof_rows);
+    hipFree(ix->d_prof_rows); hipFree(ix->d_row_norm_max);
     if (ix->own_buf) hipFree(ix->d_buf);
     if (ix->own_h_lists) hipHostFree(ix->h_lists);
     hipHostFree(ix->h_res_stage);
@@ -551,6 +639,45 @@ extern "C" int ivf_synchronize(ivf_index* ix) {
 }
 
 // ---- search -------------------------------------------------------------------------------------
+// Device-pointer search of nq queries, query by query in one launch sequence (grid.y = nq).
+static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
+                             int64_t* ids_dev, float* dists_dev) {
+    int r;
+    if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
+    const int kprime = kprime_for(k);
+    const int grid = scan_grid_for(ix, nprobe, kprime);
+    if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid))) return r;
+    if ((r = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return r;
+    return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+}
+
+// List-major batched search into device outputs.  Synchronises the stream to read the overflow
+// flags; a query whose candidate list overflowed is searched again on its own.
+static int run_batched(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
+                       int64_t* ids_dev, float* dists_dev) {
+    int r;
+    if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
+    if ((r = ensure_batched_workspace(ix, nq, nprobe))) return r;
+    if ((r = enqueue_batched(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev))) return r;
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    Workspace& w = *ix->cw;
+    const bool was_profiling = ix->profiling;
+    ix->profiling = false;
+    for (int qi = 0; qi < nq && r == IVF_OK; ++qi)
+        if (w.h_overflow[qi])
+            r = enqueue_per_query(ix, q_dev + (size_t)qi * ix->d, 1, nprobe, k, ids_dev + (size_t)qi * k, dists_dev + (size_t)qi * k);
+    ix->profiling = was_profiling;
+    if (r == IVF_OK) HIP_TRY(hipStreamSynchronize(ix->cs));
+    return r;
+}
+
+extern "C" int ivf_set_batch_mode(ivf_index* ix, int32_t mode) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (mode < 0 || mode > 2) return fail(IVF_EINVAL, "batch mode must be 0, 1 or 2");
+    ix->batch_mode = mode;
+    return IVF_OK;
+}
+
 extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, int32_t nprobe,
                                  int32_t k, int64_t* ids_dev, float* dists_dev) {
     int rc = check_query_args(ix, q_dev, nq, nprobe);
@@ -563,16 +690,8 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     nprobe = std::min(nprobe, ix->nlist);
     use_lane(ix, ix->next_lane);
     ix->next_lane = (ix->next_lane + 1) % ix->lanes.size();
-    auto body = [&]() -> int {
-        int r;
-        if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
-        const int kprime = kprime_for(k);
-        const int grid = scan_grid_for(ix, nprobe, kprime);
-        if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid))) return r;
-        if ((r = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return r;
-        return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
-    };
-    rc = body();
+    if (batched_eligible(ix, nq)) rc = run_batched(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev);
+    else rc = enqueue_per_query(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev);
     use_lane(ix, 0);
     return rc;
 }
@@ -601,6 +720,24 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
 
     memcpy(w.h_q, q_out, (size_t)nq * ix->d * sizeof(float));
     HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    if (batched_eligible(ix, nq)) {
+        // list-major batched search: every selected cluster is read once per group of 32 queries
+        if ((rc = run_batched(ix, w.d_q, nq, nprobe, k, w.d_out_ids, w.d_out_dists))) return rc;
+        HIP_TRY(hipMemcpy(ids, w.d_out_ids, (size_t)nq * k * sizeof(int64_t), hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(dists, w.d_out_dists, (size_t)nq * k * sizeof(float), hipMemcpyDeviceToHost));
+        if (stats) {
+            HIP_TRY(hipMemcpy(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost));
+            std::vector<uint8_t> seen(ix->nlist, 0);
+            for (size_t i = 0; i < (size_t)nq * nprobe; ++i) {
+                int32_t c = w.h_probe[i];
+                if (!seen[c]) { seen[c] = 1; st.bytes_gpu += (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * ix->row_bytes; }
+            }
+            st.n_probed = nq * nprobe; st.n_overlap = nq * nprobe; st.hit_rate = 1.f;
+            st.ms_total = (float)(now_ms() - t0);
+            *stats = st;
+        }
+        return IVF_OK;
+    }
     if (hybrid && ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->cs, ix->ev_pf_done, 0));
     if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe, grid))) return rc;
     const bool want_probe = hybrid || stats;

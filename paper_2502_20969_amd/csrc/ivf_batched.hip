@@ -1,0 +1,433 @@
+// Batched list scan for query batches that share probed clusters (TeleRAG Sec. 4.2 "Batching":
+// the GPU part of the search becomes a matrix-matrix product).  Each selected list is read from
+// HBM once per group of up to 32 queries that probe it; scores come from MFMA
+// (v_mfma_f32_32x32x16 f16 / bf16, fp32 accumulate) and are only used to FILTER rows: a row whose
+// approximate score reaches the query's threshold becomes a candidate, and the final ranking is
+// done on fp64 re-scores with the fp32 query, exactly as in the single-query path.
+//
+// Threshold of a query: the exact k-th best score within its nearest cluster (a lower bound of
+// its k-th best score over all selected clusters), lowered by a bound on the MFMA score error
+// (query rounded to the storage type, fp32 accumulation): eps = 2^-10 (fp16) or 2^-7 (bf16)
+// times |q| times the largest row norm.  Every true top-k row passes this filter.
+#include "ivf_device.h"
+#include <hip/hip_ext.h>
+
+namespace ivf {
+using namespace dev;
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kTileRows = 128;     // rows per task: 4 wavefronts x 32 rows
+constexpr int kGroupQ = 32;        // queries per task: one MFMA tile wide
+constexpr int kQPad = 8;           // padding (elements) of a staged query row in LDS
+
+// ---- largest row norm of the lists (one-time, at build) -------------------------------------------
+__global__ void row_norm_max_kernel(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits) {
+    const int lane = threadIdx.x & 63;
+    int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    float best = 0.f;
+    for (int64_t r = wave; r < n; r += nwaves) {
+        float s = 0.f;
+        for (int t = lane; t < d; t += 64) {
+            float x = (float)widen(lists, dtype, (size_t)r * d + t);
+            s = fmaf(x, x, s);
+        }
+        s = group_sum<64>(s);
+        best = fmaxf(best, s);
+    }
+    if (lane == 0) atomicMax(out_bits, __float_as_uint(best));   // non-negative floats order as integers
+}
+
+hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 3) / 4;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(row_norm_max_kernel, dim3((unsigned)blocks), dim3(256), 0, s, lists, dtype, n, d, out_bits);
+    return hipGetLastError();
+}
+
+// ---- threshold sample --------------------------------------------------------------------------------------
+// One workgroup per query: fp32 scores (fp32 query) of the first sample_rows rows of the query's
+// nearest cluster, reduced to the k-th best.  Any subset of the selected rows gives a valid lower
+// bound of the k-th best score over all of them.
+template <typename T>
+__global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
+    extern __shared__ unsigned char smem[];
+    __shared__ float m_key[3 * kMaxKPrime];
+    __shared__ uint32_t m_row[3 * kMaxKPrime];
+    constexpr int EPL = T::kPerLoad;
+    const int qi = blockIdx.x, lane = lane_id(), wave = wave_id();
+    float* ql = (float*)smem;
+    for (int i = threadIdx.x; i < a.d; i += blockDim.x) ql[i] = a.q[(size_t)qi * a.d + i];
+    __syncthreads();
+    const int c = a.probe[(size_t)qi * a.nprobe];
+    const int64_t lo = a.off[c];
+    const uint32_t n = (uint32_t)min((int64_t)a.sample_rows, a.off[c + 1] - lo);
+    const int chunks = a.d / EPL;
+    const RowOrder order{nullptr};              // ties inside the sample do not matter for a bound
+    WaveTopK<2> top;
+    top.init();
+    for (uint32_t r = wave; r < n; r += 4) {
+        const unsigned char* rp = (const unsigned char*)a.lists + ((size_t)lo + r) * a.d * 2;
+        float s = 0.f;
+        for (int ch = lane; ch < chunks; ch += 64) {
+            uint4 v = *(const uint4*)(rp + (size_t)ch * 16);
+            float x[EPL];
+            Unpack<T>::run(v, x);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) s = fmaf(ql[ch * EPL + e], x[e], s);
+        }
+        s = group_total_last_lane<64>(s);
+        float ck = read_lane(s, 63);
+        if (ck >= top.thr) {
+            top.push(ck, r);
+            if (top.pcount == 64) top.flush(order, a.k);
+        }
+    }
+    top.flush(order, a.k);
+    if (wave > 0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            int e = j * 64 + lane;
+            if (e < a.k) { m_key[(wave - 1) * a.k + e] = top.top[j].k; m_row[(wave - 1) * a.k + e] = top.top[j].r; }
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        for (int w = 0; w < 3; ++w) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                int e = j * 64 + lane;
+                RowCand run = e < a.k ? RowCand{m_key[w * a.k + e], m_row[w * a.k + e]} : empty_row_cand();
+                if (read_lane(run.r, 0) != kNoRow) top.merge_run(run, order, a.k);
+            }
+        }
+        if (lane == 0) a.thr[qi] = top.thr;     // key of entry k-1; -inf when the sample has fewer than k rows
+    }
+}
+
+// ---- queries in the storage type, thresholds ---------------------------------------------------------
+__global__ void prep_queries_kernel(BatchedArgs a) {
+    const int qi = blockIdx.x, lane = threadIdx.x & 63;
+    const float* q = a.q + (size_t)qi * a.d;
+    float s = 0.f;
+    for (int t = threadIdx.x; t < a.d; t += 64) {
+        float x = q[t];
+        s = fmaf(x, x, s);
+        if (a.dtype == 1) ((_Float16*)a.q_store)[(size_t)qi * a.d + t] = (_Float16)x;
+        else ((__bf16*)a.q_store)[(size_t)qi * a.d + t] = (__bf16)x;
+    }
+    s = group_sum<64>(s);
+    if (lane == 0) {
+        // k-th best fp32 score of the sample, lowered by the error bounds of the MFMA score
+        // (query rounded to the storage type) and of the fp32 sample score
+        float kth = a.thr[qi];
+        float ymax = sqrtf(__uint_as_float(*a.row_norm_max_bits));
+        float eps = ((a.dtype == 1 ? 0x1p-10f : 0x1p-7f) + 0x1p-13f) * sqrtf(s) * ymax;
+        a.thr[qi] = kth - eps;            // -inf stays -inf
+        a.cand_count[qi] = 0;
+    }
+}
+
+// ---- cluster -> queries map and the task list ------------------------------------------------------------
+__global__ void zero_u32_kernel(uint32_t* p, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+__global__ void count_pairs_kernel(BatchedArgs a) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.nq * a.nprobe) atomicAdd(&a.list_count[a.probe[i]], 1u);
+}
+
+// one workgroup: prefix sums over all clusters of (queries per cluster) and (tasks per cluster)
+__global__ __launch_bounds__(1024) void scan_lists_kernel(BatchedArgs a) {
+    __shared__ uint32_t wsum_q[17], wsum_t[17];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t carry_q = 0, carry_t = 0;
+    for (int base = 0; base < a.nlist; base += 1024) {
+        int c = base + tid;
+        uint32_t cq = 0, ct = 0;
+        if (c < a.nlist) {
+            cq = a.list_count[c];
+            uint32_t n = (uint32_t)(a.off[c + 1] - a.off[c]);
+            ct = cq ? ((n + kTileRows - 1) / kTileRows) * ((cq + kGroupQ - 1) / kGroupQ) : 0;
+            a.cursor[c] = 0;
+        }
+        uint32_t iq = cq, it = ct;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t uq = __shfl_up(iq, o), ut = __shfl_up(it, o);
+            if (lane >= o) { iq += uq; it += ut; }
+        }
+        if (lane == 63) { wsum_q[wave] = iq; wsum_t[wave] = it; }
+        __syncthreads();
+        uint32_t oq = 0, ot = 0, tq = 0, tt = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) { oq += wsum_q[w]; ot += wsum_t[w]; }
+            tq += wsum_q[w]; tt += wsum_t[w];
+        }
+        if (c < a.nlist) { a.qstart[c] = carry_q + oq + iq - cq; a.tstart[c] = carry_t + ot + it - ct; }
+        carry_q += tq; carry_t += tt;
+        __syncthreads();
+    }
+    if (tid == 0) { a.qstart[a.nlist] = carry_q; a.tstart[a.nlist] = carry_t; }
+    // rows the scan covers once per cluster (for the roofline accounting)
+    if (a.rows_counter) {
+        unsigned long long rows = 0;
+        for (int c = tid; c < a.nlist; c += 1024) if (a.list_count[c]) rows += (unsigned long long)(a.off[c + 1] - a.off[c]);
+        for (int m = 32; m >= 1; m >>= 1) rows += __shfl_xor(rows, m);
+        if (lane == 0 && rows) atomicAdd(a.rows_counter, rows);
+    }
+}
+
+__global__ void fill_pairs_kernel(BatchedArgs a) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.nq * a.nprobe) return;
+    int c = a.probe[i];
+    uint32_t pos = atomicAdd(&a.cursor[c], 1u);
+    a.qidx[a.qstart[c] + pos] = (uint32_t)(i / a.nprobe);
+}
+
+// tasks of cluster c, ordered (query group, row tile) so that tiles of one group are consecutive
+__global__ void make_tasks_kernel(BatchedArgs a) {
+    for (int c = blockIdx.x; c < a.nlist; c += gridDim.x) {
+        const uint32_t t0 = a.tstart[c], t1 = a.tstart[c + 1];
+        if (t0 == t1) continue;
+        const uint32_t n = (uint32_t)(a.off[c + 1] - a.off[c]);
+        const uint32_t tiles = (n + kTileRows - 1) / kTileRows;
+        for (uint32_t i = threadIdx.x; i < t1 - t0; i += blockDim.x) {
+            BatchTask t;
+            t.cluster = (uint32_t)c;
+            t.group = i / tiles;
+            t.tile = i % tiles;
+            a.tasks[t0 + i] = t;
+        }
+    }
+}
+
+// ---- the MFMA scan -------------------------------------------------------------------------------------
+template <typename T> struct Mfma;
+template <> struct Mfma<F16> {
+    typedef half8_t frag;
+    __device__ static __forceinline__ float16_t run(frag a, frag b, float16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mfma<BF16> {
+    typedef bf16x8_t frag;
+    __device__ static __forceinline__ float16_t run(frag a, frag b, float16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+// One workgroup (4 wavefronts) per task: 128 rows of one cluster against up to 32 of the queries
+// that probe it.  The queries (storage type) are staged in LDS once per (cluster, group); each
+// wavefront streams its 32 rows from HBM straight into MFMA A fragments (lane l: row l % 32,
+// elements (l / 32) * 8 .. + 7 of each 16-element step) and reads the B fragments (lane l: query
+// l % 32, same elements) from LDS.  Scores that reach the query's threshold are appended to the
+// query's candidate list.
+template <typename T>
+__global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
+    typedef typename Mfma<T>::frag frag;
+    extern __shared__ unsigned char smem[];
+    __shared__ uint32_t s_q[kGroupQ];
+    __shared__ float s_thr[kGroupQ];
+    const int lane = lane_id(), wave = wave_id();
+    const int d = a.d, qstride = d + kQPad;
+    uint16_t* qs = (uint16_t*)smem;                      // [kGroupQ][d + kQPad] storage-type queries
+    const uint32_t total = a.tstart[a.nlist];
+    const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
+    const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    uint32_t staged_cluster = 0xFFFFFFFFu, staged_group = 0xFFFFFFFFu;
+    const int col = lane & 31, khalf = lane >> 5;
+    for (uint32_t t = t_begin; t < t_end; ++t) {
+        const BatchTask task = a.tasks[t];
+        const uint32_t c = task.cluster;
+        const uint32_t qbase = a.qstart[c] + task.group * kGroupQ;
+        const uint32_t nqg = min((uint32_t)kGroupQ, a.qstart[c + 1] - qbase);
+        if (c != staged_cluster || task.group != staged_group) {
+            __syncthreads();                              // everyone is done with the previous queries
+            if (threadIdx.x < kGroupQ) {
+                bool ok = threadIdx.x < nqg;
+                uint32_t qi = ok ? a.qidx[qbase + threadIdx.x] : 0;
+                s_q[threadIdx.x] = ok ? qi : 0xFFFFFFFFu;
+                s_thr[threadIdx.x] = ok ? a.thr[qi] : INFINITY;
+            }
+            __syncthreads();
+            const int chunks = d / 8;                     // 16-byte chunks per query row
+            for (int i = threadIdx.x; i < kGroupQ * chunks; i += blockDim.x) {
+                int qq = i / chunks, ch = i - qq * chunks;
+                uint32_t qi = s_q[qq];
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (qi != 0xFFFFFFFFu) v = *(const uint4*)((const uint16_t*)a.q_store + (size_t)qi * d + ch * 8);
+                *(uint4*)(qs + (size_t)qq * qstride + ch * 8) = v;
+            }
+            __syncthreads();
+            staged_cluster = c; staged_group = task.group;
+        }
+        const int64_t lo = a.off[c];
+        const uint32_t n = (uint32_t)(a.off[c + 1] - lo);
+        const uint32_t r0 = task.tile * kTileRows + wave * 32;     // first row of this wavefront
+        if (r0 >= n) continue;
+        const uint32_t my_row = min(r0 + (uint32_t)col, n - 1);    // rows past the end re-read the last one
+        const uint16_t* arow = (const uint16_t*)a.lists + ((size_t)lo + my_row) * d + khalf * 8;
+        const uint16_t* brow = qs + (size_t)col * qstride + khalf * 8;
+        float16_t acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int k0 = 0; k0 < d; k0 += 16 * 8) {
+            uint4 av[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                av[u] = k0 + u * 16 < d ? load_stream16(arow + k0 + u * 16) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (k0 + u * 16 < d) {
+                    uint4 bv = *(const uint4*)(brow + k0 + u * 16);
+                    acc = Mfma<T>::run(__builtin_bit_cast(frag, av[u]), __builtin_bit_cast(frag, bv), acc);
+                }
+            }
+        }
+        // lane holds query `col`, rows (i / 4) * 8 + khalf * 4 + i % 4
+        const float thr = s_thr[col];
+        const uint32_t qi = s_q[col];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t r = r0 + (i / 4) * 8 + khalf * 4 + (i % 4);
+            if (acc[i] >= thr && r < n) {
+                uint32_t pos = atomicAdd(&a.cand_count[qi], 1u);
+                if (pos < (uint32_t)a.cand_cap) a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r);
+            }
+        }
+    }
+}
+
+// ---- final ranking of a query's candidates ------------------------------------------------------------------
+// One workgroup per query: fp64 re-score of every candidate row (fp32 query), then the k best by
+// (score, id) through a radix select on the 64-bit keys and a rank-by-counting of the survivors.
+__global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedArgs a) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh[8];
+    __shared__ double f_key[2 * kMaxKPrime];
+    __shared__ int64_t f_id[2 * kMaxKPrime];
+    __shared__ unsigned long long best;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id();
+    const int qi = blockIdx.x, k = a.k;
+    const uint32_t raw = a.cand_count[qi];
+    if (raw > (uint32_t)a.cand_cap) {                  // too many candidates: the host redoes this query
+        if (tid == 0) a.overflow[qi] = 1;
+        return;
+    }
+    if (tid == 0) a.overflow[qi] = 0;
+    const uint32_t n = raw;
+    const uint32_t* rows = a.cand_row + (size_t)qi * a.cand_cap;
+    uint64_t* keys = a.cand_key + (size_t)qi * a.cand_cap;
+    const float* q = a.q + (size_t)qi * a.d;
+    const size_t row_bytes = (size_t)a.d * 2;
+    for (uint32_t c = wave; c < n; c += nt / 64) {
+        const unsigned char* rp = (const unsigned char*)a.lists + (size_t)rows[c] * row_bytes;
+        double s = a.dtype == 1 ? rescore_chunks<F16>(rp, q, a.d, 0) : rescore_chunks<BF16>(rp, q, a.d, 0);
+        if (lane == 0) keys[c] = ~ordered(s);           // ascending key = best first
+    }
+    __syncthreads();
+    const uint32_t want = min((uint32_t)k, n);
+    if (tid == 0) sh[4] = 0;
+    __syncthreads();
+    auto key_at = [&](uint32_t i) { return keys[i]; };
+    auto id_at = [&](uint32_t i) { return a.ids ? a.ids[rows[i]] : (int64_t)rows[i]; };
+    auto emit = [&](uint32_t i) {
+        uint32_t p = atomicAdd(&sh[4], 1u);
+        if (p < 2 * kMaxKPrime) { f_key[p] = unordered(~keys[i]); f_id[p] = id_at(i); }
+    };
+    if (want > 0) {
+        uint64_t mask, prefix; uint32_t need, group;
+        block_radix_select<uint64_t>(key_at, n, want, hist, sh, mask, prefix, need, group);
+        const bool take_group = need == group;
+        for (uint32_t i = tid; i < n; i += nt) {
+            uint64_t hi = keys[i] & mask;
+            if (hi < prefix || (take_group && hi == prefix)) emit(i);
+        }
+        __syncthreads();
+        if (!take_group) {
+            long long last = -1;
+            for (uint32_t it = 0; it < need; ++it) {
+                if (tid == 0) best = ~0ull;
+                __syncthreads();
+                for (uint32_t i = tid; i < n; i += nt)
+                    if ((keys[i] & mask) == prefix) { long long id = id_at(i); if (id > last) atomicMin(&best, (unsigned long long)id); }
+                __syncthreads();
+                unsigned long long b = best;
+                if (b == ~0ull) break;
+                last = (long long)b;
+                for (uint32_t i = tid; i < n; i += nt)
+                    if ((keys[i] & mask) == prefix && id_at(i) == last) emit(i);
+                __syncthreads();
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t tot = min(sh[4], (uint32_t)(2 * kMaxKPrime));
+    if ((uint32_t)tid < tot) {
+        double mk = f_key[tid]; int64_t mi = f_id[tid];
+        uint32_t rank = 0;
+        for (uint32_t j = 0; j < tot; ++j) {
+            double ok = f_key[j]; int64_t oi = f_id[j];
+            rank += (ok > mk) || (ok == mk && oi < mi);
+        }
+        if (rank < (uint32_t)k) {
+            a.out_ids[(size_t)qi * k + rank] = mi;
+            a.out_dists[(size_t)qi * k + rank] = (float)mk;
+        }
+    }
+    for (uint32_t i = tot + tid; i < (uint32_t)k; i += nt) {
+        a.out_ids[(size_t)qi * k + i] = -1;
+        a.out_dists[(size_t)qi * k + i] = -INFINITY;
+    }
+}
+
+// ---- launch sequence ---------------------------------------------------------------------------------------
+size_t batched_scan_lds(int d) { return (size_t)kGroupQ * (d + kQPad) * 2; }
+
+uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe) {
+    // a cluster has at most min(nq, ...) queries; every cluster may be probed
+    uint64_t tiles = 0;
+    for (int c = 0; c < nlist; ++c) tiles += (uint64_t)((off_host[c + 1] - off_host[c] + kTileRows - 1) / kTileRows);
+    uint64_t groups = (uint64_t)(nq + kGroupQ - 1) / kGroupQ;
+    // clusters with fewer than a full group of queries still cost one group each: bound by pairs too
+    uint64_t bound = tiles * groups;
+    (void)nprobe;
+    return bound + 1;
+}
+
+int batched_resident_grid(int dtype, int d, int n_cu) {
+    int per_cu = 0;
+    const void* fn = dtype == 1 ? (const void*)batched_scan_kernel<F16> : (const void*)batched_scan_kernel<BF16>;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, batched_scan_lds(d));
+    if (e != hipSuccess || per_cu < 1) per_cu = 1;
+    if (per_cu > 4) per_cu = 4;
+    return per_cu * n_cu;
+}
+
+hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start, hipEvent_t scan_stop) {
+    const int pairs = a.nq * a.nprobe;
+    if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq), dim3(256), (size_t)a.d * 4, s, a);
+    else hipLaunchKernelGGL(thr_sample_kernel<BF16>, dim3(a.nq), dim3(256), (size_t)a.d * 4, s, a);
+    hipLaunchKernelGGL(prep_queries_kernel, dim3(a.nq), dim3(64), 0, s, a);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3((a.nlist + 255) / 256), dim3(256), 0, s, a.list_count, a.nlist);
+    hipLaunchKernelGGL(count_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(scan_lists_kernel, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(fill_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(make_tasks_kernel, dim3(min(a.nlist, 4096)), dim3(256), 0, s, a);
+    if (a.dtype == 1)
+        hipExtLaunchKernelGGL(batched_scan_kernel<F16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, 0, a);
+    else
+        hipExtLaunchKernelGGL(batched_scan_kernel<BF16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, 0, a);
+    hipLaunchKernelGGL(batched_merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace ivf

@@ -7,6 +7,9 @@ namespace ivf {
 namespace dev {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() {
+    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform: kept in an SGPR
+}
 
 // Development aid (off in the product build): timestamps of kernel phases, 10 ns ticks.
 #ifdef IVF_TRACE
@@ -121,6 +124,39 @@ __device__ __forceinline__ double widen(const void* base, int dtype, size_t idx)
     return (double)__uint_as_float((uint32_t)b << 16);
 }
 
+// fp64 score of one stored row against q, by one wavefront; rows of whole 16-byte chunks are
+// read with up to four 16-byte loads per lane in flight.
+template <typename T>
+__device__ __forceinline__ double rescore_chunks(const unsigned char* row, const float* q, int d, int metric) {
+    constexpr int EPL = T::kPerLoad;
+    const int lane = lane_id();
+    const int chunks = d / EPL;
+    double acc = 0.0;
+    for (int c0 = lane; c0 < chunks; c0 += 256) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 64;
+            v[u] = c < chunks ? *(const uint4*)(row + (size_t)c * 16) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 64;
+            if (c < chunks) {
+                float x[EPL];
+                Unpack<T>::run(v[u], x);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    double qv = (double)q[c * EPL + e], y = (double)x[e];
+                    if (metric == 0) acc = fma(qv, y, acc);
+                    else { double df = qv - y; acc = fma(df, df, acc); }
+                }
+            }
+        }
+    }
+    return wave_sum(acc);
+}
+
 // ---- order-preserving integer keys ------------------------------------------------------------
 // Unsigned keys whose ascending order is the ascending order of the floating value.
 __device__ __forceinline__ uint32_t ordered(float f) {
@@ -130,6 +166,10 @@ __device__ __forceinline__ uint32_t ordered(float f) {
 __device__ __forceinline__ uint64_t ordered(double f) {
     uint64_t u = (uint64_t)__double_as_longlong(f);
     return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double unordered(uint64_t o) {       // inverse of ordered(double)
+    uint64_t u = (o >> 63) ? (o & 0x7FFFFFFFFFFFFFFFull) : ~o;
+    return __longlong_as_double((long long)u);
 }
 
 // ---- block-wide radix select -----------------------------------------------------------------

@@ -102,6 +102,39 @@ struct MergeArgs {
 };
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
+// ---- batched (list-major) search: ivf_batched.hip ------------------------------------------------
+struct BatchTask { uint32_t cluster, group, tile; };    // 128 rows of a cluster x up to 32 of its queries
+
+struct BatchedArgs {
+    const void* lists;           // device lists (device placement), fp16 or bf16
+    const int64_t* off;          // [nlist+1]
+    const int64_t* ids;          // [n] or nullptr
+    const float* q;              // [nq x d] fp32 queries
+    const int32_t* probe;        // [nq x nprobe] selected clusters
+    void* q_store;               // [nq x d] queries rounded to the storage type (out)
+    float* thr;                  // [nq] in: k-th best fp32 score of the sample; out: filter threshold
+    const unsigned int* row_norm_max_bits;   // largest squared row norm of the lists, as float bits
+    uint32_t* list_count;        // [nlist] queries probing each cluster
+    uint32_t* cursor;            // [nlist]
+    uint32_t* qstart;            // [nlist+1] prefix of list_count
+    uint32_t* tstart;            // [nlist+1] prefix of tasks per cluster
+    uint32_t* qidx;              // [nq x nprobe] queries grouped by cluster
+    BatchTask* tasks;            // [task capacity]
+    uint32_t* cand_count;        // [nq]
+    uint32_t* cand_row;          // [nq x cand_cap] global rows that passed the filter
+    uint64_t* cand_key;          // [nq x cand_cap] fp64 re-scores as ascending keys
+    int32_t* overflow;           // [nq] 1 when a query had more candidates than cand_cap
+    int64_t* out_ids; float* out_dists;      // [nq x k]
+    unsigned long long* rows_counter;        // nullable: rows covered by the scan tasks (profiling)
+    int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap, sample_rows;
+};
+// upper bound of the number of tasks for a batch of nq queries
+uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe);
+hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, hipStream_t s);
+hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start = nullptr,
+                          hipEvent_t scan_stop = nullptr);
+int batched_resident_grid(int dtype, int d, int n_cu);
+
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
 hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,
                                size_t row_bytes, hipStream_t s);

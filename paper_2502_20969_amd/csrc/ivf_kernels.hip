@@ -8,10 +8,6 @@
 namespace ivf {
 using namespace dev;
 
-__device__ __forceinline__ int wave_id() {
-    return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform: kept in an SGPR
-}
-
 // =============================================================================================
 // Coarse scoring (App. B, first step): scores[q][j] = d(x_q, c_j) for every centroid, in fp64.
 // One wavefront per centroid row; the queries are staged in LDS and widened on use.
@@ -806,39 +802,6 @@ __device__ __forceinline__ void gather_radix(const MergeArgs& a, const float* pk
         }
     }
     __syncthreads();
-}
-
-// fp64 score of one stored row against q, by one wavefront; rows of whole 16-byte chunks are
-// read with up to four 16-byte loads per lane in flight.
-template <typename T>
-__device__ __forceinline__ double rescore_chunks(const unsigned char* row, const float* q, int d, int metric) {
-    constexpr int EPL = T::kPerLoad;
-    const int lane = lane_id();
-    const int chunks = d / EPL;
-    double acc = 0.0;
-    for (int c0 = lane; c0 < chunks; c0 += 256) {
-        uint4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int c = c0 + u * 64;
-            v[u] = c < chunks ? *(const uint4*)(row + (size_t)c * 16) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int c = c0 + u * 64;
-            if (c < chunks) {
-                float x[EPL];
-                Unpack<T>::run(v[u], x);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    double qv = (double)q[c * EPL + e], y = (double)x[e];
-                    if (metric == 0) acc = fma(qv, y, acc);
-                    else { double df = qv - y; acc = fma(df, df, acc); }
-                }
-            }
-        }
-    }
-    return wave_sum(acc);
 }
 
 __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int fast) {

@@ -1,0 +1,83 @@
+"""GPU parity of the list-major batched search (Sec. 4.2 'Batching': the GPU part becomes a
+matrix-matrix product) against the oracle and against the query-by-query path."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2502_20969_amd as P
+import workloads as W
+from parity import check_topk
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def streams():
+    assert torch.cuda.is_available()
+    return torch.cuda.Stream(), torch.cuda.Stream()
+
+
+def _stored_numpy(ds):
+    if ds.dtype == "f16":
+        return ds.rows.cpu().numpy(), O.F16
+    return ds.rows.cpu().view(torch.int16).numpy().view(np.uint16), O.BF16
+
+
+@pytest.mark.parametrize("dtype,d,nq,k,nprobe", [
+    ("f16", 768, 32, 10, 24), ("bf16", 1024, 37, 10, 16), ("f16", 128, 5, 100, 40), ("bf16", 256, 64, 1, 7),
+])
+def test_list_major_equals_oracle_and_per_query(streams, dtype, d, nq, k, nprobe):
+    nlist = 96
+    sizes = W.zipf_sizes(60000 if d <= 256 else 30000, nlist, 1.1, 3)
+    sizes[5] += sizes[7]; sizes[7] = 0                  # an empty cluster
+    ds = W.cluster_major_datastore(sizes, d, 0.3, 4, dtype=dtype, device="cuda")
+    q = W.shared_batch_queries(ds, nq, max(2, nq // 8), 5).cpu().numpy()
+    lists, odt = _stored_numpy(ds)
+    off = ds.offsets.numpy()
+    cent = ds.centroids.cpu().numpy()
+    ids = (np.random.default_rng(1).permutation(ds.n) * 2 + 3).astype(np.int64)
+    index = P.ivf_adopt_layout(ds.rows, dtype, off, cent, ids=ids, metric=P.IVF_IP,
+                               compute_stream=streams[0], copy_stream=streams[1])
+    index.ivf_set_batch_mode(2)
+    bi, bd, st = index.ivf_search(q, nprobe, k, with_stats=True)
+    index.ivf_set_batch_mode(1)
+    pi, pd = index.ivf_search(q, nprobe, k)
+    assert np.array_equal(bi, pi) and np.array_equal(bd, pd)
+    exempt = 0
+    for b in range(nq):
+        exempt += check_topk(bi[b], bd[b], lists, odt, off, ids, cent, q[b], nprobe, k, O.IP)
+    assert exempt == 0
+    # bytes reported: the union of the selected clusters, each once
+    union = set()
+    for b in range(nq):
+        union |= set(O.probe(cent, q[b], nprobe, O.IP))
+    assert st.bytes_gpu == sum(int(off[c + 1] - off[c]) for c in union) * d * 2
+    # device-pointer entry point, automatic mode (nq >= 4 goes list-major)
+    index.ivf_set_batch_mode(0)
+    q_dev = torch.from_numpy(q).cuda()
+    ids_dev = torch.empty(nq, k, dtype=torch.int64, device="cuda")
+    d_dev = torch.empty(nq, k, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    index.ivf_search_device(q_dev, nprobe, k, ids_dev, d_dev)
+    index.ivf_synchronize()
+    assert np.array_equal(ids_dev.cpu().numpy(), pi) and np.array_equal(d_dev.cpu().numpy(), pd)
+    index.close()
+
+
+def test_candidate_overflow_falls_back(streams):
+    """Identical rows make every row a candidate: the per-query redo must give the oracle's answer."""
+    n, d, nlist = 40000, 64, 4
+    rows = torch.full((n, d), 0.125, dtype=torch.float16, device="cuda")
+    off = np.array([0, 10000, 20000, 30000, 40000], dtype=np.int64)
+    cent = np.eye(nlist, d, dtype=np.float32)
+    index = P.ivf_adopt_layout(rows, "f16", off, cent, metric=P.IVF_IP, compute_stream=streams[0], copy_stream=streams[1])
+    index.ivf_set_batch_mode(2)
+    q = np.abs(np.random.default_rng(2).standard_normal((4, d))).astype(np.float32)
+    gi, gd = index.ivf_search(q, 3, 5)
+    lists = rows.cpu().numpy()
+    for b in range(4):
+        oi, osc = O.search(lists, O.F16, off, None, cent, q[b], 3, 5, O.IP)
+        assert list(gi[b]) == list(oi)
+        np.testing.assert_allclose(gd[b], osc, rtol=2e-3)
+    index.close()

@@ -16,6 +16,7 @@ from .generators import (  # noqa: F401
     kmeans_datastore,
     mixture_rows,
     query_pairs,
+    shared_batch_queries,
     zipf_sizes,
     config1_tiny,
     config2_single_query,

@@ -174,3 +174,17 @@ def config2_single_query(seed=20970, device="cpu", n=1_000_000, d=768, nlist=102
                           dtype=dtype, device=device)
     q_in, q_out = query_pairs(ds.rows, nq, 0.3, seed + 2)
     return ds, q_in, q_out
+
+
+def shared_batch_queries(ds, nq, n_groups, seed, noise=0.5):
+    """nq unit-norm float32 queries drawn around `n_groups` of the datastore's mixture centres, so
+    that the queries of one group probe largely the same clusters (a batch that shares lists).
+    n_groups = nq gives queries from distinct components."""
+    device = ds.centres.device
+    g = _gen(seed, device)
+    d = ds.centres.shape[1]
+    pick = torch.randperm(ds.centres.shape[0], generator=g, device=device)[:n_groups]
+    which = torch.arange(nq, device=device) % n_groups
+    base = _normalize(ds.centres[pick][which])
+    q = _normalize(base + noise * (d ** -0.5) * torch.randn(nq, d, generator=g, device=device))
+    return q.contiguous()
