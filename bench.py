@@ -201,6 +201,99 @@ def run_lookahead(args):
     print(json.dumps(out))
 
 
+def run_batched(args):
+    """Benchmark configs[2] (c3: 10M x 768 fp16, nlist 4096 Zipf(1.1), nprobe 128, k 10, batch 32
+    sharing about 40 % of the probed clusters) and configs[4] (c5: 30M x 1024 bf16, nlist 8192
+    Zipf(1.2), nprobe 512, k 100, batch 256 from distinct components), all lists resident in HBM,
+    searched list-major.  A step is one whole batch.  One JSON line."""
+    import numpy as np
+    import torch
+    import paper_2502_20969_amd as P
+    import workloads as W
+    torch.cuda.set_device(0)
+    c3 = args.workload == "c3"
+    n = int((10_000_000 if c3 else 30_000_000) * args.scale)
+    d, nlist, nprobe, k, B = (768, 4096, 128, 10, 32) if c3 else (1024, 8192, 512, 100, 256)
+    dtype, zipf = ("f16", 1.1) if c3 else ("bf16", 1.2)
+    t0 = time.time()
+    sizes = W.zipf_sizes(n, nlist, zipf, 20975 if c3 else 20977)
+    ds = W.cluster_major_datastore(sizes, d, 0.3, 20976 if c3 else 20978, dtype=dtype, device="cuda", chunk=1 << 20)
+    torch.cuda.synchronize()
+    print(f"[{args.workload}] datastore of {n * d * 2 / 1e9:.1f} GB ready after {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    n_sets = 8                                            # distinct batches cycled through the timed steps
+    groups = args.groups if args.groups > 0 else (6 if c3 else B)
+    qs = [W.shared_batch_queries(ds, B, groups, 20980 + i) for i in range(n_sets)]
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    index = P.ivf_adopt_layout(ds.rows, dtype, ds.offsets, ds.centroids.cpu(), metric=P.IVF_IP,
+                               compute_stream=compute, copy_stream=copy)
+    index.ivf_set_batch_mode(2)
+    ids = torch.empty(B, k, dtype=torch.int64, device="cuda")
+    dists = torch.empty(B, k, dtype=torch.float32, device="cuda")
+    index.ivf_reserve(B, nprobe, k)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def run(nprobe_, steps, warmup):
+        for i in range(warmup):
+            index.ivf_search_device(qs[i % n_sets], nprobe_, k, ids, dists)
+        index.ivf_synchronize()
+        t = time.perf_counter()
+        for i in range(steps):
+            index.ivf_search_device(qs[(warmup + i) % n_sets], nprobe_, k, ids, dists)
+        index.ivf_synchronize()
+        dt = time.perf_counter() - t
+        index.ivf_profile_enable(True); index.ivf_profile_reset()
+        for i in range(min(steps, n_sets)):
+            index.ivf_search_device(qs[i % n_sets], nprobe_, k, ids, dists)
+        p = index.ivf_profile_read(); index.ivf_profile_enable(False)
+        calls = max(int(p.calls), 1)
+        us_scan = p.ms_scan / calls * 1e3
+        return {"nprobe": nprobe_, "qps": round(B * steps / dt, 1), "ms_per_batch": round(dt / steps * 1e3, 3),
+                "us_scan": round(us_scan, 1), "us_coarse": round(p.ms_coarse / calls * 1e3, 1),
+                "us_select": round(p.ms_select / calls * 1e3, 1),
+                "scan_gb": round(p.scan_bytes / calls / 1e9, 3),
+                "scan_gbs": round((p.scan_bytes / calls / 1e9) / (us_scan / 1e6), 1) if us_scan > 0 else 0.0}
+
+    head = run(nprobe, args.steps if args.steps != 4096 else 16, 2)
+    # measured sharing of the batch: 1 - |union of probed clusters| / (B * nprobe)
+    pr = index.ivf_probe(qs[0].cpu().numpy(), nprobe)
+    share = 1.0 - len(set(pr.reshape(-1).tolist())) / float(pr.size)
+    sweep = []
+    if not args.no_sweep:
+        for np_ in ((16, 32, 64, 128, 256) if c3 else (64, 128, 256, 512)):
+            sweep.append(run(np_, 8, 1))
+    parity = None
+    if not args.no_cpu:
+        import oracle as O
+        q0 = qs[0].cpu().numpy()
+        index.ivf_search_device(qs[0], nprobe, k, ids, dists)
+        index.ivf_synchronize()
+        gi, gd = ids.cpu().numpy(), dists.cpu().numpy()
+        rows_np = ds.rows.cpu().numpy() if c3 else ds.rows.cpu().view(torch.int16).numpy().view(np.uint16)
+        off_np, cent_np = ds.offsets.numpy(), ds.centroids.cpu().numpy()
+        bad, t1, done = 0, time.perf_counter(), 0
+        for b in range(0, B, max(1, B // 4)):               # 4 sampled queries of the batch
+            oi, osc = O.search(rows_np, O.F16 if c3 else O.BF16, off_np, None, cent_np, q0[b], nprobe, k, O.IP)
+            bad += int(not np.array_equal(gi[b], oi)) + int(not np.allclose(gd[b], osc, rtol=2e-3))
+            done += 1
+        parity = {"queries": done, "mismatches": bad}
+        cpu = {"value": round(done / (time.perf_counter() - t1), 3), "unit": "queries/s", "cores": O.threads(), "kind": "oracle",
+               "sample": f"{done} queries of one batch, nprobe {nprobe}, k {k}"}
+    out = {"metric": METRIC, "value": head["qps"], "unit": "queries/s", "n_gpus": 1,
+           "steps": args.steps if args.steps != 4096 else 16, "warmup": 2, "ms_per_step": head["ms_per_batch"],
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+           "config": {"workload": f"configs[{2 if c3 else 4}] batched retrieval: {n} x {d} {dtype}, nlist {nlist} Zipf({zipf}), "
+                                  f"nprobe {nprobe}, k {k}, batch {B} from {groups} mixture components, scale {args.scale}",
+                      "measured_share": round(share, 3), "entry_point": "ivf_search_device (list-major)"},
+           "roofline": {"bound": "hbm", "achieved": head["scan_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(head["scan_gbs"] / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "batched_scan_kernel",
+                        "us_per_launch": head["us_scan"], "bytes_per_launch": head["scan_gb"] * 1e9},
+           "head": head, "nprobe_sweep": sweep, "parity_sample": parity, "setup_s": round(setup_s, 1)}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -215,9 +308,11 @@ def main():
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic for scaling rocprofv3 counters)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--workload", default="c2", choices=["c2", "c4"],
-                    help="c2: single-query retrieval (the default bench line); c4: lookahead with host-resident lists")
-    ap.add_argument("--scale", type=float, default=1.0, help="c4: fraction of the 60M-row datastore to build")
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"],
+                    help="c2: single-query retrieval (the default bench line); c4: lookahead with host-resident lists; "
+                         "c3 / c5: batched retrieval over fp16 / bf16 lists")
+    ap.add_argument("--scale", type=float, default=1.0, help="c3, c4, c5: fraction of the named datastore to build")
+    ap.add_argument("--groups", type=int, default=0, help="c3, c5: mixture components the batch's queries are drawn around")
     ap.add_argument("--pairs", type=int, default=16, help="c4: (q_in, q_out) pairs per budget")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -229,6 +324,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     if args.workload == "c4":
         return run_lookahead(args)
+    if args.workload in ("c3", "c5"):
+        return run_batched(args)
     torch.cuda.set_device(0)
     index, stream, rows_host, assign_host, cent_host, q_in, q_out, info = build_config2("cuda", args.n)
     nq = q_out.shape[0]

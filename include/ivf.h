@@ -189,7 +189,7 @@ int ivf_synchronize(ivf_index* index);
 /*
  * How a call with several queries is executed (Sec. 4.2 "Batching").
  *   0  automatic: batches of 4 or more queries on a device-resident fp16 / bf16 inner-product
- *      index with d a multiple of 16 are searched list-major (each selected cluster is read
+ *      index with d a multiple of 64 are searched list-major (each selected cluster is read
  *      once per group of up to 32 queries that probe it, scores by MFMA); anything else query
  *      by query
  *   1  always query by query

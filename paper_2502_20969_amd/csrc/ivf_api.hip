@@ -334,7 +334,7 @@ constexpr int kSampleRows = 2048;        // rows of the nearest cluster scored f
 bool batched_eligible(const ivf_index* ix, int nq) {
     if (ix->batch_mode == 1 || nq < 2) return false;
     if (ix->placement != IVF_PLACE_DEVICE || ix->metric != IVF_IP || ix->dtype == IVF_F32) return false;
-    if (ix->d % 16 != 0 || !ix->d_row_norm_max) return false;
+    if (ix->d % 64 != 0 || !ix->d_row_norm_max) return false;   // the MFMA kernel walks 64-element blocks
     return ix->batch_mode == 2 || nq >= 4;
 }
 

@@ -226,9 +226,8 @@ template <> struct Mfma<BF16> {
 
 // One workgroup (4 wavefronts) per task: 128 rows of one cluster against up to 32 of the queries
 // that probe it.  The queries (storage type) are staged in LDS once per (cluster, group); each
-// wavefront streams its 32 rows from HBM straight into MFMA A fragments (lane l: row l % 32,
-// elements (l / 32) * 8 .. + 7 of each 16-element step) and reads the B fragments (lane l: query
-// l % 32, same elements) from LDS.  Scores that reach the query's threshold are appended to the
+// wavefront streams its 32 rows from HBM straight into MFMA A fragments (lane l: row l % 32, eight
+// elements per step) and reads the B fragments (lane l: query l % 32, the same elements) from LDS.  Scores that reach the query's threshold are appended to the
 // query's candidate list.
 template <typename T>
 __global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
@@ -274,23 +273,41 @@ __global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
         const uint32_t r0 = task.tile * kTileRows + wave * 32;     // first row of this wavefront
         if (r0 >= n) continue;
         const uint32_t my_row = min(r0 + (uint32_t)col, n - 1);    // rows past the end re-read the last one
-        const uint16_t* arow = (const uint16_t*)a.lists + ((size_t)lo + my_row) * d + khalf * 8;
-        const uint16_t* brow = qs + (size_t)col * qstride + khalf * 8;
+        // Element order inside the dot product is free, so MFMA step j of a 64-element block
+        // takes, for the lane half h, elements 32 h + 8 (j % 4) .. + 7 of the block: the four
+        // 16-byte loads a lane issues per block are consecutive (64 bytes), and the two lanes
+        // of a row cover one 128-byte line.
+        const uint16_t* arow = (const uint16_t*)a.lists + ((size_t)lo + my_row) * d + khalf * 32;
+        const uint16_t* brow = qs + (size_t)col * qstride + khalf * 32;
         float16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-        for (int k0 = 0; k0 < d; k0 += 16 * 8) {
-            uint4 av[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                av[u] = k0 + u * 16 < d ? load_stream16(arow + k0 + u * 16) : make_uint4(0, 0, 0, 0);
+        // two blocks (128 elements, 8 MFMA steps) per iteration, the next iteration's rows in flight
+        uint4 av[2][8];
+        auto issue = [&](int k0, uint4 (&v)[8]) {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                if (k0 + u * 16 < d) {
-                    uint4 bv = *(const uint4*)(brow + k0 + u * 16);
-                    acc = Mfma<T>::run(__builtin_bit_cast(frag, av[u]), __builtin_bit_cast(frag, bv), acc);
+                const int k = k0 + (u / 4) * 64 + (u % 4) * 8;
+                v[u] = k < d ? *(const uint4*)(arow + k) : make_uint4(0, 0, 0, 0);
+            }
+        };
+        auto consume = [&](int k0, const uint4 (&v)[8]) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + (u / 4) * 64 + (u % 4) * 8;
+                if (k < d) {
+                    uint4 bv = *(const uint4*)(brow + k);
+                    acc = Mfma<T>::run(__builtin_bit_cast(frag, v[u]), __builtin_bit_cast(frag, bv), acc);
                 }
             }
+        };
+        issue(0, av[0]);
+        for (int k0 = 0; k0 < d; k0 += 256) {
+            if (k0 + 128 < d) issue(k0 + 128, av[1]);
+            consume(k0, av[0]);
+            if (k0 + 128 >= d) break;
+            if (k0 + 256 < d) issue(k0 + 256, av[0]);
+            consume(k0 + 128, av[1]);
         }
         // lane holds query `col`, rows (i / 4) * 8 + khalf * 4 + i % 4
         const float thr = s_thr[col];
