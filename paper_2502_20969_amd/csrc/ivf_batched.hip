@@ -50,42 +50,55 @@ hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, u
 }
 
 // ---- threshold sample --------------------------------------------------------------------------------------
-// One workgroup per query: fp32 scores (fp32 query) of the first sample_rows rows of the query's
-// nearest cluster, reduced to the k-th best.  Any subset of the selected rows gives a valid lower
-// bound of the k-th best score over all of them.
+// fp32 scores (fp32 query) of the first rows of each query's nearest cluster, reduced to the
+// k-th best.  Any subset of the selected rows gives a valid lower bound of the k-th best score
+// over all of them.  The sample of a query is split over kSampleParts workgroups of 128 rows;
+// each writes its k best keys, and prep_queries_kernel merges the parts.
+constexpr int kSampleParts = 16;
+constexpr int kSamplePartRows = 128;
+
 template <typename T>
 __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
     extern __shared__ unsigned char smem[];
     __shared__ float m_key[3 * kMaxKPrime];
     __shared__ uint32_t m_row[3 * kMaxKPrime];
     constexpr int EPL = T::kPerLoad;
-    const int qi = blockIdx.x, lane = lane_id(), wave = wave_id();
+    const int qi = blockIdx.x, part = blockIdx.y, lane = lane_id(), wave = wave_id();
     float* ql = (float*)smem;
     for (int i = threadIdx.x; i < a.d; i += blockDim.x) ql[i] = a.q[(size_t)qi * a.d + i];
     __syncthreads();
     const int c = a.probe[(size_t)qi * a.nprobe];
     const int64_t lo = a.off[c];
-    const uint32_t n = (uint32_t)min((int64_t)a.sample_rows, a.off[c + 1] - lo);
+    const uint32_t n = (uint32_t)min((int64_t)(kSampleParts * kSamplePartRows), a.off[c + 1] - lo);
+    const uint32_t r_begin = part * kSamplePartRows + wave * 32;
+    const uint32_t r_end = min(n, r_begin + 32);
     const int chunks = a.d / EPL;
     const RowOrder order{nullptr};              // ties inside the sample do not matter for a bound
     WaveTopK<2> top;
     top.init();
-    for (uint32_t r = wave; r < n; r += 4) {
-        const unsigned char* rp = (const unsigned char*)a.lists + ((size_t)lo + r) * a.d * 2;
-        float s = 0.f;
+    for (uint32_t r0 = r_begin; r0 < r_end; r0 += 4) {
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
         for (int ch = lane; ch < chunks; ch += 64) {
-            uint4 v = *(const uint4*)(rp + (size_t)ch * 16);
-            float x[EPL];
-            Unpack<T>::run(v, x);
+            uint4 v[4];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) s = fmaf(ql[ch * EPL + e], x[e], s);
+            for (int u = 0; u < 4; ++u) {
+                uint32_t r = min(r0 + u, r_end - 1);
+                v[u] = *(const uint4*)((const unsigned char*)a.lists + ((size_t)lo + r) * a.d * 2 + (size_t)ch * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float x[EPL];
+                Unpack<T>::run(v[u], x);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) s[u] = fmaf(ql[ch * EPL + e], x[e], s[u]);
+            }
         }
-        s = group_total_last_lane<64>(s);
-        float ck = read_lane(s, 63);
-        if (ck >= top.thr) {
-            top.push(ck, r);
-            if (top.pcount == 64) top.flush(order, a.k);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float ck = read_lane(group_total_last_lane<64>(s[u]), 63);
+            if (r0 + u < r_end && ck >= top.thr) top.push(ck, r0 + u);
         }
+        if (top.pcount > 60) top.flush(order, a.k);
     }
     top.flush(order, a.k);
     if (wave > 0) {
@@ -105,7 +118,12 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
                 if (read_lane(run.r, 0) != kNoRow) top.merge_run(run, order, a.k);
             }
         }
-        if (lane == 0) a.thr[qi] = top.thr;     // key of entry k-1; -inf when the sample has fewer than k rows
+        float* out = a.thr_part + ((size_t)qi * kSampleParts + part) * kMaxKPrime;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            int e = j * 64 + lane;
+            if (e < a.k) out[e] = top.top[j].r == kNoRow ? -INFINITY : top.top[j].k;
+        }
     }
 }
 
@@ -121,13 +139,26 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
         else ((__bf16*)a.q_store)[(size_t)qi * a.d + t] = (__bf16)x;
     }
     s = group_sum<64>(s);
+    // k-th best key over the sample parts
+    const RowOrder order{nullptr};
+    WaveTopK<2> top;
+    top.init();
+    for (int part = 0; part < kSampleParts; ++part) {
+        const float* in = a.thr_part + ((size_t)qi * kSampleParts + part) * kMaxKPrime;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            int e = j * 64 + lane;
+            float key = e < a.k ? in[e] : -INFINITY;
+            RowCand run{key, key == -INFINITY ? kNoRow : (uint32_t)(part * kMaxKPrime + e)};
+            if (read_lane(run.r, 0) != kNoRow && read_lane(run.k, 0) >= top.thr) top.merge_run(run, order, a.k);
+        }
+    }
     if (lane == 0) {
-        // k-th best fp32 score of the sample, lowered by the error bounds of the MFMA score
-        // (query rounded to the storage type) and of the fp32 sample score
-        float kth = a.thr[qi];
+        // lowered by the error bounds of the MFMA score (query rounded to the storage type) and
+        // of the fp32 sample score
         float ymax = sqrtf(__uint_as_float(*a.row_norm_max_bits));
         float eps = ((a.dtype == 1 ? 0x1p-10f : 0x1p-7f) + 0x1p-13f) * sqrtf(s) * ymax;
-        a.thr[qi] = kth - eps;            // -inf stays -inf
+        a.thr[qi] = top.thr - eps;        // -inf (fewer than k sampled rows) stays -inf
         a.cand_count[qi] = 0;
     }
 }
@@ -420,6 +451,8 @@ uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int npro
     return bound + 1;
 }
 
+size_t batched_thr_part_floats(int nq) { return (size_t)nq * kSampleParts * kMaxKPrime; }
+
 int batched_resident_grid(int dtype, int d, int n_cu) {
     int per_cu = 0;
     const void* fn = dtype == 1 ? (const void*)batched_scan_kernel<F16> : (const void*)batched_scan_kernel<BF16>;
@@ -431,8 +464,8 @@ int batched_resident_grid(int dtype, int d, int n_cu) {
 
 hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start, hipEvent_t scan_stop) {
     const int pairs = a.nq * a.nprobe;
-    if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq), dim3(256), (size_t)a.d * 4, s, a);
-    else hipLaunchKernelGGL(thr_sample_kernel<BF16>, dim3(a.nq), dim3(256), (size_t)a.d * 4, s, a);
+    if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
+    else hipLaunchKernelGGL(thr_sample_kernel<BF16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
     hipLaunchKernelGGL(prep_queries_kernel, dim3(a.nq), dim3(64), 0, s, a);
     hipLaunchKernelGGL(zero_u32_kernel, dim3((a.nlist + 255) / 256), dim3(256), 0, s, a.list_count, a.nlist);
     hipLaunchKernelGGL(count_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);

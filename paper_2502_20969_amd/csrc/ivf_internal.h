@@ -112,7 +112,8 @@ struct BatchedArgs {
     const float* q;              // [nq x d] fp32 queries
     const int32_t* probe;        // [nq x nprobe] selected clusters
     void* q_store;               // [nq x d] queries rounded to the storage type (out)
-    float* thr;                  // [nq] in: k-th best fp32 score of the sample; out: filter threshold
+    float* thr;                  // [nq] out: filter threshold
+    float* thr_part;             // [batched_thr_part_floats(nq)] best sample keys per (query, part)
     const unsigned int* row_norm_max_bits;   // largest squared row norm of the lists, as float bits
     uint32_t* list_count;        // [nlist] queries probing each cluster
     uint32_t* cursor;            // [nlist]
@@ -126,7 +127,7 @@ struct BatchedArgs {
     int32_t* overflow;           // [nq] 1 when a query had more candidates than cand_cap
     int64_t* out_ids; float* out_dists;      // [nq x k]
     unsigned long long* rows_counter;        // nullable: rows covered by the scan tasks (profiling)
-    int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap, sample_rows;
+    int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap;
 };
 // upper bound of the number of tasks for a batch of nq queries
 uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe);
@@ -134,6 +135,7 @@ hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, u
 hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start = nullptr,
                           hipEvent_t scan_stop = nullptr);
 int batched_resident_grid(int dtype, int d, int n_cu);
+size_t batched_thr_part_floats(int nq);
 
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
 hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,
