@@ -53,9 +53,19 @@ def time_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, k, steps, warmu
     return time.perf_counter() - t0
 
 
+NO_EVENTS = False
+
+
 def profile_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, k, steps):
-    """Same loop with HIP events around every kernel on the compute stream."""
+    """Same loop with HIP events attached to every kernel launch on the compute stream."""
     nq = q_dev.shape[0]
+    if NO_EVENTS:
+        for i in range(steps):
+            j = i % nq
+            index.ivf_search_device(q_dev[j], nprobe, k, ids_dev[j], dists_dev[j])
+        index.ivf_synchronize()
+        return {"calls": 0, "us_coarse": 0.0, "us_select": 0.0, "us_scan": 0.0, "us_merge": 0.0,
+                "scan_bytes_per_call": 0.0, "scan_gbs": 0.0}
     index.ivf_profile_enable(True)
     index.ivf_profile_reset()
     for i in range(steps):
@@ -242,7 +252,8 @@ def run_batched(args):
             index.ivf_search_device(qs[(warmup + i) % n_sets], nprobe_, k, ids, dists)
         index.ivf_synchronize()
         dt = time.perf_counter() - t
-        index.ivf_profile_enable(True); index.ivf_profile_reset()
+        if not NO_EVENTS:
+            index.ivf_profile_enable(True); index.ivf_profile_reset()
         for i in range(min(steps, n_sets)):
             index.ivf_search_device(qs[i % n_sets], nprobe_, k, ids, dists)
         p = index.ivf_profile_read(); index.ivf_profile_enable(False)
@@ -306,6 +317,8 @@ def main():
                     help="independent searches kept in flight (ivf_set_pipeline_depth); 1 = strictly one after another")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic for scaling rocprofv3 counters)")
+    ap.add_argument("--no-events", action="store_true",
+                    help="skip the passes that time kernels with HIP events (for runs under rocprofv3 --pmc)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"],
@@ -315,6 +328,8 @@ def main():
     ap.add_argument("--groups", type=int, default=0, help="c3, c5: mixture components the batch's queries are drawn around")
     ap.add_argument("--pairs", type=int, default=16, help="c4: (q_in, q_out) pairs per budget")
     args = ap.parse_args()
+    global NO_EVENTS
+    NO_EVENTS = args.no_events
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)

@@ -88,6 +88,8 @@ struct Workspace {
     void* d_q_store = nullptr;
     float* d_thr = nullptr;
     float* d_thr_part = nullptr;
+    float *d_cand_score = nullptr, *d_eps = nullptr;
+    uint32_t* d_surv_row = nullptr;
     uint32_t *d_list_count = nullptr, *d_cursor = nullptr, *d_qstart = nullptr, *d_tstart = nullptr, *d_qidx = nullptr;
     BatchTask* d_tasks = nullptr;
     uint32_t *d_cand_count = nullptr, *d_cand_row = nullptr;
@@ -157,7 +159,7 @@ void free_workspace(Workspace& w) {
     hipFree(w.d_out_ids); hipFree(w.d_out_dists);
     hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
     hipHostFree(w.h_cand); hipHostFree(w.h_cand_count); hipHostFree(w.h_scores);
-    hipFree(w.d_thr_part);
+    hipFree(w.d_thr_part); hipFree(w.d_cand_score); hipFree(w.d_eps); hipFree(w.d_surv_row);
     hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
     hipFree(w.d_tstart); hipFree(w.d_qidx); hipFree(w.d_tasks); hipFree(w.d_cand_count); hipFree(w.d_cand_row);
     hipFree(w.d_cand_key); hipFree(w.d_overflow); hipHostFree(w.h_overflow);
@@ -330,7 +332,8 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
 }
 
 // ---- batched (list-major) search ----------------------------------------------------------------
-constexpr int kCandCap = 16384;          // candidates a query may collect in the batched scan
+constexpr int kCandCap = 65536;          // candidates a query may collect in the batched scan
+constexpr int kSurvCap = 4096;           // of those, rows re-scored in fp64
 
 bool batched_eligible(const ivf_index* ix, int nq) {
     if (ix->batch_mode == 1 || nq < 2) return false;
@@ -344,11 +347,11 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
     if (nq <= w.b_nq && nprobe <= w.b_nprobe) return IVF_OK;
     const int nq2 = std::max(nq, w.b_nq), np2 = std::max(nprobe, w.b_nprobe);
     HIP_TRY(hipDeviceSynchronize());
-    hipFree(w.d_thr_part);
+    hipFree(w.d_thr_part); hipFree(w.d_cand_score); hipFree(w.d_eps); hipFree(w.d_surv_row);
     hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
     hipFree(w.d_tstart); hipFree(w.d_qidx); hipFree(w.d_tasks); hipFree(w.d_cand_count); hipFree(w.d_cand_row);
     hipFree(w.d_cand_key); hipFree(w.d_overflow); hipHostFree(w.h_overflow);
-    w.d_thr_part = nullptr;
+    w.d_thr_part = nullptr; w.d_cand_score = nullptr; w.d_eps = nullptr; w.d_surv_row = nullptr;
     w.d_q_store = nullptr; w.d_thr = nullptr; w.d_list_count = w.d_cursor = w.d_qstart = w.d_tstart = w.d_qidx = nullptr;
     w.d_tasks = nullptr; w.d_cand_count = w.d_cand_row = nullptr; w.d_cand_key = nullptr; w.d_overflow = w.h_overflow = nullptr;
     w.b_nq = w.b_nprobe = 0;
@@ -365,7 +368,10 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
     HIP_TRY(hipMalloc(&w.d_tasks, task_cap * sizeof(BatchTask)));
     HIP_TRY(hipMalloc(&w.d_cand_count, nqz * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&w.d_cand_row, nqz * kCandCap * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&w.d_cand_key, nqz * kCandCap * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&w.d_cand_score, nqz * kCandCap * sizeof(float)));
+    HIP_TRY(hipMalloc(&w.d_eps, nqz * sizeof(float)));
+    HIP_TRY(hipMalloc(&w.d_surv_row, nqz * kSurvCap * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_cand_key, nqz * kSurvCap * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&w.d_overflow, nqz * sizeof(int32_t)));
     HIP_TRY(hipHostMalloc(&w.h_overflow, nqz * sizeof(int32_t)));
     w.b_nq = nq2; w.b_nprobe = np2;
@@ -384,10 +390,10 @@ int enqueue_batched(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k
     b.q_store = w.d_q_store; b.thr = w.d_thr; b.thr_part = w.d_thr_part; b.row_norm_max_bits = ix->d_row_norm_max;
     b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
     b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
-    b.cand_key = w.d_cand_key; b.overflow = w.d_overflow; b.out_ids = out_ids; b.out_dists = out_dists;
+    b.cand_key = w.d_cand_key; b.cand_score = w.d_cand_score; b.eps = w.d_eps; b.surv_row = w.d_surv_row; b.overflow = w.d_overflow; b.out_ids = out_ids; b.out_dists = out_dists;
     b.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
     b.nlist = ix->nlist; b.d = ix->d; b.dtype = ix->dtype; b.nq = nq; b.nprobe = nprobe; b.k = k;
-    b.kprime = kprime_for(k); b.cand_cap = kCandCap;
+    b.kprime = kprime_for(k); b.cand_cap = kCandCap; b.surv_cap = kSurvCap;
     hipEvent_t e0, e1, m0, m1;
     if ((rc = prof_events(ix, 2, &e0, &e1))) return rc;
     if ((rc = prof_events(ix, 3, &m0, &m1))) return rc;

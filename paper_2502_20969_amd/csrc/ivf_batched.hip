@@ -5,10 +5,10 @@
 // approximate score reaches the query's threshold becomes a candidate, and the final ranking is
 // done on fp64 re-scores with the fp32 query, exactly as in the single-query path.
 //
-// Threshold of a query: the exact k-th best score within its nearest cluster (a lower bound of
-// its k-th best score over all selected clusters), lowered by a bound on the MFMA score error
-// (query rounded to the storage type, fp32 accumulation): eps = 2^-10 (fp16) or 2^-7 (bf16)
-// times |q| times the largest row norm.  Every true top-k row passes this filter.
+// Threshold of a query: the k-th best fp32 score over a sample of its nearest cluster (a lower
+// bound of its k-th best score over all selected clusters), lowered by a bound eps on the MFMA
+// score error (query rounded to the storage type, fp32 accumulation).  Every true top-k row
+// passes this filter.
 #include "ivf_device.h"
 #include <hip/hip_ext.h>
 
@@ -131,14 +131,16 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
 __global__ void prep_queries_kernel(BatchedArgs a) {
     const int qi = blockIdx.x, lane = threadIdx.x & 63;
     const float* q = a.q + (size_t)qi * a.d;
-    float s = 0.f;
+    float s = 0.f, res = 0.f;          // |q~|^2 of the rounded query and |q~ - q|^2 of the rounding
     for (int t = threadIdx.x; t < a.d; t += 64) {
-        float x = q[t];
-        s = fmaf(x, x, s);
-        if (a.dtype == 1) ((_Float16*)a.q_store)[(size_t)qi * a.d + t] = (_Float16)x;
-        else ((__bf16*)a.q_store)[(size_t)qi * a.d + t] = (__bf16)x;
+        float x = q[t], xr;
+        if (a.dtype == 1) { _Float16 h = (_Float16)x; ((_Float16*)a.q_store)[(size_t)qi * a.d + t] = h; xr = (float)h; }
+        else { __bf16 h = (__bf16)x; ((__bf16*)a.q_store)[(size_t)qi * a.d + t] = h; xr = (float)h; }
+        s = fmaf(xr, xr, s);
+        res = fmaf(xr - x, xr - x, res);
     }
     s = group_sum<64>(s);
+    res = group_sum<64>(res);
     // k-th best key over the sample parts
     const RowOrder order{nullptr};
     WaveTopK<2> top;
@@ -154,11 +156,14 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
         }
     }
     if (lane == 0) {
-        // lowered by the error bounds of the MFMA score (query rounded to the storage type) and
-        // of the fp32 sample score
+        // Bound of |MFMA score - exact score| for any row y: the query rounding contributes
+        // |<q~ - q, y>| <= |q~ - q| |y| (Cauchy-Schwarz, with the residual norm measured above),
+        // fp32 accumulation of d products at most d 2^-23 |q~| |y|; the fp32 sample score is
+        // covered by the same accumulation term.  A little slack absorbs the norms' own rounding.
         float ymax = sqrtf(__uint_as_float(*a.row_norm_max_bits));
-        float eps = ((a.dtype == 1 ? 0x1p-10f : 0x1p-7f) + 0x1p-13f) * sqrtf(s) * ymax;
+        float eps = 1.01f * (sqrtf(res) + (float)a.d * 0x1p-22f * sqrtf(s)) * ymax;
         a.thr[qi] = top.thr - eps;        // -inf (fewer than k sampled rows) stays -inf
+        a.eps[qi] = eps;
         a.cand_count[qi] = 0;
     }
 }
@@ -348,15 +353,19 @@ __global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
             const uint32_t r = r0 + (i / 4) * 8 + khalf * 4 + (i % 4);
             if (acc[i] >= thr && r < n) {
                 uint32_t pos = atomicAdd(&a.cand_count[qi], 1u);
-                if (pos < (uint32_t)a.cand_cap) a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r);
+                if (pos < (uint32_t)a.cand_cap) {
+                    a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r);
+                    a.cand_score[(size_t)qi * a.cand_cap + pos] = acc[i];
+                }
             }
         }
     }
 }
 
 // ---- final ranking of a query's candidates ------------------------------------------------------------------
-// One workgroup per query: fp64 re-score of every candidate row (fp32 query), then the k best by
-// (score, id) through a radix select on the 64-bit keys and a rank-by-counting of the survivors.
+// One workgroup per query: candidates are first pruned by their approximate scores, the survivors
+// are re-scored in fp64 (fp32 query), and the k best by (score, id) come from a radix select on
+// the 64-bit keys and a rank-by-counting.
 __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedArgs a) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh[8];
@@ -370,10 +379,53 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
         if (tid == 0) a.overflow[qi] = 1;
         return;
     }
+    // 1. prune by the approximate scores: with t = the k-th best approximate score, a row of the
+    //    true top k has an approximate score of at least t - 2 eps (each score is within eps of
+    //    the exact one), so only those rows are re-scored.
+    const uint32_t n0 = raw;
+    const float* sc = a.cand_score + (size_t)qi * a.cand_cap;
+    const uint32_t* rows0 = a.cand_row + (size_t)qi * a.cand_cap;
+    uint32_t* rows = a.surv_row + (size_t)qi * a.surv_cap;
+    auto skey = [&](uint32_t i) { return ~ordered(sc[i]); };      // ascending key = best first
+    if (tid == 0) { sh[4] = 0; sh[5] = 0; sh[6] = 0; }
+    __syncthreads();
+    float cut = -INFINITY;
+    if (n0 > (uint32_t)k) {
+        uint32_t mask, prefix, need, group;
+        block_radix_select<uint32_t>(skey, n0, (uint32_t)k, hist, sh, mask, prefix, need, group);
+        // key of the k-th best: the largest kept key
+        uint32_t worst = 0;
+        for (uint32_t i = tid; i < n0; i += nt) {
+            uint32_t ky = skey(i), hi = ky & mask;
+            if (hi < prefix || hi == prefix) worst = max(worst, (need == group || hi < prefix) ? ky : prefix);
+        }
+#pragma unroll
+        for (int m2 = 32; m2 >= 1; m2 >>= 1) worst = max(worst, (uint32_t)__shfl_xor((int)worst, m2));
+        if (lane == 0) atomicMax(&sh[6], worst);
+        __syncthreads();
+        const uint32_t o = ~sh[6];                        // ordered(float) of the k-th best approximate score
+        const float kth = __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+        cut = kth - 2.f * a.eps[qi];
+    }
+    for (uint32_t i0 = 0; i0 < n0; i0 += nt) {
+        uint32_t i = i0 + tid;
+        bool ok = i < n0 && sc[i] >= cut;
+        uint64_t bal = __ballot(ok);
+        uint32_t base = 0;
+        if (lane == 0 && bal) base = atomicAdd(&sh[5], (uint32_t)__popcll(bal));
+        base = read_lane(base, 0);
+        uint32_t p = base + __popcll(bal & ((1ull << lane) - 1ull));
+        if (ok && p < (uint32_t)a.surv_cap) rows[p] = rows0[i];
+    }
+    __syncthreads();
+    const uint32_t n = sh[5];
+    if (n > (uint32_t)a.surv_cap) {                    // cannot happen unless scores are massively tied
+        if (tid == 0) a.overflow[qi] = 1;
+        return;
+    }
     if (tid == 0) a.overflow[qi] = 0;
-    const uint32_t n = raw;
-    const uint32_t* rows = a.cand_row + (size_t)qi * a.cand_cap;
-    uint64_t* keys = a.cand_key + (size_t)qi * a.cand_cap;
+    // 2. fp64 re-score of the survivors
+    uint64_t* keys = a.cand_key + (size_t)qi * a.surv_cap;
     const float* q = a.q + (size_t)qi * a.d;
     const size_t row_bytes = (size_t)a.d * 2;
     for (uint32_t c = wave; c < n; c += nt / 64) {
@@ -473,9 +525,9 @@ hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEven
     hipLaunchKernelGGL(fill_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);
     hipLaunchKernelGGL(make_tasks_kernel, dim3(min(a.nlist, 4096)), dim3(256), 0, s, a);
     if (a.dtype == 1)
-        hipExtLaunchKernelGGL(batched_scan_kernel<F16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, 0, a);
+        IVF_LAUNCH(batched_scan_kernel<F16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
     else
-        hipExtLaunchKernelGGL(batched_scan_kernel<BF16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, 0, a);
+        IVF_LAUNCH(batched_scan_kernel<BF16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
     hipLaunchKernelGGL(batched_merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
     return hipGetLastError();
 }

@@ -2,6 +2,15 @@
 #pragma once
 #include "ivf_internal.h"
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+// Launch with optional events that receive the kernel's own begin and end time; the plain launch
+// is used when no events are asked for.
+#define IVF_LAUNCH(kernel, grid, block, lds, stream, ev0, ev1, ...)                                \
+    do {                                                                                            \
+        if ((ev0) || (ev1)) hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ev0, ev1, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                    \
+    } while (0)
 
 namespace ivf {
 namespace dev {

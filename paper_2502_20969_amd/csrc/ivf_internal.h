@@ -123,11 +123,14 @@ struct BatchedArgs {
     BatchTask* tasks;            // [task capacity]
     uint32_t* cand_count;        // [nq]
     uint32_t* cand_row;          // [nq x cand_cap] global rows that passed the filter
-    uint64_t* cand_key;          // [nq x cand_cap] fp64 re-scores as ascending keys
+    float* cand_score;           // [nq x cand_cap] their approximate (MFMA) scores
+    float* eps;                  // [nq] bound of |approximate - exact| score
+    uint32_t* surv_row;          // [nq x surv_cap] rows that survive the pruning by approximate score
+    uint64_t* cand_key;          // [nq x surv_cap] fp64 re-scores as ascending keys
     int32_t* overflow;           // [nq] 1 when a query had more candidates than cand_cap
     int64_t* out_ids; float* out_dists;      // [nq x k]
     unsigned long long* rows_counter;        // nullable: rows covered by the scan tasks (profiling)
-    int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap;
+    int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap, surv_cap;
 };
 // upper bound of the number of tasks for a batch of nq queries
 uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe);

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void coarse_kernel(CoarseArgs a) {
 hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     dim3 grid((a.nlist + 3) / 4, (a.nq + kCoarseQT - 1) / kCoarseQT);
     size_t lds = sizeof(float) * kCoarseQT * a.d;
-    hipExtLaunchKernelGGL(coarse_kernel, grid, dim3(256), lds, s, e0, e1, 0, a);
+    IVF_LAUNCH(coarse_kernel, grid, dim3(256), lds, s, e0, e1, a);
     return hipGetLastError();
 }
 
@@ -281,7 +281,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
     const int threads = a.nlist <= 4096 && a.grid <= 1024 ? 256 : kSelectThreads;
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
     if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64 - 1) * 64 * 12;
-    hipExtLaunchKernelGGL(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, 0, a, pad, in_lds, prefix_in_lds);
+    IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds);
     return hipGetLastError();
 }
 
@@ -635,7 +635,7 @@ hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t e0, hipEvent
     ScanFn fn = scan_fn(a.shape, a.dtype, a.metric, a.kprime);
     if (!fn) return hipErrorInvalidValue;
     dim3 grid(a.grid, a.nq);
-    hipExtLaunchKernelGGL(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.kprime, a.d), s, e0, e1, 0, a);
+    IVF_LAUNCH(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.kprime, a.d), s, e0, e1, a);
     return hipGetLastError();
 }
 
@@ -913,7 +913,7 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEve
     const int fast = a.kprime <= 64;
     const int threads = fast ? kMergeFastWaves * 64 : (n <= 8192 ? 256 : kSelectThreads);
     const size_t lds = fast ? (size_t)kMergeCandCap * 8 + 1024 * 4 : 0;
-    hipExtLaunchKernelGGL(merge_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, 0, a, fast);
+    IVF_LAUNCH(merge_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, fast);
     return hipGetLastError();
 }
 
