@@ -17,6 +17,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes one scan launch of the default workload moves, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE scaled by a 1 GiB copy (profiles/scan_kernel_c2_single_query.md): read + written
+C2_SCAN_TRAFFIC_BYTES = 89314 * 1024 + 48 * 1024
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
 
 
@@ -389,7 +392,8 @@ def main():
                    "entry_point": "ivf_search_device", "searches_in_flight": args.depth, "seed": 20970},
         "one_at_a_time": {"value": round(args.steps / dt1, 1), "ms_per_step": dt1 / args.steps * 1e3},
         "roofline": {"bound": "hbm", "achieved": round(prof["scan_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(prof["scan_gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(prof["scan_gbs"] / HBM_PEAK_GBS, 4),
+                     "traffic": C2_SCAN_TRAFFIC_BYTES if (args.n == 1_000_000 and args.nprobe == 32) else None,
                      "kernel": "scan_kernel", "us_per_launch": round(prof["us_scan"], 2),
                      "bytes_per_launch": round(prof["scan_bytes_per_call"], 1)},
         "kernels_us": {k_: round(prof[k_], 2) for k_ in ("us_coarse", "us_select", "us_scan", "us_merge")},
