@@ -106,6 +106,7 @@ struct ivf_index {
     int d = 0, dtype = 0, nlist = 0, metric = 0, placement = 0;
     size_t row_bytes = 0;
     int device = 0, n_cu = 256;
+    size_t max_lds = 65536;        // LDS bytes one workgroup may use
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
 
@@ -339,6 +340,7 @@ bool batched_eligible(const ivf_index* ix, int nq) {
     if (ix->batch_mode == 1 || nq < 2) return false;
     if (ix->placement != IVF_PLACE_DEVICE || ix->metric != IVF_IP || ix->dtype == IVF_F32) return false;
     if (ix->d % 64 != 0 || !ix->d_row_norm_max) return false;   // the MFMA kernel walks 64-element blocks
+    if (batched_scan_lds(ix->d) > ix->max_lds) return false;    // a group's queries must fit LDS
     return ix->batch_mode == 2 || nq >= 4;
 }
 
@@ -413,6 +415,7 @@ int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* cen
     hipDeviceProp_t prop;
     HIP_TRY(hipGetDeviceProperties(&prop, ix->device));
     ix->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (prop.sharedMemPerBlock > 0) ix->max_lds = prop.sharedMemPerBlock;
     if (compute_stream) ix->compute = (hipStream_t)compute_stream;
     else { HIP_TRY(hipStreamCreateWithFlags(&ix->compute, hipStreamNonBlocking)); ix->own_compute = true; }
     ix->lanes.resize(1);

@@ -11,7 +11,7 @@ namespace ivf {
 
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;   // empty slot of a candidate list
 constexpr int kMaxKPrime = 128;            // candidates kept per list: k + slack <= 128
-constexpr int kScanWaves = 8;              // scan workgroup: 12 wavefronts, one workgroup per compute unit
+constexpr int kScanWaves = 4;              // scan workgroup: 4 wavefronts, two workgroups per compute unit
 constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kSelectThreads = 1024;       // select / merge workgroup: 16 wavefronts
 constexpr int kSortLdsCap = 2048;          // select: pairs sorted in LDS up to this many
@@ -139,6 +139,7 @@ hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEven
                           hipEvent_t scan_stop = nullptr);
 int batched_resident_grid(int dtype, int d, int n_cu);
 size_t batched_thr_part_floats(int nq);
+size_t batched_scan_lds(int d);      // LDS bytes of the batched scan kernel (one group of queries)
 
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
 hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,
