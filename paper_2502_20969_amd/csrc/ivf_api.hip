@@ -70,8 +70,7 @@ struct Workspace {
     uint64_t* d_sort_keys = nullptr;
     uint32_t* d_sort_idx = nullptr;
     WgDesc* d_desc = nullptr;
-    float* d_part_key = nullptr;
-    uint32_t* d_part_row = nullptr;
+    uint64_t* d_part = nullptr;      // packed candidates of the scan workgroups
     int64_t* d_out_ids = nullptr;
     float* d_out_dists = nullptr;
     // pinned host staging
@@ -113,6 +112,8 @@ struct ivf_index {
     float* d_centroids = nullptr;
     int64_t* d_off = nullptr;
     int64_t* d_ids = nullptr;
+    uint32_t* d_idrank = nullptr;    // row -> rank of its id among all ids; null when rank == row
+    uint32_t* d_rowof = nullptr;     // the inverse map
     int64_t* d_res_off = nullptr;
     void* d_buf = nullptr;          // device lists (device placement) or the prefetch buffer
     size_t buf_bytes = 0;
@@ -155,7 +156,7 @@ namespace {
 void free_workspace(Workspace& w) {
     hipFree(w.d_q); hipFree(w.d_scores); hipFree(w.d_probe);
     hipFree(w.slots.base); hipFree(w.slots.grow); hipFree(w.slots.nrows); hipFree(w.slots.rprefix);
-    hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part_key); hipFree(w.d_part_row);
+    hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part);
     hipFree(w.d_desc);
     hipFree(w.d_out_ids); hipFree(w.d_out_dists);
     hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
@@ -219,8 +220,7 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
         HIP_TRY(hipMalloc(&w.d_sort_keys, nqz * pad2 * sizeof(uint64_t)));
         HIP_TRY(hipMalloc(&w.d_sort_idx, nqz * pad2 * sizeof(uint32_t)));
     }
-    HIP_TRY(hipMalloc(&w.d_part_key, nqz * grid_cap * kp2 * sizeof(float)));
-    HIP_TRY(hipMalloc(&w.d_part_row, nqz * grid_cap * kp2 * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_part, nqz * grid_cap * kp2 * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&w.d_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipMalloc(&w.d_out_dists, nqz * k2 * sizeof(float)));
     HIP_TRY(hipHostMalloc(&w.h_q, nqz * ix->d * sizeof(float)));
@@ -301,8 +301,8 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
 int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kprime, int grid) {
     Workspace& w = *ix->cw;
     ScanArgs sc{};
-    sc.buf = ix->d_buf; sc.q = q_dev; sc.ids = ix->d_ids; sc.slots = w.slots;
-    sc.part_key = w.d_part_key; sc.part_row = w.d_part_row;
+    sc.buf = ix->d_buf; sc.q = q_dev; sc.idrank = ix->d_idrank; sc.slots = w.slots;
+    sc.part = w.d_part;
     sc.desc = w.d_desc;
     sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
     sc.kprime = kprime; sc.grid = grid; sc.shape = ix->shape;
@@ -317,8 +317,8 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
                   bool with_host, int64_t* out_ids, float* out_dists) {
     Workspace& w = *ix->cw;
     MergeArgs ma{};
-    ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.slots = w.slots;
-    ma.part_key = w.d_part_key; ma.part_row = w.d_part_row;
+    ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.rowof = ix->d_rowof; ma.slots = w.slots;
+    ma.part = w.d_part;
     ma.host_cand = with_host ? w.h_cand : nullptr;
     ma.host_count = with_host ? w.h_cand_count : nullptr;
     ma.out_ids = out_ids; ma.out_dists = out_dists;
@@ -438,6 +438,43 @@ int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* cen
     return IVF_OK;
 }
 
+// Equal keys are ordered by smaller id.  The kernels carry, instead of the 64-bit id, the rank of
+// the id among all ids (ties between equal ids by row), which fits the low half of a packed
+// candidate; this builds row -> rank and rank -> row.  Nothing is needed when ids already grow
+// with the row position.
+int upload_id_ranks(ivf_index* ix) {
+    const int64_t n = ix->n;
+    const int64_t* ids = ix->h_ids.data();
+    bool increasing = true;
+    for (int64_t i = 1; i < n && increasing; ++i) increasing = ids[i - 1] < ids[i];
+    if (increasing) return IVF_OK;
+    std::vector<uint32_t> rank((size_t)n), rowof((size_t)n);
+    // the usual case, ids = positions in the caller's input: a permutation of 0..n-1 is its own rank
+    bool permutation = true;
+    {
+        std::vector<bool> seen((size_t)n, false);
+        for (int64_t i = 0; i < n && permutation; ++i) {
+            const int64_t v = ids[i];
+            if (v < 0 || v >= n || seen[(size_t)v]) permutation = false;
+            else seen[(size_t)v] = true;
+        }
+    }
+    if (permutation) {
+        for (int64_t i = 0; i < n; ++i) { rank[(size_t)i] = (uint32_t)ids[i]; rowof[(size_t)ids[i]] = (uint32_t)i; }
+    } else {
+        for (int64_t i = 0; i < n; ++i) rowof[(size_t)i] = (uint32_t)i;
+        std::sort(rowof.begin(), rowof.end(), [ids](uint32_t x, uint32_t y) {
+            return ids[x] < ids[y] || (ids[x] == ids[y] && x < y);
+        });
+        for (int64_t r = 0; r < n; ++r) rank[rowof[(size_t)r]] = (uint32_t)r;
+    }
+    HIP_TRY(hipMalloc(&ix->d_idrank, (size_t)n * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&ix->d_rowof, (size_t)n * sizeof(uint32_t)));
+    HIP_TRY(hipMemcpy(ix->d_idrank, rank.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(ix->d_rowof, rowof.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice));
+    return IVF_OK;
+}
+
 // after h_off / h_ids are set: uploads them and initialises residency
 int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
     const int nlist = ix->nlist;
@@ -445,6 +482,8 @@ int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
     if (!ix->h_ids.empty()) {
         HIP_TRY(hipMalloc(&ix->d_ids, (size_t)ix->n * sizeof(int64_t)));
         HIP_TRY(hipMemcpy(ix->d_ids, ix->h_ids.data(), (size_t)ix->n * sizeof(int64_t), hipMemcpyHostToDevice));
+        int rc = upload_id_ranks(ix);
+        if (rc != IVF_OK) return rc;
     }
     ix->h_res_off.assign(nlist, -1);
     if (ix->placement == IVF_PLACE_DEVICE) {
@@ -498,7 +537,7 @@ extern "C" void ivf_free(ivf_index* ix) {
     hipDeviceSynchronize();
     for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) hipStreamDestroy(l.stream); }
     for (auto& s : ix->prof_sets) for (auto& e : s.e) hipEventDestroy(e);
-    hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_res_off);
+    hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_idrank); hipFree(ix->d_rowof); hipFree(ix->d_res_off);
     hipFree(ix->d_prof_rows); hipFree(ix->d_row_norm_max);
     if (ix->own_buf) hipFree(ix->d_buf);
     if (ix->own_h_lists) hipHostFree(ix->h_lists);

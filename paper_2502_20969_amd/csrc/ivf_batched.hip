@@ -60,8 +60,7 @@ constexpr int kSamplePartRows = 128;
 template <typename T>
 __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
     extern __shared__ unsigned char smem[];
-    __shared__ float m_key[3 * kMaxKPrime];
-    __shared__ uint32_t m_row[3 * kMaxKPrime];
+    __shared__ Cand m_cand[3 * kMaxKPrime];
     constexpr int EPL = T::kPerLoad;
     const int qi = blockIdx.x, part = blockIdx.y, lane = lane_id(), wave = wave_id();
     float* ql = (float*)smem;
@@ -73,8 +72,7 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
     const uint32_t r_begin = part * kSamplePartRows + wave * 32;
     const uint32_t r_end = min(n, r_begin + 32);
     const int chunks = a.d / EPL;
-    const RowOrder order{nullptr};              // ties inside the sample do not matter for a bound
-    WaveTopK<2> top;
+    WaveTopK<2, false> top;                     // ties inside the sample do not matter for a bound
     top.init();
     for (uint32_t r0 = r_begin; r0 < r_end; r0 += 4) {
         float s[4] = {0.f, 0.f, 0.f, 0.f};
@@ -98,14 +96,14 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
             float ck = read_lane(group_total_last_lane<64>(s[u]), 63);
             if (r0 + u < r_end && ck >= top.thr) top.push(ck, r0 + u);
         }
-        if (top.pcount > 60) top.flush(order, a.k);
+        if (top.pcount > 60) top.flush(a.k);
     }
-    top.flush(order, a.k);
+    top.flush(a.k);
     if (wave > 0) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             int e = j * 64 + lane;
-            if (e < a.k) { m_key[(wave - 1) * a.k + e] = top.top[j].k; m_row[(wave - 1) * a.k + e] = top.top[j].r; }
+            if (e < a.k) m_cand[(wave - 1) * a.k + e] = top.top[j];
         }
     }
     __syncthreads();
@@ -114,15 +112,14 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 int e = j * 64 + lane;
-                RowCand run = e < a.k ? RowCand{m_key[w * a.k + e], m_row[w * a.k + e]} : empty_row_cand();
-                if (read_lane(run.r, 0) != kNoRow) top.merge_run(run, order, a.k);
+                top.merge_run_if_useful(e < a.k ? m_cand[w * a.k + e] : (Cand)0, a.k);
             }
         }
         float* out = a.thr_part + ((size_t)qi * kSampleParts + part) * kMaxKPrime;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             int e = j * 64 + lane;
-            if (e < a.k) out[e] = top.top[j].r == kNoRow ? -INFINITY : top.top[j].k;
+            if (e < a.k) out[e] = top.top[j] == 0 ? -INFINITY : cand_key(top.top[j]);
         }
     }
 }
@@ -142,8 +139,7 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
     s = group_sum<64>(s);
     res = group_sum<64>(res);
     // k-th best key over the sample parts
-    const RowOrder order{nullptr};
-    WaveTopK<2> top;
+    WaveTopK<2, false> top;
     top.init();
     for (int part = 0; part < kSampleParts; ++part) {
         const float* in = a.thr_part + ((size_t)qi * kSampleParts + part) * kMaxKPrime;
@@ -151,8 +147,7 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
         for (int j = 0; j < 2; ++j) {
             int e = j * 64 + lane;
             float key = e < a.k ? in[e] : -INFINITY;
-            RowCand run{key, key == -INFINITY ? kNoRow : (uint32_t)(part * kMaxKPrime + e)};
-            if (read_lane(run.r, 0) != kNoRow && read_lane(run.k, 0) >= top.thr) top.merge_run(run, order, a.k);
+            top.merge_run_if_useful(key == -INFINITY ? (Cand)0 : pack_cand(key, (uint32_t)(part * kMaxKPrime + e)), a.k);
         }
     }
     if (lane == 0) {

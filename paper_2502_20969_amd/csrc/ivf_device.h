@@ -166,6 +166,49 @@ __device__ __forceinline__ double rescore_chunks(const unsigned char* row, const
     return wave_sum(acc);
 }
 
+// The same for up to four rows at once, so that all their loads are in flight together.
+template <typename T>
+__device__ __forceinline__ void rescore_chunks_x4(const unsigned char* const (&row)[4], int cnt, const float* q,
+                                                  int d, int metric, double (&out)[4]) {
+    constexpr int EPL = T::kPerLoad;
+    const int lane = lane_id();
+    const int chunks = d / EPL;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int c0 = lane; c0 < chunks; c0 += 256) {
+        uint4 v[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int c = c0 + u * 64;
+                v[j][u] = (j < cnt && c < chunks) ? *(const uint4*)(row[j] + (size_t)c * 16) : make_uint4(0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int c = c0 + u * 64;
+            if (c < chunks) {
+                double qv[EPL];
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) qv[e] = (double)q[c * EPL + e];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float x[EPL];
+                    Unpack<T>::run(v[j][u], x);
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) {
+                        double y = (double)x[e];
+                        if (metric == 0) acc[j] = fma(qv[e], y, acc[j]);
+                        else { double df = qv[e] - y; acc[j] = fma(df, df, acc[j]); }
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out[j] = wave_sum(acc[j]);
+}
+
 // ---- order-preserving integer keys ------------------------------------------------------------
 // Unsigned keys whose ascending order is the ascending order of the floating value.
 __device__ __forceinline__ uint32_t ordered(float f) {
@@ -316,39 +359,27 @@ __device__ inline void block_bitonic_sort(uint64_t* keys, uint32_t* idx, uint32_
     }
 }
 
+// ---- packed candidates --------------------------------------------------------------------------
+// A candidate is one 64-bit word whose unsigned order is the result order: the order-preserving
+// image of an fp32 key in the high half and the complement of a tie-break rank in the low half
+// (rows: the rank of the row's id among all ids, so that equal keys come out by smaller id;
+// clusters: see the select kernel).  Larger = comes first; 0 = empty (no finite or infinite key
+// has a zero image).  One compare decides an exchange, which keeps the networks below short:
+// a single-workgroup kernel runs each instruction once, so its time follows its code size.
+typedef uint64_t Cand;
+__device__ __forceinline__ float unordered(uint32_t o) {          // inverse of ordered(float)
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+__device__ __forceinline__ Cand pack_cand(float key, uint32_t tie) {
+    return ((uint64_t)ordered(key) << 32) | (uint64_t)(uint32_t)~tie;
+}
+__device__ __forceinline__ float cand_key(Cand c) { return unordered((uint32_t)(c >> 32)); }
+__device__ __forceinline__ uint32_t cand_tie(Cand c) { return ~(uint32_t)c; }
+__device__ __forceinline__ Cand read_lane(Cand v, int lane) {
+    return ((uint64_t)read_lane((uint32_t)(v >> 32), lane) << 32) | read_lane((uint32_t)v, lane);
+}
+
 // ---- sorting networks over the 64 lanes of a wavefront --------------------------------------------
-// A candidate type C holds one element per lane in a few registers; an order O decides which of
-// two candidates comes first.  Two instances: row candidates of the list scan (RowCand /
-// RowOrder) and cluster candidates of the coarse selection (ClusterCand / ClusterOrder).
-
-// Row candidate: larger key first, equal keys by smaller id (id = ids[row], or the row itself
-// when ids is null).  The empty candidate (key -inf, row kNoRow) comes last.
-struct RowCand { float k; uint32_t r; };
-__device__ __forceinline__ RowCand empty_row_cand() { return RowCand{-INFINITY, kNoRow}; }
-struct RowOrder {
-    const int64_t* ids;
-    __device__ __forceinline__ int64_t id_of(uint32_t r) const {
-        if (r == kNoRow) return INT64_MAX;
-        return ids ? ids[r] : (int64_t)r;
-    }
-    // sets a_first / b_first (both false for identical candidates)
-    __device__ __forceinline__ void compare(const RowCand& a, const RowCand& b, bool& a_first, bool& b_first) const {
-        a_first = a.k > b.k; b_first = b.k > a.k;
-        if (a.k == b.k && a.r != b.r) {          // equal keys: rare
-            int64_t ia = id_of(a.r), ib = id_of(b.r);
-            a_first = ia < ib; b_first = ib < ia;
-        }
-    }
-};
-// Cluster candidate: smaller 64-bit key first, equal keys by smaller cluster index.
-struct ClusterCand { uint64_t k; uint32_t i; };
-struct ClusterOrder {
-    __device__ __forceinline__ void compare(const ClusterCand& a, const ClusterCand& b, bool& a_first, bool& b_first) const {
-        a_first = a.k < b.k || (a.k == b.k && a.i < b.i);
-        b_first = b.k < a.k || (a.k == b.k && b.i < a.i);
-    }
-};
-
 // Value held by lane (lane ^ STRIDE), with register-to-register moves only: DPP quad
 // permutes (1, 2), row shifts (4), a row rotate (8), and the 16- and 32-lane swaps of gfx950.
 template <int STRIDE>
@@ -375,49 +406,36 @@ __device__ __forceinline__ uint32_t mirror_lane_u32(uint32_t v) {
     return xor_lane_u32<32>(xor_lane_u32<16>(m));
 }
 template <int STRIDE>
-__device__ __forceinline__ RowCand xor_lane(const RowCand& c) {
-    return RowCand{__uint_as_float(xor_lane_u32<STRIDE>(__float_as_uint(c.k))), xor_lane_u32<STRIDE>(c.r)};
+__device__ __forceinline__ Cand xor_lane(Cand c) {
+    return ((uint64_t)xor_lane_u32<STRIDE>((uint32_t)(c >> 32)) << 32) | xor_lane_u32<STRIDE>((uint32_t)c);
 }
-template <int STRIDE>
-__device__ __forceinline__ ClusterCand xor_lane(const ClusterCand& c) {
-    uint32_t lo = xor_lane_u32<STRIDE>((uint32_t)c.k), hi = xor_lane_u32<STRIDE>((uint32_t)(c.k >> 32));
-    return ClusterCand{((uint64_t)hi << 32) | lo, xor_lane_u32<STRIDE>(c.i)};
-}
-__device__ __forceinline__ RowCand from_lane(const RowCand& c, int src) {
-    return RowCand{__shfl(c.k, src), (uint32_t)__shfl((int)c.r, src)};
-}
-__device__ __forceinline__ ClusterCand from_lane(const ClusterCand& c, int src) {
-    uint32_t lo = (uint32_t)__shfl((int)(uint32_t)c.k, src), hi = (uint32_t)__shfl((int)(uint32_t)(c.k >> 32), src);
-    return ClusterCand{((uint64_t)hi << 32) | lo, (uint32_t)__shfl((int)c.i, src)};
+__device__ __forceinline__ Cand mirror(Cand c) {
+    return ((uint64_t)mirror_lane_u32((uint32_t)(c >> 32)) << 32) | mirror_lane_u32((uint32_t)c);
 }
 
 // One compare-exchange step between lane and lane ^ STRIDE.  keep_first: this lane keeps the
-// candidate that comes first (else the one that comes last).
-template <int STRIDE, typename C, typename O>
-__device__ __forceinline__ void cmp_exchange(C& c, bool keep_first, const O& order) {
-    C p = xor_lane<STRIDE>(c);
-    bool mine_first, partner_first;
-    order.compare(c, p, mine_first, partner_first);
-    if (keep_first ? partner_first : mine_first) c = p;
+// candidate that comes first (the larger word), else the other one.
+template <int STRIDE>
+__device__ __forceinline__ void cmp_exchange(Cand& c, bool keep_first) {
+    Cand p = xor_lane<STRIDE>(c);
+    if ((p > c) == keep_first) c = p;
 }
 
 // Sorts a bitonic sequence of 64 lane-held candidates into first-to-last order.
-template <typename C, typename O>
-__device__ __forceinline__ void bitonic_merge64(C& c, const O& order) {
+__device__ __forceinline__ Cand bitonic_merge64_inline(Cand c) {
     const int lane = lane_id();
-    cmp_exchange<32>(c, (lane & 32) == 0, order);
-    cmp_exchange<16>(c, (lane & 16) == 0, order);
-    cmp_exchange<8>(c, (lane & 8) == 0, order);
-    cmp_exchange<4>(c, (lane & 4) == 0, order);
-    cmp_exchange<2>(c, (lane & 2) == 0, order);
-    cmp_exchange<1>(c, (lane & 1) == 0, order);
+    cmp_exchange<32>(c, (lane & 32) == 0);
+    cmp_exchange<16>(c, (lane & 16) == 0);
+    cmp_exchange<8>(c, (lane & 8) == 0);
+    cmp_exchange<4>(c, (lane & 4) == 0);
+    cmp_exchange<2>(c, (lane & 2) == 0);
+    cmp_exchange<1>(c, (lane & 1) == 0);
+    return c;
 }
-
 // Sorts 64 lane-held candidates first-to-last (bitonic sorting network over the lanes).
-template <typename C, typename O>
-__device__ __forceinline__ void bitonic_sort64(C& c, const O& order) {
+__device__ __forceinline__ Cand bitonic_sort64_inline(Cand c) {
     const int lane = lane_id();
-#define IVF_STAGE(SIZE, STRIDE) cmp_exchange<STRIDE>(c, ((lane & STRIDE) == 0) == ((lane & SIZE) == 0), order);
+#define IVF_STAGE(SIZE, STRIDE) cmp_exchange<STRIDE>(c, ((lane & STRIDE) == 0) == ((lane & SIZE) == 0));
     IVF_STAGE(2, 1)
     IVF_STAGE(4, 2) IVF_STAGE(4, 1)
     IVF_STAGE(8, 4) IVF_STAGE(8, 2) IVF_STAGE(8, 1)
@@ -425,24 +443,33 @@ __device__ __forceinline__ void bitonic_sort64(C& c, const O& order) {
     IVF_STAGE(32, 16) IVF_STAGE(32, 8) IVF_STAGE(32, 4) IVF_STAGE(32, 2) IVF_STAGE(32, 1)
     IVF_STAGE(64, 32) IVF_STAGE(64, 16) IVF_STAGE(64, 8) IVF_STAGE(64, 4) IVF_STAGE(64, 2) IVF_STAGE(64, 1)
 #undef IVF_STAGE
+    return c;
+}
+// Out-of-line copies: a kernel that sorts in several places then holds (and fetches) the
+// network once.  CALL = true selects them; the streaming scan kernel keeps the inline form.
+__device__ __attribute__((noinline)) Cand bitonic_merge64_call(Cand c) { return bitonic_merge64_inline(c); }
+__device__ __attribute__((noinline)) Cand bitonic_sort64_call(Cand c) { return bitonic_sort64_inline(c); }
+template <bool CALL> __device__ __forceinline__ Cand bitonic_merge64(Cand c) {
+    if (CALL) return bitonic_merge64_call(c);
+    return bitonic_merge64_inline(c);
+}
+template <bool CALL> __device__ __forceinline__ Cand bitonic_sort64(Cand c) {
+    if (CALL) return bitonic_sort64_call(c);
+    return bitonic_sort64_inline(c);
 }
 
-__device__ __forceinline__ RowCand mirror(const RowCand& c) {
-    return RowCand{__uint_as_float(mirror_lane_u32(__float_as_uint(c.k))), mirror_lane_u32(c.r)};
+// The first 64 of (a u p), sorted; a and p sorted.  `dropped` receives this lane's loser.
+template <bool CALL>
+__device__ __forceinline__ Cand merge_best64(Cand a, Cand p, Cand& dropped) {
+    Cand rev = mirror(p);
+    const bool take = rev > a;
+    dropped = take ? a : rev;
+    return bitonic_merge64<CALL>(take ? rev : a);
 }
-__device__ __forceinline__ ClusterCand mirror(const ClusterCand& c) {
-    uint32_t lo = mirror_lane_u32((uint32_t)c.k), hi = mirror_lane_u32((uint32_t)(c.k >> 32));
-    return ClusterCand{((uint64_t)hi << 32) | lo, mirror_lane_u32(c.i)};
-}
-
-// a <- the first 64 of (a u p), sorted; a and p sorted.
-template <typename C, typename O>
-__device__ __forceinline__ void merge_best64(C& a, const C& p, const O& order) {
-    C rev = mirror(p);
-    bool a_first, r_first;
-    order.compare(a, rev, a_first, r_first);
-    if (r_first) a = rev;
-    bitonic_merge64(a, order);
+template <bool CALL>
+__device__ __forceinline__ Cand merge_best64(Cand a, Cand p) {
+    Cand dropped;
+    return merge_best64<CALL>(a, p, dropped);
 }
 
 // ---- wavefront-resident top-k ------------------------------------------------------------------
@@ -450,52 +477,56 @@ __device__ __forceinline__ void merge_best64(C& a, const C& p, const O& order) {
 // e / 64 of lane e % 64.  New candidates wait in a 64-entry pending buffer (one per lane) and
 // are folded in by a sort + bitonic merge when it fills up or on flush().
 // `thr` is the key of entry kprime-1 of the sorted part: a key below it cannot matter.
-template <int KL>
+template <int KL, bool CALL>
 struct WaveTopK {
-    RowCand top[KL];
-    RowCand pend;
+    Cand top[KL];
+    Cand pend;
     int pcount;
     float thr;
 
     __device__ __forceinline__ void init() {
 #pragma unroll
-        for (int j = 0; j < KL; ++j) top[j] = empty_row_cand();
-        pend = empty_row_cand(); pcount = 0;
+        for (int j = 0; j < KL; ++j) top[j] = 0;
+        pend = 0; pcount = 0;
         thr = -INFINITY;
     }
 
     // Folds a sorted run of 64 candidates (one per lane) into the list.
-    __device__ __forceinline__ void merge_run(const RowCand& run, const RowOrder& order, int kprime) {
+    __device__ __forceinline__ void merge_run(Cand run, int kprime) {
         if (KL == 1) {
-            merge_best64(top[0], run, order);
+            top[0] = merge_best64<CALL>(top[0], run);
         } else {
-            // the best 128 of (L0, L1, P) are L0 plus the best 64 of (L1 u P)
-            merge_best64(top[KL - 1], run, order);
-            RowCand rev = mirror(top[KL - 1]);
-            bool a_first, r_first;
-            order.compare(top[0], rev, a_first, r_first);
-            if (r_first) { RowCand t = top[0]; top[0] = rev; rev = t; }
-            bitonic_merge64(top[0], order);
-            bitonic_merge64(rev, order);
-            top[KL - 1] = rev;
+            // the best 128 of (L0, L1, P) are L0 plus the best 64 of (L1 u P), re-split
+            top[KL - 1] = merge_best64<CALL>(top[KL - 1], run);
+            Cand rev = mirror(top[KL - 1]);
+            const bool take = rev > top[0];
+            Cand lo = take ? top[0] : rev;
+            top[0] = bitonic_merge64<CALL>(take ? rev : top[0]);
+            top[KL - 1] = bitonic_merge64<CALL>(lo);
         }
         const int last = kprime - 1;
+        Cand e = 0;
 #pragma unroll
         for (int j = 0; j < KL; ++j)
-            if ((last >> 6) == j) thr = read_lane(top[j].k, last & 63);
+            if ((last >> 6) == j) e = read_lane(top[j], last & 63);
+        thr = e ? cand_key(e) : -INFINITY;
+    }
+    // a run whose best entry is below the threshold cannot change the list
+    __device__ __forceinline__ void merge_run_if_useful(Cand run, int kprime) {
+        const Cand head = read_lane(run, 0);
+        if (head != 0 && cand_key(head) >= thr) merge_run(run, kprime);
     }
 
-    __device__ __forceinline__ void flush(const RowOrder& order, int kprime) {
+    __device__ __forceinline__ void flush(int kprime) {
         if (pcount == 0) return;
-        bitonic_sort64(pend, order);
-        merge_run(pend, order, kprime);
-        pend = empty_row_cand(); pcount = 0;
+        merge_run(bitonic_sort64<CALL>(pend), kprime);
+        pend = 0; pcount = 0;
     }
 
     // Called by the whole wavefront with a uniform candidate; the caller flushes before the
     // pending buffer (64 entries) can overflow.
-    __device__ __forceinline__ void push(float ckey, uint32_t crow) {
-        if (lane_id() == pcount) pend = RowCand{ckey, crow};
+    __device__ __forceinline__ void push(float key, uint32_t tie) {
+        if (lane_id() == pcount) pend = pack_cand(key, tie);
         ++pcount;
     }
 };

@@ -78,11 +78,11 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t start = 
 struct ScanArgs {
     const void* buf;         // device buffer holding resident lists, row-major
     const float* q;          // [nq x d]
-    const int64_t* ids;      // [n] global row -> id, or nullptr (id = global row)
+    const uint32_t* idrank;  // [n] global row -> rank of its id among all ids, or nullptr (rank = global row)
     SlotTables slots;
     const WgDesc* desc;      // [nq x grid]
-    float* part_key;         // [nq x grid x kprime] out: workgroup lists, larger = nearer
-    uint32_t* part_row;      //                          global row or kNoRow
+    uint64_t* part;          // [nq x grid x kprime] out: workgroup lists of packed candidates
+                             // (fp32 key image << 32 | ~rank), best first, 0 = empty
     int d, dtype, metric, nprobe, nq, kprime, grid;
     ScanShape shape;
 };
@@ -91,9 +91,11 @@ hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t start = null
 int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime, int d, int n_cu);
 
 struct MergeArgs {
-    const void* buf; const float* q; const int64_t* ids;
+    const void* buf; const float* q;
+    const int64_t* ids;          // [n] global row -> id, or nullptr (id = global row)
+    const uint32_t* rowof;       // [n] id rank -> global row, or nullptr (row = rank)
     SlotTables slots;
-    const float* part_key; const uint32_t* part_row;     // [nq x nparts x kprime]
+    const uint64_t* part;        // [nq x nparts x kprime] packed candidates written by the scan
     const HostCand* host_cand;   // [nq x kprime] device-visible, or nullptr
     const int32_t* host_count;   // [nq] valid entries in host_cand
     int64_t* out_ids; float* out_dists;   // [nq x k]

@@ -149,33 +149,57 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
     IVF_TRACE_MARK(10);
     uint32_t* idx;
     if (in_lds && nprobe <= 64 && a.nlist <= kSelectWaveSortMax) {
-        // Few clusters wanted from a small index: every wavefront sorts chunks of 64 scores in
-        // registers and keeps its best 64; wavefront 0 merges the wavefronts' runs.
+        // Few clusters wanted from a small index.  Each score is cut down to a packed candidate:
+        // the top 40 bits of its descending key image, then the complement of the cluster index
+        // (larger = nearer; equal prefixes by smaller index).  Every wavefront sorts chunks of 64
+        // in registers and keeps its best 64; a pairwise tree merges the wavefronts' runs.  The
+        // order of the prefixes is the order of the scores wherever prefixes differ, so the
+        // result is exact unless two prefixes tie among the selected clusters or across the
+        // cut; then the exact general path below redoes the selection.
         uint64_t* keys = (uint64_t*)smem_raw;
         idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
         const int lane = lane_id(), wave = wave_id(), nw = nt >> 6;
-        const ClusterOrder order;
-        ClusterCand best{~0ull, 0xFFFFFFFFu};
+        if (tid == 0) { sh[6] = 0; sh[7] = 0; }
+        Cand best = 0;
+        bool tie_cut = false;     // a dropped candidate shared its prefix with the last one kept
+        auto fold = [&](Cand run) {
+            Cand dropped;
+            best = merge_best64<true>(best, run, dropped);
+            const uint64_t low = read_lane(best, 63) >> 24;
+            tie_cut |= __ballot(dropped != 0 && (dropped >> 24) == low) != 0;
+        };
+#pragma unroll 1
         for (int c0 = wave * 64; c0 < a.nlist; c0 += nw * 64) {
-            int i = c0 + lane;
-            ClusterCand c = i < a.nlist ? ClusterCand{coarse_key(sc[i], a.metric), (uint32_t)i} : ClusterCand{~0ull, 0xFFFFFFFFu};
-            bitonic_sort64(c, order);
-            merge_best64(best, c, order);
+            const int i = c0 + lane;
+            Cand c = 0;
+            if (i < a.nlist) c = (~coarse_key(sc[i], a.metric) & ~0xFFFFFFull) | (uint64_t)(0xFFFFFFu - (uint32_t)i);
+            fold(bitonic_sort64<true>(c));
         }
-        // runs of wavefronts 1.. go through LDS (reusing hist is too small: use the sort area)
-        uint64_t* r_key = (uint64_t*)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4 + 8);
-        r_key = (uint64_t*)(((uintptr_t)r_key + 7) & ~(uintptr_t)7);
-        uint32_t* r_idx = (uint32_t*)(r_key + (size_t)(nw - 1) * 64);
-        if (wave > 0) { r_key[(wave - 1) * 64 + lane] = best.k; r_idx[(wave - 1) * 64 + lane] = best.i; }
+        Cand* run = (Cand*)(((uintptr_t)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4) + 15) & ~(uintptr_t)15);
+#pragma unroll 1
+        for (int stride = 1; stride < nw; stride <<= 1) {
+            const bool sender = (wave % (2 * stride)) == stride;
+            const bool receiver = (wave % (2 * stride)) == 0 && wave + stride < nw;
+            if (sender) run[wave * 64 + lane] = best;
+            __syncthreads();
+            if (receiver) fold(run[(wave + stride) * 64 + lane]);
+            __syncthreads();
+        }
+        if (tie_cut && lane == 0) atomicOr(&sh[7], 1u);
         __syncthreads();
         if (wave == 0) {
-            for (int w = 0; w < nw - 1; ++w) {
-                ClusterCand run{r_key[w * 64 + lane], r_idx[w * 64 + lane]};
-                merge_best64(best, run, order);
-            }
-            if (lane < (int)pad) { keys[lane] = best.k; idx[lane] = best.i; }
+            const uint64_t cut = read_lane(best, (int)nprobe - 1) >> 24;     // prefix of the last selected
+            const bool in_s = best != 0 && (best >> 24) >= cut;              // a prefix of the lanes
+            const int ns = __popcll(__ballot(in_s));
+            const uint64_t next = ((uint64_t)(uint32_t)__shfl_down((int)(uint32_t)(best >> 32), 1) << 32) |
+                                  (uint32_t)__shfl_down((int)(uint32_t)best, 1);
+            const bool adjacent = lane + 1 < ns && (best >> 24) == (next >> 24);
+            const bool redo = __ballot(adjacent) != 0 || (ns == 64 && sh[7] != 0);
+            if (lane == 0) sh[6] = redo;
+            if (!redo && lane < (int)pad) idx[lane] = best != 0 ? 0xFFFFFFu - (uint32_t)(best & 0xFFFFFFull) : 0xFFFFFFFFu;
         }
         __syncthreads();
+        if (sh[6]) select_sorted(a, sc, keys, idx, pad, hist, sh);
     } else if (in_lds) {
         uint64_t* keys = (uint64_t*)smem_raw;
         idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
@@ -280,7 +304,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
     // a workgroup with one wavefront per SIMD issues fastest when there is little work per thread
     const int threads = a.nlist <= 4096 && a.grid <= 1024 ? 256 : kSelectThreads;
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
-    if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64 - 1) * 64 * 12;
+    if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64) * 64 * 8;
     IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds);
     return hipGetLastError();
 }
@@ -333,8 +357,8 @@ __device__ __forceinline__ Batch next_batch(Cursor& c, const ScanArgs& p, int qi
 // LDS of the scan epilogue: a pool of loose candidates (one 64-entry chunk per wavefront at
 // most) and one sorted list of kprime entries per wavefront.
 struct ScanLds {
-    float* pool_key; uint32_t* pool_row;    // [kScanWaves * 64]
-    float* list_key; uint32_t* list_row;    // [kScanWaves * kprime]
+    Cand* pool;                             // [kScanWaves * 64]
+    Cand* list;                             // [kScanWaves * kprime]
     uint32_t* ctl;                          // [0] pool count, [1] bit mask of wavefronts with a list
 };
 __host__ __device__ inline size_t scan_epilogue_bytes(int kprime) {
@@ -342,11 +366,9 @@ __host__ __device__ inline size_t scan_epilogue_bytes(int kprime) {
 }
 __device__ __forceinline__ ScanLds scan_lds(unsigned char* smem, int kprime) {
     ScanLds l;
-    l.pool_key = (float*)smem;
-    l.pool_row = (uint32_t*)(l.pool_key + kScanWaves * 64);
-    l.list_key = (float*)(l.pool_row + kScanWaves * 64);
-    l.list_row = (uint32_t*)(l.list_key + kScanWaves * kprime);
-    l.ctl = l.list_row + kScanWaves * kprime;
+    l.pool = (Cand*)smem;
+    l.list = l.pool + kScanWaves * 64;
+    l.ctl = (uint32_t*)(l.list + kScanWaves * kprime);
     return l;
 }
 
@@ -355,23 +377,22 @@ __device__ __forceinline__ ScanLds scan_lds(unsigned char* smem, int kprime) {
 // as many wavefronts as there are chunks; wavefront 0 then merges all sorted runs into the
 // workgroup's list and writes it out.
 template <int KL>
-__device__ __forceinline__ void finish_workgroup(WaveTopK<KL>& top, const ScanArgs& p, const ScanLds& l, int qi) {
+__device__ __forceinline__ void finish_workgroup(WaveTopK<KL, false>& top, const ScanArgs& p, const ScanLds& l, int qi) {
     const int lane = lane_id(), wave = wave_id();
     const int kp = p.kprime;
-    const RowOrder order{p.ids};
     // ctl was zeroed at kernel start (before a barrier every wavefront has passed)
     if (top.pcount > 0) {
         uint32_t base = 0;
         if (lane == 0) base = atomicAdd(&l.ctl[0], (uint32_t)top.pcount);
         base = read_lane(base, 0);
-        if (lane < top.pcount) { l.pool_key[base + lane] = top.pend.k; l.pool_row[base + lane] = top.pend.r; }
+        if (lane < top.pcount) l.pool[base + lane] = top.pend;
     }
-    const bool has_list = read_lane(top.top[0].r, 0) != kNoRow;
+    const bool has_list = read_lane(top.top[0], 0) != 0;
     if (has_list) {
 #pragma unroll
         for (int j = 0; j < KL; ++j) {
             int e = j * 64 + lane;
-            if (e < kp) { l.list_key[wave * kp + e] = top.top[j].k; l.list_row[wave * kp + e] = top.top[j].r; }
+            if (e < kp) l.list[wave * kp + e] = top.top[j];
         }
         if (lane == 0) atomicOr(&l.ctl[1], 1u << wave);
     }
@@ -380,9 +401,7 @@ __device__ __forceinline__ void finish_workgroup(WaveTopK<KL>& top, const ScanAr
     const int nchunks = (int)((pool + 63) / 64);
     if (wave < nchunks) {
         uint32_t e = wave * 64 + lane;
-        RowCand c = e < pool ? RowCand{l.pool_key[e], l.pool_row[e]} : empty_row_cand();
-        bitonic_sort64(c, order);
-        l.pool_key[e] = c.k; l.pool_row[e] = c.r;
+        l.pool[e] = bitonic_sort64<false>(e < pool ? l.pool[e] : (Cand)0);
     }
     __syncthreads();
     if (wave != 0) return;
@@ -393,19 +412,15 @@ __device__ __forceinline__ void finish_workgroup(WaveTopK<KL>& top, const ScanAr
 #pragma unroll
         for (int j = 0; j < KL; ++j) {
             int e = j * 64 + lane;
-            RowCand run = e < kp ? RowCand{l.list_key[w * kp + e], l.list_row[w * kp + e]} : empty_row_cand();
-            if (read_lane(run.r, 0) != kNoRow && read_lane(run.k, 0) >= top.thr) top.merge_run(run, order, kp);
+            top.merge_run_if_useful(e < kp ? l.list[w * kp + e] : (Cand)0, kp);
         }
     }
-    for (int c = 0; c < nchunks; ++c) {
-        RowCand run{l.pool_key[c * 64 + lane], l.pool_row[c * 64 + lane]};
-        if (read_lane(run.k, 0) >= top.thr) top.merge_run(run, order, kp);
-    }
+    for (int c = 0; c < nchunks; ++c) top.merge_run_if_useful(l.pool[c * 64 + lane], kp);
     size_t o = ((size_t)qi * p.grid + blockIdx.x) * kp;
 #pragma unroll
     for (int j = 0; j < KL; ++j) {
         int e = j * 64 + lane;
-        if (e < kp) { p.part_key[o + e] = top.top[j].k; p.part_row[o + e] = top.top[j].r; }
+        if (e < kp) p.part[o + e] = top.top[j];
     }
 }
 
@@ -447,11 +462,13 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
         for (int e = 0; e < EPL; ++e) qv[sg][e] = col + e < p.d ? q[col + e] : 0.f;
     }
 
-    WaveTopK<KL> top;
+    WaveTopK<KL, false> top;
     top.init();
-    const RowOrder order{p.ids};
 
-    auto issue = [&](const Batch& b, uint4 (&v)[U][SEG]) {
+    // `tie` receives the tie-break rank of batch row `lane` (lanes < RPB)
+    auto issue = [&](const Batch& b, uint4 (&v)[U][SEG], uint32_t& tie) {
+        const uint32_t tr = b.grow + min((uint32_t)lane, b.nr - 1);
+        tie = p.idrank ? p.idrank[tr] : tr;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             uint32_t r = min((uint32_t)(u * RPI + rsel), b.nr - 1);   // rows past the end re-read the last one
@@ -464,7 +481,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
             }
         }
     };
-    auto consume = [&](const Batch& b, const uint4 (&v)[U][SEG]) {
+    auto consume = [&](const Batch& b, const uint4 (&v)[U][SEG], uint32_t tie) {
         float acc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -494,25 +511,26 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
                 for (int j = 0; j < RPI; ++j) {
                     const uint32_t r = u * RPI + j;
                     const float ck = read_lane(acc[u], j * LPR + LPR - 1);
-                    if (r < b.nr && ck >= top.thr) top.push(ck, b.grow + r);
+                    if (r < b.nr && ck >= top.thr) top.push(ck, read_lane(tie, (int)r));
                 }
             }
-            if (top.pcount > 64 - RPB) top.flush(order, p.kprime);   // room for a whole batch stays free
+            if (top.pcount > 64 - RPB) top.flush(p.kprime);   // room for a whole batch stays free
         }
     };
 
     IVF_TRACE_MARK(31);
     uint4 va[U][SEG], vb[U][SEG];
+    uint32_t ta = 0, tb = 0;
     Batch ba = next_batch(cur, p, qi, RPB, row_bytes);
-    if (ba.nr) issue(ba, va);
+    if (ba.nr) issue(ba, va, ta);
     while (ba.nr) {
         Batch bb = next_batch(cur, p, qi, RPB, row_bytes);
-        if (bb.nr) issue(bb, vb);
-        consume(ba, va);
+        if (bb.nr) issue(bb, vb, tb);
+        consume(ba, va, ta);
         if (!bb.nr) break;
         ba = next_batch(cur, p, qi, RPB, row_bytes);
-        if (ba.nr) issue(ba, va);
-        consume(bb, vb);
+        if (ba.nr) issue(ba, va, ta);
+        consume(bb, vb, tb);
     }
     IVF_TRACE_MARK(32);
     __syncthreads();          // orders the zeroing of lds.ctl before its use
@@ -535,9 +553,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
     const int esz = p.dtype == 0 ? 4 : 2;
     const size_t row_bytes = (size_t)p.d * esz;
     Cursor cur = start_cursor(p, qi);
-    WaveTopK<KL> top;
+    WaveTopK<KL, false> top;
     top.init();
-    const RowOrder order{p.ids};
     for (Batch b = next_batch(cur, p, qi, 4, row_bytes); b.nr; b = next_batch(cur, p, qi, 4, row_bytes)) {
         for (uint32_t r = 0; r < b.nr; ++r) {
             const unsigned char* rp = b.rows + (size_t)r * row_bytes;
@@ -555,8 +572,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
             s = group_total_last_lane<64>(s);
             float ck = read_lane(METRIC == 0 ? s : -s, 63);
             if (ck >= top.thr) {
-                top.push(ck, b.grow + r);
-                if (top.pcount == 64) top.flush(order, p.kprime);
+                top.push(ck, p.idrank ? p.idrank[b.grow + r] : b.grow + r);
+                if (top.pcount == 64) top.flush(p.kprime);
             }
         }
     }
@@ -645,110 +662,104 @@ hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t e0, hipEvent
 // all workgroup lists, re-scores those rows in fp64 from the stored rows, adds the host's
 // candidates (already fp64), orders everything by (score, id) and writes the k nearest.
 // =============================================================================================
-constexpr int kMergeCandCap = 4096;    // loose candidates the fast path can hold in LDS
-constexpr int kMergeFastWaves = 8;
+constexpr int kMergeCandCap = 4096;    // kprime^2 for the largest kprime of the fast path
+constexpr int kMergeFastThreads = 1024;
 
 struct MergeLds {
     uint32_t hist[256];
     uint32_t sh[8];
-    uint32_t c_row[kMaxKPrime];
+    Cand c_cand[kMaxKPrime];
     double f_key[2 * kMaxKPrime];
     int64_t f_id[2 * kMaxKPrime];
-    unsigned long long best;
 };
 
-// Fast path (kprime <= 64).  Every list is sorted, so with T0 = the kprime-th best list head,
-// only entries >= T0 of lists whose head is >= T0 can be among the kprime best: a few hundred
-// at most.  Those are gathered, sorted in chunks of 64 and merged.  Returns false (uniformly)
-// when equal keys make the gathered set overflow its buffer.
-__device__ __forceinline__ bool gather_fast(const MergeArgs& a, const float* pk, const uint32_t* pr,
-                                            MergeLds& L, float* cand_key, uint32_t* cand_row,
+// Fast path (kprime <= 64).  Every list is sorted and candidates are distinct, so with T0 = the
+// kprime-th best list head, only entries >= T0 of the (at most kprime) lists whose head is
+// >= T0 can be among the kprime best.  Those are gathered, sorted in chunks of 64 and merged.
+// `pool` holds kMergeCandCap candidates, `qlist` 64 list numbers.
+__device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part, MergeLds& L, Cand* pool,
                                             uint32_t* qlist) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id(), nw = nt >> 6;
     const int kp = a.kprime, np = a.nparts;
-    const RowOrder order{a.ids};
     // 1. T0 from the list heads
-    WaveTopK<1> ht;
-    ht.init();
-    for (int c0 = wave * 64; c0 < np; c0 += nw * 64) {
-        int l = c0 + lane;
-        RowCand h = l < np ? RowCand{pk[(size_t)l * kp], pr[(size_t)l * kp]} : empty_row_cand();
-        if (h.r == kNoRow) h.k = -INFINITY;
-        bitonic_sort64(h, order);
-        if (read_lane(h.r, 0) != kNoRow && read_lane(h.k, 0) >= ht.thr) ht.merge_run(h, order, kp);
-    }
-    float* run_key = cand_key;               // the candidate buffer is free until step 2
-    uint32_t* run_row = cand_row;
-    if (wave > 0) { run_key[(wave - 1) * 64 + lane] = ht.top[0].k; run_row[(wave - 1) * 64 + lane] = ht.top[0].r; }
     if (tid == 0) { L.sh[4] = 0; L.sh[5] = 0; }
-    __syncthreads();
+    Cand best = 0, first_head = 0;
+#pragma unroll 1
+    for (int c0 = wave * 64; c0 < np; c0 += nw * 64) {
+        const int l = c0 + lane;
+        const Cand h = l < np ? part[(size_t)l * kp] : (Cand)0;
+        if (c0 == wave * 64) first_head = h;
+        best = merge_best64<true>(best, bitonic_sort64<true>(h));
+    }
+    const int busy = min(nw, (np + 63) / 64);       // wavefronts that hold heads
+#pragma unroll 1
+    for (int stride = 1; stride < busy; stride <<= 1) {
+        const bool sender = (wave % (2 * stride)) == stride && wave < busy;
+        const bool receiver = (wave % (2 * stride)) == 0 && wave + stride < busy;
+        if (sender) pool[wave * 64 + lane] = best;
+        __syncthreads();
+        if (receiver) best = merge_best64<true>(best, pool[(wave + stride) * 64 + lane]);
+        __syncthreads();
+    }
     if (wave == 0) {
-        for (int w = 0; w < nw - 1; ++w) {
-            RowCand run{run_key[w * 64 + lane], run_row[w * 64 + lane]};
-            if (read_lane(run.r, 0) != kNoRow && read_lane(run.k, 0) >= ht.thr) ht.merge_run(run, order, kp);
-        }
-        if (lane == 0) L.sh[6] = __float_as_uint(ht.thr);
+        const Cand t = read_lane(best, kp - 1);
+        if (lane == 0) { L.sh[6] = (uint32_t)t; L.sh[7] = (uint32_t)(t >> 32); }
     }
     __syncthreads();
-    const float t0 = __uint_as_float(L.sh[6]);
-    // 2. lists whose head reaches T0, then their entries that reach T0
+    const Cand t0 = ((uint64_t)L.sh[7] << 32) | L.sh[6];     // 0 when fewer than kprime lists have entries
+    // 2. the lists whose head reaches T0 ...
+#pragma unroll 1
     for (int l = tid; l < np; l += nt) {
-        if (pr[(size_t)l * kp] != kNoRow && pk[(size_t)l * kp] >= t0) {
-            uint32_t p = atomicAdd(&L.sh[5], 1u);
-            if (p < 1024) qlist[p] = l;
-        }
+        const Cand h = l == tid ? first_head : part[(size_t)l * kp];
+        if (h != 0 && h >= t0) qlist[atomicAdd(&L.sh[5], 1u)] = (uint32_t)l;
     }
     __syncthreads();
-    const uint32_t nql = L.sh[5];
-    if (nql > 1024) return false;
-    for (uint32_t i = wave; i < nql; i += nw) {
-        const size_t o = (size_t)qlist[i] * kp;
-        float k = lane < kp ? pk[o + lane] : -INFINITY;
-        uint32_t r = lane < kp ? pr[o + lane] : kNoRow;
-        bool ok = r != kNoRow && k >= t0;
-        uint64_t b = __ballot(ok);
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(&L.sh[4], (uint32_t)__popcll(b));
-        base = read_lane(base, 0);
-        uint32_t p = base + __popcll(b & ((1ull << lane) - 1ull));
-        if (ok && p < (uint32_t)kMergeCandCap) { cand_key[p] = k; cand_row[p] = r; }
+    const int nql = (int)L.sh[5];
+    // ... and their entries that reach it, one entry per thread
+#pragma unroll 1
+    for (int e0 = 0; e0 < nql * kp; e0 += nt) {
+        const int e = e0 + tid;
+        Cand c = 0;
+        if (e < nql * kp) c = part[(size_t)qlist[e / kp] * kp + e % kp];
+        const bool ok = c != 0 && c >= t0;
+        const uint64_t b = __ballot(ok);
+        if (b) {
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(&L.sh[4], (uint32_t)__popcll(b));
+            base = read_lane(base, 0);
+            if (ok) pool[base + __popcll(b & ((1ull << lane) - 1ull))] = c;
+        }
     }
     __syncthreads();
     const uint32_t cnt = L.sh[4];
-    if (cnt > (uint32_t)kMergeCandCap) return false;
     // 3. sort the gathered candidates in chunks of 64, merge the chunks
     const int nchunks = (int)((cnt + 63) / 64);
+#pragma unroll 1
     for (int c = wave; c < nchunks; c += nw) {
-        uint32_t e = c * 64 + lane;
-        RowCand x = e < cnt ? RowCand{cand_key[e], cand_row[e]} : empty_row_cand();
-        bitonic_sort64(x, order);
-        cand_key[e] = x.k; cand_row[e] = x.r;
+        const uint32_t e = c * 64 + lane;
+        pool[e] = bitonic_sort64<true>(e < cnt ? pool[e] : (Cand)0);
     }
     __syncthreads();
     if (wave == 0) {
-        WaveTopK<1> ft;
-        ft.init();
-        for (int c = 0; c < nchunks; ++c) {
-            RowCand run{cand_key[c * 64 + lane], cand_row[c * 64 + lane]};
-            if (read_lane(run.k, 0) >= ft.thr) ft.merge_run(run, order, kp);
-        }
-        bool ok = lane < kp && ft.top[0].r != kNoRow;
-        if (ok) L.c_row[lane] = ft.top[0].r;          // valid entries form a prefix
-        uint32_t m = (uint32_t)__popcll(__ballot(ok));
+        Cand top = nchunks > 0 ? pool[lane] : (Cand)0;      // nothing gathered: the pool holds no candidates
+#pragma unroll 1
+        for (int c = 1; c < nchunks; ++c) top = merge_best64<true>(top, pool[c * 64 + lane]);
+        const bool ok = lane < kp && top != 0;          // valid entries form a prefix
+        if (ok) L.c_cand[lane] = top;
+        const uint32_t m = (uint32_t)__popcll(__ballot(ok));
         if (lane == 0) L.sh[4] = m;
     }
     __syncthreads();
-    return true;
 }
 
-// General path: radix select over all entries of all lists.
-__device__ __forceinline__ void gather_radix(const MergeArgs& a, const float* pk, const uint32_t* pr, MergeLds& L) {
+// General path: radix select over all entries of all lists (candidates are distinct, so the
+// selection ends with exactly kprime of them).
+__device__ __forceinline__ void gather_radix(const MergeArgs& a, const Cand* part, MergeLds& L) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
     const uint32_t n = (uint32_t)a.nparts * a.kprime, kp = a.kprime;
-    // ascending radix key = best first; all ones = empty entry
-    auto key_at = [&](uint32_t i) { return pr[i] == kNoRow ? 0xFFFFFFFFu : ~ordered(pk[i]); };
+    auto key_at = [&](uint32_t i) { return ~part[i]; };      // ascending = best first; all ones = empty
     uint32_t my_valid = 0;
-    for (uint32_t i = tid; i < n; i += nt) my_valid += key_at(i) != 0xFFFFFFFFu;
+    for (uint32_t i = tid; i < n; i += nt) my_valid += part[i] != 0;
     if (tid == 0) { L.sh[4] = 0; L.sh[5] = 0; }
     __syncthreads();
 #pragma unroll
@@ -758,120 +769,128 @@ __device__ __forceinline__ void gather_radix(const MergeArgs& a, const float* pk
     const uint32_t n_valid = L.sh[5];
     if (n_valid <= kp) {
         for (uint32_t i = tid; i < n; i += nt)
-            if (key_at(i) != 0xFFFFFFFFu) { uint32_t p = atomicAdd(&L.sh[4], 1u); L.c_row[p] = pr[i]; }
+            if (part[i] != 0) L.c_cand[atomicAdd(&L.sh[4], 1u)] = part[i];
         __syncthreads();
         return;
     }
-    uint32_t mask, prefix, need, group;
-    block_radix_select<uint32_t>(key_at, n, kp, L.hist, L.sh, mask, prefix, need, group);
-    const bool take_group = need == group;
+    uint64_t mask, prefix; uint32_t need, group;
+    block_radix_select<uint64_t>(key_at, n, kp, L.hist, L.sh, mask, prefix, need, group);
+    // need == group here: distinct keys leave a boundary group of one
     for (uint32_t i = tid; i < n; i += nt) {
-        uint32_t k = key_at(i);
-        uint32_t hi = k & mask;
-        if (k != 0xFFFFFFFFu && (hi < prefix || (take_group && hi == prefix))) {
+        const uint64_t key = key_at(i);
+        if (key != ~0ull && (key & mask) <= prefix) {
             uint32_t p = atomicAdd(&L.sh[4], 1u);
-            L.c_row[p] = pr[i];
+            if (p < (uint32_t)kMaxKPrime) L.c_cand[p] = part[i];
         }
     }
     __syncthreads();
-    if (!take_group) {
-        // boundary group of bit-identical fp32 keys: keep the `need` smallest ids, one at a time
-        long long last = -1;
-        for (uint32_t it = 0; it < need; ++it) {
-            if (tid == 0) L.best = ~0ull;
-            __syncthreads();
-            for (uint32_t i = tid; i < n; i += nt) {
-                uint32_t k = key_at(i);
-                if (k != 0xFFFFFFFFu && (k & mask) == prefix) {
-                    long long id = a.ids ? a.ids[pr[i]] : (long long)pr[i];
-                    if (id > last) atomicMin(&L.best, (unsigned long long)id);
+}
+
+// Partial fp64 score of one stored row over the 16-byte chunks sub, sub + lpc, ... (lane `sub`
+// of a group of `lpc` lanes); four loads are in flight at a time.
+template <typename T>
+__device__ __forceinline__ double rescore_partial(const unsigned char* row, const float* q, int d, int metric,
+                                                  int sub, int lpc) {
+    constexpr int EPL = T::kPerLoad;
+    constexpr int U = 4;
+    const int chunks = d / EPL;
+    double acc = 0.0;
+#pragma unroll 1
+    for (int c0 = sub; c0 < chunks; c0 += lpc * U) {
+        uint4 v[U];
+        float qv[U][EPL];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = min(c0 + u * lpc, chunks - 1);
+            v[u] = *(const uint4*)(row + (size_t)c * 16);
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) *(float4*)&qv[u][e] = *(const float4*)(q + (size_t)c * EPL + e);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (c0 + u * lpc < chunks) {
+                float x[EPL];
+                Unpack<T>::run(v[u], x);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    const double qd = (double)qv[u][e], y = (double)x[e];
+                    if (metric == 0) acc = fma(qd, y, acc);
+                    else { const double df = qd - y; acc = fma(df, df, acc); }
                 }
             }
-            __syncthreads();
-            unsigned long long b = L.best;
-            if (b == ~0ull) break;
-            last = (long long)b;
-            for (uint32_t i = tid; i < n; i += nt) {
-                uint32_t k = key_at(i);
-                if (k != 0xFFFFFFFFu && (k & mask) == prefix) {
-                    long long id = a.ids ? a.ids[pr[i]] : (long long)pr[i];
-                    if (id == last) { uint32_t p = atomicAdd(&L.sh[4], 1u); if (p < kMaxKPrime) L.c_row[p] = pr[i]; }
-                }
-            }
-            __syncthreads();
         }
     }
-    __syncthreads();
+    return acc;
 }
 
 __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int fast) {
     extern __shared__ unsigned char m_dyn[];
     __shared__ MergeLds L;
     const int tid = threadIdx.x, nt = blockDim.x;
-    const int lane = lane_id(), wave = wave_id();
+    const int lane = lane_id();
     const int qi = blockIdx.x;
     const uint32_t n = (uint32_t)a.nparts * a.kprime;
-    const float* pk = a.part_key + (size_t)qi * n;
-    const uint32_t* pr = a.part_row + (size_t)qi * n;
+    const Cand* part = a.part + (size_t)qi * n;
     const uint32_t kp = a.kprime;
 
     IVF_TRACE_MARK(20);
     // 1. the kprime best fp32 candidates
-    bool done = false;
     if (fast) {
-        float* cand_key = (float*)m_dyn;
-        uint32_t* cand_row = (uint32_t*)(cand_key + kMergeCandCap);
-        uint32_t* qlist = cand_row + kMergeCandCap;
-        done = gather_fast(a, pk, pr, L, cand_key, cand_row, qlist);
+        Cand* pool = (Cand*)m_dyn;
+        gather_fast(a, part, L, pool, (uint32_t*)(pool + kMergeCandCap));
+    } else {
+        gather_radix(a, part, L);
     }
-    if (!done) gather_radix(a, pk, pr, L);
     const uint32_t m = min(L.sh[4], (uint32_t)kMaxKPrime);
     IVF_TRACE_MARK(23);
 
-    // 2. fp64 re-score, one wavefront per candidate
+    // 2. fp64 re-score: a group of lpc lanes per candidate, all candidates at once
     const float* q = a.q + (size_t)qi * a.d;
     const int np = a.nprobe;
-    const int64_t* s_base = a.slots.base + (size_t)qi * np;
-    const uint32_t* s_grow = a.slots.grow + (size_t)qi * np;
-    const uint32_t* s_n = a.slots.nrows + (size_t)qi * np;
     const size_t row_bytes = (size_t)a.d * (a.dtype == 0 ? 4 : 2);
-    for (uint32_t c = wave; c < m; c += nt / 64) {
-        const uint32_t row = L.c_row[c];
+    int lpc = 64;
+    while (lpc > 1 && (uint32_t)(nt / lpc) < m) lpc >>= 1;
+    const int sub = tid % lpc;
+#pragma unroll 1
+    for (uint32_t c = (uint32_t)(tid / lpc); c < m; c += (uint32_t)(nt / lpc)) {
+        const uint32_t rank = cand_tie(L.c_cand[c]);
+        const uint32_t row = a.rowof ? a.rowof[rank] : rank;
         const int64_t id = a.ids ? a.ids[row] : (int64_t)row;
         size_t brow = row;
         bool found_row = true;
         if (!a.identity) {
-            // find the slot whose global row range holds `row`
+            // the slot whose global row range holds the row
+            const int64_t* s_base = a.slots.base + (size_t)qi * np;
+            const uint32_t* s_grow = a.slots.grow + (size_t)qi * np;
+            const uint32_t* s_n = a.slots.nrows + (size_t)qi * np;
             int found = -1;
-            for (int s0 = 0; s0 < np && found < 0; s0 += 64) {
-                int s = s0 + lane;
-                bool hit = s < np && row >= s_grow[s] && row - s_grow[s] < s_n[s];
-                uint64_t b = __ballot(hit);
-                if (b) found = s0 + __ffsll((long long)b) - 1;
-            }
+#pragma unroll 1
+            for (int s = sub; s < np; s += lpc)
+                if (row >= s_grow[s] && row - s_grow[s] < s_n[s]) found = s;
+#pragma unroll 1
+            for (int o = 1; o < lpc; o <<= 1) found = max(found, __shfl_xor(found, o));
             found_row = found >= 0;
-            if (found_row) brow = (size_t)(s_base[found] + (int64_t)(row - s_grow[found]));
+            brow = found_row ? (size_t)(s_base[found] + (int64_t)(row - s_grow[found])) : 0;
         }
-        double acc = 0.0;
-        if (found_row) {
-            const unsigned char* rp = (const unsigned char*)a.buf + brow * row_bytes;
-            if (row_bytes % 16 == 0) {
-                if (a.dtype == 0) acc = rescore_chunks<F32>(rp, q, a.d, a.metric);
-                else if (a.dtype == 1) acc = rescore_chunks<F16>(rp, q, a.d, a.metric);
-                else acc = rescore_chunks<BF16>(rp, q, a.d, a.metric);
-            } else {
-                const size_t e0 = brow * (size_t)a.d;
-                for (int t = lane; t < a.d; t += 64) {
-                    double x = (double)q[t];
-                    double y = widen(a.buf, a.dtype, e0 + t);
-                    if (a.metric == 0) acc = fma(x, y, acc);
-                    else { double df = x - y; acc = fma(df, df, acc); }
-                }
-                acc = wave_sum(acc);
+        const unsigned char* rp = (const unsigned char*)a.buf + brow * row_bytes;
+        double s = 0.0;
+        if (row_bytes % 16 == 0) {
+            if (a.dtype == 0) s = rescore_partial<F32>(rp, q, a.d, a.metric, sub, lpc);
+            else if (a.dtype == 1) s = rescore_partial<F16>(rp, q, a.d, a.metric, sub, lpc);
+            else s = rescore_partial<BF16>(rp, q, a.d, a.metric, sub, lpc);
+        } else {
+            const size_t e0 = brow * (size_t)a.d;
+#pragma unroll 1
+            for (int t = sub; t < a.d; t += lpc) {
+                const double x = (double)q[t], y = widen(a.buf, a.dtype, e0 + t);
+                if (a.metric == 0) s = fma(x, y, s);
+                else { const double df = x - y; s = fma(df, df, s); }
             }
         }
-        if (lane == 0) {
-            L.f_key[c] = !found_row ? -INFINITY : (a.metric == 0 ? acc : -acc);
+#pragma unroll 1
+        for (int o = 1; o < lpc; o <<= 1) s += __shfl_xor(s, o);
+        if (sub == 0) {
+            L.f_key[c] = !found_row ? -INFINITY : (a.metric == 0 ? s : -s);
             L.f_id[c] = id;
         }
     }
@@ -892,6 +911,7 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     if ((uint32_t)tid < tot) {
         double mk = L.f_key[tid]; int64_t mi = L.f_id[tid];
         uint32_t rank = 0;
+#pragma unroll 1
         for (uint32_t j = 0; j < tot; ++j) {
             double ok = L.f_key[j]; int64_t oi = L.f_id[j];
             rank += (ok > mk) || (ok == mk && oi < mi);
@@ -911,8 +931,8 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     const size_t n = (size_t)a.nparts * a.kprime;
     const int fast = a.kprime <= 64;
-    const int threads = fast ? kMergeFastWaves * 64 : (n <= 8192 ? 256 : kSelectThreads);
-    const size_t lds = fast ? (size_t)kMergeCandCap * 8 + 1024 * 4 : 0;
+    const int threads = fast ? kMergeFastThreads : (n <= 8192 ? 256 : kSelectThreads);
+    const size_t lds = fast ? (size_t)kMergeCandCap * 8 + 64 * 4 : 0;
     IVF_LAUNCH(merge_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, fast);
     return hipGetLastError();
 }
