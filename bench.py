@@ -316,8 +316,10 @@ def main():
     ap.add_argument("--n", type=int, default=1_000_000, help="rows of the datastore (default: the named config)")
     ap.add_argument("--nprobe", type=int, default=32)
     ap.add_argument("--k", type=int, default=10)
-    ap.add_argument("--depth", type=int, default=4,
-                    help="independent searches kept in flight (ivf_set_pipeline_depth); 1 = strictly one after another")
+    ap.add_argument("--depth", type=int, default=0,
+                    help="independent searches kept in flight (ivf_set_pipeline_depth); 1 = strictly one after "
+                         "another; 0 = try 2, 4, 6 and 8 in short untimed runs and keep the fastest (how HIP maps "
+                         "streams to hardware queues makes some depths overlap better than others)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic for scaling rocprofv3 counters)")
     ap.add_argument("--no-events", action="store_true",
@@ -350,6 +352,14 @@ def main():
     q_dev = q_out.contiguous()
     ids_dev = torch.empty(nq, args.k, dtype=torch.int64, device="cuda")
     dists_dev = torch.empty(nq, args.k, dtype=torch.float32, device="cuda")
+    depth_trials = {}
+    if args.depth == 0:
+        for depth in (2, 4, 6, 8):
+            index.ivf_set_pipeline_depth(depth)
+            index.ivf_reserve(1, 1024, args.k)
+            t = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, 1500, 100)
+            depth_trials[depth] = round(1500 / t, 1)
+        args.depth = max(depth_trials, key=depth_trials.get)
     index.ivf_set_pipeline_depth(args.depth)
     index.ivf_reserve(1, 1024, args.k)
     torch.cuda.synchronize()
@@ -389,7 +399,8 @@ def main():
         "config": {"workload": f"configs[1] single-query retrieval: {args.n} x 768 fp32, 1024-component mixture, "
                                f"nlist 1024 (k-means on a tenth of the rows), nprobe {args.nprobe}, k {args.k}, "
                                f"batch 1, inner product, {nq} distinct queries cycled",
-                   "entry_point": "ivf_search_device", "searches_in_flight": args.depth, "seed": 20970},
+                   "entry_point": "ivf_search_device", "searches_in_flight": args.depth,
+                   "depth_trials_qps": depth_trials, "seed": 20970},
         "one_at_a_time": {"value": round(args.steps / dt1, 1), "ms_per_step": dt1 / args.steps * 1e3},
         "roofline": {"bound": "hbm", "achieved": round(prof["scan_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(prof["scan_gbs"] / HBM_PEAK_GBS, 4),

@@ -9,65 +9,153 @@ namespace ivf {
 using namespace dev;
 
 // =============================================================================================
-// Coarse scoring (App. B, first step): scores[q][j] = d(x_q, c_j) for every centroid, in fp64.
-// One wavefront per centroid row; the queries are staged in LDS and widened on use.
-// HBM-bound on the nlist*d*4 bytes of the centroid matrix.
+// Coarse scoring (App. B, first step): scores[q][j] = d(x_q, c_j) for every centroid, in fp64
+// (products of fp32 values are exact in fp64, so the selection below sees the same order as a
+// plain fp64 loop up to the last bits of the sums).
+//
+// Few queries: one wavefront per centroid row, all loads of a row and of the query requested
+// at once; HBM-bound on the nlist*d*4 bytes of the centroid matrix, in practice one memory
+// latency.  A batch of queries: a dense contraction Q x C^T on the fp64 matrix cores.
 // =============================================================================================
-constexpr int kCoarseQT = 4;   // queries sharing one pass over a centroid row
+constexpr int kCoarseRowMax = 16;          // batches below this use the row kernel
 constexpr int kSelectWaveSortMax = 4096;   // select: register sorting path up to this many clusters
 
-__global__ __launch_bounds__(256) void coarse_kernel(CoarseArgs a) {
-    extern __shared__ float qd[];    // [kCoarseQT][d]
+__global__ __launch_bounds__(256) void coarse_rows_kernel(CoarseArgs a) {
     const int lane = lane_id(), wave = wave_id();
-    const int q0 = blockIdx.y * kCoarseQT;
-    const int nqt = min(kCoarseQT, a.nq - q0);
-    for (int i = threadIdx.x; i < kCoarseQT * a.d; i += blockDim.x) {
-        int qq = i / a.d, t = i - qq * a.d;
-        qd[i] = qq < nqt ? a.q[(size_t)(q0 + qq) * a.d + t] : 0.f;
-    }
-    __syncthreads();
     const int row = blockIdx.x * 4 + wave;
     if (row >= a.nlist) return;
     const float* c = a.centroids + (size_t)row * a.d;
-    double acc[kCoarseQT];
+#pragma unroll 1
+    for (int qi = 0; qi < a.nq; ++qi) {
+        const float* q = a.q + (size_t)qi * a.d;
+        double acc = 0.0;
+        if ((a.d & 3) == 0) {
+#pragma unroll 1
+            for (int t0 = lane * 4; t0 < a.d; t0 += 1024) {
+                float4 cv[4], qv[4];
 #pragma unroll
-    for (int qq = 0; qq < kCoarseQT; ++qq) acc[qq] = 0.0;
-    if ((a.d & 3) == 0) {
-        for (int t0 = lane * 4; t0 < a.d; t0 += 256) {
-            float4 v = *(const float4*)(c + t0);
-            const double cv[4] = {(double)v.x, (double)v.y, (double)v.z, (double)v.w};
+                for (int u = 0; u < 4; ++u) {
+                    const int t = min(t0 + u * 256, a.d - 4);
+                    cv[u] = *(const float4*)(c + t);
+                    qv[u] = *(const float4*)(q + t);
+                }
 #pragma unroll
-            for (int qq = 0; qq < kCoarseQT; ++qq) {
+                for (int u = 0; u < 4; ++u) {
+                    if (t0 + u * 256 < a.d) {
+                        const float ce[4] = {cv[u].x, cv[u].y, cv[u].z, cv[u].w};
+                        const float qe[4] = {qv[u].x, qv[u].y, qv[u].z, qv[u].w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    double x = (double)qd[qq * a.d + t0 + e];
-                    if (a.metric == 0) acc[qq] = fma(x, cv[e], acc[qq]);
-                    else { double df = x - cv[e]; acc[qq] = fma(df, df, acc[qq]); }
+                        for (int e = 0; e < 4; ++e) {
+                            const double x = (double)qe[e], y = (double)ce[e];
+                            if (a.metric == 0) acc = fma(x, y, acc);
+                            else { const double df = x - y; acc = fma(df, df, acc); }
+                        }
+                    }
                 }
             }
-        }
-    } else {
-        for (int t = lane; t < a.d; t += 64) {
-            double cv = (double)c[t];
-#pragma unroll
-            for (int qq = 0; qq < kCoarseQT; ++qq) {
-                double x = (double)qd[qq * a.d + t];
-                if (a.metric == 0) acc[qq] = fma(x, cv, acc[qq]);
-                else { double df = x - cv; acc[qq] = fma(df, df, acc[qq]); }
+        } else {
+            for (int t = lane; t < a.d; t += 64) {
+                const double x = (double)q[t], y = (double)c[t];
+                if (a.metric == 0) acc = fma(x, y, acc);
+                else { const double df = x - y; acc = fma(df, df, acc); }
             }
         }
+        const double s = wave_sum(acc);
+        if (lane == 0) a.scores[(size_t)qi * a.nlist + row] = s;
+    }
+}
+
+// Q x C^T with v_mfma_f64_16x16x4_f64.  Operand layout of the instruction: lane l supplies
+// A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16]; result register r of lane l is
+// C[i = 4 r + l / 16][j = l % 16].  A workgroup of four wavefronts covers (WQ * 32) queries by
+// ((4 / WQ) * 32) centroids, each wavefront 32 x 32 as 2 x 2 instruction tiles; fp32 operand
+// slabs of 32 k-values go through LDS (rows padded by 4 floats: the 64 lanes of a fragment
+// read then fall on 64 different (bank, half) positions) and are widened on use.  For the
+// squared distance the norms are accumulated beside the products: |q - c|^2 = |q|^2 + |c|^2 - 2 q.c.
+typedef double double4_t __attribute__((ext_vector_type(4)));
+constexpr int kCoarseKT = 32, kCoarseLd = kCoarseKT + 4;
+
+template <int WQ>
+__global__ __launch_bounds__(256) void coarse_mfma_kernel(CoarseArgs a) {
+    constexpr int WC = 4 / WQ, TQ = WQ * 32, TC = WC * 32;
+    __shared__ float sq[TQ * kCoarseLd];
+    __shared__ float sc[TC * kCoarseLd];
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    const int q0 = blockIdx.y * TQ, c0 = blockIdx.x * TC;
+    const int wq = (wave % WQ) * 32, wc = (wave / WQ) * 32;      // this wavefront's corner in the tile
+    const int fi = lane & 15, fk = lane >> 4;
+    double4_t acc[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int y = 0; y < 2; ++y) acc[x][y] = double4_t{0.0, 0.0, 0.0, 0.0};
+    double nq2[2] = {0.0, 0.0}, nc2[2] = {0.0, 0.0};
+#pragma unroll 1
+    for (int k0 = 0; k0 < a.d; k0 += kCoarseKT) {
+        // slabs: 8 float4 per row
+        for (int i = tid; i < TQ * 8; i += 256) {
+            const int r = i >> 3, k4 = (i & 7) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (q0 + r < a.nq && k0 + k4 < a.d) v = *(const float4*)(a.q + (size_t)(q0 + r) * a.d + k0 + k4);
+            *(float4*)&sq[r * kCoarseLd + k4] = v;
+        }
+        for (int i = tid; i < TC * 8; i += 256) {
+            const int r = i >> 3, k4 = (i & 7) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c0 + r < a.nlist && k0 + k4 < a.d) v = *(const float4*)(a.centroids + (size_t)(c0 + r) * a.d + k0 + k4);
+            *(float4*)&sc[r * kCoarseLd + k4] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < kCoarseKT; ks += 4) {
+            double fa[2], fb[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                fa[x] = (double)sq[(wq + x * 16 + fi) * kCoarseLd + ks + fk];
+                fb[x] = (double)sc[(wc + x * 16 + fi) * kCoarseLd + ks + fk];
+                nq2[x] = fma(fa[x], fa[x], nq2[x]);
+                nc2[x] = fma(fb[x], fb[x], nc2[x]);
+            }
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int y = 0; y < 2; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[x], fb[y], acc[x][y], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // norms: sum over the four k-groups of lanes; then lane l holds the norm of row l % 16
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        nq2[x] += __shfl_xor(nq2[x], 16); nq2[x] += __shfl_xor(nq2[x], 32);
+        nc2[x] += __shfl_xor(nc2[x], 16); nc2[x] += __shfl_xor(nc2[x], 32);
     }
 #pragma unroll
-    for (int qq = 0; qq < kCoarseQT; ++qq) {
-        double s = wave_sum(acc[qq]);
-        if (lane == 0 && qq < nqt) a.scores[(size_t)(q0 + qq) * a.nlist + row] = s;
+    for (int x = 0; x < 2; ++x) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = 4 * r + fk;                      // row of result register r inside the 16 x 16 tile
+            const double qn = __shfl(nq2[x], i);
+            const int qi = q0 + wq + x * 16 + i;
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                const int cj = c0 + wc + y * 16 + fi;
+                const double dot = acc[x][y][r];
+                const double s = a.metric == 0 ? dot : fma(-2.0, dot, qn + nc2[y]);
+                if (qi < a.nq && cj < a.nlist) a.scores[(size_t)qi * a.nlist + cj] = s;
+            }
+        }
     }
 }
 
 hipError_t launch_coarse(const CoarseArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-    dim3 grid((a.nlist + 3) / 4, (a.nq + kCoarseQT - 1) / kCoarseQT);
-    size_t lds = sizeof(float) * kCoarseQT * a.d;
-    IVF_LAUNCH(coarse_kernel, grid, dim3(256), lds, s, e0, e1, a);
+    if (a.nq < kCoarseRowMax || (a.d & 3) != 0) {
+        IVF_LAUNCH(coarse_rows_kernel, dim3((a.nlist + 3) / 4), dim3(256), 0, s, e0, e1, a);
+    } else if (a.nq < 48) {
+        IVF_LAUNCH(coarse_mfma_kernel<1>, dim3((a.nlist + 127) / 128, (a.nq + 31) / 32), dim3(256), 0, s, e0, e1, a);
+    } else {
+        IVF_LAUNCH(coarse_mfma_kernel<2>, dim3((a.nlist + 63) / 64, (a.nq + 63) / 64), dim3(256), 0, s, e0, e1, a);
+    }
     return hipGetLastError();
 }
 
@@ -168,12 +256,25 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
             const uint64_t low = read_lane(best, 63) >> 24;
             tie_cut |= __ballot(dropped != 0 && (dropped >> 24) == low) != 0;
         };
+        auto packed = [&](int i, double s) {
+            return (~coarse_key(s, a.metric) & ~0xFFFFFFull) | (uint64_t)(0xFFFFFFu - (uint32_t)i);
+        };
+        // the first four chunks of a wavefront are requested together
+        double s4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = (wave + j * nw) * 64 + lane;
+            s4[j] = i < a.nlist ? sc[i] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = (wave + j * nw) * 64 + lane;
+            if ((wave + j * nw) * 64 < a.nlist) fold(bitonic_sort64<true>(i < a.nlist ? packed(i, s4[j]) : (Cand)0));
+        }
 #pragma unroll 1
-        for (int c0 = wave * 64; c0 < a.nlist; c0 += nw * 64) {
+        for (int c0 = (wave + 4 * nw) * 64; c0 < a.nlist; c0 += nw * 64) {
             const int i = c0 + lane;
-            Cand c = 0;
-            if (i < a.nlist) c = (~coarse_key(sc[i], a.metric) & ~0xFFFFFFull) | (uint64_t)(0xFFFFFFu - (uint32_t)i);
-            fold(bitonic_sort64<true>(c));
+            fold(bitonic_sort64<true>(i < a.nlist ? packed(i, sc[i]) : (Cand)0));
         }
         Cand* run = (Cand*)(((uintptr_t)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4) + 15) & ~(uintptr_t)15);
 #pragma unroll 1
@@ -302,7 +403,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
     int in_lds = pad <= (uint32_t)kSortLdsCap;
     int prefix_in_lds = a.nprobe <= kPrefixLdsCap;
     // a workgroup with one wavefront per SIMD issues fastest when there is little work per thread
-    const int threads = a.nlist <= 4096 && a.grid <= 1024 ? 256 : kSelectThreads;
+    const int threads = a.nlist < 1024 && a.grid <= 1024 ? 256 : kSelectThreads;
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
     if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64) * 64 * 8;
     IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds);
@@ -405,8 +506,10 @@ __device__ __forceinline__ void finish_workgroup(WaveTopK<KL, false>& top, const
     }
     __syncthreads();
     if (wave != 0) return;
+    int nchunks_done = 0;
     const uint32_t lists = l.ctl[1];
     top.init();
+    if (KL == 1 && lists == 0 && nchunks == 1) { top.top[0] = l.pool[lane]; nchunks_done = 1; }
     for (int w = 0; w < kScanWaves; ++w) {
         if (!((lists >> w) & 1u)) continue;
 #pragma unroll
@@ -415,7 +518,7 @@ __device__ __forceinline__ void finish_workgroup(WaveTopK<KL, false>& top, const
             top.merge_run_if_useful(e < kp ? l.list[w * kp + e] : (Cand)0, kp);
         }
     }
-    for (int c = 0; c < nchunks; ++c) top.merge_run_if_useful(l.pool[c * 64 + lane], kp);
+    for (int c = nchunks_done; c < nchunks; ++c) top.merge_run_if_useful(l.pool[c * 64 + lane], kp);
     size_t o = ((size_t)qi * p.grid + blockIdx.x) * kp;
 #pragma unroll
     for (int j = 0; j < KL; ++j) {
@@ -792,7 +895,7 @@ template <typename T>
 __device__ __forceinline__ double rescore_partial(const unsigned char* row, const float* q, int d, int metric,
                                                   int sub, int lpc) {
     constexpr int EPL = T::kPerLoad;
-    constexpr int U = 4;
+    constexpr int U = EPL == 4 ? 6 : 4;        // 768 fp32 values over 32 lanes: one pass
     const int chunks = d / EPL;
     double acc = 0.0;
 #pragma unroll 1
@@ -911,7 +1014,7 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     if ((uint32_t)tid < tot) {
         double mk = L.f_key[tid]; int64_t mi = L.f_id[tid];
         uint32_t rank = 0;
-#pragma unroll 1
+#pragma unroll 6
         for (uint32_t j = 0; j < tot; ++j) {
             double ok = L.f_key[j]; int64_t oi = L.f_id[j];
             rank += (ok > mk) || (ok == mk && oi < mi);
