@@ -19,7 +19,10 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kTileRows = 128;     // rows per task: 4 wavefronts x 32 rows
+constexpr int kBatchWaves = 8;      // wavefronts of a batched scan workgroup
+constexpr int kBatchThreads = kBatchWaves * 64;
+constexpr int kTileRows = kBatchWaves * 32;     // rows per task: 32 per wavefront
+constexpr int kStageLd = 64 + 8;   // elements per row of a wavefront's staging area: 64 + padding
 constexpr int kGroupQ = 32;        // queries per task: one MFMA tile wide
 constexpr int kQPad = 8;           // padding (elements) of a staged query row in LDS
 
@@ -255,13 +258,15 @@ template <> struct Mfma<BF16> {
     }
 };
 
-// One workgroup (4 wavefronts) per task: 128 rows of one cluster against up to 32 of the queries
-// that probe it.  The queries (storage type) are staged in LDS once per (cluster, group); each
-// wavefront streams its 32 rows from HBM straight into MFMA A fragments (lane l: row l % 32, eight
-// elements per step) and reads the B fragments (lane l: query l % 32, the same elements) from LDS.  Scores that reach the query's threshold are appended to the
-// query's candidate list.
+// One workgroup (8 wavefronts) per task: 256 rows of one cluster against up to 32 of the queries
+// that probe it.  The queries (storage type) are staged in LDS once per (cluster, group).  Each
+// wavefront streams its 32 rows from HBM with coalesced loads (8 lanes cover one 128-byte line of
+// a row, an instruction 8 rows), turns each block of 64 elements into MFMA A fragments (lane l:
+// row l % 32, eight elements per step) through a small LDS area of its own, and reads the B
+// fragments (lane l: query l % 32, the same elements) from the staged queries.  Scores that reach
+// the query's threshold are appended to the query's candidate list.
 template <typename T>
-__global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
+__global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs a) {
     typedef typename Mfma<T>::frag frag;
     extern __shared__ unsigned char smem[];
     __shared__ uint32_t s_q[kGroupQ];
@@ -269,6 +274,7 @@ __global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
     const int lane = lane_id(), wave = wave_id();
     const int d = a.d, qstride = d + kQPad;
     uint16_t* qs = (uint16_t*)smem;                      // [kGroupQ][d + kQPad] storage-type queries
+    uint16_t* stage = qs + (size_t)kGroupQ * qstride + (size_t)wave * 32 * kStageLd;   // [32][kStageLd], this wavefront's
     const uint32_t total = a.tstart[a.nlist];
     const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
     const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
@@ -303,32 +309,45 @@ __global__ __launch_bounds__(256) void batched_scan_kernel(BatchedArgs a) {
         const uint32_t n = (uint32_t)(a.off[c + 1] - lo);
         const uint32_t r0 = task.tile * kTileRows + wave * 32;     // first row of this wavefront
         if (r0 >= n) continue;
-        const uint32_t my_row = min(r0 + (uint32_t)col, n - 1);    // rows past the end re-read the last one
-        // Element order inside the dot product is free, so MFMA step j of a 64-element block
-        // takes, for the lane half h, elements 32 h + 8 (j % 4) .. + 7 of the block: the four
-        // 16-byte loads a lane issues per block are consecutive (64 bytes), and the two lanes
-        // of a row cover one 128-byte line.
-        const uint16_t* arow = (const uint16_t*)a.lists + ((size_t)lo + my_row) * d + khalf * 32;
+        // Loading role of a lane: 16-byte chunk lane % 8 of rows lane / 8 + {0, 8, 16, 24} of each
+        // 64-element block (rows past the end re-read the last one).  Element order inside the dot
+        // product is free, so MFMA step j of a block takes, for the lane half h, elements
+        // 32 h + 8 j .. + 7 of the block from both operands.
+        const int lrow = lane >> 3, lchunk = lane & 7;
+        const uint16_t* lptr[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            lptr[u] = (const uint16_t*)a.lists + ((size_t)lo + min(r0 + (uint32_t)(lrow + 8 * u), n - 1)) * d + lchunk * 8;
         const uint16_t* brow = qs + (size_t)col * qstride + khalf * 32;
+        uint16_t* wpos = stage + lrow * kStageLd + lchunk * 8;
+        const uint16_t* rpos = stage + col * kStageLd + khalf * 32;
         float16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-        // two blocks (128 elements, 8 MFMA steps) per iteration, the next iteration's rows in flight
+        // two blocks (128 elements, 8 MFMA steps) per stage, the next stage's rows in flight
         uint4 av[2][8];
         auto issue = [&](int k0, uint4 (&v)[8]) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int k = k0 + (u / 4) * 64 + (u % 4) * 8;
-                v[u] = k < d ? *(const uint4*)(arow + k) : make_uint4(0, 0, 0, 0);
+            for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    v[b * 4 + u] = k0 + b * 64 < d ? load_stream16(lptr[u] + k0 + b * 64) : make_uint4(0, 0, 0, 0);
             }
         };
         auto consume = [&](int k0, const uint4 (&v)[8]) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int k = k0 + (u / 4) * 64 + (u % 4) * 8;
-                if (k < d) {
-                    uint4 bv = *(const uint4*)(brow + k);
-                    acc = Mfma<T>::run(__builtin_bit_cast(frag, v[u]), __builtin_bit_cast(frag, bv), acc);
+            for (int b = 0; b < 2; ++b) {
+                if (k0 + b * 64 < d) {
+                    // through LDS: written in the loading layout, read back as fragments.  A
+                    // wavefront's LDS operations complete in order, so no barrier is needed.
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) *(uint4*)(wpos + u * 8 * kStageLd) = v[b * 4 + u];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint4 av4 = *(const uint4*)(rpos + j * 8);
+                        const uint4 bv = *(const uint4*)(brow + k0 + b * 64 + j * 8);
+                        acc = Mfma<T>::run(__builtin_bit_cast(frag, av4), __builtin_bit_cast(frag, bv), acc);
+                    }
                 }
             }
         };
@@ -485,7 +504,9 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
 }
 
 // ---- launch sequence ---------------------------------------------------------------------------------------
-size_t batched_scan_lds(int d) { return (size_t)kGroupQ * (d + kQPad) * 2; }
+size_t batched_scan_lds(int d) {
+    return (size_t)kGroupQ * (d + kQPad) * 2 + (size_t)kBatchWaves * 32 * kStageLd * 2;
+}
 
 uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe) {
     // a cluster has at most min(nq, ...) queries; every cluster may be probed
@@ -503,7 +524,7 @@ size_t batched_thr_part_floats(int nq) { return (size_t)nq * kSampleParts * kMax
 int batched_resident_grid(int dtype, int d, int n_cu) {
     int per_cu = 0;
     const void* fn = dtype == 1 ? (const void*)batched_scan_kernel<F16> : (const void*)batched_scan_kernel<BF16>;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, batched_scan_lds(d));
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kBatchThreads, batched_scan_lds(d));
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (per_cu > 4) per_cu = 4;
     return per_cu * n_cu;
@@ -520,9 +541,9 @@ hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEven
     hipLaunchKernelGGL(fill_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);
     hipLaunchKernelGGL(make_tasks_kernel, dim3(min(a.nlist, 4096)), dim3(256), 0, s, a);
     if (a.dtype == 1)
-        IVF_LAUNCH(batched_scan_kernel<F16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
+        IVF_LAUNCH(batched_scan_kernel<F16>, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
     else
-        IVF_LAUNCH(batched_scan_kernel<BF16>, dim3(grid), dim3(256), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
+        IVF_LAUNCH(batched_scan_kernel<BF16>, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
     hipLaunchKernelGGL(batched_merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
     return hipGetLastError();
 }
