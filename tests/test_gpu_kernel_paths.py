@@ -1,0 +1,110 @@
+"""Parity of kernel variants the shape sweep does not reach: the matrix-core coarse kernels, the
+select kernel's exact redo when packed score prefixes tie, and the three ways id ranks arise."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2502_20969_amd as P
+from parity import check_topk
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def streams():
+    assert torch.cuda.is_available()
+    return torch.cuda.Stream(), torch.cuda.Stream()
+
+
+def _index(streams, cent, d, metric, seed=0):
+    """A small index over `cent`: two rows per cluster."""
+    rng = np.random.default_rng(seed)
+    nlist = cent.shape[0]
+    n = 2 * nlist
+    assign = (np.arange(n) % nlist).astype(np.int32)
+    rows = rng.standard_normal((n, d)).astype(np.float32)
+    return P.ivf_build_layout(rows, "f32", cent, assign, metric=metric,
+                              compute_stream=streams[0], copy_stream=streams[1])
+
+
+@pytest.mark.parametrize("nq", [16, 47, 48, 130])
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+@pytest.mark.parametrize("nlist,d", [(130, 36), (1000, 100), (257, 768)])
+def test_coarse_scores_of_a_batch(streams, nq, metric, nlist, d):
+    """16 or more queries go through the fp64 matrix-core kernels (two tile layouts); tiles are
+    ragged in queries, centroids and the k dimension."""
+    pm, om = (P.IVF_IP, O.IP) if metric == "ip" else (P.IVF_L2, O.L2)
+    rng = np.random.default_rng(1000 * nq + nlist + d)
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    index = _index(streams, cent, d, pm)
+    cs = index.ivf_coarse_scores(q)
+    pr = index.ivf_probe(q, 20)
+    for b in range(nq):
+        oc, osc = O.probe(cent, q[b], nlist, om, with_scores=True)
+        np.testing.assert_allclose(cs[b][oc], osc, rtol=1e-12, atol=1e-10)
+        assert list(pr[b]) == list(oc[:20]), f"query {b}: selected clusters differ"
+    index.close()
+
+
+@pytest.mark.parametrize("nprobe", [1, 10, 63, 64])
+def test_select_redoes_prefix_ties_exactly(streams, nprobe):
+    """Centroids that differ from one another by a few ulps of one small component have fp64 scores
+    that agree in far more than their leading 28 mantissa bits: the packed fast path cannot order
+    them and the exact path must take over, also when the tie straddles the cut at 64."""
+    rng = np.random.default_rng(5)
+    d, near, far = 16, 150, 100
+    base = rng.standard_normal(d).astype(np.float32)
+    base[0] = np.float32(1e-3)
+    cent = np.empty((near + far, d), dtype=np.float32)
+    step = np.float32(base[0])
+    for j in range(near):
+        cent[j] = base
+        cent[j, 0] = step
+        step = np.nextafter(step, np.float32(1.0), dtype=np.float32)
+    cent[near:] = 0.1 * rng.standard_normal((far, d)).astype(np.float32)
+    order = rng.permutation(near + far)
+    cent = np.ascontiguousarray(cent[order])
+    index = _index(streams, cent, d, P.IVF_IP)
+    q = np.stack([base + 0.01 * rng.standard_normal(d).astype(np.float32) for _ in range(4)]).astype(np.float32)
+    q[:, 0] = np.abs(q[:, 0]) + 0.5          # the varied component counts, with a fixed sign
+    pr = index.ivf_probe(q, nprobe)
+    for b in range(4):
+        oc, osc = O.probe(cent, q[b], nprobe, O.IP, with_scores=True)
+        assert list(pr[b]) == list(oc)
+        # the case is what it claims: neighbours in the oracle order agree to better than 2^-28
+        full = O.probe(cent, q[b], near + far, O.IP, with_scores=True)[1]
+        assert abs(full[1] - full[0]) < abs(full[0]) * 2.0 ** -30
+    index.close()
+
+
+@pytest.mark.parametrize("kind", ["increasing", "permutation", "sparse"])
+def test_id_rank_tables(streams, kind):
+    """Adopted layouts whose ids grow with the row (no rank table), are a permutation of the row
+    numbers (the permutation is the table) or are arbitrary distinct values (sorted).  Half of the
+    rows are exact duplicates, so equal scores must come out by smaller id."""
+    rng = np.random.default_rng(9)
+    n, d, nlist = 6000, 64, 12
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    assign = np.sort(rng.integers(0, nlist, n)).astype(np.int32)          # already cluster-major
+    rows = (cent[assign] + 0.5 * rng.standard_normal((n, d))).astype(np.float32)
+    src, dst = rng.integers(0, n, n // 2), rng.integers(0, n, n // 2)
+    rows[dst] = rows[src]
+    off = np.zeros(nlist + 1, dtype=np.int64)
+    off[1:] = np.cumsum(np.bincount(assign, minlength=nlist))
+    if kind == "increasing":
+        ids = np.cumsum(rng.integers(1, 5, n)).astype(np.int64)
+    elif kind == "permutation":
+        ids = rng.permutation(n).astype(np.int64)
+    else:
+        ids = (rng.permutation(n).astype(np.int64) * 1_000_003 + 17) % (1 << 40)
+        assert len(np.unique(ids)) == n
+    lists_dev = torch.from_numpy(rows).cuda()
+    index = P.ivf_adopt_layout(lists_dev, "f32", off, cent, ids=ids, metric=P.IVF_IP,
+                               compute_stream=streams[0], copy_stream=streams[1])
+    q = (cent[rng.integers(0, nlist, 6)] + 0.3 * rng.standard_normal((6, d))).astype(np.float32)
+    gi, gd = index.ivf_search(q, 5, 30)
+    for b in range(6):
+        assert check_topk(gi[b], gd[b], rows, O.F32, off, ids, cent, q[b], 5, 30, O.IP) == 0
+    index.close()
