@@ -23,7 +23,7 @@ C2_SCAN_TRAFFIC_BYTES = 89314 * 1024 + 48 * 1024
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
 
 
-def build_config2(device, n, seed=20970):
+def build_config2(device, n, seed=20970, metric="ip"):
     import torch
     import paper_2502_20969_amd as P
     import workloads as W
@@ -34,7 +34,8 @@ def build_config2(device, n, seed=20970):
     assign_host = ds.assign.cpu().numpy()
     cent_host = ds.centroids.cpu().numpy()
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
-    index = P.ivf_build_layout(rows_host, "f32", cent_host, assign_host, metric=P.IVF_IP,
+    index = P.ivf_build_layout(rows_host, "f32", cent_host, assign_host,
+                               metric=P.IVF_IP if metric == "ip" else P.IVF_L2,
                                compute_stream=compute, copy_stream=copy)
     info = {"gen_build_s": round(time.time() - t0, 2)}
     return index, compute, rows_host, assign_host, cent_host, q_in, q_out, info
@@ -86,7 +87,7 @@ def profile_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, k, steps):
     }
 
 
-def cpu_baseline(rows_host, assign_host, cent_host, q_out, nprobe, k, budget_s=12.0):
+def cpu_baseline(rows_host, assign_host, cent_host, q_out, nprobe, k, budget_s=12.0, metric="ip"):
     """The oracle as it stands, timed on the host cores over as many of the same queries as fit
     the time budget (at least 4)."""
     import numpy as np
@@ -98,7 +99,8 @@ def cpu_baseline(rows_host, assign_host, cent_host, q_out, nprobe, k, budget_s=1
     done, t0 = 0, time.perf_counter()
     results = []
     while done < q.shape[0] and (done < 4 or time.perf_counter() - t0 < budget_s):
-        results.append(O.search(lists, O.F32, off, perm, cent_host, q[done], nprobe, k, O.IP))
+        results.append(O.search(lists, O.F32, off, perm, cent_host, q[done], nprobe, k,
+                                O.IP if metric == "ip" else O.L2))
         done += 1
     dt = time.perf_counter() - t0
     return {"value": done / dt, "unit": "queries/s", "cores": O.threads(), "kind": "oracle",
@@ -308,6 +310,119 @@ def run_batched(args):
     print(json.dumps(out))
 
 
+def run_paper_shape(args):
+    """A resident datastore of the size and shape the paper evaluates on (Sec. 5 set-up: 21 M x 768
+    fp32 rows, 4096 clusters, inner product, top-3 retrieval), here with seeded synthetic rows and
+    Zipf(1.1) list sizes: nprobe sweep 64..1024 at batch 1, and batches of 2, 4 and 8 independent
+    queries per call at nprobe 256.  Parity on sampled queries: the oracle scans, on the host, copies
+    of exactly the lists it selects.  One JSON line."""
+    import numpy as np
+    import torch
+    import paper_2502_20969_amd as P
+    import workloads as W
+    torch.cuda.set_device(0)
+    n = int(21_000_000 * args.scale)
+    d, nlist, k, nq = 768, 4096, 3, 64
+    t0 = time.time()
+    sizes = W.zipf_sizes(n, nlist, 1.1, 20985)
+    ds = W.cluster_major_datastore(sizes, d, 0.3, 20986, dtype="f32", device="cuda", chunk=1 << 20)
+    pick = torch.randint(0, n, (4096,), generator=torch.Generator().manual_seed(20987)).cuda()
+    _, q_out = W.query_pairs(ds.rows[pick], nq, 0.3, 20988)
+    torch.cuda.synchronize()
+    print(f"[n1] datastore of {n * d * 4 / 1e9:.1f} GB ready after {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    cent_np = ds.centroids.cpu().numpy()
+    index = P.ivf_adopt_layout(ds.rows, "f32", ds.offsets, cent_np, metric=P.IVF_IP,
+                               compute_stream=compute, copy_stream=copy)
+    ids = torch.empty(nq, k, dtype=torch.int64, device="cuda")
+    dists = torch.empty(nq, k, dtype=torch.float32, device="cuda")
+    index.ivf_reserve(8, 1024, k)
+
+    def run(nprobe, B, depth, steps):
+        index.ivf_set_pipeline_depth(depth)
+        index.ivf_reserve(B, 1024, k)
+        def one(i):
+            j = (i * B) % nq
+            index.ivf_search_device(q_out[j:j + B], nprobe, k, ids[j:j + B], dists[j:j + B])
+        for i in range(8):
+            one(i)
+        index.ivf_synchronize()
+        t = time.perf_counter()
+        for i in range(steps):
+            one(8 + i)
+        index.ivf_synchronize()
+        dt = time.perf_counter() - t
+        index.ivf_set_pipeline_depth(1)
+        index.ivf_reserve(B, 1024, k)
+        if not NO_EVENTS:
+            index.ivf_profile_enable(True); index.ivf_profile_reset()
+        for i in range(min(steps, 64)):
+            one(i)
+        index.ivf_synchronize()
+        p = index.ivf_profile_read(); index.ivf_profile_enable(False)
+        calls = max(int(p.calls), 1)
+        us_scan = p.ms_scan / calls * 1e3
+        gbs = (p.scan_bytes / calls / 1e9) / (us_scan / 1e6) if us_scan > 0 else 0.0
+        return {"nprobe": nprobe, "batch": B, "searches_in_flight": depth, "qps": round(B * steps / dt, 1),
+                "us_scan": round(us_scan, 1), "scan_mb": round(p.scan_bytes / calls / 1e6, 1),
+                "scan_gbs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+    depth = args.depth if args.depth > 0 else 6
+    steps = args.steps if args.steps != 4096 else 512
+    head = run(256, 1, depth, steps)
+    sweep = []
+    if not args.no_sweep:
+        for nprobe in (64, 128, 256, 512, 1024):
+            sweep.append(run(nprobe, 1, depth, max(64, steps * 64 // nprobe)))
+        sweep.append(run(256, 1, 1, steps))
+        for B in (2, 4, 8):
+            sweep.append(run(256, B, 1, max(32, steps // B)))
+    parity, cpu = None, None
+    if not args.no_cpu:
+        import oracle as O
+        nprobe = 256
+        index.ivf_search_device(q_out, nprobe, k, ids, dists)
+        index.ivf_synchronize()
+        gi, gd = ids.cpu().numpy(), dists.cpu().numpy()
+        q_np = q_out.cpu().numpy()
+        off_np = ds.offsets.numpy()
+        bad, done, t1, t_oracle = 0, 0, time.perf_counter(), 0.0
+        for b in range(0, nq, nq // 4):
+            sel = O.probe(cent_np, q_np[b], nprobe, O.IP)
+            # a host datastore that holds only the selected lists, under their global row numbers
+            coff = np.zeros(nlist + 1, dtype=np.int64)
+            cnt = np.zeros(nlist, dtype=np.int64)
+            cnt[sel] = off_np[sel + 1] - off_np[sel]
+            coff[1:] = np.cumsum(cnt)
+            rows = np.empty((int(coff[-1]), d), dtype=np.float32)
+            gids = np.empty(int(coff[-1]), dtype=np.int64)
+            for c in sel:
+                lo, hi = int(off_np[c]), int(off_np[c + 1])
+                rows[coff[c]:coff[c + 1]] = ds.rows[lo:hi].cpu().numpy()
+                gids[coff[c]:coff[c + 1]] = np.arange(lo, hi)
+            t2 = time.perf_counter()
+            oi, osc = O.search(rows, O.F32, coff, gids, cent_np, q_np[b], nprobe, k, O.IP)
+            t_oracle += time.perf_counter() - t2
+            bad += int(not np.array_equal(gi[b], oi)) + int(not np.allclose(gd[b], osc, rtol=1e-4))
+            done += 1
+        parity = {"queries": done, "mismatches": bad}
+        cpu = {"value": round(done / t_oracle, 3), "unit": "queries/s", "cores": O.threads(), "kind": "oracle",
+               "sample": f"{done} queries, nprobe {nprobe}, k {k}, lists copied to the host beforehand"}
+    out = {"metric": METRIC, "value": head["qps"], "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": 8,
+           "ms_per_step": round(1e3 / head["qps"], 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"paper-shaped resident datastore: {n} x {d} fp32, nlist {nlist} Zipf(1.1), nprobe 256, "
+                                  f"k {k}, batch 1, inner product, scale {args.scale}",
+                      "entry_point": "ivf_search_device", "searches_in_flight": depth},
+           "roofline": {"bound": "hbm", "achieved": head["scan_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": head["frac"], "traffic": None, "kernel": "scan_kernel", "us_per_launch": head["us_scan"],
+                        "bytes_per_launch": head["scan_mb"] * 1e6},
+           "head": head, "sweep": sweep, "parity_sample": parity, "setup_s": round(time.time() - t0, 1)}
+    if cpu:
+        out["cpu_baseline"] = cpu
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -326,7 +441,8 @@ def main():
                     help="skip the passes that time kernels with HIP events (for runs under rocprofv3 --pmc)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"],
+    ap.add_argument("--metric", default="ip", choices=["ip", "l2"], help="c2: distance function")
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5", "n1"],
                     help="c2: single-query retrieval (the default bench line); c4: lookahead with host-resident lists; "
                          "c3 / c5: batched retrieval over fp16 / bf16 lists")
     ap.add_argument("--scale", type=float, default=1.0, help="c3, c4, c5: fraction of the named datastore to build")
@@ -346,8 +462,10 @@ def main():
         return run_lookahead(args)
     if args.workload in ("c3", "c5"):
         return run_batched(args)
+    if args.workload == "n1":
+        return run_paper_shape(args)
     torch.cuda.set_device(0)
-    index, stream, rows_host, assign_host, cent_host, q_in, q_out, info = build_config2("cuda", args.n)
+    index, stream, rows_host, assign_host, cent_host, q_in, q_out, info = build_config2("cuda", args.n, metric=args.metric)
     nq = q_out.shape[0]
     q_dev = q_out.contiguous()
     ids_dev = torch.empty(nq, args.k, dtype=torch.int64, device="cuda")
@@ -398,13 +516,13 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[1] single-query retrieval: {args.n} x 768 fp32, 1024-component mixture, "
                                f"nlist 1024 (k-means on a tenth of the rows), nprobe {args.nprobe}, k {args.k}, "
-                               f"batch 1, inner product, {nq} distinct queries cycled",
+                               f"batch 1, {'inner product' if args.metric == 'ip' else 'squared L2'}, {nq} distinct queries cycled",
                    "entry_point": "ivf_search_device", "searches_in_flight": args.depth,
                    "depth_trials_qps": depth_trials, "seed": 20970},
         "one_at_a_time": {"value": round(args.steps / dt1, 1), "ms_per_step": dt1 / args.steps * 1e3},
         "roofline": {"bound": "hbm", "achieved": round(prof["scan_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(prof["scan_gbs"] / HBM_PEAK_GBS, 4),
-                     "traffic": C2_SCAN_TRAFFIC_BYTES if (args.n == 1_000_000 and args.nprobe == 32) else None,
+                     "traffic": C2_SCAN_TRAFFIC_BYTES if (args.n == 1_000_000 and args.nprobe == 32 and args.metric == "ip") else None,
                      "kernel": "scan_kernel", "us_per_launch": round(prof["us_scan"], 2),
                      "bytes_per_launch": round(prof["scan_bytes_per_call"], 1)},
         "kernels_us": {k_: round(prof[k_], 2) for k_ in ("us_coarse", "us_select", "us_scan", "us_merge")},
@@ -412,7 +530,8 @@ def main():
         "setup": info,
     }
     if not args.no_cpu:
-        base, (off, perm, lists, results) = cpu_baseline(rows_host, assign_host, cent_host, q_out, args.nprobe, args.k)
+        base, (off, perm, lists, results) = cpu_baseline(rows_host, assign_host, cent_host, q_out, args.nprobe, args.k,
+                                                         metric=args.metric)
         out["cpu_baseline"] = base
         # the timed outputs of those queries must equal the oracle's
         torch.cuda.synchronize()
