@@ -97,3 +97,43 @@ def test_built_host_index_with_ids_and_batches(streams):
         for b in range(4):
             assert check_topk(gi[b], gd[b], rows[perm], O.F32, off, ids[perm], cent, q[b], 5, 10, O.IP) == 0
         index.close()
+
+
+def test_batched_prefetch_splits_the_budget(streams):
+    """Sec. 4.2 'Batching design': one total budget, an equal share per query of the batch; a
+    cluster an earlier query of the batch already brought in is not copied (or charged) again.
+    Followed by a second round without reset (Sec. 4.3 'Prefetching for multi-round') and a
+    batched hybrid search."""
+    n, d, nlist, L, k, B = 30000, 256, 48, 12, 10, 4
+    ds, q_in, q_out = _problem(61, n, d, nlist, "f16")
+    off, cent = ds.offsets.numpy(), ds.centroids.numpy()
+    st, odt = stored(ds.rows.float().numpy(), "f16")
+    sizes = np.diff(off) * d * 2
+    cap = int(n * d * 2 // 2)
+    index = P.ivf_adopt_layout(ds.rows.pin_memory(), "f16", off, cent, metric=P.IVF_IP, placement=P.IVF_PLACE_HOST,
+                               device_buffer_bytes=cap, compute_stream=streams[0], copy_stream=streams[1])
+    for total in (int(sizes.sum() // 6), int(sizes.sum() // 3), 1 << 40):
+        res = O.Residency(nlist, cap)
+        taken, skipped, nbytes = 0, 0, 0
+        for b in range(B):
+            c, s, nb = O.prefetch(cent, off, odt, q_in[b], L, total // B, res, O.IP)
+            taken += len(c); skipped += s; nbytes += nb
+        ps = index.ivf_prefetch(q_in[:B], L, total, flags=P.IVF_PREFETCH_RESET)
+        assert (ps.n_taken, ps.n_skipped, ps.bytes) == (taken, skipped, nbytes)
+        assert list(index.ivf_resident()) == list(res.clusters())
+        # second round, same batch after the rewrite: only clusters not yet resident are fetched
+        taken2, nbytes2 = 0, 0
+        for b in range(B):
+            c, s, nb = O.prefetch(cent, off, odt, q_out[b], L, total // B, res, O.IP)
+            taken2 += len(c); nbytes2 += nb
+        ps2 = index.ivf_prefetch(q_out[:B], L, total)
+        assert (ps2.n_taken, ps2.bytes) == (taken2, nbytes2)
+        assert list(index.ivf_resident()) == list(res.clusters())
+        gi, gd, ss = index.ivf_search(q_out[:B], L, k, with_stats=True)
+        hit = 0.0
+        for b in range(B):
+            ov, ms = O.split(cent, q_out[b], L, res.flags, O.IP)
+            hit += len(ov) / float(len(ov) + len(ms))
+            assert check_topk(gi[b], gd[b], st, odt, off, None, cent, q_out[b], L, k, O.IP) == 0
+        assert abs(ss.hit_rate - hit / B) < 1e-6
+    index.close()
