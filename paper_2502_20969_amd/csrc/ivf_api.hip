@@ -200,7 +200,7 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     Workspace& w = *ix->cw;
     const int kprime = kprime_for(k);
     const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
-    const int grid_cap = ix->n_cu * 2;
+    const int grid_cap = ix->n_cu * kScanMaxWgPerCu;
     if (nq <= w.nq && nprobe <= w.nprobe && k <= w.k && pad <= w.pad) return IVF_OK;
     const int nq2 = std::max(nq, w.nq), np2 = std::max(nprobe, w.nprobe), k2 = std::max(k, w.k);
     const uint32_t pad2 = std::max(pad, w.pad);
@@ -282,6 +282,8 @@ int prof_events(ivf_index* ix, int which, hipEvent_t* e0, hipEvent_t* e1) {
 int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid, bool count_rows = true) {
     Workspace& w = *ix->cw;
     int rc;
+    // the per-workgroup tables of the workspace were sized for w.grid workgroups and w.nq queries
+    if (grid > w.grid || nq > w.nq) return fail(IVF_ESTATE, "workspace holds %d scan workgroups x %d queries, asked for %d x %d", w.grid, w.nq, grid, nq);
     hipEvent_t e0, e1;
     if ((rc = prof_events(ix, 0, &e0, &e1))) return rc;
     CoarseArgs ca{ix->d_centroids, q_dev, w.d_scores, ix->nlist, ix->d, nq, ix->metric};

@@ -747,7 +747,7 @@ int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, kScanThreads,
                                                                 scan_lds_bytes(shape, kprime, d));
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
-    if (per_cu > 2) per_cu = 2;
+    if (per_cu > kScanMaxWgPerCu) per_cu = kScanMaxWgPerCu;
     return per_cu * n_cu;
 }
 
