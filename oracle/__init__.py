@@ -37,7 +37,10 @@ def lib():
             "orc_prefetch": [vp, i32, i32, ci, vp, ci, vp, i32, u64, u64, vp, vp, vp, vp, vp],
             "orc_split": [vp, i32, i32, ci, vp, i32, vp, vp, vp, vp, vp],
             "orc_hybrid": [vp, ci, vp, vp, vp, i32, i32, ci, vp, i32, i32, vp, vp, vp, vp],
+            "orc_cache_round": [vp, vp, vp, vp, i32, i32, ci, C.c_float, C.c_float, C.c_double, u64, vp, vp],
         }
+        L.orc_cache_admit.restype = None
+        L.orc_cache_admit.argtypes = [vp, vp, i32, C.c_float]
         for name, args in sigs.items():
             getattr(L, name).restype = C.c_int32
             getattr(L, name).argtypes = args
@@ -160,6 +163,26 @@ def prefetch(centroids, off, dtype, x_in, L, budget, res, metric):
                              C.byref(res.used), _p(chosen), C.byref(skipped), C.byref(nbytes))
     assert got >= 0
     return chosen[:got], skipped.value, nbytes.value
+
+
+def cache_admit(hot, res, h_init):
+    """Newly resident clusters (hot < 0) start at h_init.  hot: float32[nlist], updated in place."""
+    assert hot.dtype == np.float32 and hot.flags.c_contiguous
+    lib().orc_cache_admit(_p(hot), _p(res.flags), len(hot), C.c_float(h_init))
+
+
+def cache_round(hot, used_flags, res, off, d, dtype, decay, h_inc, fraction):
+    """One hotness round and the eviction that ends a batch; updates hot, used_flags (cleared),
+    res.flags and res.used in place.  Returns the evicted clusters in the order they left."""
+    assert hot.dtype == np.float32 and used_flags.dtype == np.uint8
+    off = np.ascontiguousarray(off, dtype=np.int64)
+    nlist = len(hot)
+    evicted = np.zeros(max(nlist, 1), dtype=np.int32)
+    n = lib().orc_cache_round(_p(hot), _p(used_flags), _p(res.flags), _p(off), nlist, d, dtype,
+                              C.c_float(decay), C.c_float(h_inc), C.c_double(fraction), C.c_uint64(res.cap),
+                              C.byref(res.used), _p(evicted))
+    assert n >= 0
+    return evicted[:n]
 
 
 def split(centroids, x_out, L, res_flags, metric):

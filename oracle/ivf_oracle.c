@@ -345,6 +345,60 @@ int orc_hybrid(const void *lists, int dtype, const int64_t *off, const int64_t *
     return 0;
 }
 
+/* ---- cluster cache with decaying hotness (Sec. 4.2 "Cache design"; appendix on
+ *      scheduling and cache: the hotness transition and the cache fraction) ------- */
+
+/* A cluster that has just been fetched is cached and starts with hotness h_init.
+ * hot[c] < 0 means "not cached". */
+void orc_cache_admit(float *hot, const uint8_t *resident, int32_t nlist, float h_init)
+{
+    for (int32_t c = 0; c < nlist; ++c)
+        if (resident[c] && hot[c] < 0.0f) hot[c] = h_init;
+}
+
+/* One hotness round followed by the eviction that ends a batch.
+ *
+ * Hotness: for every cached cluster h <- h / decay, plus h_inc when the cluster
+ * was used in the round that ends (used[c] != 0); used[] is cleared.  The
+ * arithmetic is single precision, one division and one addition per cluster,
+ * because the outcome decides an integer (which clusters leave) and the device
+ * keeps hotness in single precision.
+ *
+ * Eviction: the cache may hold at most fraction*cap bytes.  While the resident
+ * bytes exceed that, the cached cluster of lowest hotness leaves (equal
+ * hotness: the larger cluster index leaves first); its resident flag is
+ * cleared, its hotness becomes -1 and its payload n_c*d*elem_size is given back.
+ * Returns the number evicted, listed in evicted[] in the order they left. */
+int32_t orc_cache_round(float *hot, uint8_t *used_flags, uint8_t *resident, const int64_t *off,
+                        int32_t nlist, int32_t d, int dtype, float decay, float h_inc,
+                        double fraction, uint64_t cap, uint64_t *used_bytes, int32_t *evicted)
+{
+    for (int32_t c = 0; c < nlist; ++c) {
+        if (resident[c] && hot[c] >= 0.0f) {
+            float h = hot[c] / decay;
+            if (used_flags[c]) h = h + h_inc;
+            hot[c] = h;
+        }
+        used_flags[c] = 0;
+    }
+    const uint64_t limit = (uint64_t)(fraction * (double)cap);
+    int32_t n_evicted = 0;
+    while (*used_bytes > limit) {
+        int32_t victim = -1;
+        for (int32_t c = 0; c < nlist; ++c) {
+            if (!resident[c]) continue;
+            if (victim < 0 || hot[c] < hot[victim] || (hot[c] == hot[victim] && c > victim)) victim = c;
+        }
+        if (victim < 0) break;
+        uint64_t bytes = (uint64_t)(off[victim + 1] - off[victim]) * (uint64_t)d * (uint64_t)orc_elem_size(dtype);
+        resident[victim] = 0;
+        hot[victim] = -1.0f;
+        *used_bytes -= bytes;
+        evicted[n_evicted++] = victim;
+    }
+    return n_evicted;
+}
+
 /* Number of OpenMP threads the scoring loop will use (for the baseline report). */
 int orc_threads(void)
 {

@@ -380,3 +380,92 @@ def test_workload_generators_are_seeded():
     assert ds.rows.shape == (10000, 16) and ds.offsets[-1] == 10000
     c0 = ds.rows[ds.offsets[5]:ds.offsets[6]].float().mean(0)
     np.testing.assert_allclose(ds.centroids[5].numpy(), c0.numpy(), rtol=1e-4, atol=1e-6)
+
+
+# ---- cluster cache with decaying hotness (Sec. 4.2 "Cache design"; appendix, hotness transition) ----
+def _cache_state(row_counts, d, cap, resident):
+    nlist = len(row_counts)
+    off = np.zeros(nlist + 1, dtype=np.int64)
+    off[1:] = np.cumsum(row_counts)
+    res = O.Residency(nlist, cap)
+    res.flags[list(resident)] = 1
+    res.used.value = int(sum(row_counts[c] for c in resident) * d * 4)
+    hot = np.full(nlist, -1.0, dtype=np.float32)
+    return off, res, hot, np.zeros(nlist, dtype=np.uint8)
+
+
+def test_handworked_cache_round():
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "handworked_cache.json")))
+    off, res, hot, used = _cache_state(g["row_counts"], g["d"], g["cap_bytes"], g["resident"])
+    O.cache_admit(hot, res, g["h_init"])
+    assert [c for c in range(len(hot)) if hot[c] == g["h_init"]] == g["resident"]
+    used[g["used"]] = 1
+    ev = O.cache_round(hot, used, res, off, g["d"], O.F32, g["decay"], g["h_inc"], g["fraction"])
+    assert list(ev) == g["evicted"] and res.used.value == g["bytes_after"]
+    assert list(hot) == g["hot_after"] and not used.any()
+    assert list(res.clusters()) == [c for c in g["resident"] if c not in g["evicted"]]
+
+
+def test_hotness_closed_forms():
+    """Never used: h_r = h_init / d^r.  Used every round: h_r = h_init / d^r + h_inc (1 - d^-r) / (1 - 1/d)
+    (a geometric series); with d = 2, h_init = h_inc = 1 that is 2 - 2^-r, exact in single precision."""
+    off, res, hot, used = _cache_state([4, 4], 4, 1 << 20, [0, 1])
+    O.cache_admit(hot, res, 1.0)
+    for r in range(1, 21):
+        used[1] = 1
+        assert len(O.cache_round(hot, used, res, off, 4, O.F32, 2.0, 1.0, 0.5)) == 0
+        assert hot[0] == np.float32(2.0 ** -r) and hot[1] == np.float32(2.0 - 2.0 ** -r)
+    off, res, hot, used = _cache_state([4, 4], 4, 1 << 20, [0, 1])
+    O.cache_admit(hot, res, 0.7)
+    dcy, inc = 3.0, 0.25
+    for r in range(1, 15):
+        used[1] = 1
+        O.cache_round(hot, used, res, off, 4, O.F32, dcy, inc, 0.5)
+        assert abs(hot[0] - 0.7 / dcy ** r) <= 1e-6 * 0.7 / dcy ** r + 1e-12
+        want = 0.7 / dcy ** r + inc * (1.0 - dcy ** -r) / (1.0 - 1.0 / dcy)
+        assert abs(hot[1] - want) <= 2e-6 * want
+
+
+def test_cache_eviction_invariants():
+    """Random states: the evicted clusters are exactly the coldest ones, as few as bring the cache
+    under its share; nothing leaves a cache that is under it; absent clusters stay absent."""
+    rng = np.random.default_rng(77)
+    for trial in range(200):
+        nlist = int(rng.integers(1, 40))
+        counts = rng.integers(0, 50, nlist)
+        d = 8
+        resident = [c for c in range(nlist) if rng.random() < 0.6]
+        cap = int(max(1, counts.sum()) * d * 4 * rng.uniform(0.5, 2.0))
+        off, res, hot, used = _cache_state(counts, d, cap, resident)
+        if res.used.value > cap:
+            continue
+        for c in resident:
+            hot[c] = np.float32(rng.choice([0.25, 0.5, 1.0, 1.5, 3.0]))        # many ties
+        used[rng.random(nlist) < 0.3] = 1
+        used_before = used.copy()
+        hot_before, bytes_before = hot.copy(), res.used.value
+        fraction = float(rng.choice([0.0, 0.25, 0.5, 1.0]))
+        ev = O.cache_round(hot, used, res, off, d, O.F32, 2.0, 1.0, fraction)
+        limit = int(fraction * cap)
+        sizes = counts * d * 4
+        upd = {c: np.float32(np.float32(hot_before[c] / np.float32(2.0)) + (np.float32(1.0) if used_before[c] else np.float32(0.0)))
+               for c in resident}
+        assert not used.any()
+        assert all(hot[c] == -1.0 for c in range(nlist) if c not in resident)
+        kept = [c for c in resident if c not in set(ev)]
+        assert sorted(kept) == list(res.clusters())
+        assert all(hot[c] == upd[c] for c in kept) and all(hot[c] == -1.0 for c in ev)
+        assert res.used.value == bytes_before - int(sizes[list(ev)].sum())
+        if bytes_before <= limit:
+            assert len(ev) == 0
+        else:
+            assert res.used.value <= limit or not kept
+            # one eviction fewer would not have been enough
+            assert res.used.value + int(sizes[ev[-1]]) > limit
+            # every evicted cluster is at most as hot as every kept one; equal hotness: larger index left
+            for e in ev:
+                for c in kept:
+                    assert upd[e] < upd[c] or (upd[e] == upd[c] and e > c)
+            # and they left coldest first
+            for a, b in zip(ev[:-1], ev[1:]):
+                assert upd[a] < upd[b] or (upd[a] == upd[b] and a > b)
