@@ -217,6 +217,34 @@ int ivf_profile_enable(ivf_index* index, int on);
 int ivf_profile_read(ivf_index* index, ivf_profile* out); /* synchronises compute_stream */
 int ivf_profile_reset(ivf_index* index);
 
+/*
+ * Cluster cache (Sec. 4.2 "Cache design"; appendix on scheduling and cache: decay-based hotness,
+ * cache fraction, eviction and consolidation after each batch).  IVF_PLACE_HOST only.
+ *
+ * With the cache configured, a cluster copied in by ivf_prefetch is cached with hotness h_init.
+ * ivf_cache_end_round closes a round: every cached cluster's hotness becomes h / decay, plus
+ * h_inc if a search since the previous round selected the cluster while it was resident; then,
+ * while the resident bytes exceed fraction * device_buffer_bytes, the cached cluster of lowest
+ * hotness is evicted (equal hotness: the larger cluster index first); the survivors are moved
+ * to the front of the device buffer, in their order, so that the freed space is contiguous.
+ * Call it between batches, with no ivf_prefetch reset in between that should keep the cache:
+ * IVF_PREFETCH_RESET drops the cache too.  Hotness is single precision on the device.
+ *   fraction in [0, 1]; h_init >= 0; decay >= 1; h_inc >= 0.  fraction < 0 switches the cache off.
+ * ivf_cache_hotness: host array of nlist floats, < 0 for clusters that are not cached.
+ */
+typedef struct ivf_cache_stats {
+    int32_t n_cached;      /* cached clusters when the round ended, before eviction */
+    int32_t n_evicted;
+    uint64_t bytes_cached; /* their payload bytes, before eviction */
+    uint64_t bytes_kept;   /* payload bytes still cached afterwards (= device buffer in use) */
+    uint64_t bytes_moved;  /* bytes moved inside the device buffer by the consolidation */
+    float ms_update;       /* hotness kernel + read-back */
+    float ms_compact;      /* device-to-device moves */
+} ivf_cache_stats;
+int ivf_cache_configure(ivf_index* index, float fraction, float h_init, float decay, float h_inc);
+int ivf_cache_end_round(ivf_index* index, ivf_cache_stats* stats /* or NULL */);
+int ivf_cache_hotness(ivf_index* index, float* hotness);
+
 /* Number of host threads used for the scan of C_miss (default: hardware threads, at most 64). */
 int ivf_set_host_threads(ivf_index* index, int32_t n);
 

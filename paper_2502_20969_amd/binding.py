@@ -24,8 +24,15 @@ EXPORTS = [
     "ivf_search", "ivf_search_device", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
-    "ivf_set_batch_mode", "ivf_strerror", "ivf_last_error",
+    "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
+    "ivf_strerror", "ivf_last_error",
 ]
+
+
+class CacheStats(C.Structure):
+    _fields_ = [("n_cached", C.c_int32), ("n_evicted", C.c_int32), ("bytes_cached", C.c_uint64),
+                ("bytes_kept", C.c_uint64), ("bytes_moved", C.c_uint64), ("ms_update", C.c_float),
+                ("ms_compact", C.c_float)]
 
 
 class PrefetchStats(C.Structure):
@@ -83,6 +90,9 @@ def load():
     L.ivf_set_pipeline_depth.argtypes = [vp, i32]
     L.ivf_synchronize.argtypes = [vp]
     L.ivf_set_batch_mode.argtypes = [vp, i32]
+    L.ivf_cache_configure.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float]
+    L.ivf_cache_end_round.argtypes = [vp, C.POINTER(CacheStats)]
+    L.ivf_cache_hotness.argtypes = [vp, vp]
     L.ivf_strerror.argtypes = [ci]
     L.ivf_strerror.restype = C.c_char_p
     L.ivf_last_error.restype = C.c_char_p
@@ -216,6 +226,21 @@ class Index:
         ids = np.empty(self.n, dtype=np.int64)
         _check(load().ivf_get_layout(self._h, _ptr(off), _ptr(ids)))
         return off, ids
+
+    # -- cluster cache -----------------------------------------------------------------------
+    def ivf_cache_configure(self, fraction=0.5, h_init=1.0, decay=2.0, h_inc=1.0):
+        _check(load().ivf_cache_configure(self._h, C.c_float(fraction), C.c_float(h_init), C.c_float(decay),
+                                          C.c_float(h_inc)))
+
+    def ivf_cache_end_round(self):
+        st = CacheStats()
+        _check(load().ivf_cache_end_round(self._h, C.byref(st)))
+        return st
+
+    def ivf_cache_hotness(self):
+        out = np.empty(self.nlist, dtype=np.float32)
+        _check(load().ivf_cache_hotness(self._h, _ptr(out)))
+        return out
 
     # -- profiling ---------------------------------------------------------------------------
     def ivf_profile_enable(self, on=True):

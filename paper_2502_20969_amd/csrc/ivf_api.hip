@@ -114,6 +114,14 @@ struct ivf_index {
     int64_t* d_ids = nullptr;
     uint32_t* d_idrank = nullptr;    // row -> rank of its id among all ids; null when rank == row
     uint32_t* d_rowof = nullptr;     // the inverse map
+    // cluster cache (host placement): hotness per cluster (< 0 = not cached), use marks of the round
+    bool cache_on = false;
+    float cache_fraction = 0.5f, cache_h_init = 1.f, cache_decay = 2.f, cache_h_inc = 1.f;
+    float* d_hot = nullptr;
+    uint32_t* d_used = nullptr;
+    void* d_move_tmp = nullptr;      // staging for a cluster whose old and new place overlap
+    size_t move_tmp_bytes = 0;
+    hipEvent_t ev_cache[4] = {nullptr, nullptr, nullptr, nullptr};
     int64_t* d_res_off = nullptr;
     void* d_buf = nullptr;          // device lists (device placement) or the prefetch buffer
     size_t buf_bytes = 0;
@@ -279,7 +287,8 @@ int prof_events(ivf_index* ix, int which, hipEvent_t* e0, hipEvent_t* e1) {
 // ---- kernel sequences ---------------------------------------------------------------------
 // coarse scoring + selection for nq queries already in d_q (device); leaves the probe lists
 // and slot tables in the workspace
-int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid, bool count_rows = true) {
+int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid, bool count_rows = true,
+                  bool is_search = false) {
     Workspace& w = *ix->cw;
     int rc;
     // the per-workgroup tables of the workspace were sized for w.grid workgroups and w.nq queries
@@ -296,6 +305,7 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
     sa.grid = grid;
     sa.desc = w.d_desc;
     sa.rows_counter = ix->profiling && count_rows ? ix->d_prof_rows : nullptr;
+    sa.used = is_search && ix->cache_on ? ix->d_used : nullptr;
     HIP_TRY(launch_select(sa, ix->cs, e0, e1));
     return IVF_OK;
 }
@@ -387,7 +397,7 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
 int enqueue_batched(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int64_t* out_ids, float* out_dists) {
     Workspace& w = *ix->cw;
     int rc;
-    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe, 1, false))) return rc;
+    if ((rc = enqueue_probe(ix, q_dev, nq, nprobe, 1, false, true))) return rc;
     if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->d, ix->n_cu);
     BatchedArgs b{};
     b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.q = q_dev; b.probe = w.d_probe;
@@ -539,7 +549,10 @@ extern "C" void ivf_free(ivf_index* ix) {
     hipDeviceSynchronize();
     for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) hipStreamDestroy(l.stream); }
     for (auto& s : ix->prof_sets) for (auto& e : s.e) hipEventDestroy(e);
-    hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_idrank); hipFree(ix->d_rowof); hipFree(ix->d_res_off);
+    hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_idrank); hipFree(ix->d_rowof);
+    hipFree(ix->d_hot); hipFree(ix->d_used); hipFree(ix->d_move_tmp);
+    for (auto& e : ix->ev_cache) if (e) hipEventDestroy(e);
+    hipFree(ix->d_res_off);
     hipFree(ix->d_prof_rows); hipFree(ix->d_row_norm_max);
     if (ix->own_buf) hipFree(ix->d_buf);
     if (ix->own_h_lists) hipHostFree(ix->h_lists);
@@ -700,7 +713,7 @@ static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int npro
     if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
     const int kprime = kprime_for(k);
     const int grid = scan_grid_for(ix, nprobe, kprime);
-    if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid))) return r;
+    if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid, true, true))) return r;
     if ((r = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return r;
     return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
 }
@@ -793,7 +806,7 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
         return IVF_OK;
     }
     if (hybrid && ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->cs, ix->ev_pf_done, 0));
-    if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe, grid))) return rc;
+    if ((rc = enqueue_probe(ix, w.d_q, nq, nprobe, grid, true, true))) return rc;
     const bool want_probe = hybrid || stats;
     if (want_probe) {
         HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
@@ -893,9 +906,143 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     // the residency table follows the data on the same stream
     memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)ix->nlist * sizeof(int64_t));
     HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)ix->nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->copy));
+    if (ix->cache_on)     // clusters that arrived are cached from now on; a reset drops the cache
+        HIP_TRY(launch_cache_admit(ix->d_hot, ix->d_used, ix->d_res_off, ix->nlist, ix->cache_h_init,
+                                   (flags & IVF_PREFETCH_RESET) ? 1 : 0, ix->copy));
     HIP_TRY(hipEventRecord(ix->ev_pf_done, ix->copy));
     ix->pf_recorded = true;
     st.buffer_used = ix->buf_used;
+    if (stats) *stats = st;
+    return IVF_OK;
+}
+
+// ---- cluster cache -------------------------------------------------------------------------------------
+extern "C" int ivf_cache_configure(ivf_index* ix, float fraction, float h_init, float decay, float h_inc) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (ix->placement != IVF_PLACE_HOST) return fail(IVF_ESTATE, "the cluster cache needs a host-placed index");
+    if (fraction < 0.f) { ix->cache_on = false; return IVF_OK; }
+    if (!(fraction <= 1.f) || !(h_init >= 0.f) || !(decay >= 1.f) || !(h_inc >= 0.f))
+        return fail(IVF_EINVAL, "cache parameters: fraction in [0, 1], h_init >= 0, decay >= 1, h_inc >= 0");
+    int rc = settle_on_lane0(ix);
+    if (rc) return rc;
+    if (!ix->d_hot) {
+        HIP_TRY(hipMalloc(&ix->d_hot, (size_t)ix->nlist * sizeof(float)));
+        HIP_TRY(hipMalloc(&ix->d_used, (size_t)ix->nlist * sizeof(uint32_t)));
+        for (auto& e : ix->ev_cache) HIP_TRY(hipEventCreate(&e));
+    }
+    ix->cache_fraction = fraction; ix->cache_h_init = h_init; ix->cache_decay = decay; ix->cache_h_inc = h_inc;
+    // what is resident now becomes cached at h_init; nothing has been used yet
+    if (ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->cs, ix->ev_pf_done, 0));
+    HIP_TRY(launch_cache_admit(ix->d_hot, ix->d_used, ix->d_res_off, ix->nlist, h_init, 1, ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    ix->cache_on = true;
+    return IVF_OK;
+}
+
+extern "C" int ivf_cache_hotness(ivf_index* ix, float* hotness) {
+    if (!ix || !hotness) return fail(IVF_EINVAL, "index or hotness is NULL");
+    if (!ix->cache_on) return fail(IVF_ESTATE, "the cluster cache is not configured");
+    int rc = settle_on_lane0(ix);
+    if (rc) return rc;
+    if (ix->pf_recorded) HIP_TRY(hipEventSynchronize(ix->ev_pf_done));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    HIP_TRY(hipMemcpy(hotness, ix->d_hot, (size_t)ix->nlist * sizeof(float), hipMemcpyDeviceToHost));
+    return IVF_OK;
+}
+
+extern "C" int ivf_cache_end_round(ivf_index* ix, ivf_cache_stats* stats) {
+    if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    if (!ix->cache_on) return fail(IVF_ESTATE, "the cluster cache is not configured");
+    int rc = settle_on_lane0(ix);
+    if (rc) return rc;
+    const int nlist = ix->nlist;
+    const size_t rb = ix->row_bytes;
+    ivf_cache_stats st{};
+    // 1. hotness update on the device, after every copy and search of the round
+    if (ix->pf_recorded) HIP_TRY(hipStreamWaitEvent(ix->cs, ix->ev_pf_done, 0));
+    HIP_TRY(hipEventRecord(ix->ev_cache[0], ix->cs));
+    HIP_TRY(launch_cache_round(ix->d_hot, ix->d_used, nlist, ix->cache_decay, ix->cache_h_inc, ix->cs));
+    std::vector<float> hot((size_t)nlist);
+    HIP_TRY(hipMemcpyAsync(hot.data(), ix->d_hot, (size_t)nlist * sizeof(float), hipMemcpyDeviceToHost, ix->cs));
+    HIP_TRY(hipEventRecord(ix->ev_cache[1], ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    // 2. eviction: coldest first (equal hotness: larger index first) until the cache fits its share
+    struct Item { float h; int32_t c; };
+    std::vector<Item> cached;
+    for (int c = 0; c < nlist; ++c)
+        if (ix->h_res_off[c] >= 0) cached.push_back(Item{hot[c], (int32_t)c});
+    st.n_cached = (int32_t)cached.size();
+    st.bytes_cached = ix->buf_used;
+    const uint64_t limit = (uint64_t)((double)ix->cache_fraction * (double)ix->buf_bytes);
+    std::sort(cached.begin(), cached.end(), [](const Item& x, const Item& y) {
+        return x.h < y.h || (x.h == y.h && x.c > y.c);
+    });
+    uint64_t in_use = ix->buf_used;
+    bool changed = false;
+    for (size_t i = 0; i < cached.size() && in_use > limit; ++i) {
+        const int c = cached[i].c;
+        in_use -= (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
+        ix->h_res_off[c] = -1;
+        hot[c] = -1.f;
+        st.n_evicted += 1;
+        changed = true;
+    }
+    // 3. consolidation: survivors move to the front of the buffer in their current order.  A
+    //    cluster only ever moves towards lower addresses and never onto a later cluster's old
+    //    place; it can overlap its own old place, and then goes through a staging buffer.
+    std::vector<std::pair<int64_t, int32_t>> order;
+    for (int c = 0; c < nlist; ++c)
+        if (ix->h_res_off[c] >= 0) order.push_back({ix->h_res_off[c], (int32_t)c});
+    std::sort(order.begin(), order.end());
+    size_t need_tmp = 0;
+    {
+        uint64_t at = 0;
+        for (auto& oc : order) {
+            const int c = oc.second;
+            const uint64_t bytes = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb, old = (uint64_t)oc.first * rb;
+            if (old != at && old - at < bytes) need_tmp = std::max<size_t>(need_tmp, bytes);
+            at += bytes;
+        }
+    }
+    if (need_tmp > ix->move_tmp_bytes) {
+        if (ix->d_move_tmp) HIP_TRY(hipFree(ix->d_move_tmp));
+        ix->d_move_tmp = nullptr; ix->move_tmp_bytes = 0;
+        HIP_TRY(hipMalloc(&ix->d_move_tmp, need_tmp));
+        ix->move_tmp_bytes = need_tmp;
+    }
+    HIP_TRY(hipEventRecord(ix->ev_cache[2], ix->cs));
+    uint64_t at = 0;
+    for (auto& oc : order) {
+        const int c = oc.second;
+        const uint64_t bytes = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb, old = (uint64_t)oc.first * rb;
+        if (old != at && bytes > 0) {
+            char* dst = (char*)ix->d_buf + at;
+            const char* src = (const char*)ix->d_buf + old;
+            if (old - at >= bytes) {
+                HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, ix->cs));
+            } else {
+                HIP_TRY(hipMemcpyAsync(ix->d_move_tmp, src, bytes, hipMemcpyDeviceToDevice, ix->cs));
+                HIP_TRY(hipMemcpyAsync(dst, ix->d_move_tmp, bytes, hipMemcpyDeviceToDevice, ix->cs));
+            }
+            st.bytes_moved += bytes;
+            changed = true;
+        }
+        ix->h_res_off[c] = (int64_t)(at / rb);
+        at += bytes;
+    }
+    ix->buf_used = at;
+    HIP_TRY(hipEventRecord(ix->ev_cache[3], ix->cs));
+    if (changed) {
+        memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)nlist * sizeof(int64_t));
+        HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->cs));
+        HIP_TRY(hipMemcpyAsync(ix->d_hot, hot.data(), (size_t)nlist * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    }
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    // later prefetch copies (copy stream) must not start before the moves are done: they are, the
+    // compute stream was just drained
+    st.bytes_kept = ix->buf_used;
+    HIP_TRY(hipEventElapsedTime(&st.ms_update, ix->ev_cache[0], ix->ev_cache[1]));
+    HIP_TRY(hipEventElapsedTime(&st.ms_compact, ix->ev_cache[2], ix->ev_cache[3]));
     if (stats) *stats = st;
     return IVF_OK;
 }

@@ -72,6 +72,7 @@ struct SelectArgs {
     uint64_t* sort_keys;     // global scratch [nq x pad] when the sort does not fit LDS
     uint32_t* sort_idx;
     unsigned long long* rows_counter;  // nullable: receives the rows of all resident selected lists
+    uint32_t* used;          // nullable [nlist]: set to 1 for every selected cluster that is resident
     int nlist, nprobe, nq, metric, grid;
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
@@ -104,6 +105,11 @@ struct MergeArgs {
     int identity;            // 1: buffer row == global row (device placement)
 };
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+
+// cluster cache bookkeeping: hot[c] < 0 = not cached
+hipError_t launch_cache_admit(float* hot, uint32_t* used, const int64_t* res_off, int nlist, float h_init, int reset,
+                              hipStream_t s);
+hipError_t launch_cache_round(float* hot, uint32_t* used, int nlist, float decay, float h_inc, hipStream_t s);
 
 // ---- batched (list-major) search: ivf_batched.hip ------------------------------------------------
 struct BatchTask { uint32_t cluster, group, tile; };    // 128 rows of a cluster x up to 32 of its queries

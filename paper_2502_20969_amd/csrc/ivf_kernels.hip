@@ -333,6 +333,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
             s_grow[i] = (uint32_t)lo;
             s_n[i] = n;
             rows = ro >= 0 ? n : 0;
+            if (a.used && ro >= 0) a.used[c] = 1u;        // cache bookkeeping: resident and selected
         }
         // block-wide exclusive scan of `rows`
         uint32_t incl = rows;
@@ -1067,6 +1068,44 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, i
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                        (const unsigned char*)src, (unsigned char*)dst, pos, n, row_bytes);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Cluster cache bookkeeping (Sec. 4.2 "Cache design"; appendix: hotness h <- h / d, + h_inc when
+// the cluster was used in the round).  hot[c] < 0 marks a cluster that is not cached.
+// Single precision, one correctly rounded division and one addition per cluster.
+// =============================================================================================
+// reset: the cache starts over (hotness and use marks are dropped) before the admission
+__global__ void cache_admit_kernel(float* hot, uint32_t* used, const int64_t* res_off, int nlist, float h_init, int reset) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= nlist) return;
+    if (reset) used[c] = 0u;
+    float h = reset ? -1.f : hot[c];
+    if (res_off[c] < 0) h = -1.f;
+    else if (h < 0.f) h = h_init;            // fetched since the last call: cached from now on
+    hot[c] = h;
+}
+
+__global__ void cache_round_kernel(float* hot, uint32_t* used, int nlist, float decay, float h_inc) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= nlist) return;
+    float h = hot[c];
+    if (h >= 0.f) {
+        h = h / decay;
+        if (used[c]) h = h + h_inc;
+        hot[c] = h;
+    }
+    used[c] = 0u;
+}
+
+hipError_t launch_cache_admit(float* hot, uint32_t* used, const int64_t* res_off, int nlist, float h_init, int reset,
+                              hipStream_t s) {
+    hipLaunchKernelGGL(cache_admit_kernel, dim3((nlist + 255) / 256), dim3(256), 0, s, hot, used, res_off, nlist, h_init, reset);
+    return hipGetLastError();
+}
+hipError_t launch_cache_round(float* hot, uint32_t* used, int nlist, float decay, float h_inc, hipStream_t s) {
+    hipLaunchKernelGGL(cache_round_kernel, dim3((nlist + 255) / 256), dim3(256), 0, s, hot, used, nlist, decay, h_inc);
     return hipGetLastError();
 }
 

@@ -137,3 +137,63 @@ def test_batched_prefetch_splits_the_budget(streams):
             assert check_topk(gi[b], gd[b], st, odt, off, None, cent, q_out[b], L, k, O.IP) == 0
         assert abs(ss.hit_rate - hit / B) < 1e-6
     index.close()
+
+
+@pytest.mark.parametrize("fraction,decay,h_inc", [(0.5, 2.0, 1.0), (0.25, 3.0, 0.25)])
+def test_cluster_cache_rounds(streams, fraction, decay, h_inc):
+    """Sec. 4.2 'Cache design' and the appendix's hotness transition: prefetch (admission at
+    h_init), search (use marks), end of round (decay, eviction down to the cache fraction,
+    consolidation of the buffer) over several rounds, against the oracle's cache round.  Hotness
+    is compared bit for bit, residency exactly, and every search after a consolidation must still
+    return the oracle's neighbours, so the moved lists are intact."""
+    n, d, nlist, L, k = 30000, 128, 40, 10, 10
+    ds, q_in, q_out = _problem(71, n, d, nlist, "f16")
+    rng = np.random.default_rng(3)
+    off, cent = ds.offsets.numpy(), ds.centroids.numpy()
+    st, odt = stored(ds.rows.float().numpy(), "f16")
+    sizes = np.diff(off) * d * 2
+    cap = int(sizes.sum() * 0.6)
+    h_init = 1.0
+    index = P.ivf_adopt_layout(ds.rows.pin_memory(), "f16", off, cent, metric=P.IVF_IP, placement=P.IVF_PLACE_HOST,
+                               device_buffer_bytes=cap, compute_stream=streams[0], copy_stream=streams[1])
+    index.ivf_cache_configure(fraction, h_init, decay, h_inc)
+    res = O.Residency(nlist, cap)
+    hot = np.full(nlist, -1.0, dtype=np.float32)
+    used = np.zeros(nlist, dtype=np.uint8)
+    moved_any, evicted_any = False, False
+    for rnd in range(8):
+        b = rnd % q_in.shape[0]
+        # a different neighbourhood every other round, so that old clusters cool down
+        qi = q_in[b] if rnd % 2 == 0 else (cent[rng.integers(0, nlist)] + 0.1 * rng.standard_normal(d)).astype(np.float32)
+        qo = q_out[b] if rnd % 2 == 0 else qi
+        budget = int(sizes.sum() // 4)
+        chosen, skipped, nbytes = O.prefetch(cent, off, odt, qi, L, budget, res, O.IP)
+        O.cache_admit(hot, res, h_init)
+        ps = index.ivf_prefetch(qi, L, budget)
+        assert (ps.n_taken, ps.n_skipped, ps.bytes) == (len(chosen), skipped, nbytes)
+        gi, gd, ss = index.ivf_search(qo, L, k, with_stats=True)
+        ov, ms = O.split(cent, qo, L, res.flags, O.IP)
+        used[ov] = 1
+        assert ss.n_overlap == len(ov) and ss.n_miss == len(ms)
+        assert check_topk(gi[0], gd[0], st, odt, off, None, cent, qo, L, k, O.IP) == 0
+        np.testing.assert_array_equal(index.ivf_cache_hotness(), hot)
+        before = res.used.value
+        ev = O.cache_round(hot, used, res, off, d, odt, decay, h_inc, fraction)
+        cs = index.ivf_cache_end_round()
+        assert cs.n_evicted == len(ev) and cs.bytes_cached == before and cs.bytes_kept == res.used.value
+        assert cs.bytes_kept <= int(fraction * cap)
+        np.testing.assert_array_equal(index.ivf_cache_hotness(), hot)
+        assert list(index.ivf_resident()) == list(res.clusters())
+        moved_any |= cs.bytes_moved > 0
+        evicted_any |= cs.n_evicted > 0
+        # the consolidated buffer still holds the right rows
+        gi, gd, ss = index.ivf_search(qo, L, k, with_stats=True)
+        ov2, _ = O.split(cent, qo, L, res.flags, O.IP)
+        used[ov2] = 1
+        assert ss.n_overlap == len(ov2)
+        assert check_topk(gi[0], gd[0], st, odt, off, None, cent, qo, L, k, O.IP) == 0
+    assert moved_any and evicted_any
+    # a reset prefetch drops the cache
+    index.ivf_prefetch(q_in[0], L, 0, flags=P.IVF_PREFETCH_RESET)
+    assert (index.ivf_cache_hotness() < 0).all() and len(index.ivf_resident()) == 0
+    index.close()
