@@ -191,6 +191,47 @@ def run_lookahead(args):
                      "host_scan_ms": round(m["ms_host"], 3), "gpu_scan_gb": round(m["gpu_bytes"] / 1e9, 3),
                      "host_scan_gb": round(m["host_bytes"] / 1e9, 3),
                      "host_scan_gbs": round((m["host_bytes"] / 1e9) / (m["ms_host"] / 1e3), 1) if m["ms_host"] > 0 else 0.0})
+    # Cluster cache (Sec. 4.2 "Cache design"): a stream of requests around a few topics, each
+    # request = prefetch(q_in) under the 1.28 GB budget, decode, search(q_out); once with a cold
+    # buffer per request, once with the cache keeping at most half of the buffer between requests.
+    cache_rows = []
+    n_req, topics = 3 * args.pairs, 6
+    tq_in = W.shared_batch_queries(ds, n_req, topics, 20981)
+    tq_out = W.perturbed(tq_in, 0.3, 20982)
+    tq_in, tq_out = tq_in.cpu().numpy(), tq_out.cpu().numpy()
+    budget = int(1.28e9 * min(1.0, scale * 4))
+    for j in range(n_req):               # untimed: first host touch of the lists these requests scan
+        index.ivf_prefetch(tq_in[j], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
+        index.ivf_search(tq_out[j], nprobe, k)
+    for mode in ("cold buffer per request", "cache fraction 0.5"):
+        cached = mode.startswith("cache")
+        index.ivf_prefetch(tq_in[0], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
+        index.ivf_cache_configure(0.5 if cached else -1.0, 1.0, 2.0, 1.0)
+        acc = {"hit": [], "ms_search": [], "bytes": [], "ms_update": [], "ms_compact": [], "moved": [], "evicted": [],
+               "ms_round_call": []}
+        for j in range(n_req):
+            ps = index.ivf_prefetch(tq_in[j], nprobe, budget, flags=0 if cached else P.IVF_PREFETCH_RESET)
+            decode(reps)
+            torch.cuda.synchronize()
+            index.ivf_prefetch_wait()
+            ids, dists, st = index.ivf_search(tq_out[j], nprobe, k, with_stats=True)
+            acc["hit"].append(st.hit_rate); acc["ms_search"].append(st.ms_total); acc["bytes"].append(ps.bytes)
+            if cached:
+                t = time.perf_counter()
+                cs = index.ivf_cache_end_round()
+                acc["ms_round_call"].append((time.perf_counter() - t) * 1e3)
+                acc["ms_update"].append(cs.ms_update); acc["ms_compact"].append(cs.ms_compact)
+                acc["moved"].append(cs.bytes_moved); acc["evicted"].append(cs.n_evicted)
+        m = {k_: float(np.mean(v)) if v else 0.0 for k_, v in acc.items()}
+        row = {"mode": mode, "requests": n_req, "topics": topics, "hit_rate": round(m["hit"], 4),
+               "prefetched_gb": round(m["bytes"] / 1e9, 3), "search_ms": round(m["ms_search"], 3)}
+        if cached:
+            row.update({"end_round_ms": round(m["ms_round_call"], 3), "hotness_update_ms": round(m["ms_update"], 3),
+                        "compact_ms": round(m["ms_compact"], 3), "moved_gb": round(m["moved"] / 1e9, 3),
+                        "evicted_clusters": round(m["evicted"], 1),
+                        "move_gbs": round((m["moved"] / 1e9) / (m["ms_compact"] / 1e3), 1) if m["ms_compact"] > 0 else 0.0})
+        cache_rows.append(row)
+    index.ivf_cache_configure(-1.0, 1.0, 2.0, 1.0)
     # sampled parity at this size: two hybrid searches against the oracle on the same pinned lists
     parity = None
     if not args.no_cpu:
@@ -212,7 +253,7 @@ def run_lookahead(args):
            "config": {"workload": f"configs[3] limited-GPU-memory lookahead: {n} x 768 fp16 in pinned host memory, nlist {nlist}, "
                                   f"nprobe {nprobe}, k {k}, batch 1, device buffer {cap / 1e9:.1f} GB, scale {scale}",
                       "host_threads": threads, "decode_alone_ms": round(decode_alone_ms, 2), "decode_matmuls": reps},
-           "budget_sweep": rows, "parity_sample": parity, "setup_s": round(setup_s, 1)}
+           "budget_sweep": rows, "cluster_cache": cache_rows, "parity_sample": parity, "setup_s": round(setup_s, 1)}
     print(json.dumps(out))
 
 

@@ -15,6 +15,7 @@ from .generators import (  # noqa: F401
     cluster_major_datastore,
     kmeans_datastore,
     mixture_rows,
+    perturbed,
     query_pairs,
     shared_batch_queries,
     zipf_sizes,

@@ -155,6 +155,13 @@ def query_pairs(anchor_rows, nq, alpha, seed, anchor_noise=0.1):
     return q_in.contiguous(), q_out.contiguous()
 
 
+def perturbed(q, alpha, seed):
+    """normalize(q + alpha * g), g ~ N(0, I/d): the rewritten form of each query in q [nq, d]."""
+    g = _gen(seed, q.device)
+    d = q.shape[1]
+    return _normalize(q + alpha * (d ** -0.5) * torch.randn(q.shape, generator=g, device=q.device)).contiguous()
+
+
 # ---- the named workloads ------------------------------------------------------
 
 def config1_tiny(seed=20969, device="cpu", dtype="f32"):
