@@ -37,6 +37,7 @@ def lib():
             "orc_prefetch": [vp, i32, i32, ci, vp, ci, vp, i32, u64, u64, vp, vp, vp, vp, vp],
             "orc_split": [vp, i32, i32, ci, vp, i32, vp, vp, vp, vp, vp],
             "orc_hybrid": [vp, ci, vp, vp, vp, i32, i32, ci, vp, i32, i32, vp, vp, vp, vp],
+            "orc_schedule": [vp, i32, i32, i32, vp],
             "orc_cache_round": [vp, vp, vp, vp, i32, i32, ci, C.c_float, C.c_float, C.c_double, u64, vp, vp],
         }
         L.orc_cache_admit.restype = None
@@ -183,6 +184,15 @@ def cache_round(hot, used_flags, res, off, d, dtype, decay, h_inc, fraction):
                               C.byref(res.used), _p(evicted))
     assert n >= 0
     return evicted[:n]
+
+
+def schedule(q, micro):
+    """Greedy grouping of the queries q [B, d] into micro-batches of `micro`; returns the order."""
+    q = _f32(q)
+    B, d = q.shape
+    order = np.zeros(B, dtype=np.int32)
+    assert lib().orc_schedule(_p(q), B, d, int(micro), _p(order)) == B
+    return order
 
 
 def split(centroids, x_out, L, res_flags, metric):

@@ -399,6 +399,46 @@ int32_t orc_cache_round(float *hot, uint8_t *used_flags, uint8_t *resident, cons
     return n_evicted;
 }
 
+/* ---- prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching") -- */
+
+/* Groups the B queries of a global batch into micro-batches of m by a greedy
+ * search on squared L2 distance.  While queries remain: the seed is the
+ * remaining query of lowest index; its micro-batch is the seed followed by the
+ * m-1 remaining queries nearest to the seed, nearest first (equal distance:
+ * lower index first).  order[] receives the B query indices, micro-batch after
+ * micro-batch (the last one may be short).  Distances are plain double sums of
+ * squared differences in index order. */
+int32_t orc_schedule(const float *q, int32_t B, int32_t d, int32_t m, int32_t *order)
+{
+    if (B < 1 || d < 1 || m < 1) return -1;
+    uint8_t *taken = (uint8_t *)calloc((size_t)B, 1);
+    if (!taken) return -2;
+    int32_t pos = 0;
+    while (pos < B) {
+        int32_t seed = 0;
+        while (taken[seed]) ++seed;
+        taken[seed] = 1;
+        order[pos++] = seed;
+        for (int32_t slot = 1; slot < m && pos < B; ++slot) {
+            int32_t best = -1;
+            double best_dist = 0.0;
+            for (int32_t j = 0; j < B; ++j) {
+                if (taken[j]) continue;
+                double dist = 0.0;
+                for (int32_t t = 0; t < d; ++t) {
+                    double diff = (double)q[(int64_t)seed * d + t] - (double)q[(int64_t)j * d + t];
+                    dist += diff * diff;
+                }
+                if (best < 0 || dist < best_dist) { best = j; best_dist = dist; }
+            }
+            taken[best] = 1;
+            order[pos++] = best;
+        }
+    }
+    free(taken);
+    return B;
+}
+
 /* Number of OpenMP threads the scoring loop will use (for the baseline report). */
 int orc_threads(void)
 {

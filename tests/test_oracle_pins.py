@@ -469,3 +469,58 @@ def test_cache_eviction_invariants():
             # and they left coldest first
             for a, b in zip(ev[:-1], ev[1:]):
                 assert upd[a] < upd[b] or (upd[a] == upd[b] and a > b)
+
+
+# ---- prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching") ----------------------
+def test_schedule_handworked_line():
+    """Points on a line at 0, 10, 1, 11, 2, 12 (as one-hot-scaled vectors along the first axis), micro-batches
+    of 3: the seed 0 takes its two nearest (1, then 2), the next seed is index 1 (at 10) and takes 11, 12."""
+    pos = np.array([0.0, 10.0, 1.0, 11.0, 2.0, 12.0], dtype=np.float32)
+    q = np.zeros((6, 4), dtype=np.float32)
+    q[:, 0] = pos
+    assert list(O.schedule(q, 3)) == [0, 2, 4, 1, 3, 5]
+    assert list(O.schedule(q, 1)) == [0, 1, 2, 3, 4, 5]
+    assert list(O.schedule(q, 2)) == [0, 2, 1, 3, 4, 5]          # 0 with 1; then 10 with 11; then 2 with 12
+    # equal distances: the lower index first (seed at 0; 1 and -1 are equally far)
+    q2 = np.zeros((3, 2), dtype=np.float32)
+    q2[:, 0] = [0.0, 1.0, -1.0]
+    assert list(O.schedule(q2, 3)) == [0, 1, 2]
+    q2[:, 0] = [0.0, -1.0, 1.0]
+    assert list(O.schedule(q2, 3)) == [0, 1, 2]
+
+
+def test_schedule_whole_batch_is_an_argsort_and_invariants():
+    rng = np.random.default_rng(21)
+    for B, d, m in ((17, 5, 17), (40, 8, 100), (64, 16, 8), (33, 7, 4), (50, 3, 1)):
+        q = rng.standard_normal((B, d)).astype(np.float32)
+        order = O.schedule(q, m)
+        assert sorted(order) == list(range(B))
+        dist = ((q[:, None, :].astype(np.float64) - q[None, :, :].astype(np.float64)) ** 2).sum(-1)
+        if m >= B:
+            # one micro-batch: the seed, then everyone else by distance to it (numpy's stable argsort)
+            assert order[0] == 0 and list(order[1:]) == list(np.argsort(dist[0][1:], kind="stable") + 1)
+        left = set(range(B))
+        for g0 in range(0, B, m):
+            grp = list(order[g0:g0 + m])
+            seed = grp[0]
+            assert seed == min(left)                       # the lowest remaining index seeds the group
+            left.remove(seed)
+            for a, b in zip(grp[1:-1], grp[2:]):
+                assert dist[seed, a] <= dist[seed, b]      # nearest first
+            for x in grp[1:]:
+                left.remove(x)
+            if grp[1:] and left:
+                assert dist[seed, grp[-1]] <= min(dist[seed, y] for y in left)   # nobody nearer was left out
+
+
+def test_schedule_recovers_separated_groups():
+    """Queries drawn tightly around well-separated centres, as many per centre as the micro-batch
+    holds: every micro-batch is one centre's queries."""
+    rng = np.random.default_rng(22)
+    centres, m, d = 6, 5, 12
+    c = 10.0 * rng.standard_normal((centres, d))
+    label = rng.permutation(np.repeat(np.arange(centres), m))
+    q = (c[label] + 0.01 * rng.standard_normal((centres * m, d))).astype(np.float32)
+    order = O.schedule(q, m)
+    for g0 in range(0, centres * m, m):
+        assert len(set(label[order[g0:g0 + m]])) == 1
