@@ -245,6 +245,17 @@ int ivf_cache_configure(ivf_index* index, float fraction, float h_init, float de
 int ivf_cache_end_round(ivf_index* index, ivf_cache_stats* stats /* or NULL */);
 int ivf_cache_hotness(ivf_index* index, float* hotness);
 
+/*
+ * Prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching"): groups the nq
+ * queries of a global batch (host, nq x d float32, nq <= 4096) into micro-batches of `micro`
+ * by a greedy search on squared L2 distance, on the GPU.  While queries remain, the remaining
+ * query of lowest index seeds a micro-batch and the micro - 1 remaining queries nearest to it
+ * follow, nearest first (equal distance: lower index first).  order (host, nq entries) receives
+ * the query indices micro-batch after micro-batch; the last micro-batch may be short.
+ * *ms_gpu (or NULL) receives the time of the two kernels.  Blocks until order is filled.
+ */
+int ivf_schedule(ivf_index* index, const float* q, int32_t nq, int32_t micro, int32_t* order, float* ms_gpu);
+
 /* Number of host threads used for the scan of C_miss (default: hardware threads, at most 64). */
 int ivf_set_host_threads(ivf_index* index, int32_t n);
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
-    "ivf_strerror", "ivf_last_error",
+    "ivf_schedule", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -93,6 +93,7 @@ def load():
     L.ivf_cache_configure.argtypes = [vp, C.c_float, C.c_float, C.c_float, C.c_float]
     L.ivf_cache_end_round.argtypes = [vp, C.POINTER(CacheStats)]
     L.ivf_cache_hotness.argtypes = [vp, vp]
+    L.ivf_schedule.argtypes = [vp, vp, i32, i32, vp, C.POINTER(C.c_float)]
     L.ivf_strerror.argtypes = [ci]
     L.ivf_strerror.restype = C.c_char_p
     L.ivf_last_error.restype = C.c_char_p
@@ -226,6 +227,14 @@ class Index:
         ids = np.empty(self.n, dtype=np.int64)
         _check(load().ivf_get_layout(self._h, _ptr(off), _ptr(ids)))
         return off, ids
+
+    # -- prefetching scheduler ---------------------------------------------------------------
+    def ivf_schedule(self, q, micro, with_time=False):
+        q = _host(q, np.float32).reshape(-1, self.d)
+        order = np.empty(q.shape[0], dtype=np.int32)
+        ms = C.c_float(0)
+        _check(load().ivf_schedule(self._h, _ptr(q), q.shape[0], int(micro), _ptr(order), C.byref(ms)))
+        return (order, ms.value) if with_time else order
 
     # -- cluster cache -----------------------------------------------------------------------
     def ivf_cache_configure(self, fraction=0.5, h_init=1.0, decay=2.0, h_inc=1.0):

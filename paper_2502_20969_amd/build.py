@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libivf.so")
 
-HIP_SOURCES = ["ivf_kernels.hip", "ivf_batched.hip", "ivf_api.hip"]
+HIP_SOURCES = ["ivf_kernels.hip", "ivf_batched.hip", "ivf_sched.hip", "ivf_api.hip"]
 HOST_SOURCES = ["host_scan.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

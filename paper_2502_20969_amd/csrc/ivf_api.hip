@@ -916,6 +916,38 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     return IVF_OK;
 }
 
+// ---- prefetching scheduler ---------------------------------------------------------------------------
+extern "C" int ivf_schedule(ivf_index* ix, const float* q, int32_t nq, int32_t micro, int32_t* order, float* ms_gpu) {
+    if (!ix || !q || !order) return fail(IVF_EINVAL, "index, q or order is NULL");
+    if (nq < 1 || micro < 1) return fail(IVF_EINVAL, "nq and micro must be at least 1");
+    if (nq > kScheduleMaxQueries) return fail(IVF_ELIMIT, "at most %d queries per global batch", kScheduleMaxQueries);
+    int rc = settle_on_lane0(ix);
+    if (rc) return rc;
+    float* d_q = nullptr; double* d_dist = nullptr; int32_t* d_order = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto cleanup = [&]() {
+        hipFree(d_q); hipFree(d_dist); hipFree(d_order);
+        if (e0) hipEventDestroy(e0);
+        if (e1) hipEventDestroy(e1);
+    };
+#define SCHED_TRY(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { cleanup(); return fail(IVF_EHIP, "%s: %s", #call, hipGetErrorString(e_)); } } while (0)
+    SCHED_TRY(hipMalloc(&d_q, (size_t)nq * ix->d * sizeof(float)));
+    SCHED_TRY(hipMalloc(&d_dist, (size_t)nq * nq * sizeof(double)));
+    SCHED_TRY(hipMalloc(&d_order, (size_t)nq * sizeof(int32_t)));
+    SCHED_TRY(hipEventCreate(&e0));
+    SCHED_TRY(hipEventCreate(&e1));
+    SCHED_TRY(hipMemcpyAsync(d_q, q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    SCHED_TRY(hipEventRecord(e0, ix->cs));
+    SCHED_TRY(launch_schedule(d_q, nq, ix->d, micro, d_dist, d_order, ix->cs));
+    SCHED_TRY(hipEventRecord(e1, ix->cs));
+    SCHED_TRY(hipMemcpyAsync(order, d_order, (size_t)nq * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
+    SCHED_TRY(hipStreamSynchronize(ix->cs));
+    if (ms_gpu) SCHED_TRY(hipEventElapsedTime(ms_gpu, e0, e1));
+#undef SCHED_TRY
+    cleanup();
+    return IVF_OK;
+}
+
 // ---- cluster cache -------------------------------------------------------------------------------------
 extern "C" int ivf_cache_configure(ivf_index* ix, float fraction, float h_init, float decay, float h_inc) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");

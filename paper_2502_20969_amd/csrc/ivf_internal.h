@@ -111,6 +111,10 @@ hipError_t launch_cache_admit(float* hot, uint32_t* used, const int64_t* res_off
                               hipStream_t s);
 hipError_t launch_cache_round(float* hot, uint32_t* used, int nlist, float decay, float h_inc, hipStream_t s);
 
+// prefetching scheduler (ivf_sched.hip): pairwise squared L2 distances [B x B] and the greedy grouping
+hipError_t launch_schedule(const float* q_dev, int B, int d, int m, double* dist, int32_t* order, hipStream_t s);
+constexpr int kScheduleMaxQueries = 4096;
+
 // ---- batched (list-major) search: ivf_batched.hip ------------------------------------------------
 struct BatchTask { uint32_t cluster, group, tile; };    // 128 rows of a cluster x up to 32 of its queries
 

@@ -108,3 +108,35 @@ def test_id_rank_tables(streams, kind):
     for b in range(6):
         assert check_topk(gi[b], gd[b], rows, O.F32, off, ids, cent, q[b], 5, 30, O.IP) == 0
     index.close()
+
+
+@pytest.mark.parametrize("B,d,micro", [(1, 8, 4), (7, 5, 3), (64, 33, 8), (256, 768, 32), (300, 100, 7),
+                                       (1500, 16, 64), (130, 64, 1), (90, 12, 500)])
+def test_prefetching_scheduler(streams, B, d, micro):
+    """Greedy grouping of a global batch into micro-batches (Sec. 4.2 'Scheduling optimization for
+    prefetching') against the oracle: the distances are added in the oracle's order, so the
+    orders agree exactly, ties included (a quarter of the queries are exact duplicates)."""
+    rng = np.random.default_rng(B * 31 + d)
+    centres = rng.standard_normal((max(1, B // 6), d)).astype(np.float32)
+    q = (centres[rng.integers(0, centres.shape[0], B)] + 0.3 * rng.standard_normal((B, d))).astype(np.float32)
+    dup = rng.integers(0, B, B // 4)
+    q[rng.integers(0, B, B // 4)] = q[dup]
+    cent = rng.standard_normal((4, d)).astype(np.float32)
+    index = _index(streams, cent, d, P.IVF_IP)
+    order, ms = index.ivf_schedule(q, micro, with_time=True)
+    assert list(order) == list(O.schedule(q, micro))
+    assert ms >= 0.0
+    index.close()
+
+
+def test_scheduler_rejects_bad_arguments(streams):
+    cent = np.zeros((4, 8), dtype=np.float32)
+    index = _index(streams, cent, 8, P.IVF_IP)
+    q = np.zeros((5000, 8), dtype=np.float32)
+    with pytest.raises(P.binding.IvfError) as e:
+        index.ivf_schedule(q, 8)
+    assert e.value.status == -5
+    with pytest.raises(P.binding.IvfError) as e:
+        index.ivf_schedule(q[:10], 0)
+    assert e.value.status == -1
+    index.close()
