@@ -232,6 +232,37 @@ def run_lookahead(args):
                         "move_gbs": round((m["moved"] / 1e9) / (m["ms_compact"] / 1e3), 1) if m["ms_compact"] > 0 else 0.0})
         cache_rows.append(row)
     index.ivf_cache_configure(-1.0, 1.0, 2.0, 1.0)
+    # Prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching"): a global batch of
+    # requests around many topics, served in micro-batches that share one prefetch budget; once in
+    # arrival order, once grouped by ivf_schedule.
+    sched_rows = []
+    gB, micro, g_topics = 8 * args.pairs, 8, 2 * args.pairs
+    gq_in = W.shared_batch_queries(ds, gB, g_topics, 20983)
+    gq_out = W.perturbed(gq_in, 0.3, 20984)
+    perm = torch.randperm(gB, generator=torch.Generator().manual_seed(20985))
+    gq_in, gq_out = gq_in.cpu()[perm].numpy(), gq_out.cpu()[perm].numpy()       # topics arrive interleaved
+    index.ivf_schedule(gq_in, micro)                                             # untimed first call
+    t = time.perf_counter()
+    order, ms_sched = index.ivf_schedule(gq_in, micro, with_time=True)
+    ms_sched_call = (time.perf_counter() - t) * 1e3
+    index.ivf_reserve(micro, nprobe, k)
+    for j in range(0, gB, micro):            # untimed first touch
+        index.ivf_prefetch(gq_in[j:j + micro], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
+        index.ivf_search(gq_out[j:j + micro], nprobe, k)
+    for mode, seq in (("arrival order", np.arange(gB)), ("grouped by ivf_schedule", order)):
+        hits, ms_s, copied = [], [], []
+        for j in range(0, gB, micro):
+            g = seq[j:j + micro]
+            ps = index.ivf_prefetch(gq_in[g], nprobe, budget, flags=P.IVF_PREFETCH_RESET)
+            decode(reps)
+            torch.cuda.synchronize()
+            index.ivf_prefetch_wait()
+            ids, dists, st = index.ivf_search(gq_out[g], nprobe, k, with_stats=True)
+            hits.append(st.hit_rate); ms_s.append(st.ms_total); copied.append(ps.bytes)
+        sched_rows.append({"mode": mode, "global_batch": gB, "micro_batch": micro, "topics": g_topics,
+                           "hit_rate": round(float(np.mean(hits)), 4), "search_ms_per_micro_batch": round(float(np.mean(ms_s)), 3),
+                           "prefetched_gb": round(float(np.mean(copied)) / 1e9, 3)})
+    sched_rows.append({"ivf_schedule_gpu_ms": round(ms_sched, 3), "ivf_schedule_call_ms": round(ms_sched_call, 3)})
     # sampled parity at this size: two hybrid searches against the oracle on the same pinned lists
     parity = None
     if not args.no_cpu:
@@ -253,7 +284,7 @@ def run_lookahead(args):
            "config": {"workload": f"configs[3] limited-GPU-memory lookahead: {n} x 768 fp16 in pinned host memory, nlist {nlist}, "
                                   f"nprobe {nprobe}, k {k}, batch 1, device buffer {cap / 1e9:.1f} GB, scale {scale}",
                       "host_threads": threads, "decode_alone_ms": round(decode_alone_ms, 2), "decode_matmuls": reps},
-           "budget_sweep": rows, "cluster_cache": cache_rows, "parity_sample": parity, "setup_s": round(setup_s, 1)}
+           "budget_sweep": rows, "cluster_cache": cache_rows, "prefetch_scheduler": sched_rows, "parity_sample": parity, "setup_s": round(setup_s, 1)}
     print(json.dumps(out))
 
 
