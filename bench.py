@@ -1,7 +1,7 @@
 """Benchmark of the IVF search hot path on one MI355X.
 
-Workload: benchmark configs[1] -- single-query retrieval over 1,000,000 x 768 fp32 rows in
-1024 k-means lists, nprobe 32, k 10, batch 1, synthetic (seeded mixture of Gaussians).  A step is
+Workload: single-query retrieval (configs[1] of the benchmark definition) over 1,000,000 x 768
+fp32 rows in 1024 k-means lists, nprobe 32, k 10, batch 1, synthetic (seeded mixture of Gaussians).  A step is
 one whole search (coarse scoring, top-nprobe selection, list scan, top-k merge) of one query
 through ivf_search_device; query and outputs are resident in HBM; 256 distinct queries are
 cycled so that consecutive steps scan different lists.  Prints one JSON line.
@@ -19,7 +19,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes one scan launch of the default workload moves, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 1 GiB copy (profiles/scan_kernel_c2_single_query.md): read + written
-C2_SCAN_TRAFFIC_BYTES = 89314 * 1024 + 48 * 1024
+C2_SCAN_TRAFFIC_BYTES = 89266 * 1024 + 80 * 1024
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
 
 
@@ -109,7 +109,7 @@ def cpu_baseline(rows_host, assign_host, cent_host, q_out, nprobe, k, budget_s=1
 
 
 def run_lookahead(args):
-    """Benchmark configs[3]: lists in pinned host memory, an 8 GB device prefetch buffer,
+    """Lookahead configuration (configs[3]): lists in pinned host memory, an 8 GB device prefetch buffer,
     ivf_prefetch(q_in) overlapped with a synthetic ~20 ms decode, then ivf_search(q_out) with the
     resident clusters on the GPU and the others on the host.  One JSON line with a budget sweep."""
     import numpy as np
@@ -289,7 +289,7 @@ def run_lookahead(args):
 
 
 def run_batched(args):
-    """Benchmark configs[2] (c3: 10M x 768 fp16, nlist 4096 Zipf(1.1), nprobe 128, k 10, batch 32
+    """Batched configurations: configs[2] (c3: 10M x 768 fp16, nlist 4096 Zipf(1.1), nprobe 128, k 10, batch 32
     sharing about 40 % of the probed clusters) and configs[4] (c5: 30M x 1024 bf16, nlist 8192
     Zipf(1.2), nprobe 512, k 100, batch 256 from distinct components), all lists resident in HBM,
     searched list-major.  A step is one whole batch.  One JSON line."""

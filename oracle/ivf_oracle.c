@@ -25,7 +25,7 @@
  * independent candidates over threads; each candidate's sum is still the plain
  * sequential loop.
  *
- * Readings of points the paper leaves open (all restated in the design doc):
+ * Readings of points the paper leaves open:
  *   - "inner product" as a distance means: larger is nearer;
  *   - "L2" is the squared Euclidean distance, smaller is nearer;
  *   - the same metric is used for the coarse and the fine stage;

@@ -134,7 +134,7 @@ struct ivf_index {
     std::vector<int64_t> h_res_off; // host mirror of d_res_off
     int64_t* h_res_stage = nullptr; // pinned copy used as the source of the table upload
     size_t buf_used = 0;
-    hipEvent_t ev_pf_begin = nullptr, ev_pf_done = nullptr, ev_probe = nullptr;
+    hipEvent_t ev_pf_begin = nullptr, ev_pf_done = nullptr, ev_probe = nullptr, ev_pf_table = nullptr;
     bool pf_recorded = false;
 
     std::vector<uint64_t> rows_desc_prefix;   // prefix sums of list sizes, largest first
@@ -439,6 +439,7 @@ int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* cen
     HIP_TRY(hipEventCreate(&ix->ev_pf_begin));
     HIP_TRY(hipEventCreate(&ix->ev_pf_done));
     HIP_TRY(hipEventCreateWithFlags(&ix->ev_probe, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&ix->ev_pf_table, hipEventDisableTiming));
     HIP_TRY(hipMalloc(&ix->d_centroids, (size_t)nlist * d * sizeof(float)));
     HIP_TRY(hipMemcpy(ix->d_centroids, centroids, (size_t)nlist * d * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(hipMalloc(&ix->d_off, (size_t)(nlist + 1) * sizeof(int64_t)));
@@ -560,6 +561,7 @@ extern "C" void ivf_free(ivf_index* ix) {
     if (ix->ev_pf_begin) hipEventDestroy(ix->ev_pf_begin);
     if (ix->ev_pf_done) hipEventDestroy(ix->ev_pf_done);
     if (ix->ev_probe) hipEventDestroy(ix->ev_probe);
+    if (ix->ev_pf_table) hipEventDestroy(ix->ev_pf_table);
     if (ix->own_compute) hipStreamDestroy(ix->compute);
     if (ix->own_copy) hipStreamDestroy(ix->copy);
     delete ix;
@@ -903,9 +905,12 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
             }
         }
     }
-    // the residency table follows the data on the same stream
+    // the residency table follows the data on the same stream; the pinned staging copy is reused,
+    // so the previous upload from it must have finished
+    if (ix->pf_recorded) HIP_TRY(hipEventSynchronize(ix->ev_pf_table));
     memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)ix->nlist * sizeof(int64_t));
     HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)ix->nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->copy));
+    HIP_TRY(hipEventRecord(ix->ev_pf_table, ix->copy));
     if (ix->cache_on)     // clusters that arrived are cached from now on; a reset drops the cache
         HIP_TRY(launch_cache_admit(ix->d_hot, ix->d_used, ix->d_res_off, ix->nlist, ix->cache_h_init,
                                    (flags & IVF_PREFETCH_RESET) ? 1 : 0, ix->copy));

@@ -166,49 +166,6 @@ __device__ __forceinline__ double rescore_chunks(const unsigned char* row, const
     return wave_sum(acc);
 }
 
-// The same for up to four rows at once, so that all their loads are in flight together.
-template <typename T>
-__device__ __forceinline__ void rescore_chunks_x4(const unsigned char* const (&row)[4], int cnt, const float* q,
-                                                  int d, int metric, double (&out)[4]) {
-    constexpr int EPL = T::kPerLoad;
-    const int lane = lane_id();
-    const int chunks = d / EPL;
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int c0 = lane; c0 < chunks; c0 += 256) {
-        uint4 v[4][4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                int c = c0 + u * 64;
-                v[j][u] = (j < cnt && c < chunks) ? *(const uint4*)(row[j] + (size_t)c * 16) : make_uint4(0, 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int c = c0 + u * 64;
-            if (c < chunks) {
-                double qv[EPL];
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) qv[e] = (double)q[c * EPL + e];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float x[EPL];
-                    Unpack<T>::run(v[j][u], x);
-#pragma unroll
-                    for (int e = 0; e < EPL; ++e) {
-                        double y = (double)x[e];
-                        if (metric == 0) acc[j] = fma(qv[e], y, acc[j]);
-                        else { double df = qv[e] - y; acc[j] = fma(df, df, acc[j]); }
-                    }
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) out[j] = wave_sum(acc[j]);
-}
-
 // ---- order-preserving integer keys ------------------------------------------------------------
 // Unsigned keys whose ascending order is the ascending order of the floating value.
 __device__ __forceinline__ uint32_t ordered(float f) {
