@@ -301,6 +301,12 @@ def run_batched(args):
     c3 = args.workload == "c3"
     n = int((10_000_000 if c3 else 30_000_000) * args.scale)
     d, nlist, nprobe, k, B = (768, 4096, 128, 10, 32) if c3 else (1024, 8192, 512, 100, 256)
+    if args.dim > 0:
+        d = args.dim
+    if args.batch > 0:
+        B = args.batch
+    if args.topk > 0:
+        k = args.topk
     dtype, zipf = ("f16", 1.1) if c3 else ("bf16", 1.2)
     t0 = time.time()
     sizes = W.zipf_sizes(n, nlist, zipf, 20975 if c3 else 20977)
@@ -518,6 +524,9 @@ def main():
                     help="c2: single-query retrieval (the default bench line); c4: lookahead with host-resident lists; "
                          "c3 / c5: batched retrieval over fp16 / bf16 lists")
     ap.add_argument("--scale", type=float, default=1.0, help="c3, c4, c5: fraction of the named datastore to build")
+    ap.add_argument("--dim", type=int, default=0, help="c3, c5: row dimension instead of the named one (a multiple of 64)")
+    ap.add_argument("--batch", type=int, default=0, help="c3, c5: queries per batch instead of the named number")
+    ap.add_argument("--topk", type=int, default=0, help="c3, c5: k instead of the named one")
     ap.add_argument("--groups", type=int, default=0, help="c3, c5: mixture components the batch's queries are drawn around")
     ap.add_argument("--pairs", type=int, default=16, help="c4: (q_in, q_out) pairs per budget")
     args = ap.parse_args()

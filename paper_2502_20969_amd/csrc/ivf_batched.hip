@@ -53,9 +53,10 @@ hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, u
 }
 
 // ---- threshold sample --------------------------------------------------------------------------------------
-// fp32 scores (fp32 query) of the first rows of each query's nearest cluster, reduced to the
-// k-th best.  Any subset of the selected rows gives a valid lower bound of the k-th best score
-// over all of them.  The sample of a query is split over kSampleParts workgroups of 128 rows;
+// fp32 scores (fp32 query) of the first 2048 rows of each query's selected clusters, taken in
+// probe order (usually all from the nearest cluster; more clusters when those are small), reduced
+// to the k-th best.  Any subset of the selected rows gives a valid lower bound of the k-th best
+// score over all of them.  The sample of a query is split over kSampleParts workgroups of 128 rows;
 // each writes its k best keys, and prep_queries_kernel merges the parts.
 constexpr int kSampleParts = 16;
 constexpr int kSamplePartRows = 128;
@@ -69,22 +70,39 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
     float* ql = (float*)smem;
     for (int i = threadIdx.x; i < a.d; i += blockDim.x) ql[i] = a.q[(size_t)qi * a.d + i];
     __syncthreads();
-    const int c = a.probe[(size_t)qi * a.nprobe];
-    const int64_t lo = a.off[c];
-    const uint32_t n = (uint32_t)min((int64_t)(kSampleParts * kSamplePartRows), a.off[c + 1] - lo);
+    // cursor over the rows of the selected clusters laid end to end; sample rows are asked for in
+    // increasing order, so it only moves forward
+    const int32_t* pr = a.probe + (size_t)qi * a.nprobe;
+    int ci = 0;
+    uint32_t c_begin = 0, c_n = 0;
+    int64_t c_lo = 0;
+    auto enter = [&](int i) { const int c = pr[i]; c_lo = a.off[c]; c_n = (uint32_t)(a.off[c + 1] - c_lo); };
+    enter(0);
+    auto locate = [&](uint32_t r) -> int64_t {           // global row of sample row r, -1 past the last row
+        while (r >= c_begin + c_n) {
+            if (ci + 1 >= a.nprobe) return -1;
+            c_begin += c_n;
+            enter(++ci);
+        }
+        return c_lo + (int64_t)(r - c_begin);
+    };
     const uint32_t r_begin = part * kSamplePartRows + wave * 32;
-    const uint32_t r_end = min(n, r_begin + 32);
+    const uint32_t r_end = r_begin + 32;
     const int chunks = a.d / EPL;
     WaveTopK<2, false> top;                     // ties inside the sample do not matter for a bound
     top.init();
     for (uint32_t r0 = r_begin; r0 < r_end; r0 += 4) {
+        int64_t g[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) g[u] = locate(r0 + u);
+        if (g[0] < 0) break;                              // the selected clusters hold no more rows
         float s[4] = {0.f, 0.f, 0.f, 0.f};
         for (int ch = lane; ch < chunks; ch += 64) {
             uint4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                uint32_t r = min(r0 + u, r_end - 1);
-                v[u] = *(const uint4*)((const unsigned char*)a.lists + ((size_t)lo + r) * a.d * 2 + (size_t)ch * 16);
+                const int64_t row = g[u] >= 0 ? g[u] : g[0];      // past the end: re-read a valid row
+                v[u] = *(const uint4*)((const unsigned char*)a.lists + (size_t)row * a.d * 2 + (size_t)ch * 16);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -97,7 +115,7 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             float ck = read_lane(group_total_last_lane<64>(s[u]), 63);
-            if (r0 + u < r_end && ck >= top.thr) top.push(ck, r0 + u);
+            if (g[u] >= 0 && ck >= top.thr) top.push(ck, r0 + u);
         }
         if (top.pcount > 60) top.flush(a.k);
     }
@@ -362,14 +380,23 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs
         // lane holds query `col`, rows (i / 4) * 8 + khalf * 4 + i % 4
         const float thr = s_thr[col];
         const uint32_t qi = s_q[col];
+        uint32_t pass = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const uint32_t r = r0 + (i / 4) * 8 + khalf * 4 + (i % 4);
-            if (acc[i] >= thr && r < n) {
-                uint32_t pos = atomicAdd(&a.cand_count[qi], 1u);
-                if (pos < (uint32_t)a.cand_cap) {
-                    a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r);
-                    a.cand_score[(size_t)qi * a.cand_cap + pos] = acc[i];
+            if (acc[i] >= thr && r < n) pass |= 1u << i;
+        }
+        if (pass) {
+            // one reservation for all rows of this lane that passed
+            uint32_t pos = atomicAdd(&a.cand_count[qi], (uint32_t)__popc(pass));
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if ((pass >> i) & 1u) {
+                    if (pos < (uint32_t)a.cand_cap) {
+                        a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r0 + (i / 4) * 8 + khalf * 4 + (i % 4));
+                        a.cand_score[(size_t)qi * a.cand_cap + pos] = acc[i];
+                    }
+                    ++pos;
                 }
             }
         }
