@@ -515,9 +515,20 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
     if ((uint32_t)tid < tot) {
         double mk = f_key[tid]; int64_t mi = f_id[tid];
         uint32_t rank = 0;
-        for (uint32_t j = 0; j < tot; ++j) {
-            double ok = f_key[j]; int64_t oi = f_id[j];
-            rank += (ok > mk) || (ok == mk && oi < mi);
+        // eight others per pass, all read before any is compared, and no branches
+#pragma unroll 1
+        for (uint32_t j0 = 0; j0 < tot; j0 += 8) {
+            double ok[8]; int64_t oi[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t j = min(j0 + u, tot - 1);
+                ok[u] = f_key[j]; oi[u] = f_id[j];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool ahead = (ok[u] > mk) | ((ok[u] == mk) & (oi[u] < mi));
+                rank += (uint32_t)(ahead & (j0 + u < tot));
+            }
         }
         if (rank < (uint32_t)k) {
             a.out_ids[(size_t)qi * k + rank] = mi;

@@ -320,48 +320,79 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
     uint32_t* s_rp = a.slots.rprefix + (size_t)qi * (nprobe + 1);
     uint32_t* l_rp = (uint32_t*)(smem_raw + sort_bytes);     // LDS copy of the row prefix
     uint32_t carry = 0;
-    for (uint32_t base = 0; base < nprobe; base += nt) {
-        uint32_t i = base + tid;
-        uint32_t rows = 0;
-        if (i < nprobe) {
-            uint32_t c = in_lds ? ((uint32_t*)(smem_raw + sizeof(uint64_t) * pad))[i] : idx[i];
-            a.probe[(size_t)qi * nprobe + i] = (int32_t)c;
-            int64_t lo = off[c];
-            uint32_t n = (uint32_t)(off[c + 1] - lo);
-            int64_t ro = a.res_off[c];
-            s_base[i] = ro;
-            s_grow[i] = (uint32_t)lo;
-            s_n[i] = n;
-            rows = ro >= 0 ? n : 0;
-            if (a.used && ro >= 0) a.used[c] = 1u;        // cache bookkeeping: resident and selected
-        }
-        // block-wide exclusive scan of `rows`
-        uint32_t incl = rows;
+    // one selected cluster: its table entries; returns the rows it contributes to the scan
+    auto fill_slot = [&](uint32_t i) -> uint32_t {
+        uint32_t c = in_lds ? ((uint32_t*)(smem_raw + sizeof(uint64_t) * pad))[i] : idx[i];
+        a.probe[(size_t)qi * nprobe + i] = (int32_t)c;
+        int64_t lo = off[c];
+        uint32_t n = (uint32_t)(off[c + 1] - lo);
+        int64_t ro = a.res_off[c];
+        s_base[i] = ro;
+        s_grow[i] = (uint32_t)lo;
+        s_n[i] = n;
+        if (a.used && ro >= 0) a.used[c] = 1u;            // cache bookkeeping: resident and selected
+        return ro >= 0 ? n : 0;
+    };
+    if (nprobe <= 64) {
+        // the whole table fits one wavefront: prefix inside it, no LDS round trips
+        if (wave_id() == 0) {
+            const uint32_t i = (uint32_t)tid;
+            const uint32_t rows = i < nprobe ? fill_slot(i) : 0;
+            uint32_t incl = rows;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            uint32_t up = __shfl_up(incl, o);
-            if ((tid & 63) >= o) incl += up;
+            for (int o = 1; o < 64; o <<= 1) {
+                uint32_t up = __shfl_up(incl, o);
+                if (tid >= o) incl += up;
+            }
+            if (i < nprobe) {
+                s_rp[i] = incl - rows;
+                if (prefix_in_lds) l_rp[i] = incl - rows;
+            }
+            const uint32_t total = read_lane(incl, 63);
+            if (tid == 0) {
+                scan_buf[0] = total;
+                s_rp[nprobe] = total;
+                if (prefix_in_lds) l_rp[nprobe] = total;
+                if (a.rows_counter) atomicAdd(a.rows_counter, (unsigned long long)total);
+            }
         }
-        if ((tid & 63) == 63) scan_buf[tid >> 6] = incl;
         __syncthreads();
-        uint32_t wave_off = 0;
-        for (int w = 0; w < (tid >> 6); ++w) wave_off += scan_buf[w];
-        uint32_t total = 0;
-        for (int w = 0; w < nt / 64; ++w) total += scan_buf[w];
-        if (i < nprobe) {
-            uint32_t ex = carry + wave_off + incl - rows;
-            s_rp[i] = ex;
-            if (prefix_in_lds) l_rp[i] = ex;
+        carry = scan_buf[0];
+    } else {
+        for (uint32_t base = 0; base < nprobe; base += nt) {
+            uint32_t i = base + tid;
+            uint32_t rows = i < nprobe ? fill_slot(i) : 0;
+            // block-wide exclusive scan of `rows`
+            uint32_t incl = rows;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                uint32_t up = __shfl_up(incl, o);
+                if ((tid & 63) >= o) incl += up;
+            }
+            if ((tid & 63) == 63) scan_buf[tid >> 6] = incl;
+            __syncthreads();
+            uint32_t wave_off = 0, total = 0;
+#pragma unroll
+            for (int w = 0; w < kSelectThreads / 64; ++w) {        // all sums read at once
+                const uint32_t v = w < nt / 64 ? scan_buf[w] : 0;
+                total += v;
+                wave_off += w < (tid >> 6) ? v : 0;
+            }
+            if (i < nprobe) {
+                uint32_t ex = carry + wave_off + incl - rows;
+                s_rp[i] = ex;
+                if (prefix_in_lds) l_rp[i] = ex;
+            }
+            carry += total;
+            __syncthreads();
         }
-        carry += total;
+        if (tid == 0) {
+            s_rp[nprobe] = carry;
+            if (prefix_in_lds) l_rp[nprobe] = carry;
+            if (a.rows_counter) atomicAdd(a.rows_counter, (unsigned long long)carry);
+        }
         __syncthreads();
     }
-    if (tid == 0) {
-        s_rp[nprobe] = carry;
-        if (prefix_in_lds) l_rp[nprobe] = carry;
-        if (a.rows_counter) atomicAdd(a.rows_counter, (unsigned long long)carry);
-    }
-    __syncthreads();
 
     IVF_TRACE_MARK(12);
     // workgroup shares: rows split evenly, each share starting inside some slot
@@ -1015,10 +1046,21 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     if ((uint32_t)tid < tot) {
         double mk = L.f_key[tid]; int64_t mi = L.f_id[tid];
         uint32_t rank = 0;
-#pragma unroll 6
-        for (uint32_t j = 0; j < tot; ++j) {
-            double ok = L.f_key[j]; int64_t oi = L.f_id[j];
-            rank += (ok > mk) || (ok == mk && oi < mi);
+        // eight others per pass, all read before any is compared, and no branches: a compare that
+        // waits for its own LDS read every time costs more than the whole pass
+#pragma unroll 1
+        for (uint32_t j0 = 0; j0 < tot; j0 += 8) {
+            double ok[8]; int64_t oi[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t j = min(j0 + u, tot - 1);
+                ok[u] = L.f_key[j]; oi[u] = L.f_id[j];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool ahead = (ok[u] > mk) | ((ok[u] == mk) & (oi[u] < mi));
+                rank += (uint32_t)(ahead & (j0 + u < tot));
+            }
         }
         if (rank < (uint32_t)k) {
             a.out_ids[(size_t)qi * k + rank] = mi;
