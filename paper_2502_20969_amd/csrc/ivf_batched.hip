@@ -469,10 +469,16 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
     uint64_t* keys = a.cand_key + (size_t)qi * a.surv_cap;
     const float* q = a.q + (size_t)qi * a.d;
     const size_t row_bytes = (size_t)a.d * 2;
-    for (uint32_t c = wave; c < n; c += nt / 64) {
+    // a group of 16 lanes per survivor, 64 survivors per pass, so that their row loads overlap
+    constexpr int kLpc = 16;
+    const int sub = tid % kLpc;
+#pragma unroll 1
+    for (uint32_t c = (uint32_t)(tid / kLpc); c < n; c += (uint32_t)(nt / kLpc)) {
         const unsigned char* rp = (const unsigned char*)a.lists + (size_t)rows[c] * row_bytes;
-        double s = a.dtype == 1 ? rescore_chunks<F16>(rp, q, a.d, 0) : rescore_chunks<BF16>(rp, q, a.d, 0);
-        if (lane == 0) keys[c] = ~ordered(s);           // ascending key = best first
+        double s = a.dtype == 1 ? rescore_partial<F16>(rp, q, a.d, 0, sub, kLpc) : rescore_partial<BF16>(rp, q, a.d, 0, sub, kLpc);
+#pragma unroll
+        for (int o = 1; o < kLpc; o <<= 1) s += __shfl_xor(s, o);
+        if (sub == 0) keys[c] = ~ordered(s);            // ascending key = best first
     }
     __syncthreads();
     const uint32_t want = min((uint32_t)k, n);

@@ -133,37 +133,41 @@ __device__ __forceinline__ double widen(const void* base, int dtype, size_t idx)
     return (double)__uint_as_float((uint32_t)b << 16);
 }
 
-// fp64 score of one stored row against q, by one wavefront; rows of whole 16-byte chunks are
-// read with up to four 16-byte loads per lane in flight.
+// Partial fp64 score of one stored row over the 16-byte chunks sub, sub + lpc, ... (lane `sub`
+// of a group of `lpc` lanes); four loads are in flight at a time.
 template <typename T>
-__device__ __forceinline__ double rescore_chunks(const unsigned char* row, const float* q, int d, int metric) {
+__device__ __forceinline__ double rescore_partial(const unsigned char* row, const float* q, int d, int metric,
+                                                  int sub, int lpc) {
     constexpr int EPL = T::kPerLoad;
-    const int lane = lane_id();
+    constexpr int U = EPL == 4 ? 6 : 4;        // 768 fp32 values over 32 lanes: one pass
     const int chunks = d / EPL;
     double acc = 0.0;
-    for (int c0 = lane; c0 < chunks; c0 += 256) {
-        uint4 v[4];
+#pragma unroll 1
+    for (int c0 = sub; c0 < chunks; c0 += lpc * U) {
+        uint4 v[U];
+        float qv[U][EPL];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int c = c0 + u * 64;
-            v[u] = c < chunks ? *(const uint4*)(row + (size_t)c * 16) : make_uint4(0, 0, 0, 0);
+        for (int u = 0; u < U; ++u) {
+            const int c = min(c0 + u * lpc, chunks - 1);
+            v[u] = *(const uint4*)(row + (size_t)c * 16);
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) *(float4*)&qv[u][e] = *(const float4*)(q + (size_t)c * EPL + e);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int c = c0 + u * 64;
-            if (c < chunks) {
+        for (int u = 0; u < U; ++u) {
+            if (c0 + u * lpc < chunks) {
                 float x[EPL];
                 Unpack<T>::run(v[u], x);
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) {
-                    double qv = (double)q[c * EPL + e], y = (double)x[e];
-                    if (metric == 0) acc = fma(qv, y, acc);
-                    else { double df = qv - y; acc = fma(df, df, acc); }
+                    const double qd = (double)qv[u][e], y = (double)x[e];
+                    if (metric == 0) acc = fma(qd, y, acc);
+                    else { const double df = qd - y; acc = fma(df, df, acc); }
                 }
             }
         }
     }
-    return wave_sum(acc);
+    return acc;
 }
 
 // ---- order-preserving integer keys ------------------------------------------------------------

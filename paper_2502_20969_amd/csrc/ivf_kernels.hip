@@ -921,43 +921,6 @@ __device__ __forceinline__ void gather_radix(const MergeArgs& a, const Cand* par
     __syncthreads();
 }
 
-// Partial fp64 score of one stored row over the 16-byte chunks sub, sub + lpc, ... (lane `sub`
-// of a group of `lpc` lanes); four loads are in flight at a time.
-template <typename T>
-__device__ __forceinline__ double rescore_partial(const unsigned char* row, const float* q, int d, int metric,
-                                                  int sub, int lpc) {
-    constexpr int EPL = T::kPerLoad;
-    constexpr int U = EPL == 4 ? 6 : 4;        // 768 fp32 values over 32 lanes: one pass
-    const int chunks = d / EPL;
-    double acc = 0.0;
-#pragma unroll 1
-    for (int c0 = sub; c0 < chunks; c0 += lpc * U) {
-        uint4 v[U];
-        float qv[U][EPL];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = min(c0 + u * lpc, chunks - 1);
-            v[u] = *(const uint4*)(row + (size_t)c * 16);
-#pragma unroll
-            for (int e = 0; e < EPL; e += 4) *(float4*)&qv[u][e] = *(const float4*)(q + (size_t)c * EPL + e);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (c0 + u * lpc < chunks) {
-                float x[EPL];
-                Unpack<T>::run(v[u], x);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    const double qd = (double)qv[u][e], y = (double)x[e];
-                    if (metric == 0) acc = fma(qd, y, acc);
-                    else { const double df = qd - y; acc = fma(df, df, acc); }
-                }
-            }
-        }
-    }
-    return acc;
-}
-
 __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int fast) {
     extern __shared__ unsigned char m_dyn[];
     __shared__ MergeLds L;
