@@ -53,9 +53,9 @@ hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, u
 }
 
 // ---- threshold sample --------------------------------------------------------------------------------------
-// fp32 scores (fp32 query) of the first 2048 rows of each query's selected clusters, taken in
-// probe order (usually all from the nearest cluster; more clusters when those are small), reduced
-// to the k-th best.  Any subset of the selected rows gives a valid lower bound of the k-th best
+// fp32 scores (fp32 query) of the first 2048 rows of each query's (at most 64 nearest) selected
+// clusters, taken in probe order (usually all from the nearest cluster; more clusters when those
+// are small), reduced to the k-th best.  Any subset of the selected rows gives a valid lower bound of the k-th best
 // score over all of them.  The sample of a query is split over kSampleParts workgroups of 128 rows;
 // each writes its k best keys, and prep_queries_kernel merges the parts.
 constexpr int kSampleParts = 16;
@@ -70,21 +70,30 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
     float* ql = (float*)smem;
     for (int i = threadIdx.x; i < a.d; i += blockDim.x) ql[i] = a.q[(size_t)qi * a.d + i];
     __syncthreads();
-    // cursor over the rows of the selected clusters laid end to end; sample rows are asked for in
-    // increasing order, so it only moves forward
+    // The rows of the first 64 selected clusters laid end to end: lane i holds cluster i's first
+    // row and the running total of rows up to and including it (one parallel prefix, so that
+    // finding the cluster of a sample row is a ballot instead of a walk through dependent loads).
     const int32_t* pr = a.probe + (size_t)qi * a.nprobe;
-    int ci = 0;
-    uint32_t c_begin = 0, c_n = 0;
-    int64_t c_lo = 0;
-    auto enter = [&](int i) { const int c = pr[i]; c_lo = a.off[c]; c_n = (uint32_t)(a.off[c + 1] - c_lo); };
-    enter(0);
+    int64_t my_lo = 0;
+    uint32_t my_n = 0;
+    if (lane < a.nprobe) {
+        const int c = pr[lane];
+        my_lo = a.off[c];
+        my_n = (uint32_t)(a.off[c + 1] - my_lo);
+    }
+    uint32_t my_end = my_n;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(my_end, o);
+        if (lane >= o) my_end += up;
+    }
     auto locate = [&](uint32_t r) -> int64_t {           // global row of sample row r, -1 past the last row
-        while (r >= c_begin + c_n) {
-            if (ci + 1 >= a.nprobe) return -1;
-            c_begin += c_n;
-            enter(++ci);
-        }
-        return c_lo + (int64_t)(r - c_begin);
+        const uint64_t b = __ballot(r < my_end);
+        if (b == 0) return -1;
+        const int i = __ffsll((long long)b) - 1;
+        const uint32_t end_i = read_lane(my_end, i), n_i = read_lane(my_n, i);
+        const int64_t lo_i = ((int64_t)read_lane((uint32_t)((uint64_t)my_lo >> 32), i) << 32) | read_lane((uint32_t)my_lo, i);
+        return lo_i + (int64_t)(r - (end_i - n_i));
     };
     const uint32_t r_begin = part * kSamplePartRows + wave * 32;
     const uint32_t r_end = r_begin + 32;
