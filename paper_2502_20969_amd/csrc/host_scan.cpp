@@ -4,6 +4,8 @@
 #include "host_scan.h"
 
 #include <math.h>
+
+#include <cmath>
 #include <string.h>
 
 #include <algorithm>
@@ -107,15 +109,36 @@ inline float row_key(const float* q, const T* y, int d) {
     return METRIC == 0 ? s : -s;
 }
 
+// fp64 key of one row in the order of operations the device's re-score uses, so that a row
+// scanned here and an identical row scanned on the GPU get bit-identical scores: 32
+// accumulators; accumulator s takes the 16-byte chunks s, s + 32, ... of the row in that order
+// (elements in memory order, one fused multiply-add each; single elements instead of chunks when
+// the row is not a whole number of chunks); the accumulators are added by a butterfly over the
+// distances 1, 2, 4, 8, 16, of which entry 0 is the result.
 template <typename T>
 inline double row_key_f64(const float* q, const T* y, int d, int metric) {
-    double s = 0.0;
-    for (int t = 0; t < d; ++t) {
-        double x = (double)load_elem(y, t);
-        if (metric == 0) s += (double)q[t] * x;
-        else { double df = (double)q[t] - x; s += df * df; }
+    constexpr int kLanes = 32;
+    double acc[kLanes];
+    for (int s = 0; s < kLanes; ++s) acc[s] = 0.0;
+    auto add = [&](double& a, int t) {
+        const double x = (double)q[t], v = (double)load_elem(y, t);
+        if (metric == 0) a = std::fma(x, v, a);
+        else { const double df = x - v; a = std::fma(df, df, a); }
+    };
+    const int epl = (int)(16 / sizeof(T));
+    if (((size_t)d * sizeof(T)) % 16 == 0) {
+        const int chunks = d / epl;
+        for (int c = 0; c < chunks; ++c)
+            for (int e = 0; e < epl; ++e) add(acc[c % kLanes], c * epl + e);
+    } else {
+        for (int t = 0; t < d; ++t) add(acc[t % kLanes], t);
     }
-    return metric == 0 ? s : -s;
+    for (int o = 1; o < kLanes; o <<= 1) {
+        double next[kLanes];
+        for (int s = 0; s < kLanes; ++s) next[s] = acc[s] + acc[s ^ o];
+        for (int s = 0; s < kLanes; ++s) acc[s] = next[s];
+    }
+    return metric == 0 ? acc[0] : -acc[0];
 }
 
 struct Cand { float key; int64_t id; int64_t row; };

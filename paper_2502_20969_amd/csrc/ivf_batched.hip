@@ -478,8 +478,9 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
     uint64_t* keys = a.cand_key + (size_t)qi * a.surv_cap;
     const float* q = a.q + (size_t)qi * a.d;
     const size_t row_bytes = (size_t)a.d * 2;
-    // a group of 16 lanes per survivor, 64 survivors per pass, so that their row loads overlap
-    constexpr int kLpc = 16;
+    // a group of lanes per survivor, 32 survivors per pass, so that their row loads overlap; the
+    // same order of operations as the query-by-query merge
+    constexpr int kLpc = kRescoreLanes;
     const int sub = tid % kLpc;
 #pragma unroll 1
     for (uint32_t c = (uint32_t)(tid / kLpc); c < n; c += (uint32_t)(nt / kLpc)) {

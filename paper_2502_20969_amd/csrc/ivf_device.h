@@ -133,8 +133,17 @@ __device__ __forceinline__ double widen(const void* base, int dtype, size_t idx)
     return (double)__uint_as_float((uint32_t)b << 16);
 }
 
+// The fp64 re-score has one fixed order of operations, shared by the merge kernels and by the
+// host's scan of the clusters that are not resident, so that identical rows get bit-identical
+// scores wherever they are scored and equal scores are then ordered by id alone: kRescoreLanes
+// accumulators; accumulator s takes the 16-byte chunks s, s + 32, ... of the row in that order
+// (elements in memory order, one fused multiply-add each); the accumulators are added by a
+// butterfly over the lane distances 1, 2, 4, 8, 16.  Rows that are not whole 16-byte chunks use
+// the same scheme over single elements.
+constexpr int kRescoreLanes = 32;
+
 // Partial fp64 score of one stored row over the 16-byte chunks sub, sub + lpc, ... (lane `sub`
-// of a group of `lpc` lanes); four loads are in flight at a time.
+// of a group of `lpc` lanes); several loads are in flight at a time.
 template <typename T>
 __device__ __forceinline__ double rescore_partial(const unsigned char* row, const float* q, int d, int metric,
                                                   int sub, int lpc) {

@@ -942,12 +942,13 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     const uint32_t m = min(L.sh[4], (uint32_t)kMaxKPrime);
     IVF_TRACE_MARK(23);
 
-    // 2. fp64 re-score: a group of lpc lanes per candidate, all candidates at once
+    // 2. fp64 re-score: a group of kRescoreLanes lanes per candidate, nt / kRescoreLanes
+    //    candidates at once.  The order of operations is fixed (see rescore_partial), so a row has
+    //    the same fp64 score whichever kernel, or the host, computes it.
     const float* q = a.q + (size_t)qi * a.d;
     const int np = a.nprobe;
     const size_t row_bytes = (size_t)a.d * (a.dtype == 0 ? 4 : 2);
-    int lpc = 64;
-    while (lpc > 1 && (uint32_t)(nt / lpc) < m) lpc >>= 1;
+    constexpr int lpc = kRescoreLanes;
     const int sub = tid % lpc;
 #pragma unroll 1
     for (uint32_t c = (uint32_t)(tid / lpc); c < m; c += (uint32_t)(nt / lpc)) {

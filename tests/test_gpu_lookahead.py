@@ -197,3 +197,32 @@ def test_cluster_cache_rounds(streams, fraction, decay, h_inc):
     index.ivf_prefetch(q_in[0], L, 0, flags=P.IVF_PREFETCH_RESET)
     assert (index.ivf_cache_hotness() < 0).all() and len(index.ivf_resident()) == 0
     index.close()
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 768), ("f16", 100), ("bf16", 64), ("f32", 7)])
+def test_identical_rows_split_between_host_and_gpu(streams, dtype, d):
+    """The fp64 re-score has one order of operations on the device and on the host, so copies of a
+    row score bit for bit the same whether their cluster was prefetched or not, and come out by id
+    exactly as in the oracle: no near-tie exemption is needed."""
+    rng = np.random.default_rng(17)
+    n, nlist, L, k = 6000, 12, 8, 40
+    base = rng.standard_normal((25, d)).astype(np.float32)          # every row is one of 25 vectors
+    rows = base[rng.integers(0, 25, n)]
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    assign = rng.integers(0, nlist, n).astype(np.int32)
+    ids = rng.permutation(n).astype(np.int64) * 5 + 2
+    st, odt = stored(rows, dtype)
+    off, perm = O.build_layout(assign, nlist)
+    esz = 4 if dtype == "f32" else 2
+    index = P.ivf_build_layout(st, dtype, cent, assign, ids=ids, placement=P.IVF_PLACE_HOST,
+                               device_buffer_bytes=n * d * esz, compute_stream=streams[0], copy_stream=streams[1])
+    q = rng.standard_normal((3, d)).astype(np.float32)
+    for frac in (0.0, 0.35, 0.7, 2.0):
+        index.ivf_prefetch(q, L, int(frac * n * d * esz), flags=P.IVF_PREFETCH_RESET)
+        gi, gd, ss = index.ivf_search(q, L, k, with_stats=True)
+        if 0.0 < frac < 1.0:
+            assert ss.n_overlap > 0 and ss.n_miss > 0
+        for b in range(3):
+            oi, _ = O.search(st[perm], odt, off, ids[perm], cent, q[b], L, k, O.IP)
+            assert list(gi[b]) == list(oi)
+    index.close()
