@@ -1,0 +1,113 @@
+"""Seeded random configurations of the whole path against the oracle: shapes, storage types,
+metrics, placements, id kinds, duplicates and empty lists drawn together, so that combinations no
+hand-written case names are still exercised.  Every case is a fixed seed."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2502_20969_amd as P
+import workloads as W
+from parity import check_topk, stored
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def streams():
+    assert torch.cuda.is_available()
+    return torch.cuda.Stream(), torch.cuda.Stream()
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_search_case(streams, seed):
+    rng = np.random.default_rng(9000 + seed)
+    dtype = str(rng.choice(["f32", "f16", "bf16"]))
+    metric = str(rng.choice(["ip", "l2"]))
+    d = int(rng.choice([4, 7, 16, 24, 40, 64, 96, 100, 128, 200, 256, 384, 512, 768, 1024]))
+    nlist = int(rng.choice([1, 2, 5, 17, 64, 100, 333, 1024, 1500, 3000]))
+    n = int(rng.integers(max(1, nlist // 2), 25000))
+    nprobe = int(rng.choice([1, 2, 3, 8, 31, 32, 63, 64, 65, 100, 400, 5000]))
+    k = int(rng.choice([1, 2, 5, 10, 33, 56, 57, 64, 100, 112]))
+    nq = int(rng.choice([1, 1, 2, 3, 5, 9, 17, 40]))
+    placement = str(rng.choice(["device", "device", "host"]))
+    idkind = str(rng.choice(["none", "perm", "sparse"]))
+    dup = int(rng.choice([0, 0, n // 3, n]))
+    pm, om = (P.IVF_IP, O.IP) if metric == "ip" else (P.IVF_L2, O.L2)
+    centres = rng.standard_normal((nlist, d)).astype(np.float32)
+    assign = rng.integers(0, nlist, n).astype(np.int32)
+    if rng.random() < 0.3 and nlist > 2:
+        assign[assign == 1] = 0                      # an empty list
+    rows = centres[assign] + 0.5 * rng.standard_normal((n, d)).astype(np.float32)
+    if dup:
+        rows[rng.integers(0, n, dup)] = rows[rng.integers(0, n, dup)]
+    ids = None if idkind == "none" else (rng.permutation(n).astype(np.int64) if idkind == "perm"
+                                         else rng.permutation(n).astype(np.int64) * 7 + 3)
+    st, odt = stored(rows, dtype)
+    esz = 4 if dtype == "f32" else 2
+    kw = {}
+    if placement == "host":
+        kw = dict(placement=P.IVF_PLACE_HOST, device_buffer_bytes=int(n * d * esz * rng.choice([0.0, 0.3, 1.0])) + 64)
+    index = P.ivf_build_layout(st, dtype, centres, assign, ids=ids, metric=pm, compute_stream=streams[0],
+                               copy_stream=streams[1], **kw)
+    off, perm = O.build_layout(assign, nlist)
+    lists = st[perm]
+    lid = perm.astype(np.int64) if ids is None else ids[perm]
+    q = (centres[rng.integers(0, nlist, nq)] + 0.5 * rng.standard_normal((nq, d))).astype(np.float32)
+    if placement == "host":
+        index.ivf_prefetch(q, nprobe, int(n * d * esz * rng.choice([0.1, 0.5, 2.0])), flags=P.IVF_PREFETCH_RESET)
+    pr = index.ivf_probe(q, nprobe)
+    for b in range(nq):
+        assert list(pr[b]) == list(O.probe(centres, q[b], nprobe, om))
+    gi, gd = index.ivf_search(q, nprobe, k)
+    exempt = 0
+    for b in range(nq):
+        exempt += check_topk(gi[b], gd[b], lists, odt, off, lid, centres, q[b], nprobe, k, om)
+    assert exempt == 0
+    if placement == "device":
+        q_dev = torch.from_numpy(q).cuda()
+        ids_dev = torch.empty(nq, k, dtype=torch.int64, device="cuda")
+        d_dev = torch.empty(nq, k, device="cuda")
+        torch.cuda.synchronize()
+        index.ivf_search_device(q_dev, nprobe, k, ids_dev, d_dev)
+        index.ivf_synchronize()
+        assert np.array_equal(ids_dev.cpu().numpy(), gi) and np.array_equal(d_dev.cpu().numpy(), gd)
+    index.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_batched_case(streams, seed):
+    """List-major batched search: equal to the oracle and, bit for bit, to the query-by-query path."""
+    rng = np.random.default_rng(9500 + seed)
+    dtype = str(rng.choice(["f16", "bf16"]))
+    d = int(rng.choice([64, 128, 192, 256, 768, 1024]))
+    nlist = int(rng.choice([3, 16, 64, 200, 1000]))
+    n = int(rng.integers(nlist, 40000))
+    nprobe = int(rng.choice([1, 4, 16, 64, 100]))
+    k = int(rng.choice([1, 10, 50, 100]))
+    nq = int(rng.choice([2, 4, 7, 32, 33, 70]))
+    zipf = float(rng.choice([0.0, 1.1, 1.5]))
+    sizes = W.zipf_sizes(n, nlist, zipf, 9500 + seed, min_rows=int(rng.choice([0, 1])))
+    ds = W.cluster_major_datastore(sizes, d, 0.4, 9600 + seed, dtype=dtype)
+    rows = ds.rows.float().numpy()
+    if rng.random() < 0.4:
+        rows[rng.integers(0, n, n // 2)] = rows[rng.integers(0, n, n // 2)]
+    st, odt = stored(rows, dtype)
+    off, cent = ds.offsets.numpy(), ds.centroids.numpy()
+    ids = None if rng.random() < 0.5 else rng.permutation(n).astype(np.int64) * 3 + 1
+    t = torch.from_numpy(st.view(np.int16) if dtype == "bf16" else st).cuda()
+    if dtype == "bf16":
+        t = t.view(torch.bfloat16)
+    index = P.ivf_adopt_layout(t, dtype, off, cent, ids=ids, metric=P.IVF_IP, compute_stream=streams[0],
+                               copy_stream=streams[1])
+    q = (cent[rng.integers(0, nlist, nq)] + 0.3 * rng.standard_normal((nq, d))).astype(np.float32)
+    index.ivf_set_batch_mode(2)
+    gi, gd = index.ivf_search(q, nprobe, k)
+    exempt = 0
+    for b in range(nq):
+        exempt += check_topk(gi[b], gd[b], st, odt, off, ids, cent, q[b], nprobe, k, O.IP)
+    assert exempt == 0
+    index.ivf_set_batch_mode(1)
+    hi, hd = index.ivf_search(q, nprobe, k)
+    assert np.array_equal(gi, hi) and np.array_equal(gd, hd)
+    index.close()
