@@ -511,7 +511,7 @@ def main():
     ap.add_argument("--k", type=int, default=10)
     ap.add_argument("--depth", type=int, default=0,
                     help="independent searches kept in flight (ivf_set_pipeline_depth); 1 = strictly one after "
-                         "another; 0 = try 2, 4, 6 and 8 in short untimed runs and keep the fastest (how HIP maps "
+                         "another; 0 = try 2, 4, 6, 8, 12 and 16 in short untimed runs and keep the fastest (how HIP maps "
                          "streams to hardware queues makes some depths overlap better than others)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic for scaling rocprofv3 counters)")
@@ -553,7 +553,7 @@ def main():
     dists_dev = torch.empty(nq, args.k, dtype=torch.float32, device="cuda")
     depth_trials = {}
     if args.depth == 0:
-        for depth in (2, 4, 6, 8):
+        for depth in (2, 4, 6, 8, 12, 16):
             index.ivf_set_pipeline_depth(depth)
             index.ivf_reserve(1, 1024, args.k)
             t = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, 1500, 100)

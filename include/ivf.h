@@ -180,7 +180,8 @@ int ivf_reserve(ivf_index* index, int32_t nq, int32_t nprobe, int32_t k);
  * n > 1, successive ivf_search_device calls rotate over n internal streams (the first is
  * compute_stream), each with its own workspace; inputs must be complete when the call is made,
  * and outputs are complete after ivf_synchronize().  Depth 1 (the default) keeps everything on
- * compute_stream.  Changing the depth synchronises the device.  IVF_PLACE_DEVICE only.
+ * compute_stream.  Changing the depth synchronises the device.  IVF_PLACE_DEVICE only; depth
+ * in [1, 16].
  */
 int ivf_set_pipeline_depth(ivf_index* index, int32_t depth);
 /* Blocks the host until every search enqueued by ivf_search_device has finished. */

@@ -681,7 +681,7 @@ extern "C" int ivf_reserve(ivf_index* ix, int32_t nq, int32_t nprobe, int32_t k)
 
 extern "C" int ivf_set_pipeline_depth(ivf_index* ix, int32_t depth) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
-    if (depth < 1 || depth > 8) return fail(IVF_EINVAL, "pipeline depth must be in [1, 8]");
+    if (depth < 1 || depth > 16) return fail(IVF_EINVAL, "pipeline depth must be in [1, 16]");
     if (ix->placement != IVF_PLACE_DEVICE) return fail(IVF_ESTATE, "pipelining needs a device-resident index");
     HIP_TRY(hipDeviceSynchronize());
     while ((int)ix->lanes.size() > depth) {
