@@ -20,6 +20,10 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes one scan launch of the default workload moves, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 1 GiB copy (profiles/scan_kernel_c2_single_query.md): read + written
 C2_SCAN_TRAFFIC_BYTES = 89266 * 1024 + 80 * 1024
+# the same for the batched scan launch of configs[2] (default 24 components) and configs[4]
+# (profiles/batched_scan_kernel_c3_c5.md): FETCH_SIZE KiB x 2.0 x 1024
+C3_SCAN_TRAFFIC_BYTES = 5027107 * 2048
+C5_SCAN_TRAFFIC_BYTES = 30003315 * 2048
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
 
 
@@ -314,7 +318,7 @@ def run_batched(args):
     torch.cuda.synchronize()
     print(f"[{args.workload}] datastore of {n * d * 2 / 1e9:.1f} GB ready after {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
     n_sets = 8                                            # distinct batches cycled through the timed steps
-    groups = args.groups if args.groups > 0 else (6 if c3 else B)
+    groups = args.groups if args.groups > 0 else (24 if c3 else B)      # 24 components: measured share 0.40
     qs = [W.shared_batch_queries(ds, B, groups, 20980 + i) for i in range(n_sets)]
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     index = P.ivf_adopt_layout(ds.rows, dtype, ds.offsets, ds.centroids.cpu(), metric=P.IVF_IP,
@@ -380,7 +384,11 @@ def run_batched(args):
                                   f"nprobe {nprobe}, k {k}, batch {B} from {groups} mixture components, scale {args.scale}",
                       "measured_share": round(share, 3), "entry_point": "ivf_search_device (list-major)"},
            "roofline": {"bound": "hbm", "achieved": head["scan_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(head["scan_gbs"] / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "batched_scan_kernel",
+                        "frac": round(head["scan_gbs"] / HBM_PEAK_GBS, 4),
+                        "traffic": ((C3_SCAN_TRAFFIC_BYTES if c3 else C5_SCAN_TRAFFIC_BYTES)
+                                    if (args.scale == 1.0 and args.dim == 0 and args.batch == 0 and args.topk == 0
+                                        and args.groups == 0) else None),
+                        "kernel": "batched_scan_kernel",
                         "us_per_launch": head["us_scan"], "bytes_per_launch": head["scan_gb"] * 1e9},
            "head": head, "nprobe_sweep": sweep, "parity_sample": parity, "setup_s": round(setup_s, 1)}
     if not args.no_cpu:
