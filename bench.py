@@ -630,8 +630,12 @@ def main():
             index.ivf_search_device(q_dev[j], args.nprobe, args.k, ids_dev[j], dists_dev[j])
         index.ivf_synchronize()
         got = ids_dev.cpu().numpy()
+        got_d = dists_dev.cpu().numpy().astype(np.float64)
         bad = sum(int(not np.array_equal(got[j], results[j][0])) for j in range(len(results)))
-        out["parity_sample"] = {"queries": len(results), "id_mismatches": bad}
+        rel = max(float(np.max(np.abs(got_d[j] - results[j][1]) / np.maximum(np.abs(results[j][1]), 1e-30)))
+                  for j in range(len(results)))
+        out["parity_sample"] = {"queries": len(results), "id_mismatches": bad, "near_tie_exemptions": 0 if bad == 0 else None,
+                                "max_rel_distance_error": rel}
     print(json.dumps(out))
 
 
