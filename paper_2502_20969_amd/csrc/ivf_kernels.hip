@@ -399,7 +399,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
     const uint32_t R = carry;
     const uint32_t per = R / (uint32_t)a.grid, extra = R % (uint32_t)a.grid;
     const uint32_t* rp = prefix_in_lds ? l_rp : s_rp;
-    for (int b = tid; b < a.grid; b += nt) {
+    for (int b = tid; b < (nprobe > kLaneTableSlots ? a.grid : 0); b += nt) {   // few slots: the scan finds its share itself
         WgDesc ds;
         ds.r_begin = per * (uint32_t)b + min((uint32_t)b, extra);        // the first `extra` shares get one more row
         ds.r_end = per * (uint32_t)(b + 1) + min((uint32_t)(b + 1), extra);
@@ -467,17 +467,54 @@ struct Batch {
     uint32_t grow;               // global row of the first row
 };
 
+// With at most kLaneTableSlots selected clusters a wavefront keeps the query's slot table in its
+// lanes: lane i holds the end of slot i in the row sequence, its first global row and its place
+// in the device buffer.  Finding the slot of a row is then one ballot, and stepping to the next
+// slot costs no memory access.
+struct LaneTable {
+    bool on;
+    int nprobe;
+    uint32_t end, grow;
+    int64_t base;
+    __device__ __forceinline__ void load(const ScanArgs& p, int qi) {
+        on = p.nprobe <= kLaneTableSlots;
+        nprobe = p.nprobe;
+        end = 0; grow = 0; base = 0;
+        const int lane = lane_id();
+        if (on && lane < p.nprobe) {
+            const size_t o = (size_t)qi * p.nprobe + lane;
+            end = p.slots.rprefix[o + qi + 1];
+            grow = p.slots.grow[o];
+            base = p.slots.base[o];
+        }
+    }
+    __device__ __forceinline__ uint32_t total() const { return read_lane(end, nprobe - 1); }
+    // points the cursor at the slot that holds row c.r (c.r below the total)
+    __device__ __forceinline__ void seek(Cursor& c) const {
+        const int slot = __popcll(__ballot(lane_id() < nprobe && end <= c.r));     // ends are non-decreasing
+        c.slot = (uint32_t)slot;
+        c.s_rb = slot ? read_lane(end, slot - 1) : 0u;
+        c.s_re = read_lane(end, slot);
+        c.s_grow = read_lane(grow, slot);
+        c.s_base = (int64_t)(((uint64_t)read_lane((uint32_t)((uint64_t)base >> 32), slot) << 32) | read_lane((uint32_t)base, slot));
+    }
+};
+
 __device__ __forceinline__ Batch next_batch(Cursor& c, const ScanArgs& p, int qi, int rows_per_batch,
-                                            size_t row_bytes) {
+                                            size_t row_bytes, const LaneTable& tab) {
     Batch b{nullptr, 0, 0};
     if (c.r >= c.r_end) return b;
-    while (c.r >= c.s_re) {      // step to the slot that holds row r (skips empty / absent lists)
-        c.slot += 1;
-        const size_t o = (size_t)qi * p.nprobe + c.slot;
-        c.s_rb = c.s_re;
-        c.s_re = p.slots.rprefix[o + qi + 1];
-        c.s_grow = p.slots.grow[o];
-        c.s_base = p.slots.base[o];
+    if (tab.on) {
+        if (c.r >= c.s_re) tab.seek(c);
+    } else {
+        while (c.r >= c.s_re) {      // step to the slot that holds row r (skips empty / absent lists)
+            c.slot += 1;
+            const size_t o = (size_t)qi * p.nprobe + c.slot;
+            c.s_rb = c.s_re;
+            c.s_re = p.slots.rprefix[o + qi + 1];
+            c.s_grow = p.slots.grow[o];
+            c.s_base = p.slots.base[o];
+        }
     }
     const uint32_t in_slot = c.r - c.s_rb;
     b.nr = min((uint32_t)rows_per_batch, min(c.r_end, c.s_re) - c.r);
@@ -559,11 +596,24 @@ __device__ __forceinline__ void finish_workgroup(WaveTopK<KL, false>& top, const
     }
 }
 
-__device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi) {
-    const WgDesc ds = p.desc[(size_t)qi * p.grid + blockIdx.x];
+__device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi, const LaneTable& tab) {
     const int wave = wave_id();
-    const uint32_t cnt = ds.r_end - ds.r_begin;
     Cursor c;
+    if (tab.on) {
+        // the workgroup's share of the rows, as the select kernel would have described it: rows
+        // split evenly over the workgroups, the first `extra` shares one row longer
+        const uint32_t R = tab.total(), g = (uint32_t)p.grid, b = blockIdx.x;
+        const uint32_t per = R / g, extra = R % g;
+        const uint32_t r_begin = per * b + min(b, extra), r_end = per * (b + 1) + min(b + 1, extra);
+        const uint32_t cnt = r_end - r_begin;
+        c.r = r_begin + (uint32_t)((uint64_t)cnt * wave / kScanWaves);
+        c.r_end = r_begin + (uint32_t)((uint64_t)cnt * (wave + 1) / kScanWaves);
+        c.slot = 0; c.s_rb = 0; c.s_re = 0; c.s_grow = 0; c.s_base = 0;
+        if (c.r < c.r_end) tab.seek(c);
+        return c;
+    }
+    const WgDesc ds = p.desc[(size_t)qi * p.grid + blockIdx.x];
+    const uint32_t cnt = ds.r_end - ds.r_begin;
     c.r = ds.r_begin + (uint32_t)((uint64_t)cnt * wave / kScanWaves);
     c.r_end = ds.r_begin + (uint32_t)((uint64_t)cnt * (wave + 1) / kScanWaves);
     c.slot = ds.slot; c.s_rb = ds.slot_rbegin; c.s_re = ds.slot_rend;
@@ -585,7 +635,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     if (threadIdx.x < 2) lds.ctl[threadIdx.x] = 0;
     const size_t row_bytes = (size_t)p.d * T::kBytes;
 
-    Cursor cur = start_cursor(p, qi);
+    LaneTable tab;
+    tab.load(p, qi);
+    Cursor cur = start_cursor(p, qi, tab);
 
     // this lane's slice of the query
     float qv[SEG][EPL];
@@ -656,14 +708,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     IVF_TRACE_MARK(31);
     uint4 va[U][SEG], vb[U][SEG];
     uint32_t ta = 0, tb = 0;
-    Batch ba = next_batch(cur, p, qi, RPB, row_bytes);
+    Batch ba = next_batch(cur, p, qi, RPB, row_bytes, tab);
     if (ba.nr) issue(ba, va, ta);
     while (ba.nr) {
-        Batch bb = next_batch(cur, p, qi, RPB, row_bytes);
+        Batch bb = next_batch(cur, p, qi, RPB, row_bytes, tab);
         if (bb.nr) issue(bb, vb, tb);
         consume(ba, va, ta);
         if (!bb.nr) break;
-        ba = next_batch(cur, p, qi, RPB, row_bytes);
+        ba = next_batch(cur, p, qi, RPB, row_bytes, tab);
         if (ba.nr) issue(ba, va, ta);
         consume(bb, vb, tb);
     }
@@ -687,10 +739,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
     __syncthreads();
     const int esz = p.dtype == 0 ? 4 : 2;
     const size_t row_bytes = (size_t)p.d * esz;
-    Cursor cur = start_cursor(p, qi);
+    LaneTable tab;
+    tab.load(p, qi);
+    Cursor cur = start_cursor(p, qi, tab);
     WaveTopK<KL, false> top;
     top.init();
-    for (Batch b = next_batch(cur, p, qi, 4, row_bytes); b.nr; b = next_batch(cur, p, qi, 4, row_bytes)) {
+    for (Batch b = next_batch(cur, p, qi, 4, row_bytes, tab); b.nr; b = next_batch(cur, p, qi, 4, row_bytes, tab)) {
         for (uint32_t r = 0; r < b.nr; ++r) {
             const unsigned char* rp = b.rows + (size_t)r * row_bytes;
             float s = 0.f;
