@@ -71,6 +71,7 @@ struct Workspace {
     uint32_t* d_sort_idx = nullptr;
     WgDesc* d_desc = nullptr;
     uint64_t* d_part = nullptr;      // packed candidates of the scan workgroups
+    uint64_t* d_heads = nullptr;     // their first entries, densely
     int64_t* d_out_ids = nullptr;
     float* d_out_dists = nullptr;
     // pinned host staging
@@ -164,7 +165,7 @@ namespace {
 void free_workspace(Workspace& w) {
     hipFree(w.d_q); hipFree(w.d_scores); hipFree(w.d_probe);
     hipFree(w.slots.base); hipFree(w.slots.grow); hipFree(w.slots.nrows); hipFree(w.slots.rprefix);
-    hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part);
+    hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part); hipFree(w.d_heads);
     hipFree(w.d_desc);
     hipFree(w.d_out_ids); hipFree(w.d_out_dists);
     hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
@@ -229,6 +230,7 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
         HIP_TRY(hipMalloc(&w.d_sort_idx, nqz * pad2 * sizeof(uint32_t)));
     }
     HIP_TRY(hipMalloc(&w.d_part, nqz * grid_cap * kp2 * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&w.d_heads, nqz * grid_cap * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&w.d_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipMalloc(&w.d_out_dists, nqz * k2 * sizeof(float)));
     HIP_TRY(hipHostMalloc(&w.h_q, nqz * ix->d * sizeof(float)));
@@ -314,7 +316,7 @@ int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kpri
     Workspace& w = *ix->cw;
     ScanArgs sc{};
     sc.buf = ix->d_buf; sc.q = q_dev; sc.idrank = ix->d_idrank; sc.slots = w.slots;
-    sc.part = w.d_part;
+    sc.part = w.d_part; sc.heads = w.d_heads;
     sc.desc = w.d_desc;
     sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
     sc.kprime = kprime; sc.grid = grid; sc.shape = ix->shape;
@@ -330,7 +332,7 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     Workspace& w = *ix->cw;
     MergeArgs ma{};
     ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.rowof = ix->d_rowof; ma.slots = w.slots;
-    ma.part = w.d_part;
+    ma.part = w.d_part; ma.heads = w.d_heads;
     ma.host_cand = with_host ? w.h_cand : nullptr;
     ma.host_count = with_host ? w.h_cand_count : nullptr;
     ma.out_ids = out_ids; ma.out_dists = out_dists;

@@ -86,6 +86,7 @@ struct ScanArgs {
     const WgDesc* desc;      // [nq x grid]
     uint64_t* part;          // [nq x grid x kprime] out: workgroup lists of packed candidates
                              // (fp32 key image << 32 | ~rank), best first, 0 = empty
+    uint64_t* heads;         // [nq x grid] out: entry 0 of every list again, packed densely for the merge
     int d, dtype, metric, nprobe, nq, kprime, grid;
     ScanShape shape;
 };
@@ -99,6 +100,7 @@ struct MergeArgs {
     const uint32_t* rowof;       // [n] id rank -> global row, or nullptr (row = rank)
     SlotTables slots;
     const uint64_t* part;        // [nq x nparts x kprime] packed candidates written by the scan
+    const uint64_t* heads;       // [nq x nparts] the lists' first entries
     const HostCand* host_cand;   // [nq x kprime] device-visible, or nullptr
     const int32_t* host_count;   // [nq] valid entries in host_cand
     int64_t* out_ids; float* out_dists;   // [nq x k]

@@ -594,6 +594,7 @@ __device__ __forceinline__ void finish_workgroup(WaveTopK<KL, false>& top, const
         int e = j * 64 + lane;
         if (e < kp) p.part[o + e] = top.top[j];
     }
+    if (lane == 0) p.heads[(size_t)qi * p.grid + blockIdx.x] = top.top[0];
 }
 
 __device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi, const LaneTable& tab) {
@@ -866,8 +867,8 @@ struct MergeLds {
 // kprime-th best list head, only entries >= T0 of the (at most kprime) lists whose head is
 // >= T0 can be among the kprime best.  Those are gathered, sorted in chunks of 64 and merged.
 // `pool` holds kMergeCandCap candidates, `qlist` 64 list numbers.
-__device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part, MergeLds& L, Cand* pool,
-                                            uint32_t* qlist) {
+__device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part, const Cand* heads, MergeLds& L,
+                                            Cand* pool, uint32_t* qlist) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id(), nw = nt >> 6;
     const int kp = a.kprime, np = a.nparts;
     // 1. T0 from the list heads
@@ -876,7 +877,7 @@ __device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part
 #pragma unroll 1
     for (int c0 = wave * 64; c0 < np; c0 += nw * 64) {
         const int l = c0 + lane;
-        const Cand h = l < np ? part[(size_t)l * kp] : (Cand)0;
+        const Cand h = l < np ? heads[l] : (Cand)0;
         if (c0 == wave * 64) first_head = h;
         best = merge_best64<true>(best, bitonic_sort64<true>(h));
     }
@@ -899,7 +900,7 @@ __device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part
     // 2. the lists whose head reaches T0 ...
 #pragma unroll 1
     for (int l = tid; l < np; l += nt) {
-        const Cand h = l == tid ? first_head : part[(size_t)l * kp];
+        const Cand h = l == tid ? first_head : heads[l];
         if (h != 0 && h >= t0) qlist[atomicAdd(&L.sh[5], 1u)] = (uint32_t)l;
     }
     __syncthreads();
@@ -989,7 +990,7 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     // 1. the kprime best fp32 candidates
     if (fast) {
         Cand* pool = (Cand*)m_dyn;
-        gather_fast(a, part, L, pool, (uint32_t*)(pool + kMergeCandCap));
+        gather_fast(a, part, a.heads + (size_t)qi * a.nparts, L, pool, (uint32_t*)(pool + kMergeCandCap));
     } else {
         gather_radix(a, part, L);
     }
