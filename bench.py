@@ -19,7 +19,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes one scan launch of the default workload moves, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 1 GiB copy (profiles/scan_kernel_c2_single_query.md): read + written
-C2_SCAN_TRAFFIC_BYTES = 89266 * 1024 + 80 * 1024
+C2_SCAN_TRAFFIC_BYTES = 89207 * 1024 + 96 * 1024
 # the same for the batched scan launch of configs[2] (default 24 components) and configs[4]
 # (profiles/batched_scan_kernel_c3_c5.md): FETCH_SIZE KiB x 2.0 x 1024
 C3_SCAN_TRAFFIC_BYTES = 5027107 * 2048
