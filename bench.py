@@ -585,6 +585,17 @@ def main():
     dt1 = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, args.steps, args.warmup)
     prof = profile_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, min(args.steps, 2048))
 
+    # the same searches handed over as host buffers (ivf_search): adds the copy of the query to the
+    # device, the copy of the k results back and a stream synchronisation per call
+    q_host = q_out.cpu().numpy()
+    n_host = min(args.steps, 1024)
+    for i in range(32):
+        index.ivf_search(q_host[i % nq], args.nprobe, args.k)
+    t_h = time.perf_counter()
+    for i in range(n_host):
+        index.ivf_search(q_host[i % nq], args.nprobe, args.k)
+    dt_host = time.perf_counter() - t_h
+
     sweep = []
     if not args.no_sweep:
         for nprobe in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024):
@@ -609,6 +620,8 @@ def main():
                    "entry_point": "ivf_search_device", "searches_in_flight": args.depth,
                    "depth_trials_qps": depth_trials, "seed": 20970},
         "one_at_a_time": {"value": round(args.steps / dt1, 1), "ms_per_step": dt1 / args.steps * 1e3},
+        "host_buffers": {"value": round(n_host / dt_host, 1), "ms_per_step": dt_host / n_host * 1e3,
+                         "entry_point": "ivf_search (query and results cross PCIe, one call at a time)"},
         "roofline": {"bound": "hbm", "achieved": round(prof["scan_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(prof["scan_gbs"] / HBM_PEAK_GBS, 4),
                      "traffic": C2_SCAN_TRAFFIC_BYTES if (args.n == 1_000_000 and args.nprobe == 32 and args.metric == "ip") else None,
