@@ -79,6 +79,8 @@ struct Workspace {
     int32_t* h_probe = nullptr;
     int64_t* h_out_ids = nullptr;
     float* h_out_dists = nullptr;
+    int64_t* hd_out_ids = nullptr;   // the same pinned buffers as the device addresses them: the merge
+    float* hd_out_dists = nullptr;   // kernel of ivf_search writes its few results straight to the host
     HostCand* h_cand = nullptr;
     int32_t* h_cand_count = nullptr;
     double* h_scores = nullptr;   // only for ivf_coarse_scores (allocated on demand)
@@ -237,6 +239,8 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     HIP_TRY(hipHostMalloc(&w.h_probe, nqz * npz * sizeof(int32_t)));
     HIP_TRY(hipHostMalloc(&w.h_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipHostMalloc(&w.h_out_dists, nqz * k2 * sizeof(float)));
+    HIP_TRY(hipHostGetDevicePointer((void**)&w.hd_out_ids, w.h_out_ids, 0));
+    HIP_TRY(hipHostGetDevicePointer((void**)&w.hd_out_dists, w.h_out_dists, 0));
     HIP_TRY(hipHostMalloc(&w.h_cand, nqz * kp2 * sizeof(HostCand)));
     HIP_TRY(hipHostMalloc(&w.h_cand_count, nqz * sizeof(int32_t)));
     memset(w.h_cand_count, 0, nqz * sizeof(int32_t));
@@ -845,9 +849,8 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
         st.ms_host_scan = (float)(now_ms() - ts);
         st.hit_rate = (float)(hit_sum / nq);
     }
-    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.d_out_ids, w.d_out_dists))) return rc;
-    HIP_TRY(hipMemcpyAsync(w.h_out_ids, w.d_out_ids, (size_t)nq * k * sizeof(int64_t), hipMemcpyDeviceToHost, ix->cs));
-    HIP_TRY(hipMemcpyAsync(w.h_out_dists, w.d_out_dists, (size_t)nq * k * sizeof(float), hipMemcpyDeviceToHost, ix->cs));
+    // nq x k results: the kernel stores them in the pinned host buffers itself (no copy to enqueue)
+    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.hd_out_ids, w.hd_out_dists))) return rc;
     HIP_TRY(hipStreamSynchronize(ix->cs));
     memcpy(ids, w.h_out_ids, (size_t)nq * k * sizeof(int64_t));
     memcpy(dists, w.h_out_dists, (size_t)nq * k * sizeof(float));
