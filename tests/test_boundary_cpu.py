@@ -53,3 +53,17 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.ivf_search(None, vp(rows), 1, 1, 1, vp(rows), vp(rows), None) == -1
     assert L.ivf_prefetch(None, vp(rows), 1, 1, 0, 0, None) == -1
     L.ivf_free(None)
+
+
+def test_entry_point_build_calls_both_builders(monkeypatch):
+    """__graft_entry__.build() must reach the HIP build and the oracle build (the oracle package also
+    exports a function called build, which once shadowed the module of that name)."""
+    import sys
+    import __graft_entry__ as entry
+    import oracle.build  # noqa: F401
+    import paper_2502_20969_amd.build  # noqa: F401
+    calls = []
+    monkeypatch.setattr(sys.modules["paper_2502_20969_amd.build"], "build", lambda: calls.append("hip"))
+    monkeypatch.setattr(sys.modules["oracle.build"], "build", lambda: calls.append("oracle"))
+    entry.build()
+    assert calls == ["hip", "oracle"]
