@@ -111,3 +111,50 @@ def test_random_batched_case(streams, seed):
     hi, hd = index.ivf_search(q, nprobe, k)
     assert np.array_equal(gi, hi) and np.array_equal(gd, hd)
     index.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_cache_rounds(streams, seed):
+    """Prefetch, search and end-of-round over random cache parameters, against the oracle's cache round."""
+    rng = np.random.default_rng(9700 + seed)
+    dtype = str(rng.choice(["f32", "f16"]))
+    d = int(rng.choice([32, 96, 256]))
+    nlist = int(rng.choice([8, 40, 150]))
+    n = int(rng.integers(nlist * 20, 30000))
+    L, k = int(rng.choice([2, 6, 16])), 10
+    fraction = float(rng.choice([0.0, 0.25, 0.5, 1.0]))
+    decay = float(rng.choice([1.0, 2.0, 3.0]))
+    h_inc = float(rng.choice([0.0, 0.5, 1.0]))
+    sizes = W.zipf_sizes(n, nlist, 1.1, 9700 + seed)
+    ds = W.cluster_major_datastore(sizes, d, 0.4, 9800 + seed, dtype=dtype)
+    off, cent = ds.offsets.numpy(), ds.centroids.numpy()
+    st, odt = stored(ds.rows.float().numpy(), dtype)
+    bsz = np.diff(off) * d * (4 if dtype == "f32" else 2)
+    cap = int(bsz.sum() * rng.choice([0.3, 0.6, 1.0]))
+    index = P.ivf_adopt_layout(ds.rows.pin_memory(), dtype, off, cent, metric=P.IVF_IP, placement=P.IVF_PLACE_HOST,
+                               device_buffer_bytes=cap, compute_stream=streams[0], copy_stream=streams[1])
+    index.ivf_cache_configure(fraction, 1.0, decay, h_inc)
+    res = O.Residency(nlist, cap)
+    hot = np.full(nlist, -1.0, np.float32)
+    used = np.zeros(nlist, np.uint8)
+    for rnd in range(6):
+        q = (cent[rng.integers(0, nlist)] + 0.2 * rng.standard_normal(d)).astype(np.float32)
+        budget = int(bsz.sum() * rng.choice([0.05, 0.2, 0.5]))
+        chosen, skipped, nbytes = O.prefetch(cent, off, odt, q, L, budget, res, O.IP)
+        O.cache_admit(hot, res, 1.0)
+        ps = index.ivf_prefetch(q, L, budget)
+        assert (ps.n_taken, ps.n_skipped, ps.bytes) == (len(chosen), skipped, nbytes)
+        gi, gd = index.ivf_search(q, L, k)
+        ov, _ = O.split(cent, q, L, res.flags, O.IP)
+        used[ov] = 1
+        assert check_topk(gi[0], gd[0], st, odt, off, None, cent, q, L, k, O.IP) == 0
+        ev = O.cache_round(hot, used, res, off, d, odt, decay, h_inc, fraction)
+        cs = index.ivf_cache_end_round()
+        assert cs.n_evicted == len(ev) and cs.bytes_kept == res.used.value
+        assert np.array_equal(index.ivf_cache_hotness(), hot)
+        assert list(index.ivf_resident()) == list(res.clusters())
+        gi, gd = index.ivf_search(q, L, k)
+        ov, _ = O.split(cent, q, L, res.flags, O.IP)
+        used[ov] = 1
+        assert check_topk(gi[0], gd[0], st, odt, off, None, cent, q, L, k, O.IP) == 0
+    index.close()
