@@ -585,8 +585,8 @@ def main():
     dt1 = time_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, args.steps, args.warmup)
     prof = profile_steps(index, stream, q_dev, ids_dev, dists_dev, args.nprobe, args.k, min(args.steps, 2048))
 
-    # the same searches handed over as host buffers (ivf_search): adds the copy of the query to the
-    # device, the copy of the k results back and a stream synchronisation per call
+    # the same searches handed over as host buffers (ivf_search): every call starts from an idle
+    # stream, the query is read from pinned host memory and the k results are stored there
     q_host = q_out.cpu().numpy()
     n_host = min(args.steps, 1024)
     for i in range(32):

@@ -154,7 +154,9 @@ int ivf_prefetch_wait(ivf_index* index, float* ms);
  * IVF search (App. B; with host placement: Sec. 4.1 steps 2-4).
  *   q_out  host, nq x d float32      ids    host, nq x k, nearest first
  *   dists  host, nq x k float32
- * On return the outputs are complete.  With IVF_PLACE_HOST the clusters selected for
+ * On return the outputs are complete (for nq = 1 the call returns as soon as the last kernel
+ * has published them; work enqueued later on compute_stream is ordered behind that kernel).
+ * With IVF_PLACE_HOST the clusters selected for
  * q_out that are resident are scanned on the GPU while the others are scanned by host
  * threads; the result equals a search with every list resident.
  */

@@ -76,6 +76,10 @@ struct Workspace {
     float* d_out_dists = nullptr;
     // pinned host staging
     float* h_q = nullptr;
+    float* hd_q = nullptr;           // h_q as the device addresses it
+    unsigned long long* h_done = nullptr;    // completion word of single-query host searches (pinned)
+    unsigned long long* hd_done = nullptr;   // ... as the device addresses it
+    unsigned long long done_seq = 0;
     int32_t* h_probe = nullptr;
     int64_t* h_out_ids = nullptr;
     float* h_out_dists = nullptr;
@@ -170,7 +174,7 @@ void free_workspace(Workspace& w) {
     hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part); hipFree(w.d_heads);
     hipFree(w.d_desc);
     hipFree(w.d_out_ids); hipFree(w.d_out_dists);
-    hipHostFree(w.h_q); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
+    hipHostFree(w.h_q); hipHostFree(w.h_done); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
     hipHostFree(w.h_cand); hipHostFree(w.h_cand_count); hipHostFree(w.h_scores);
     hipFree(w.d_thr_part); hipFree(w.d_cand_score); hipFree(w.d_eps); hipFree(w.d_surv_row);
     hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
@@ -236,6 +240,10 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     HIP_TRY(hipMalloc(&w.d_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipMalloc(&w.d_out_dists, nqz * k2 * sizeof(float)));
     HIP_TRY(hipHostMalloc(&w.h_q, nqz * ix->d * sizeof(float)));
+    HIP_TRY(hipHostGetDevicePointer((void**)&w.hd_q, w.h_q, 0));
+    HIP_TRY(hipHostMalloc(&w.h_done, sizeof(unsigned long long)));
+    HIP_TRY(hipHostGetDevicePointer((void**)&w.hd_done, w.h_done, 0));
+    *w.h_done = 0; w.done_seq = 0;
     HIP_TRY(hipHostMalloc(&w.h_probe, nqz * npz * sizeof(int32_t)));
     HIP_TRY(hipHostMalloc(&w.h_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipHostMalloc(&w.h_out_dists, nqz * k2 * sizeof(float)));
@@ -291,6 +299,17 @@ int prof_events(ivf_index* ix, int which, hipEvent_t* e0, hipEvent_t* e1) {
 }
 
 // ---- kernel sequences ---------------------------------------------------------------------
+// queries from the caller's host memory into d_q of the current workspace (which holds nq of them):
+// through the pinned buffer, then by a kernel when they are few and by the copy engine otherwise
+static int stage_queries(ivf_index* ix, const float* q_host, int nq) {
+    Workspace& w = *ix->cw;
+    const size_t n = (size_t)nq * ix->d;
+    memcpy(w.h_q, q_host, n * sizeof(float));
+    if (n * sizeof(float) <= (size_t)256 << 10) HIP_TRY(launch_stage_query(w.hd_q, w.d_q, n, ix->cs));
+    else HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, n * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    return IVF_OK;
+}
+
 // coarse scoring + selection for nq queries already in d_q (device); leaves the probe lists
 // and slot tables in the workspace
 int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int grid, bool count_rows = true,
@@ -332,7 +351,7 @@ int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kpri
 }
 
 int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, int grid,
-                  bool with_host, int64_t* out_ids, float* out_dists) {
+                  bool with_host, int64_t* out_ids, float* out_dists, bool signal_done = false) {
     Workspace& w = *ix->cw;
     MergeArgs ma{};
     ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.rowof = ix->d_rowof; ma.slots = w.slots;
@@ -343,6 +362,7 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     ma.d = ix->d; ma.dtype = ix->dtype; ma.metric = ix->metric; ma.nprobe = nprobe; ma.nq = nq;
     ma.k = k; ma.kprime = kprime; ma.nparts = grid;
     ma.identity = ix->placement == IVF_PLACE_DEVICE;
+    if (signal_done) { ma.done = w.hd_done; ma.done_value = ++w.done_seq; }
     hipEvent_t e0, e1;
     int rc = prof_events(ix, 3, &e0, &e1);
     if (rc) return rc;
@@ -714,6 +734,24 @@ extern "C" int ivf_synchronize(ivf_index* ix) {
 }
 
 // ---- search -------------------------------------------------------------------------------------
+static double now_ms() {
+    using namespace std::chrono;
+    return duration<double, std::milli>(steady_clock::now().time_since_epoch()).count();
+}
+
+// Watches a completion word for up to two milliseconds; false when it did not arrive in that time
+// (the caller then waits for the stream, which also brings any launch error to light).
+static bool wait_done_word(const unsigned long long* word, unsigned long long want) {
+    const double t_end = now_ms() + 2.0;
+    for (;;) {
+        for (int i = 0; i < 256; ++i) {
+            if (__atomic_load_n(word, __ATOMIC_ACQUIRE) == want) return true;
+            __builtin_ia32_pause();
+        }
+        if (now_ms() > t_end) return false;
+    }
+}
+
 // Device-pointer search of nq queries, query by query in one launch sequence (grid.y = nq).
 static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
                              int64_t* ids_dev, float* dists_dev) {
@@ -771,10 +809,6 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     return rc;
 }
 
-static double now_ms() {
-    using namespace std::chrono;
-    return duration<double, std::milli>(steady_clock::now().time_since_epoch()).count();
-}
 
 extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t nprobe, int32_t k,
                           int64_t* ids, float* dists, ivf_search_stats* stats) {
@@ -793,8 +827,7 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
     const bool hybrid = ix->placement == IVF_PLACE_HOST;
     ivf_search_stats st{};
 
-    memcpy(w.h_q, q_out, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    if ((rc = stage_queries(ix, q_out, nq))) return rc;
     if (batched_eligible(ix, nq)) {
         // list-major batched search: every selected cluster is read once per group of 32 queries
         if ((rc = run_batched(ix, w.d_q, nq, nprobe, k, w.d_out_ids, w.d_out_dists))) return rc;
@@ -850,8 +883,11 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
         st.hit_rate = (float)(hit_sum / nq);
     }
     // nq x k results: the kernel stores them in the pinned host buffers itself (no copy to enqueue)
-    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.hd_out_ids, w.hd_out_dists))) return rc;
-    HIP_TRY(hipStreamSynchronize(ix->cs));
+    // One query: the kernel also sets a completion word after the results; the host watches that
+    // word instead of waiting for the stream to drain (the stream keeps its order for later calls).
+    const bool watch = nq == 1;
+    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.hd_out_ids, w.hd_out_dists, watch))) return rc;
+    if (!watch || !wait_done_word(w.h_done, w.done_seq)) HIP_TRY(hipStreamSynchronize(ix->cs));
     memcpy(ids, w.h_out_ids, (size_t)nq * k * sizeof(int64_t));
     memcpy(dists, w.h_out_dists, (size_t)nq * k * sizeof(float));
     st.ms_total = (float)(now_ms() - t0);
@@ -870,8 +906,7 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     if ((rc = ensure_workspace(ix, nq, nprobe, 1))) return rc;
     Workspace& w = *ix->cw;
     // rank the clusters by q_in on the GPU
-    memcpy(w.h_q, q_in, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    if ((rc = stage_queries(ix, q_in, nq))) return rc;
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
     rc = enqueue_probe(ix, w.d_q, nq, nprobe, 1);
@@ -1107,8 +1142,7 @@ extern "C" int ivf_coarse_scores(ivf_index* ix, const float* q, int32_t nq, doub
     if ((rc = settle_on_lane0(ix))) return rc;
     if ((rc = ensure_workspace(ix, nq, 1, 1))) return rc;
     Workspace& w = *ix->cw;
-    memcpy(w.h_q, q, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    if ((rc = stage_queries(ix, q, nq))) return rc;
     CoarseArgs ca{ix->d_centroids, w.d_q, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
     HIP_TRY(launch_coarse(ca, ix->cs));
     HIP_TRY(hipStreamSynchronize(ix->cs));
@@ -1124,8 +1158,7 @@ extern "C" int ivf_probe(ivf_index* ix, const float* q, int32_t nq, int32_t npro
     if ((rc = settle_on_lane0(ix))) return rc;
     if ((rc = ensure_workspace(ix, nq, nprobe, 1))) return rc;
     Workspace& w = *ix->cw;
-    memcpy(w.h_q, q, (size_t)nq * ix->d * sizeof(float));
-    HIP_TRY(hipMemcpyAsync(w.d_q, w.h_q, (size_t)nq * ix->d * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+    if ((rc = stage_queries(ix, q, nq))) return rc;
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
     rc = enqueue_probe(ix, w.d_q, nq, nprobe, 1);

@@ -106,6 +106,9 @@ struct MergeArgs {
     int64_t* out_ids; float* out_dists;   // [nq x k]
     int d, dtype, metric, nprobe, nq, k, kprime, nparts;
     int identity;            // 1: buffer row == global row (device placement)
+    // Completion word in pinned host memory (device address) or nullptr: set to done_value after
+    // the results are visible to the host.  Only for nq == 1 (one workgroup writes it).
+    unsigned long long* done; unsigned long long done_value;
 };
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 
@@ -158,6 +161,8 @@ size_t batched_thr_part_floats(int nq);
 size_t batched_scan_lds(int d);      // LDS bytes of the batched scan kernel (one group of queries)
 
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
+// n floats from a pinned host buffer (its device address) to device memory, by a kernel
+hipError_t launch_stage_query(const float* src_pinned, float* dst, size_t n, hipStream_t s);
 hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, int64_t n,
                                size_t row_bytes, hipStream_t s);
 

@@ -4,6 +4,7 @@
 // centroids, fine search over the rows of the selected clusters, k nearest by a sort.
 #include "ivf_device.h"
 #include <hip/hip_ext.h>
+#include <algorithm>
 
 namespace ivf {
 using namespace dev;
@@ -1090,10 +1091,18 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
         a.out_ids[(size_t)qi * k + i] = -1;
         a.out_dists[(size_t)qi * k + i] = a.metric == 0 ? -INFINITY : INFINITY;
     }
+    if (a.done) {       // uniform; every thread of the workgroup arrives here
+        __syncthreads();
+        if (tid == 0) {
+            __threadfence_system();
+            __hip_atomic_store(a.done, a.done_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
     IVF_TRACE_MARK(25);
 }
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+    if (a.done && a.nq != 1) return hipErrorInvalidValue;
     const size_t n = (size_t)a.nparts * a.kprime;
     const int fast = a.kprime <= 64;
     const int threads = fast ? kMergeFastThreads : (n <= 8192 ? 256 : kSelectThreads);
@@ -1129,6 +1138,22 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, i
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                        (const unsigned char*)src, (unsigned char*)dst, pos, n, row_bytes);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Queries handed over in host memory: a few KB that a kernel reads from the pinned buffer itself
+// (one dispatch on the search stream) instead of a copy engine transfer set up by the runtime.
+// =============================================================================================
+__global__ void stage_query_kernel(const float* src, float* dst, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_stage_query(const float* src_pinned, float* dst, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const size_t blocks = std::min<size_t>((n + 255) / 256, 64);
+    hipLaunchKernelGGL(stage_query_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src_pinned, dst, n);
     return hipGetLastError();
 }
 
