@@ -140,3 +140,75 @@ def test_scheduler_rejects_bad_arguments(streams):
         index.ivf_schedule(q[:10], 0)
     assert e.value.status == -1
     index.close()
+
+
+def test_back_to_back_host_searches_return_their_own_results(streams):
+    """A single-query ivf_search returns when the last kernel has published its results in pinned
+    memory, while the stream may still be finishing: 400 calls in a row, alternating queries with
+    different answers, must each return the answer of their own query (a stale or early read of the
+    result buffer would return the previous one)."""
+    rng = np.random.default_rng(77)
+    n, d, nlist = 20000, 96, 40
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    assign = rng.integers(0, nlist, n).astype(np.int32)
+    rows = (cent[assign] + 0.4 * rng.standard_normal((n, d))).astype(np.float32)
+    index = P.ivf_build_layout(rows, "f32", cent, assign, metric=P.IVF_IP,
+                               compute_stream=streams[0], copy_stream=streams[1])
+    q = (cent[rng.integers(0, nlist, 8)] + 0.3 * rng.standard_normal((8, d))).astype(np.float32)
+    off, perm = O.build_layout(assign, nlist)
+    first = [index.ivf_search(q[b], 10, 7) for b in range(8)]
+    assert len({tuple(f[0][0]) for f in first}) > 1           # the queries do differ in their answers
+    for it in range(400):
+        b = (it * 5) % 8
+        gi, gd = index.ivf_search(q[b], 10, 7)
+        assert np.array_equal(gi, first[b][0]) and np.array_equal(gd, first[b][1]), f"call {it}"
+    for b in range(8):
+        assert check_topk(first[b][0][0], first[b][1][0], rows[perm], O.F32, off, perm.astype(np.int64), cent, q[b],
+                          10, 7, O.IP) == 0
+    index.close()
+
+
+@pytest.mark.parametrize("metric", ["ip", "l2"])
+@pytest.mark.parametrize("nlist,d", [(1024, 64), (1039, 37), (4097, 100), (5000, 768), (20000, 32)])
+def test_single_query_probe_of_large_indexes(streams, metric, nlist, d):
+    """One query against 1024 or more centroids, several calls in a row: every selection path
+    (register sort up to 64, the general sort, the selection pass before it, global sort memory
+    for the full order), ragged last workgroups, rows that are not a multiple of 16 bytes, and
+    centroids that tie exactly."""
+    pm, om = (P.IVF_IP, O.IP) if metric == "ip" else (P.IVF_L2, O.L2)
+    rng = np.random.default_rng(nlist + d)
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    cent[rng.integers(0, nlist, nlist // 8)] = cent[rng.integers(0, nlist, nlist // 8)]    # exact ties
+    index = _index(streams, cent, d, pm)
+    q = rng.standard_normal((6, d)).astype(np.float32)
+    for nprobe in (1, 32, 64, 65, 200, nlist):
+        for b in range(6):
+            pr = index.ivf_probe(q[b], nprobe)
+            assert list(pr[0]) == list(O.probe(cent, q[b], nprobe, om)), f"nprobe {nprobe}, query {b}"
+    pr = index.ivf_probe(q[:3], 32)                  # three queries in one call: same answers
+    for b in range(3):
+        assert list(pr[b]) == list(O.probe(cent, q[b], 32, om))
+    index.close()
+
+
+def test_single_query_probe_redoes_prefix_ties(streams):
+    """The prefix-tie case of the register sort with more than 1024 centroids, one query per call."""
+    rng = np.random.default_rng(6)
+    d, near, far = 16, 150, 1000
+    base = rng.standard_normal(d).astype(np.float32)
+    base[0] = np.float32(1e-3)
+    cent = np.empty((near + far, d), dtype=np.float32)
+    step = np.float32(base[0])
+    for j in range(near):
+        cent[j] = base
+        cent[j, 0] = step
+        step = np.nextafter(step, np.float32(1.0), dtype=np.float32)
+    cent[near:] = 0.1 * rng.standard_normal((far, d)).astype(np.float32)
+    cent = np.ascontiguousarray(cent[rng.permutation(near + far)])
+    index = _index(streams, cent, d, P.IVF_IP)
+    for nprobe in (1, 10, 63, 64):
+        for b in range(4):
+            q = (base + 0.01 * rng.standard_normal(d)).astype(np.float32)
+            q[0] = abs(q[0]) + 0.5
+            assert list(index.ivf_probe(q, nprobe)[0]) == list(O.probe(cent, q, nprobe, O.IP))
+    index.close()
