@@ -436,7 +436,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
     int in_lds = pad <= (uint32_t)kSortLdsCap;
     int prefix_in_lds = a.nprobe <= kPrefixLdsCap;
     // a workgroup with one wavefront per SIMD issues fastest when there is little work per thread
-    const int threads = a.nlist < 1024 && a.grid <= 1024 ? 256 : kSelectThreads;
+    const int threads = a.nlist <= 1024 && a.grid <= 1024 ? 256 : kSelectThreads;
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
     if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64) * 64 * 8;
     IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds);
