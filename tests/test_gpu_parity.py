@@ -270,3 +270,36 @@ def test_search_device_and_adopt(streams):
     assert p.ms_scan > 0
     index.ivf_profile_enable(False)
     index.close()
+
+
+@pytest.mark.parametrize("dtype,d,n", [("f32", 32, 4500), ("f32", 64, 4500), ("f16", 128, 4500), ("f32", 96, 4500),
+                                       ("f16", 256, 4500), ("f32", 768, 4500), ("bf16", 1024, 4500), ("f32", 100, 4500),
+                                       ("f16", 36, 4500), ("f32", 768, 9500), ("f16", 512, 20000)])
+def test_every_row_is_found_by_its_own_query(streams, dtype, d, n):
+    """Coverage of the scan: with every list selected, the stored row itself is the nearest
+    neighbour of its own values (normalised, distinct rows; inner product), whichever workgroup
+    and wavefront its place in the row sequence falls to.  All rows are asked, in calls of 512
+    queries (scan grids of 512 queries) and, for every 11th row, one query per call; lists are
+    ragged and some are empty; the two largest cases fill the whole scan grid of a single query.
+    Expected ids come from a float64 Gram matrix of the stored rows."""
+    nlist = 9
+    st, odt, cent, assign, ids, rng = _random_problem(1000 + d, n, d, nlist, dtype, empty=(2, 5))
+    index = P.ivf_build_layout(st, dtype, cent, assign, ids=ids, metric=P.IVF_IP,
+                               compute_stream=streams[0], copy_stream=streams[1])
+    if dtype == "bf16":
+        wide = torch.from_numpy(st.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    else:
+        wide = st.astype(np.float64)
+    self_ip = np.einsum("ij,ij->i", wide, wide)
+    for lo in range(0, n, 1000):                      # the case is what it claims: every row wins its own query
+        assert np.array_equal(np.argmax(wide[lo:lo + 1000] @ wide.T, axis=1), np.arange(lo, min(lo + 1000, n)))
+    q = wide.astype(np.float32)                       # exact: stored values fit float32
+    index.ivf_set_batch_mode(1)                       # query by query, also inside one call
+    for lo in range(0, n, 512):
+        gi, gd = index.ivf_search(q[lo:lo + 512], nlist, 1)
+        assert np.array_equal(gi[:, 0], ids[lo:lo + 512]), f"rows {lo}..: {np.flatnonzero(gi[:, 0] != ids[lo:lo + 512])[:8] + lo}"
+    for i in range(0, n, 11):
+        gi, gd = index.ivf_search(q[i], nlist, 1)
+        assert gi[0, 0] == ids[i], f"row {i}"
+        np.testing.assert_allclose(gd[0, 0], self_ip[i], rtol=2e-3 if dtype != "f32" else 1e-4)
+    index.close()
