@@ -81,3 +81,32 @@ def test_candidate_overflow_falls_back(streams):
         assert list(gi[b]) == list(oi)
         np.testing.assert_allclose(gd[b], osc, rtol=2e-3)
     index.close()
+
+
+@pytest.mark.parametrize("dtype,d,nq", [("f16", 128, 256), ("bf16", 256, 200), ("f16", 768, 32), ("bf16", 64, 77)])
+def test_list_major_finds_every_row_by_its_own_query(streams, dtype, d, nq):
+    """Coverage of the batched scan: with every list selected, each stored row is the nearest
+    neighbour of its own values (normalised, distinct rows), whichever tile of 256 rows and group of
+    queries it falls into.  All rows are asked, nq queries per call; lists are ragged (Zipf sizes
+    from thousands of rows down to a handful) and one is empty.  A row's query is its stored values,
+    so the rounding of the query to the storage type changes nothing."""
+    nlist = 12
+    sizes = W.zipf_sizes(7000, nlist, 1.2, 9)
+    sizes[3] += sizes[8]; sizes[8] = 0
+    ds = W.cluster_major_datastore(sizes, d, 0.3, 10, dtype=dtype, device="cuda")
+    wide = ds.rows.to(torch.float64).cpu().numpy()
+    n = ds.n
+    for lo in range(0, n, 1000):                      # the case is what it claims
+        assert np.array_equal(np.argmax(wide[lo:lo + 1000] @ wide.T, axis=1), np.arange(lo, min(lo + 1000, n)))
+    ids = (np.random.default_rng(2).permutation(n) * 5 + 2).astype(np.int64)
+    index = P.ivf_adopt_layout(ds.rows, dtype, ds.offsets.numpy(), ds.centroids.cpu().numpy(), ids=ids, metric=P.IVF_IP,
+                               compute_stream=streams[0], copy_stream=streams[1])
+    index.ivf_set_batch_mode(2)
+    q = wide.astype(np.float32)
+    for lo in range(0, n, nq):
+        hi = min(lo + nq, n)
+        if hi - lo < 2:                               # a single query is never list-major
+            break
+        gi, gd = index.ivf_search(q[lo:hi], nlist, 1)
+        assert np.array_equal(gi[:, 0], ids[lo:hi]), f"rows {np.flatnonzero(gi[:, 0] != ids[lo:hi])[:8] + lo}"
+    index.close()
