@@ -226,3 +226,36 @@ def test_identical_rows_split_between_host_and_gpu(streams, dtype, d):
             oi, _ = O.search(st[perm], odt, off, ids[perm], cent, q[b], L, k, O.IP)
             assert list(gi[b]) == list(oi)
     index.close()
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("f32", 96), ("bf16", 320)])
+def test_hybrid_search_finds_every_row_by_its_own_query(streams, dtype, d):
+    """Coverage of the hybrid search: with every list selected and about half of the lists
+    resident, each stored row is the nearest neighbour of its own values (normalised, distinct
+    rows) whether its list is scanned on the GPU or by the host threads.  All rows are asked, 64
+    per call."""
+    nlist = 14
+    sizes = W.zipf_sizes(5000, nlist, 1.1, 21)
+    sizes[4] += sizes[9]; sizes[9] = 0
+    ds = W.cluster_major_datastore(sizes, d, 0.3, 22, dtype=dtype)
+    off, cent = ds.offsets.numpy(), ds.centroids.numpy()
+    wide = ds.rows.to(torch.float64).numpy()
+    n = ds.n
+    for lo in range(0, n, 1000):                      # the case is what it claims
+        assert np.array_equal(np.argmax(wide[lo:lo + 1000] @ wide.T, axis=1), np.arange(lo, min(lo + 1000, n)))
+    esz = 4 if dtype == "f32" else 2
+    index = P.ivf_adopt_layout(ds.rows.pin_memory(), dtype, off, cent, metric=P.IVF_IP, placement=P.IVF_PLACE_HOST,
+                               device_buffer_bytes=n * d * esz, compute_stream=streams[0], copy_stream=streams[1])
+    q = wide.astype(np.float32)
+    index.ivf_prefetch(q[0], nlist, n * d * esz // 2, flags=P.IVF_PREFETCH_RESET)      # whole lists up to half of the bytes
+    res = set(index.ivf_resident())
+    assert 0 < len(res) < nlist
+    on_gpu = np.zeros(n, dtype=bool)
+    for c in res:
+        on_gpu[off[c]:off[c + 1]] = True
+    assert on_gpu.any() and (~on_gpu).any()
+    for lo in range(0, n, 64):
+        gi, gd = index.ivf_search(q[lo:lo + 64], nlist, 1)
+        want = np.arange(lo, min(lo + 64, n))
+        assert np.array_equal(gi[:, 0], want), f"rows {want[gi[:, 0] != want][:8]} (on the GPU: {on_gpu[want[gi[:, 0] != want][:8]]})"
+    index.close()
