@@ -168,18 +168,22 @@ struct ivf_index {
 
 namespace {
 
+// releases without a status: used on teardown and on error paths, where nothing can be done about a failure
+void dfree(void* p) { if (p) (void)hipFree(p); }
+void hfree(void* p) { if (p) (void)hipHostFree(p); }
+
 void free_workspace(Workspace& w) {
-    hipFree(w.d_q); hipFree(w.d_scores); hipFree(w.d_probe);
-    hipFree(w.slots.base); hipFree(w.slots.grow); hipFree(w.slots.nrows); hipFree(w.slots.rprefix);
-    hipFree(w.d_sort_keys); hipFree(w.d_sort_idx); hipFree(w.d_part); hipFree(w.d_heads);
-    hipFree(w.d_desc);
-    hipFree(w.d_out_ids); hipFree(w.d_out_dists);
-    hipHostFree(w.h_q); hipHostFree(w.h_done); hipHostFree(w.h_probe); hipHostFree(w.h_out_ids); hipHostFree(w.h_out_dists);
-    hipHostFree(w.h_cand); hipHostFree(w.h_cand_count); hipHostFree(w.h_scores);
-    hipFree(w.d_thr_part); hipFree(w.d_cand_score); hipFree(w.d_eps); hipFree(w.d_surv_row);
-    hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
-    hipFree(w.d_tstart); hipFree(w.d_qidx); hipFree(w.d_tasks); hipFree(w.d_cand_count); hipFree(w.d_cand_row);
-    hipFree(w.d_cand_key); hipFree(w.d_overflow); hipHostFree(w.h_overflow);
+    dfree(w.d_q); dfree(w.d_scores); dfree(w.d_probe);
+    dfree(w.slots.base); dfree(w.slots.grow); dfree(w.slots.nrows); dfree(w.slots.rprefix);
+    dfree(w.d_sort_keys); dfree(w.d_sort_idx); dfree(w.d_part); dfree(w.d_heads);
+    dfree(w.d_desc);
+    dfree(w.d_out_ids); dfree(w.d_out_dists);
+    hfree(w.h_q); hfree(w.h_done); hfree(w.h_probe); hfree(w.h_out_ids); hfree(w.h_out_dists);
+    hfree(w.h_cand); hfree(w.h_cand_count); hfree(w.h_scores);
+    dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row);
+    dfree(w.d_q_store); dfree(w.d_thr); dfree(w.d_list_count); dfree(w.d_cursor); dfree(w.d_qstart);
+    dfree(w.d_tstart); dfree(w.d_qidx); dfree(w.d_tasks); dfree(w.d_cand_count); dfree(w.d_cand_row);
+    dfree(w.d_cand_key); dfree(w.d_overflow); hfree(w.h_overflow);
     w = Workspace{};
 }
 
@@ -387,10 +391,10 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
     if (nq <= w.b_nq && nprobe <= w.b_nprobe) return IVF_OK;
     const int nq2 = std::max(nq, w.b_nq), np2 = std::max(nprobe, w.b_nprobe);
     HIP_TRY(hipDeviceSynchronize());
-    hipFree(w.d_thr_part); hipFree(w.d_cand_score); hipFree(w.d_eps); hipFree(w.d_surv_row);
-    hipFree(w.d_q_store); hipFree(w.d_thr); hipFree(w.d_list_count); hipFree(w.d_cursor); hipFree(w.d_qstart);
-    hipFree(w.d_tstart); hipFree(w.d_qidx); hipFree(w.d_tasks); hipFree(w.d_cand_count); hipFree(w.d_cand_row);
-    hipFree(w.d_cand_key); hipFree(w.d_overflow); hipHostFree(w.h_overflow);
+    dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row);
+    dfree(w.d_q_store); dfree(w.d_thr); dfree(w.d_list_count); dfree(w.d_cursor); dfree(w.d_qstart);
+    dfree(w.d_tstart); dfree(w.d_qidx); dfree(w.d_tasks); dfree(w.d_cand_count); dfree(w.d_cand_row);
+    dfree(w.d_cand_key); dfree(w.d_overflow); hfree(w.h_overflow);
     w.d_thr_part = nullptr; w.d_cand_score = nullptr; w.d_eps = nullptr; w.d_surv_row = nullptr;
     w.d_q_store = nullptr; w.d_thr = nullptr; w.d_list_count = w.d_cursor = w.d_qstart = w.d_tstart = w.d_qidx = nullptr;
     w.d_tasks = nullptr; w.d_cand_count = w.d_cand_row = nullptr; w.d_cand_key = nullptr; w.d_overflow = w.h_overflow = nullptr;
@@ -573,23 +577,23 @@ int check_build_args(const void* data, int64_t n, int32_t d, int dtype, const fl
 
 extern "C" void ivf_free(ivf_index* ix) {
     if (!ix) return;
-    hipDeviceSynchronize();
-    for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) hipStreamDestroy(l.stream); }
-    for (auto& s : ix->prof_sets) for (auto& e : s.e) hipEventDestroy(e);
-    hipFree(ix->d_centroids); hipFree(ix->d_off); hipFree(ix->d_ids); hipFree(ix->d_idrank); hipFree(ix->d_rowof);
-    hipFree(ix->d_hot); hipFree(ix->d_used); hipFree(ix->d_move_tmp);
-    for (auto& e : ix->ev_cache) if (e) hipEventDestroy(e);
-    hipFree(ix->d_res_off);
-    hipFree(ix->d_prof_rows); hipFree(ix->d_row_norm_max);
-    if (ix->own_buf) hipFree(ix->d_buf);
-    if (ix->own_h_lists) hipHostFree(ix->h_lists);
-    hipHostFree(ix->h_res_stage);
-    if (ix->ev_pf_begin) hipEventDestroy(ix->ev_pf_begin);
-    if (ix->ev_pf_done) hipEventDestroy(ix->ev_pf_done);
-    if (ix->ev_probe) hipEventDestroy(ix->ev_probe);
-    if (ix->ev_pf_table) hipEventDestroy(ix->ev_pf_table);
-    if (ix->own_compute) hipStreamDestroy(ix->compute);
-    if (ix->own_copy) hipStreamDestroy(ix->copy);
+    (void)hipDeviceSynchronize();
+    for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) (void)hipStreamDestroy(l.stream); }
+    for (auto& s : ix->prof_sets) for (auto& e : s.e) (void)hipEventDestroy(e);
+    dfree(ix->d_centroids); dfree(ix->d_off); dfree(ix->d_ids); dfree(ix->d_idrank); dfree(ix->d_rowof);
+    dfree(ix->d_hot); dfree(ix->d_used); dfree(ix->d_move_tmp);
+    for (auto& e : ix->ev_cache) if (e) (void)hipEventDestroy(e);
+    dfree(ix->d_res_off);
+    dfree(ix->d_prof_rows); dfree(ix->d_row_norm_max);
+    if (ix->own_buf) dfree(ix->d_buf);
+    if (ix->own_h_lists) hfree(ix->h_lists);
+    hfree(ix->h_res_stage);
+    if (ix->ev_pf_begin) (void)hipEventDestroy(ix->ev_pf_begin);
+    if (ix->ev_pf_done) (void)hipEventDestroy(ix->ev_pf_done);
+    if (ix->ev_probe) (void)hipEventDestroy(ix->ev_probe);
+    if (ix->ev_pf_table) (void)hipEventDestroy(ix->ev_pf_table);
+    if (ix->own_compute) (void)hipStreamDestroy(ix->compute);
+    if (ix->own_copy) (void)hipStreamDestroy(ix->copy);
     delete ix;
 }
 
@@ -645,7 +649,7 @@ extern "C" int ivf_build_layout(const void* vectors, int64_t n, int32_t d, int d
                 if (e == hipSuccess) e = hipStreamSynchronize(ix->cs);
                 if (e != hipSuccess) status = fail(IVF_EHIP, "layout upload: %s", hipGetErrorString(e));
             }
-            hipFree(d_stage); hipFree(d_pos);
+            dfree(d_stage); dfree(d_pos);
             if (status) return status;
         } else {
             if (n > 0) HIP_TRY(hipHostMalloc(&ix->h_lists, (size_t)n * rb));
@@ -713,7 +717,7 @@ extern "C" int ivf_set_pipeline_depth(ivf_index* ix, int32_t depth) {
     while ((int)ix->lanes.size() > depth) {
         auto& l = ix->lanes.back();
         free_workspace(l.ws);
-        if (l.own) hipStreamDestroy(l.stream);
+        if (l.own) (void)hipStreamDestroy(l.stream);
         ix->lanes.pop_back();
     }
     while ((int)ix->lanes.size() < depth) {
@@ -971,9 +975,9 @@ extern "C" int ivf_schedule(ivf_index* ix, const float* q, int32_t nq, int32_t m
     float* d_q = nullptr; double* d_dist = nullptr; int32_t* d_order = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     auto cleanup = [&]() {
-        hipFree(d_q); hipFree(d_dist); hipFree(d_order);
-        if (e0) hipEventDestroy(e0);
-        if (e1) hipEventDestroy(e1);
+        dfree(d_q); dfree(d_dist); dfree(d_order);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
     };
 #define SCHED_TRY(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { cleanup(); return fail(IVF_EHIP, "%s: %s", #call, hipGetErrorString(e_)); } } while (0)
     SCHED_TRY(hipMalloc(&d_q, (size_t)nq * ix->d * sizeof(float)));

@@ -422,7 +422,7 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
     __shared__ double f_key[2 * kMaxKPrime];
     __shared__ int64_t f_id[2 * kMaxKPrime];
     __shared__ unsigned long long best;
-    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id();
+    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
     const int qi = blockIdx.x, k = a.k;
     const uint32_t raw = a.cand_count[qi];
     if (raw > (uint32_t)a.cand_cap) {                  // too many candidates: the host redoes this query

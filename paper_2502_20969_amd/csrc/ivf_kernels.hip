@@ -981,7 +981,6 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     extern __shared__ unsigned char m_dyn[];
     __shared__ MergeLds L;
     const int tid = threadIdx.x, nt = blockDim.x;
-    const int lane = lane_id();
     const int qi = blockIdx.x;
     const uint32_t n = (uint32_t)a.nparts * a.kprime;
     const Cand* part = a.part + (size_t)qi * n;
