@@ -607,7 +607,9 @@ def main():
             pr = profile_steps(index, stream, q_dev, ids_dev, dists_dev, nprobe, args.k, min(steps, 512))
             sweep.append({"nprobe": nprobe, "qps": round(steps / t, 1), "us_scan": round(pr["us_scan"], 2),
                           "scan_gbs": round(pr["scan_gbs"], 1), "frac": round(pr["scan_gbs"] / HBM_PEAK_GBS, 4),
-                          "scan_mb": round(pr["scan_bytes_per_call"] / 1e6, 2)})
+                          "scan_mb": round(pr["scan_bytes_per_call"] / 1e6, 2),
+                          # selected bytes over the wall time of the whole search, searches in flight as for `value`
+                          "e2e_gbs": round(pr["scan_bytes_per_call"] * steps / t / 1e9, 1)})
 
     out = {
         "metric": METRIC, "value": round(args.steps / dt, 1), "unit": "queries/s", "n_gpus": 1,
