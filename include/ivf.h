@@ -213,6 +213,21 @@ int ivf_probe(ivf_index* index, const float* q, int32_t nq, int32_t nprobe, int3
 int ivf_resident(ivf_index* index, int32_t* clusters, int32_t* n);
 /* layout as built: offsets (host, nlist + 1) and/or ids (host, n); either may be NULL */
 int ivf_get_layout(ivf_index* index, int64_t* offsets, int64_t* ids);
+/*
+ * The host part of the hybrid search on its own (Sec. 4.1 step 3: the clusters of q_out that were
+ * not prefetched are searched by CPU threads).  Needs no index and no GPU.
+ *   lists     host, cluster-major rows of `dtype`, list c = rows offsets[c] .. offsets[c+1]
+ *   offsets   host, enough entries for every listed cluster (c + 1 is read)
+ *   ids       host, row -> id, or NULL (id = row)
+ *   q         host, d float32         clusters  host, n_clusters lists to scan
+ *   out_ids / out_scores   host, room for k + max(8, k / 8) entries: the candidates the merge step
+ *             would receive, unordered, with their float64 scores (inner product, or squared L2)
+ *   *n_out    number of candidates written; the k best by (score, id) are among them
+ * threads: host threads to use (at least 1).  Caller keeps every array.
+ */
+int ivf_host_scan(const void* lists, const int64_t* offsets, const int64_t* ids, int32_t d, int dtype,
+                  int metric, const float* q, const int32_t* clusters, int32_t n_clusters, int32_t k,
+                  int32_t threads, int64_t* out_ids, double* out_scores, int32_t* n_out);
 
 /* Kernel timing with HIP events on compute_stream around each kernel of every search while
  * enabled (adds event records to the stream; leave off when timing throughput). */

@@ -25,7 +25,7 @@ EXPORTS = [
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
-    "ivf_schedule", "ivf_strerror", "ivf_last_error",
+    "ivf_schedule", "ivf_host_scan", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -312,3 +312,23 @@ def ivf_adopt_layout(lists, dtype, offsets, centroids, ids=None, metric=IVF_IP,
                                    nlist, metric, placement, int(device_buffer_bytes),
                                    _stream(compute_stream), _stream(copy_stream), C.byref(h)))
     return Index(h, d, nlist, n, keep=(lists,))
+
+
+def ivf_host_scan(lists, dtype, offsets, q, clusters, k, ids=None, metric=IVF_IP, threads=4):
+    """Host scan of the listed clusters for one query: (ids, float64 scores) of the candidates the
+    merge step would receive, unordered.  lists: host array [n, d] in the stored type."""
+    rows = _rows_host(lists, dtype)
+    off = _host(offsets, np.int64)
+    idv = _host(ids, np.int64)
+    qv = _host(q, np.float32).reshape(-1)
+    cl = _host(clusters, np.int32).reshape(-1)
+    d = rows.shape[1]
+    assert qv.shape[0] == d
+    cap = k + max(8, k // 8)
+    out_ids = np.empty(cap, dtype=np.int64)
+    out_scores = np.empty(cap, dtype=np.float64)
+    n_out = C.c_int32(0)
+    L = load()
+    _check(L.ivf_host_scan(_ptr(rows), _ptr(off), _ptr(idv), d, DTYPE_CODE[dtype], metric, _ptr(qv), _ptr(cl),
+                           cl.shape[0], k, threads, _ptr(out_ids), _ptr(out_scores), C.byref(n_out)))
+    return out_ids[:n_out.value], out_scores[:n_out.value]

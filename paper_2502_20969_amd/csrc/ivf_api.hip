@@ -1226,6 +1226,29 @@ extern "C" int ivf_profile_reset(ivf_index* ix) {
     return IVF_OK;
 }
 
+extern "C" int ivf_host_scan(const void* lists, const int64_t* offsets, const int64_t* ids, int32_t d, int dtype,
+                             int metric, const float* q, const int32_t* clusters, int32_t n_clusters, int32_t k,
+                             int32_t threads, int64_t* out_ids, double* out_scores, int32_t* n_out) {
+    if (!lists || !offsets || !q || !out_ids || !out_scores || !n_out) return fail(IVF_EINVAL, "NULL argument");
+    if (n_clusters > 0 && !clusters) return fail(IVF_EINVAL, "clusters is NULL");
+    if (d < 1 || n_clusters < 0 || threads < 1 || threads > 256) return fail(IVF_EINVAL, "bad size (d %d, clusters %d, threads %d)", d, n_clusters, threads);
+    if (dtype < IVF_F32 || dtype > IVF_BF16) return fail(IVF_EINVAL, "unknown dtype %d", dtype);
+    if (metric != IVF_IP && metric != IVF_L2) return fail(IVF_EINVAL, "unknown metric %d", metric);
+    if (k < 1) return fail(IVF_EINVAL, "k must be at least 1 (got %d)", k);
+    if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
+    const int kprime = kprime_for(k);
+    ThreadPool pool(threads);
+    std::vector<HostCand> cand((size_t)kprime);
+    HostScanArgs ha{lists, offsets, ids, d, dtype, metric, q, clusters, n_clusters, kprime};
+    const int n = host_scan_query(ha, pool, cand.data(), nullptr);
+    for (int i = 0; i < n; ++i) {
+        out_ids[i] = cand[i].id;
+        out_scores[i] = metric == IVF_IP ? cand[i].key : -cand[i].key;
+    }
+    *n_out = n;
+    return IVF_OK;
+}
+
 extern "C" int ivf_set_host_threads(ivf_index* ix, int32_t n) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
     if (n < 1 || n > 256) return fail(IVF_EINVAL, "thread count must be in [1, 256]");
