@@ -214,6 +214,21 @@ int ivf_resident(ivf_index* index, int32_t* clusters, int32_t* n);
 /* layout as built: offsets (host, nlist + 1) and/or ids (host, n); either may be NULL */
 int ivf_get_layout(ivf_index* index, int64_t* offsets, int64_t* ids);
 /*
+ * The plan of ivf_prefetch on its own (Sec. 4.3 "Prefetching target", Sec. 4.2 "Batching"): the
+ * budget walk over clusters that are already ranked.  Needs no index and no GPU; ivf_prefetch runs
+ * the same code after ranking on the GPU.
+ *   ranked        host, nq x nprobe cluster numbers, nearest first for each query
+ *   offsets       host, nlist + 1 row offsets; a cluster's size is its rows x row_bytes
+ *   resident_off  host, nlist entries, in/out: row offset of a resident cluster in the buffer, -1 = absent
+ *   *buffer_used  in/out: bytes of the buffer in use (clusters are placed at this mark)
+ *   taken         host, room for nq x nprobe entries: the clusters to copy, in order; *n_taken = count
+ * stats (or NULL) as ivf_prefetch fills it.
+ */
+int ivf_prefetch_plan(const int32_t* ranked, int32_t nq, int32_t nprobe, const int64_t* offsets,
+                      int32_t nlist, size_t row_bytes, size_t budget_bytes, size_t buffer_bytes,
+                      int64_t* resident_off, size_t* buffer_used, int32_t* taken, int32_t* n_taken,
+                      ivf_prefetch_stats* stats /* or NULL */);
+/*
  * The host part of the hybrid search on its own (Sec. 4.1 step 3: the clusters of q_out that were
  * not prefetched are searched by CPU threads).  Needs no index and no GPU.
  *   lists     host, cluster-major rows of `dtype`, list c = rows offsets[c] .. offsets[c+1]

@@ -25,7 +25,7 @@ EXPORTS = [
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
-    "ivf_schedule", "ivf_host_scan", "ivf_strerror", "ivf_last_error",
+    "ivf_schedule", "ivf_host_scan", "ivf_prefetch_plan", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -332,3 +332,26 @@ def ivf_host_scan(lists, dtype, offsets, q, clusters, k, ids=None, metric=IVF_IP
     _check(L.ivf_host_scan(_ptr(rows), _ptr(off), _ptr(idv), d, DTYPE_CODE[dtype], metric, _ptr(qv), _ptr(cl),
                            cl.shape[0], k, threads, _ptr(out_ids), _ptr(out_scores), C.byref(n_out)))
     return out_ids[:n_out.value], out_scores[:n_out.value]
+
+
+def ivf_prefetch_plan(ranked, offsets, row_bytes, budget_bytes, buffer_bytes, resident_off, buffer_used):
+    """The budget walk of ivf_prefetch over already ranked clusters (ranked: [nq, nprobe] int32).
+    resident_off (int64[nlist], -1 = absent) is updated in place.  Returns (clusters to copy in
+    order, PrefetchStats, buffer bytes in use afterwards)."""
+    rk = _host(ranked, np.int32)
+    rk = rk.reshape(1, -1) if rk.ndim == 1 else rk
+    off = _host(offsets, np.int64)
+    assert resident_off.dtype == np.int64 and resident_off.flags["C_CONTIGUOUS"]
+    nlist = off.shape[0] - 1
+    assert resident_off.shape[0] == nlist
+    taken = np.empty(rk.size, dtype=np.int32)
+    n_taken = C.c_int32(0)
+    used = C.c_size_t(int(buffer_used))
+    st = PrefetchStats()
+    L = load()
+    L.ivf_prefetch_plan.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_size_t, C.c_size_t,
+                                    C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(L.ivf_prefetch_plan(_ptr(rk), rk.shape[0], rk.shape[1], _ptr(off), nlist, int(row_bytes), int(budget_bytes),
+                               int(buffer_bytes), _ptr(resident_off), C.byref(used), _ptr(taken), C.byref(n_taken),
+                               C.byref(st)))
+    return taken[:n_taken.value], st, used.value

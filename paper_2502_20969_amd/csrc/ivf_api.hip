@@ -900,6 +900,56 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
 }
 
 // ---- lookahead prefetch --------------------------------------------------------------------------
+// The plan of one prefetch call (Sec. 4.3 "Prefetching target"; several queries: Sec. 4.2 "Batching"):
+// every query gets an equal share of the budget and walks its ranked clusters nearest first; a
+// cluster that is resident (also: taken for an earlier query of the call) costs nothing, one that
+// fits the query's remaining share and the remaining buffer is taken whole at the buffer's fill
+// mark, any other is skipped and the walk goes on.  Pure host arithmetic: res_off (row offset in
+// the buffer or -1) and buf_used are updated, `taken` lists the clusters to copy, in order.
+static void plan_prefetch(const int32_t* ranked, int nq, int nprobe, const int64_t* off, size_t row_bytes,
+                          size_t budget_bytes, size_t buf_bytes, size_t& buf_used, int64_t* res_off,
+                          std::vector<int32_t>& taken, ivf_prefetch_stats& st) {
+    const size_t per_query = budget_bytes / (size_t)nq;
+    for (int qi = 0; qi < nq; ++qi) {
+        size_t remaining = per_query;
+        for (int i = 0; i < nprobe; ++i) {
+            const int32_t c = ranked[(size_t)qi * nprobe + i];
+            st.n_ranked += 1;
+            if (res_off[c] >= 0) { st.n_resident += 1; continue; }
+            const size_t bytes = (size_t)(off[c + 1] - off[c]) * row_bytes;
+            if (bytes <= remaining && bytes <= buf_bytes - buf_used) {
+                res_off[c] = (int64_t)(buf_used / row_bytes);
+                buf_used += bytes;
+                remaining -= bytes;
+                st.bytes += bytes;
+                st.n_taken += 1;
+                taken.push_back(c);
+            } else {
+                st.n_skipped += 1;
+            }
+        }
+    }
+    st.buffer_used = buf_used;
+}
+
+extern "C" int ivf_prefetch_plan(const int32_t* ranked, int32_t nq, int32_t nprobe, const int64_t* offsets,
+                                 int32_t nlist, size_t row_bytes, size_t budget_bytes, size_t buffer_bytes,
+                                 int64_t* resident_off, size_t* buffer_used, int32_t* taken, int32_t* n_taken,
+                                 ivf_prefetch_stats* stats) {
+    if (!ranked || !offsets || !resident_off || !buffer_used || !taken || !n_taken) return fail(IVF_EINVAL, "NULL argument");
+    if (nq < 1 || nprobe < 1 || nlist < 1 || row_bytes < 1) return fail(IVF_EINVAL, "nq, nprobe, nlist and row_bytes must be at least 1");
+    if (*buffer_used > buffer_bytes) return fail(IVF_EINVAL, "buffer_used is above buffer_bytes");
+    for (size_t i = 0; i < (size_t)nq * nprobe; ++i)
+        if (ranked[i] < 0 || ranked[i] >= nlist) return fail(IVF_EINVAL, "ranked[%zu] = %d is not a cluster", i, ranked[i]);
+    std::vector<int32_t> t;
+    ivf_prefetch_stats st{};
+    plan_prefetch(ranked, nq, nprobe, offsets, row_bytes, budget_bytes, buffer_bytes, *buffer_used, resident_off, t, st);
+    std::copy(t.begin(), t.end(), taken);
+    *n_taken = (int32_t)t.size();
+    if (stats) *stats = st;
+    return IVF_OK;
+}
+
 extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_t nprobe,
                             size_t budget_bytes, uint32_t flags, ivf_prefetch_stats* stats) {
     int rc = check_query_args(ix, q_in, nq, nprobe);
@@ -925,29 +975,16 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     }
     ivf_prefetch_stats st{};
     HIP_TRY(hipEventRecord(ix->ev_pf_begin, ix->copy));
-    const size_t per_query = budget_bytes / (size_t)nq;
     const size_t rb = ix->row_bytes;
-    for (int qi = 0; qi < nq; ++qi) {
-        size_t remaining = per_query;
-        for (int i = 0; i < nprobe; ++i) {
-            const int32_t c = w.h_probe[(size_t)qi * nprobe + i];
-            st.n_ranked += 1;
-            if (ix->h_res_off[c] >= 0) { st.n_resident += 1; continue; }
-            const size_t bytes = (size_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
-            if (bytes <= remaining && bytes <= ix->buf_bytes - ix->buf_used) {
-                if (bytes > 0)
-                    HIP_TRY(hipMemcpyAsync((char*)ix->d_buf + ix->buf_used,
-                                           (const char*)ix->h_lists + (size_t)ix->h_off[c] * rb, bytes,
-                                           hipMemcpyHostToDevice, ix->copy));
-                ix->h_res_off[c] = (int64_t)(ix->buf_used / rb);
-                ix->buf_used += bytes;
-                remaining -= bytes;
-                st.bytes += bytes;
-                st.n_taken += 1;
-            } else {
-                st.n_skipped += 1;
-            }
-        }
+    std::vector<int32_t> taken;
+    plan_prefetch(w.h_probe, nq, nprobe, ix->h_off.data(), rb, budget_bytes, ix->buf_bytes, ix->buf_used,
+                  ix->h_res_off.data(), taken, st);
+    for (int32_t c : taken) {
+        const size_t bytes = (size_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
+        if (bytes > 0)
+            HIP_TRY(hipMemcpyAsync((char*)ix->d_buf + (size_t)ix->h_res_off[c] * rb,
+                                   (const char*)ix->h_lists + (size_t)ix->h_off[c] * rb, bytes,
+                                   hipMemcpyHostToDevice, ix->copy));
     }
     // the residency table follows the data on the same stream; the pinned staging copy is reused,
     // so the previous upload from it must have finished
