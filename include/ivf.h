@@ -229,6 +229,27 @@ int ivf_prefetch_plan(const int32_t* ranked, int32_t nq, int32_t nprobe, const i
                       int64_t* resident_off, size_t* buffer_used, int32_t* taken, int32_t* n_taken,
                       ivf_prefetch_stats* stats /* or NULL */);
 /*
+ * The host part of ivf_cache_end_round on its own (Sec. 4.2 "Cache design"), after the hotness
+ * update: which clusters leave and how the survivors are moved.  Needs no index and no GPU;
+ * ivf_cache_end_round runs the same code and then performs the moves with device copies.
+ *   hotness       host, nlist float32, in/out: evicted clusters get -1
+ *   resident_off  host, nlist, in/out: row offset in the buffer, -1 = not cached
+ *   *buffer_used  in/out: bytes in use
+ *   evicted       host, room for nlist entries, in the order the clusters leave; *n_evicted = count
+ *   moves         host, room for nlist entries, in the order to carry them out; *n_moves = count.
+ *                 A move copies `bytes` bytes from from_byte to to_byte of the buffer; via_staging = 1
+ *                 when source and destination overlap (copy out to a staging area first).
+ */
+typedef struct ivf_cache_move {
+    int32_t cluster;
+    int32_t via_staging;
+    uint64_t from_byte, to_byte, bytes;
+} ivf_cache_move;
+int ivf_cache_plan(float* hotness, const int64_t* offsets, int32_t nlist, size_t row_bytes,
+                   int64_t* resident_off, size_t* buffer_used, size_t buffer_bytes, float fraction,
+                   int32_t* evicted, int32_t* n_evicted, ivf_cache_move* moves, int32_t* n_moves);
+
+/*
  * The host part of the hybrid search on its own (Sec. 4.1 step 3: the clusters of q_out that were
  * not prefetched are searched by CPU threads).  Needs no index and no GPU.
  *   lists     host, cluster-major rows of `dtype`, list c = rows offsets[c] .. offsets[c+1]

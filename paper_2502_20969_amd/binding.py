@@ -25,7 +25,7 @@ EXPORTS = [
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
-    "ivf_schedule", "ivf_host_scan", "ivf_prefetch_plan", "ivf_strerror", "ivf_last_error",
+    "ivf_schedule", "ivf_host_scan", "ivf_prefetch_plan", "ivf_cache_plan", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -355,3 +355,30 @@ def ivf_prefetch_plan(ranked, offsets, row_bytes, budget_bytes, buffer_bytes, re
                                int(buffer_bytes), _ptr(resident_off), C.byref(used), _ptr(taken), C.byref(n_taken),
                                C.byref(st)))
     return taken[:n_taken.value], st, used.value
+
+
+class CacheMove(C.Structure):
+    _fields_ = [("cluster", C.c_int32), ("via_staging", C.c_int32), ("from_byte", C.c_uint64),
+                ("to_byte", C.c_uint64), ("bytes", C.c_uint64)]
+
+
+def ivf_cache_plan(hotness, offsets, row_bytes, resident_off, buffer_used, buffer_bytes, fraction):
+    """Eviction and consolidation plan of a cache round.  hotness (float32[nlist]) and resident_off
+    (int64[nlist]) are updated in place.  Returns (evicted clusters in order, list of moves as
+    (cluster, via_staging, from_byte, to_byte, bytes), buffer bytes in use afterwards)."""
+    assert hotness.dtype == np.float32 and hotness.flags["C_CONTIGUOUS"]
+    assert resident_off.dtype == np.int64 and resident_off.flags["C_CONTIGUOUS"]
+    off = _host(offsets, np.int64)
+    nlist = off.shape[0] - 1
+    assert hotness.shape[0] == nlist and resident_off.shape[0] == nlist
+    evicted = np.empty(nlist, dtype=np.int32)
+    moves = (CacheMove * nlist)()
+    n_ev, n_mv = C.c_int32(0), C.c_int32(0)
+    used = C.c_size_t(int(buffer_used))
+    L = load()
+    L.ivf_cache_plan.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p, C.c_size_t,
+                                 C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    _check(L.ivf_cache_plan(_ptr(hotness), _ptr(off), nlist, int(row_bytes), _ptr(resident_off), C.byref(used),
+                            int(buffer_bytes), float(fraction), _ptr(evicted), C.byref(n_ev), moves, C.byref(n_mv)))
+    mv = [(m.cluster, m.via_staging, m.from_byte, m.to_byte, m.bytes) for m in moves[:n_mv.value]]
+    return evicted[:n_ev.value], mv, used.value

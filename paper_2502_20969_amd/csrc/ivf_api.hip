@@ -1068,6 +1068,74 @@ extern "C" int ivf_cache_hotness(ivf_index* ix, float* hotness) {
     return IVF_OK;
 }
 
+// The host part of a cache round (Sec. 4.2 "Cache design"), after the hotness update.
+// Eviction: while the cached bytes exceed fraction x buffer, the cached cluster of lowest hotness
+// leaves (equal hotness: the larger index first); its hotness becomes -1.  Consolidation: the
+// survivors move to the front of the buffer in their current order.  A cluster only ever moves
+// towards lower addresses and never onto a later cluster's old place; it can overlap its own old
+// place, and then goes through a staging buffer (need_tmp: the largest such cluster).
+static void plan_cache_round(float* hot, const int64_t* off, int nlist, size_t rb, int64_t* res_off,
+                             size_t& buf_used, size_t buf_bytes, float fraction, std::vector<int32_t>& evicted,
+                             std::vector<ivf_cache_move>& moves, size_t& need_tmp, ivf_cache_stats& st) {
+    struct Item { float h; int32_t c; };
+    std::vector<Item> cached;
+    for (int c = 0; c < nlist; ++c)
+        if (res_off[c] >= 0) cached.push_back(Item{hot[c], (int32_t)c});
+    st.n_cached = (int32_t)cached.size();
+    st.bytes_cached = buf_used;
+    const uint64_t limit = (uint64_t)((double)fraction * (double)buf_bytes);
+    std::sort(cached.begin(), cached.end(), [](const Item& x, const Item& y) {
+        return x.h < y.h || (x.h == y.h && x.c > y.c);
+    });
+    uint64_t in_use = buf_used;
+    for (size_t i = 0; i < cached.size() && in_use > limit; ++i) {
+        const int c = cached[i].c;
+        in_use -= (uint64_t)(off[c + 1] - off[c]) * rb;
+        res_off[c] = -1;
+        hot[c] = -1.f;
+        st.n_evicted += 1;
+        evicted.push_back(c);
+    }
+    std::vector<std::pair<int64_t, int32_t>> order;
+    for (int c = 0; c < nlist; ++c)
+        if (res_off[c] >= 0) order.push_back({res_off[c], (int32_t)c});
+    std::sort(order.begin(), order.end());
+    need_tmp = 0;
+    uint64_t at = 0;
+    for (auto& oc : order) {
+        const int c = oc.second;
+        const uint64_t bytes = (uint64_t)(off[c + 1] - off[c]) * rb, old = (uint64_t)oc.first * rb;
+        if (old != at && bytes > 0) {
+            const bool overlap = old - at < bytes;
+            if (overlap) need_tmp = std::max<size_t>(need_tmp, bytes);
+            moves.push_back(ivf_cache_move{(int32_t)c, overlap ? 1 : 0, old, at, bytes});
+            st.bytes_moved += bytes;
+        }
+        res_off[c] = (int64_t)(at / rb);
+        at += bytes;
+    }
+    buf_used = at;
+}
+
+extern "C" int ivf_cache_plan(float* hotness, const int64_t* offsets, int32_t nlist, size_t row_bytes,
+                              int64_t* resident_off, size_t* buffer_used, size_t buffer_bytes, float fraction,
+                              int32_t* evicted, int32_t* n_evicted, ivf_cache_move* moves, int32_t* n_moves) {
+    if (!hotness || !offsets || !resident_off || !buffer_used || !evicted || !n_evicted || !moves || !n_moves)
+        return fail(IVF_EINVAL, "NULL argument");
+    if (nlist < 1 || row_bytes < 1) return fail(IVF_EINVAL, "nlist and row_bytes must be at least 1");
+    if (!(fraction >= 0.f && fraction <= 1.f)) return fail(IVF_EINVAL, "fraction must be in [0, 1]");
+    std::vector<int32_t> ev;
+    std::vector<ivf_cache_move> mv;
+    size_t need_tmp = 0;
+    ivf_cache_stats st{};
+    plan_cache_round(hotness, offsets, nlist, row_bytes, resident_off, *buffer_used, buffer_bytes, fraction, ev, mv, need_tmp, st);
+    std::copy(ev.begin(), ev.end(), evicted);
+    std::copy(mv.begin(), mv.end(), moves);
+    *n_evicted = (int32_t)ev.size();
+    *n_moves = (int32_t)mv.size();
+    return IVF_OK;
+}
+
 extern "C" int ivf_cache_end_round(ivf_index* ix, ivf_cache_stats* stats) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
     if (!ix->cache_on) return fail(IVF_ESTATE, "the cluster cache is not configured");
@@ -1084,44 +1152,14 @@ extern "C" int ivf_cache_end_round(ivf_index* ix, ivf_cache_stats* stats) {
     HIP_TRY(hipMemcpyAsync(hot.data(), ix->d_hot, (size_t)nlist * sizeof(float), hipMemcpyDeviceToHost, ix->cs));
     HIP_TRY(hipEventRecord(ix->ev_cache[1], ix->cs));
     HIP_TRY(hipStreamSynchronize(ix->cs));
-    // 2. eviction: coldest first (equal hotness: larger index first) until the cache fits its share
-    struct Item { float h; int32_t c; };
-    std::vector<Item> cached;
-    for (int c = 0; c < nlist; ++c)
-        if (ix->h_res_off[c] >= 0) cached.push_back(Item{hot[c], (int32_t)c});
-    st.n_cached = (int32_t)cached.size();
-    st.bytes_cached = ix->buf_used;
-    const uint64_t limit = (uint64_t)((double)ix->cache_fraction * (double)ix->buf_bytes);
-    std::sort(cached.begin(), cached.end(), [](const Item& x, const Item& y) {
-        return x.h < y.h || (x.h == y.h && x.c > y.c);
-    });
-    uint64_t in_use = ix->buf_used;
-    bool changed = false;
-    for (size_t i = 0; i < cached.size() && in_use > limit; ++i) {
-        const int c = cached[i].c;
-        in_use -= (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
-        ix->h_res_off[c] = -1;
-        hot[c] = -1.f;
-        st.n_evicted += 1;
-        changed = true;
-    }
-    // 3. consolidation: survivors move to the front of the buffer in their current order.  A
-    //    cluster only ever moves towards lower addresses and never onto a later cluster's old
-    //    place; it can overlap its own old place, and then goes through a staging buffer.
-    std::vector<std::pair<int64_t, int32_t>> order;
-    for (int c = 0; c < nlist; ++c)
-        if (ix->h_res_off[c] >= 0) order.push_back({ix->h_res_off[c], (int32_t)c});
-    std::sort(order.begin(), order.end());
+    // 2. eviction and 3. consolidation: planned on the host, then carried out by device copies
+    std::vector<int32_t> evicted;
+    std::vector<ivf_cache_move> moves;
     size_t need_tmp = 0;
-    {
-        uint64_t at = 0;
-        for (auto& oc : order) {
-            const int c = oc.second;
-            const uint64_t bytes = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb, old = (uint64_t)oc.first * rb;
-            if (old != at && old - at < bytes) need_tmp = std::max<size_t>(need_tmp, bytes);
-            at += bytes;
-        }
-    }
+    const std::vector<int64_t> before(ix->h_res_off);
+    plan_cache_round(hot.data(), ix->h_off.data(), nlist, rb, ix->h_res_off.data(), ix->buf_used, ix->buf_bytes,
+                     ix->cache_fraction, evicted, moves, need_tmp, st);
+    const bool changed = before != ix->h_res_off;        // evictions and moves both show in the table
     if (need_tmp > ix->move_tmp_bytes) {
         if (ix->d_move_tmp) HIP_TRY(hipFree(ix->d_move_tmp));
         ix->d_move_tmp = nullptr; ix->move_tmp_bytes = 0;
@@ -1129,26 +1167,16 @@ extern "C" int ivf_cache_end_round(ivf_index* ix, ivf_cache_stats* stats) {
         ix->move_tmp_bytes = need_tmp;
     }
     HIP_TRY(hipEventRecord(ix->ev_cache[2], ix->cs));
-    uint64_t at = 0;
-    for (auto& oc : order) {
-        const int c = oc.second;
-        const uint64_t bytes = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb, old = (uint64_t)oc.first * rb;
-        if (old != at && bytes > 0) {
-            char* dst = (char*)ix->d_buf + at;
-            const char* src = (const char*)ix->d_buf + old;
-            if (old - at >= bytes) {
-                HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, ix->cs));
-            } else {
-                HIP_TRY(hipMemcpyAsync(ix->d_move_tmp, src, bytes, hipMemcpyDeviceToDevice, ix->cs));
-                HIP_TRY(hipMemcpyAsync(dst, ix->d_move_tmp, bytes, hipMemcpyDeviceToDevice, ix->cs));
-            }
-            st.bytes_moved += bytes;
-            changed = true;
+    for (const ivf_cache_move& m : moves) {
+        char* dst = (char*)ix->d_buf + m.to_byte;
+        const char* src = (const char*)ix->d_buf + m.from_byte;
+        if (!m.via_staging) {
+            HIP_TRY(hipMemcpyAsync(dst, src, m.bytes, hipMemcpyDeviceToDevice, ix->cs));
+        } else {
+            HIP_TRY(hipMemcpyAsync(ix->d_move_tmp, src, m.bytes, hipMemcpyDeviceToDevice, ix->cs));
+            HIP_TRY(hipMemcpyAsync(dst, ix->d_move_tmp, m.bytes, hipMemcpyDeviceToDevice, ix->cs));
         }
-        ix->h_res_off[c] = (int64_t)(at / rb);
-        at += bytes;
     }
-    ix->buf_used = at;
     HIP_TRY(hipEventRecord(ix->ev_cache[3], ix->cs));
     if (changed) {
         memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)nlist * sizeof(int64_t));
