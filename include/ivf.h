@@ -166,7 +166,8 @@ int ivf_search(ivf_index* index, const float* q_out, int32_t nq, int32_t nprobe,
 /*
  * The same search with device-resident queries and outputs (all device pointers), enqueued
  * on compute_stream without waiting: outputs are complete once that stream has reached
- * this point (with a pipeline depth above 1: see ivf_set_pipeline_depth).  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
+ * this point (with a pipeline depth above 1: see ivf_set_pipeline_depth; searched list-major:
+ * see ivf_set_batch_mode, after ivf_synchronize()).  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
  * ivf_reserve() or an earlier search has sized the workspace for, else the call sizes it
  * itself, which synchronises the device.
  */
@@ -198,9 +199,13 @@ int ivf_synchronize(ivf_index* index);
  *   1  always query by query
  *   2  list-major whenever the index allows it (from 2 queries on)
  * The results are the same in every mode (the MFMA scores only filter rows; the ranking uses
- * fp64 re-scores with the fp32 query).  A list-major call synchronises compute_stream before
- * it returns, also through ivf_search_device.  With bytes_gpu of ivf_search_stats a
- * list-major call reports the bytes of the union of the selected clusters.
+ * fp64 re-scores with the fp32 query).  A list-major batch may leave a few queries to be
+ * searched again one by one (their candidate lists overflowed): ivf_search does that before it
+ * returns; ivf_search_device returns without waiting and the library finishes the batch when
+ * its stream is next needed or in ivf_synchronize(), so the outputs of a list-major
+ * ivf_search_device call are complete after ivf_synchronize() only, and q_dev, ids_dev and
+ * dists_dev must stay valid until then.  With bytes_gpu of ivf_search_stats a list-major call
+ * reports the bytes of the union of the selected clusters.
  */
 int ivf_set_batch_mode(ivf_index* index, int32_t mode);
 

@@ -152,7 +152,11 @@ struct ivf_index {
     ScanShape shape{0, 0, 0, 4};
     // Searches through ivf_search_device rotate over `lanes` (stream + workspace each) so that
     // independent queries overlap; lane 0 runs on compute_stream.  cs / cw: lane in use.
-    struct Lane { hipStream_t stream = nullptr; bool own = false; Workspace ws; };
+    // A list-major batch whose candidate-overflow flags have not been looked at yet: the queries
+    // that overflowed still have to be searched again one by one (settle_lane).
+    struct Pending { bool on = false; const float* q = nullptr; int nq = 0, nprobe = 0, k = 0;
+                     int64_t* ids = nullptr; float* dists = nullptr; };
+    struct Lane { hipStream_t stream = nullptr; bool own = false; Workspace ws; Pending pending; };
     std::vector<Lane> lanes;
     size_t next_lane = 0;
     hipStream_t cs = nullptr;
@@ -165,6 +169,9 @@ struct ivf_index {
     ivf_profile prof{};
     unsigned long long* d_prof_rows = nullptr;
 };
+
+static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
+                             int64_t* ids_dev, float* dists_dev);
 
 namespace {
 
@@ -209,7 +216,40 @@ void use_lane(ivf_index* ix, size_t i) {
 }
 
 // waits on the host for every lane other than lane 0, then selects lane 0
+// Finishes what lane i still owes: waits for its list-major batch and searches the queries whose
+// candidate lists overflowed again, one by one.  Leaves the lane idle.  The lane in use is kept.
+int settle_lane(ivf_index* ix, size_t i) {
+    ivf_index::Lane& l = ix->lanes[i];
+    if (!l.pending.on) return IVF_OK;
+    hipStream_t cs = ix->cs; Workspace* cw = ix->cw;
+    use_lane(ix, i);
+    l.pending.on = false;
+    const ivf_index::Pending pd = l.pending;
+    int r = IVF_OK;
+    hipError_t e = hipStreamSynchronize(l.stream);
+    if (e != hipSuccess) r = fail(IVF_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    const bool was_profiling = ix->profiling;
+    ix->profiling = false;
+    bool redone = false;
+    for (int qi = 0; qi < pd.nq && r == IVF_OK; ++qi)
+        if (l.ws.h_overflow[qi]) {
+            r = enqueue_per_query(ix, pd.q + (size_t)qi * ix->d, 1, pd.nprobe, pd.k, pd.ids + (size_t)qi * pd.k,
+                                  pd.dists + (size_t)qi * pd.k);
+            redone = true;
+        }
+    ix->profiling = was_profiling;
+    if (r == IVF_OK && redone) {
+        e = hipStreamSynchronize(l.stream);
+        if (e != hipSuccess) r = fail(IVF_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    }
+    ix->cs = cs; ix->cw = cw;
+    return r;
+}
+
 int settle_on_lane0(ivf_index* ix) {
+    int rc;
+    for (size_t i = 0; i < ix->lanes.size(); ++i)
+        if ((rc = settle_lane(ix, i))) return rc;
     for (size_t i = 1; i < ix->lanes.size(); ++i) HIP_TRY(hipStreamSynchronize(ix->lanes[i].stream));
     use_lane(ix, 0);
     return IVF_OK;
@@ -270,6 +310,10 @@ int check_query_args(const ivf_index* ix, const void* q, int32_t nq, int32_t npr
 
 // ---- profiling events ---------------------------------------------------------------------
 int drain_profile(ivf_index* ix) {
+    for (size_t i = 0; i < ix->lanes.size(); ++i) {
+        int rc = settle_lane(ix, i);
+        if (rc) return rc;
+    }
     if (ix->prof_used == 0) return IVF_OK;
     for (auto& l : ix->lanes) HIP_TRY(hipStreamSynchronize(l.stream));
     for (size_t i = 0; i < ix->prof_used; ++i) {
@@ -701,6 +745,10 @@ extern "C" int ivf_reserve(ivf_index* ix, int32_t nq, int32_t nprobe, int32_t k)
     if (nq < 1 || nprobe < 1 || k < 1) return fail(IVF_EINVAL, "nq, nprobe and k must be at least 1");
     if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
     for (size_t i = 0; i < ix->lanes.size(); ++i) {
+        int rc = settle_lane(ix, i);           // a workspace that grows is freed first
+        if (rc) return rc;
+    }
+    for (size_t i = 0; i < ix->lanes.size(); ++i) {
         use_lane(ix, i);
         int rc = ensure_workspace(ix, nq, std::min(nprobe, ix->nlist), k);
         if (rc) { use_lane(ix, 0); return rc; }
@@ -713,6 +761,10 @@ extern "C" int ivf_set_pipeline_depth(ivf_index* ix, int32_t depth) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
     if (depth < 1 || depth > 16) return fail(IVF_EINVAL, "pipeline depth must be in [1, 16]");
     if (ix->placement != IVF_PLACE_DEVICE) return fail(IVF_ESTATE, "pipelining needs a device-resident index");
+    for (size_t i = 0; i < ix->lanes.size(); ++i) {
+        int rc = settle_lane(ix, i);
+        if (rc) return rc;
+    }
     HIP_TRY(hipDeviceSynchronize());
     while ((int)ix->lanes.size() > depth) {
         auto& l = ix->lanes.back();
@@ -733,6 +785,10 @@ extern "C" int ivf_set_pipeline_depth(ivf_index* ix, int32_t depth) {
 
 extern "C" int ivf_synchronize(ivf_index* ix) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
+    for (size_t i = 0; i < ix->lanes.size(); ++i) {
+        int rc = settle_lane(ix, i);
+        if (rc) return rc;
+    }
     for (auto& l : ix->lanes) HIP_TRY(hipStreamSynchronize(l.stream));
     return IVF_OK;
 }
@@ -770,22 +826,17 @@ static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int npro
 
 // List-major batched search into device outputs.  Synchronises the stream to read the overflow
 // flags; a query whose candidate list overflowed is searched again on its own.
-static int run_batched(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
-                       int64_t* ids_dev, float* dists_dev) {
+static int run_batched(ivf_index* ix, size_t lane, const float* q_dev, int nq, int nprobe, int k,
+                       int64_t* ids_dev, float* dists_dev, bool defer) {
     int r;
     if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
     if ((r = ensure_batched_workspace(ix, nq, nprobe))) return r;
     if ((r = enqueue_batched(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev))) return r;
-    HIP_TRY(hipStreamSynchronize(ix->cs));
-    Workspace& w = *ix->cw;
-    const bool was_profiling = ix->profiling;
-    ix->profiling = false;
-    for (int qi = 0; qi < nq && r == IVF_OK; ++qi)
-        if (w.h_overflow[qi])
-            r = enqueue_per_query(ix, q_dev + (size_t)qi * ix->d, 1, nprobe, k, ids_dev + (size_t)qi * k, dists_dev + (size_t)qi * k);
-    ix->profiling = was_profiling;
-    if (r == IVF_OK) HIP_TRY(hipStreamSynchronize(ix->cs));
-    return r;
+    ivf_index::Pending& pd = ix->lanes[lane].pending;
+    pd.on = true; pd.q = q_dev; pd.nq = nq; pd.nprobe = nprobe; pd.k = k; pd.ids = ids_dev; pd.dists = dists_dev;
+    // the overflow flags are looked at when the lane is next needed (or at ivf_synchronize), so that
+    // the first kernels of the next batch, on another lane, run beside this batch's scan
+    return defer ? IVF_OK : settle_lane(ix, lane);
 }
 
 extern "C" int ivf_set_batch_mode(ivf_index* ix, int32_t mode) {
@@ -805,9 +856,11 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     if (ix->placement != IVF_PLACE_DEVICE)
         return fail(IVF_ESTATE, "ivf_search_device needs a device-resident index");
     nprobe = std::min(nprobe, ix->nlist);
-    use_lane(ix, ix->next_lane);
+    const size_t lane = ix->next_lane;
+    if ((rc = settle_lane(ix, lane))) return rc;
+    use_lane(ix, lane);
     ix->next_lane = (ix->next_lane + 1) % ix->lanes.size();
-    if (batched_eligible(ix, nq)) rc = run_batched(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev);
+    if (batched_eligible(ix, nq)) rc = run_batched(ix, lane, q_dev, nq, nprobe, k, ids_dev, dists_dev, true);
     else rc = enqueue_per_query(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev);
     use_lane(ix, 0);
     return rc;
@@ -834,7 +887,7 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
     if ((rc = stage_queries(ix, q_out, nq))) return rc;
     if (batched_eligible(ix, nq)) {
         // list-major batched search: every selected cluster is read once per group of 32 queries
-        if ((rc = run_batched(ix, w.d_q, nq, nprobe, k, w.d_out_ids, w.d_out_dists))) return rc;
+        if ((rc = run_batched(ix, 0, w.d_q, nq, nprobe, k, w.d_out_ids, w.d_out_dists, false))) return rc;
         HIP_TRY(hipMemcpy(ids, w.d_out_ids, (size_t)nq * k * sizeof(int64_t), hipMemcpyDeviceToHost));
         HIP_TRY(hipMemcpy(dists, w.d_out_dists, (size_t)nq * k * sizeof(float), hipMemcpyDeviceToHost));
         if (stats) {

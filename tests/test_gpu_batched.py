@@ -83,6 +83,43 @@ def test_candidate_overflow_falls_back(streams):
     index.close()
 
 
+@pytest.mark.parametrize("depth", [1, 2, 3])
+def test_batches_in_flight_are_finished_by_synchronize(streams, depth):
+    """ivf_search_device does not wait for a list-major batch: the queries whose candidate lists
+    overflowed are searched again when the batch's stream is next needed or in ivf_synchronize.
+    Six batches in a row over `depth` streams, every second one on identical rows in cluster 0
+    (all of them overflow), each with its own outputs: all equal the oracle afterwards."""
+    n, d, nlist = 24000, 64, 6
+    rng = np.random.default_rng(11)
+    rows_np = rng.standard_normal((n, d)).astype(np.float16)
+    rows_np[:8000] = np.float16(0.125)                         # cluster 0 and 1: identical rows
+    off = np.arange(0, n + 1, 4000, dtype=np.int64)
+    cent = rng.standard_normal((nlist, d)).astype(np.float32)
+    cent[0] = 1.0; cent[1] = 0.9                               # positive queries select them first
+    rows = torch.from_numpy(rows_np).cuda()
+    index = P.ivf_adopt_layout(rows, "f16", off, cent, metric=P.IVF_IP, compute_stream=streams[0], copy_stream=streams[1])
+    index.ivf_set_batch_mode(2)
+    index.ivf_set_pipeline_depth(depth)
+    nq, k, nprobe = 6, 5, 2
+    qs, outs = [], []
+    for j in range(6):
+        q = rng.standard_normal((nq, d)).astype(np.float32)
+        if j % 2 == 0:
+            q = np.abs(q)                                      # nearest clusters: the two of identical rows
+        qs.append(torch.from_numpy(q).cuda())
+        outs.append((torch.empty(nq, k, dtype=torch.int64, device="cuda"), torch.empty(nq, k, device="cuda")))
+    torch.cuda.synchronize()
+    for j in range(6):
+        index.ivf_search_device(qs[j], nprobe, k, outs[j][0], outs[j][1])
+    index.ivf_synchronize()
+    for j in range(6):
+        gi, gd = outs[j][0].cpu().numpy(), outs[j][1].cpu().numpy()
+        q = qs[j].cpu().numpy()
+        for b in range(nq):
+            assert check_topk(gi[b], gd[b], rows_np, O.F16, off, None, cent, q[b], nprobe, k, O.IP) == 0, f"batch {j} query {b}"
+    index.close()
+
+
 @pytest.mark.parametrize("dtype,d,nq", [("f16", 128, 256), ("bf16", 256, 200), ("f16", 768, 32), ("bf16", 64, 77)])
 def test_list_major_finds_every_row_by_its_own_query(streams, dtype, d, nq):
     """Coverage of the batched scan: with every list selected, each stored row is the nearest
