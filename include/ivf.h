@@ -182,8 +182,9 @@ int ivf_reserve(ivf_index* index, int32_t nq, int32_t nprobe, int32_t k);
  * merge run on a few compute units while another query's scan streams its lists).  With depth
  * n > 1, successive ivf_search_device calls rotate over n internal streams (the first is
  * compute_stream), each with its own workspace; inputs must be complete when the call is made,
- * and outputs are complete after ivf_synchronize().  Depth 1 (the default) keeps everything on
- * compute_stream.  Changing the depth synchronises the device.  IVF_PLACE_DEVICE only; depth
+ * and outputs are complete after ivf_synchronize().  List-major batches overlap in the same way
+ * (the kernels that prepare one batch run beside the scan of the one before).  Depth 1 (the
+ * default) keeps everything on compute_stream.  Changing the depth synchronises the device.  IVF_PLACE_DEVICE only; depth
  * in [1, 16].
  */
 int ivf_set_pipeline_depth(ivf_index* index, int32_t depth);
