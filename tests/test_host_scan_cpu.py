@@ -69,3 +69,25 @@ def test_host_scan_rejects_bad_arguments():
     with pytest.raises(P.binding.IvfError) as e:
         P.ivf_host_scan(rows, "f32", off, q, np.array([0], dtype=np.int32), P.IVF_MAX_K + 1)
     assert e.value.status == -5
+
+
+def test_host_scan_of_the_hand_worked_miss_list():
+    """Hand-worked fixture (tests/golden/handworked_ivf.json): with an unlimited budget q_out's
+    cluster 1 is the miss; its rows are ids 2 and 3 with inner products 0.25 and 0.3125, squared
+    distances 0.8125 and 0.3125 (exact binary fractions)."""
+    import json
+    import os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "handworked_ivf.json")))
+    rows, ids, off = [], [], [0]
+    for c in range(4):
+        rows += g["lists"][str(c)]["rows"]
+        ids += g["lists"][str(c)]["ids"]
+        off.append(len(rows))
+    rows = np.array(rows, dtype=np.float32)
+    miss = np.array(g["lookahead_ip_fp32"]["budget_inf"]["miss"], dtype=np.int32)
+    for metric, key in ((P.IVF_IP, "ip"), (P.IVF_L2, "l2")):
+        gi, gs = P.ivf_host_scan(rows, "f32", np.array(off, dtype=np.int64), np.array(g["q_out"], dtype=np.float32),
+                                 miss, 3, ids=np.array(ids, dtype=np.int64), metric=metric, threads=2)
+        got = dict(zip(gi.tolist(), gs.tolist()))
+        want = {i: g[key]["row_scores_q_out"][str(i)] for i in (2, 3)}
+        assert got == want
