@@ -1,6 +1,7 @@
 """Builds libivf.so (HIP kernels + C-ABI) for gfx950 with hipcc, in-tree."""
 import os
 import subprocess
+import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -13,8 +14,11 @@ HOST_SOURCES = ["host_scan.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result"]
-# packed-fp32 instructions are switched off for all device code
+# packed-fp32 instructions are switched off for all device code.  The driver cannot forward
+# -Xclang through -Xarch_device, so the host pass sees the feature too and says it does not know
+# it; that one line is dropped from the compiler's output below.
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+HOST_PASS_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target"
 HOST_SIMD = ["-mavx2", "-mfma", "-mf16c"]
 
 
@@ -25,7 +29,12 @@ def _compile(src):
         cmd = [HIPCC, *COMMON, *DEVICE, "-c", path, "-o", obj]
     else:
         cmd = [HIPCC, *COMMON, *HOST_SIMD, "-x", "c++", "-c", path, "-o", obj]
-    subprocess.run(cmd, check=True)
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    noise = [l for l in r.stderr.splitlines() if HOST_PASS_NOTE not in l]
+    if noise:
+        print("\n".join(noise), file=sys.stderr)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
     return obj
 
 

@@ -20,14 +20,6 @@ __device__ __forceinline__ int wave_id() {
     return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform: kept in an SGPR
 }
 
-// Development aid (off in the product build): timestamps of kernel phases, 10 ns ticks.
-#ifdef IVF_TRACE
-__device__ unsigned long long g_trace[64];
-#define IVF_TRACE_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) g_trace[i] = wall_clock64(); } while (0)
-#else
-#define IVF_TRACE_MARK(i) do { } while (0)
-#endif
-
 // ---- cross-lane sums ----------------------------------------------------------------------
 // DPP controls (GFX9): quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E,
 // row_half_mirror = 0x141, row_mirror = 0x140.  Applied in this order to a value each lane

@@ -235,7 +235,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
     const double* sc = a.scores + (size_t)qi * a.nlist;
     const uint32_t nprobe = a.nprobe;
     const size_t sort_bytes = in_lds ? (size_t)pad * 12 : 0;
-    IVF_TRACE_MARK(10);
     uint32_t* idx;
     if (in_lds && nprobe <= 64 && a.nlist <= kSelectWaveSortMax) {
         // Few clusters wanted from a small index.  Each score is cut down to a packed candidate:
@@ -312,7 +311,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
         select_sorted(a, sc, keys, idx, pad, hist, sh);
     }
 
-    IVF_TRACE_MARK(11);
     // slot tables: per selected cluster its placement and its rows
     const int64_t* off = a.off;
     int64_t* s_base = a.slots.base + (size_t)qi * nprobe;
@@ -395,7 +393,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
         __syncthreads();
     }
 
-    IVF_TRACE_MARK(12);
     // workgroup shares: rows split evenly, each share starting inside some slot
     const uint32_t R = carry;
     const uint32_t per = R / (uint32_t)a.grid, extra = R % (uint32_t)a.grid;
@@ -420,7 +417,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
         ds.slot_base = s_base[slot];
         a.desc[(size_t)qi * a.grid + b] = ds;
     }
-    IVF_TRACE_MARK(13);
 }
 
 static uint32_t next_pow2(uint32_t v) { uint32_t p = 1; while (p < v) p <<= 1; return p; }
@@ -632,7 +628,6 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     const int lane = lane_id();
     const int sub = lane % LPR, rsel = lane / LPR;
     const int qi = blockIdx.y;
-    IVF_TRACE_MARK(30);
     const ScanLds lds = scan_lds(smem, p.kprime);
     if (threadIdx.x < 2) lds.ctl[threadIdx.x] = 0;
     const size_t row_bytes = (size_t)p.d * T::kBytes;
@@ -707,7 +702,6 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
         }
     };
 
-    IVF_TRACE_MARK(31);
     uint4 va[U][SEG], vb[U][SEG];
     uint32_t ta = 0, tb = 0;
     Batch ba = next_batch(cur, p, qi, RPB, row_bytes, tab);
@@ -721,11 +715,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
         if (ba.nr) issue(ba, va, ta);
         consume(bb, vb, tb);
     }
-    IVF_TRACE_MARK(32);
     __syncthreads();          // orders the zeroing of lds.ctl before its use
-    IVF_TRACE_MARK(33);
     finish_workgroup<KL>(top, p, lds, qi);
-    IVF_TRACE_MARK(34);
 }
 
 // Fallback for any d and any row alignment: element-wise loads, query in LDS, 4 rows per batch.
@@ -986,7 +977,6 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     const Cand* part = a.part + (size_t)qi * n;
     const uint32_t kp = a.kprime;
 
-    IVF_TRACE_MARK(20);
     // 1. the kprime best fp32 candidates
     if (fast) {
         Cand* pool = (Cand*)m_dyn;
@@ -995,7 +985,6 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
         gather_radix(a, part, L);
     }
     const uint32_t m = min(L.sh[4], (uint32_t)kMaxKPrime);
-    IVF_TRACE_MARK(23);
 
     // 2. fp64 re-score: a group of kRescoreLanes lanes per candidate, nt / kRescoreLanes
     //    candidates at once.  The order of operations is fixed (see rescore_partial), so a row has
@@ -1058,7 +1047,6 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
         }
     }
     __syncthreads();
-    IVF_TRACE_MARK(24);
     // 4. rank by counting; nearest first, ties by smaller id
     const uint32_t tot = m + nh;
     const int k = a.k;
@@ -1097,7 +1085,6 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
             __hip_atomic_store(a.done, a.done_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
-    IVF_TRACE_MARK(25);
 }
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
@@ -1193,11 +1180,5 @@ hipError_t launch_cache_round(float* hot, uint32_t* used, int nlist, float decay
     hipLaunchKernelGGL(cache_round_kernel, dim3((nlist + 255) / 256), dim3(256), 0, s, hot, used, nlist, decay, h_inc);
     return hipGetLastError();
 }
-
-#ifdef IVF_TRACE
-extern "C" int ivf_debug_trace(unsigned long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dev::g_trace), sizeof(unsigned long long) * 64);
-}
-#endif
 
 }  // namespace ivf
