@@ -178,6 +178,24 @@ int ivf_search_device(ivf_index* index, const float* q_dev, int32_t nq, int32_t 
 int ivf_reserve(ivf_index* index, int32_t nq, int32_t nprobe, int32_t k);
 
 /*
+ * ivf_search_device for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as a
+ * query-by-query ivf_search_device, enqueued on compute_stream, but the workspace (coarse scores,
+ * selected clusters and their tables, the scan workgroups' candidate lists) lives in one fixed
+ * device array of IVF_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it runs on until
+ * the process ends.  The call allocates and frees nothing, on the host side of HIP or on the device.
+ *   - A search whose workspace does not fit (roughly nq x (8 nlist + 8 grid k' + 32 nprobe) bytes,
+ *     grid <= 2 x compute units, k' = k + max(8, k / 8)) is refused with IVF_ELIMIT and nothing is enqueued.
+ *   - Always query by query (the batch mode and the pipeline depth are ignored).  IVF_PLACE_DEVICE only.
+ *   - Every call on a GPU shares that GPU's array, also across indexes: calls whose kernels could
+ *     overlap on one GPU (other streams, other threads) race.  Calls on one compute_stream are
+ *     ordered by the stream.  IVF_ESTATE while a list-major ivf_search_device batch is unfinished.
+ */
+#define IVF_NOALLOC_SCRATCH_BYTES (8u << 20)
+int ivf_search_device_noalloc(ivf_index* index, const float* q_dev, int32_t nq, int32_t nprobe,
+                              int32_t k, int64_t* ids_dev, float* dists_dev);
+
+/*
  * Overlap of independent searches (batch-1 serving: one query's coarse scoring, selection and
  * merge run on a few compute units while another query's scan streams its lists).  With depth
  * n > 1, successive ivf_search_device calls rotate over n internal streams (the first is

@@ -21,7 +21,7 @@ DTYPE_CODE = {"f32": IVF_F32, "f16": IVF_F16, "bf16": IVF_BF16}
 
 EXPORTS = [
     "ivf_build_layout", "ivf_adopt_layout", "ivf_free", "ivf_prefetch", "ivf_prefetch_wait",
-    "ivf_search", "ivf_search_device", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
+    "ivf_search", "ivf_search_device", "ivf_search_device_noalloc", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
     "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
@@ -78,6 +78,7 @@ def load():
     L.ivf_prefetch_wait.argtypes = [vp, C.POINTER(C.c_float)]
     L.ivf_search.argtypes = [vp, vp, i32, i32, i32, vp, vp, C.POINTER(SearchStats)]
     L.ivf_search_device.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    L.ivf_search_device_noalloc.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     L.ivf_reserve.argtypes = [vp, i32, i32, i32]
     L.ivf_coarse_scores.argtypes = [vp, vp, i32, vp]
     L.ivf_probe.argtypes = [vp, vp, i32, i32, vp]
@@ -199,6 +200,14 @@ class Index:
         nq = q_dev.numel() // self.d
         assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
         _check(load().ivf_search_device(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
+
+    def ivf_search_device_noalloc(self, q_dev, nprobe, k, ids_dev, dists_dev):
+        """ivf_search_device on the library's fixed scratch area: allocates nothing."""
+        assert q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda
+        assert q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()
+        nq = q_dev.numel() // self.d
+        assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
+        _check(load().ivf_search_device_noalloc(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
 
     def ivf_reserve(self, nq, nprobe, k):
         _check(load().ivf_reserve(self._h, nq, nprobe, k))

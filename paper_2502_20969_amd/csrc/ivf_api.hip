@@ -173,6 +173,28 @@ struct ivf_index {
 static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
                              int64_t* ids_dev, float* dists_dev);
 
+// ---- workspace for callers that cannot allocate (ivf_search_device_noalloc) -----------------------
+// One fixed array per GPU, held until the process ends.  In host code the array's name is only a
+// handle: its device address is looked up once per device (scratch_for_device) and that pointer
+// is what is carved into buffers and handed to the kernels.
+constexpr size_t kScratchBytes = IVF_NOALLOC_SCRATCH_BYTES;
+constexpr int kScratchMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static unsigned char* g_scratch_ptr[kScratchMaxDevices];
+
+// device address of `scratch` on the current device (which must be `device`); looked up on first use
+static int scratch_for_device(int device, unsigned char** out) {
+    if (device < 0 || device >= kScratchMaxDevices) return fail(IVF_ELIMIT, "device %d has no scratch slot", device);
+    if (!g_scratch_ptr[device]) {
+        unsigned char* p = nullptr;
+        hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(IVF_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return IVF_OK;
+}
+
 namespace {
 
 // releases without a status: used on teardown and on error paths, where nothing can be done about a failure
@@ -522,6 +544,12 @@ int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* cen
     HIP_TRY(hipMemset(ix->d_prof_rows, 0, sizeof(unsigned long long)));
     HIP_TRY(hipDeviceSynchronize());
     ix->shape = pick_scan_shape(d, dtype);
+    // looked up here so that the entry point that must not allocate does no first-use work
+    unsigned char* sp = nullptr;
+    int rc = scratch_for_device(ix->device, &sp);
+    if (rc) return rc;
+    for (int cls = 0; cls < 2; ++cls)
+        ix->resident_grid[cls] = scan_resident_grid(ix->shape, dtype, metric, cls ? 128 : 64, d, ix->n_cu);
     return IVF_OK;
 }
 
@@ -863,6 +891,68 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     if (batched_eligible(ix, nq)) rc = run_batched(ix, lane, q_dev, nq, nprobe, k, ids_dev, dists_dev, true);
     else rc = enqueue_per_query(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev);
     use_lane(ix, 0);
+    return rc;
+}
+
+// Carves the device buffers of a query-by-query search out of `base` (256-byte aligned pieces) and
+// returns the bytes needed; with base == nullptr only the size is computed.
+static size_t carve_search_buffers(Workspace& w, unsigned char* base, const ivf_index* ix, int nq, int nprobe,
+                                   int kprime, int grid, uint32_t pad) {
+    size_t at = 0;
+    auto take = [&](size_t bytes) -> void* {
+        void* p = base ? base + at : nullptr;
+        at += (bytes + 255) & ~(size_t)255;
+        return p;
+    };
+    const size_t nqz = nq, npz = nprobe, gz = grid;
+    w.d_scores = (double*)take(nqz * ix->nlist * sizeof(double));
+    w.d_probe = (int32_t*)take(nqz * npz * sizeof(int32_t));
+    w.slots.base = (int64_t*)take(nqz * npz * sizeof(int64_t));
+    w.slots.grow = (uint32_t*)take(nqz * npz * sizeof(uint32_t));
+    w.slots.nrows = (uint32_t*)take(nqz * npz * sizeof(uint32_t));
+    w.slots.rprefix = (uint32_t*)take(nqz * (npz + 1) * sizeof(uint32_t));
+    w.d_desc = (WgDesc*)take(nqz * gz * sizeof(WgDesc));
+    if (pad > (uint32_t)kSortLdsCap) {
+        w.d_sort_keys = (uint64_t*)take(nqz * pad * sizeof(uint64_t));
+        w.d_sort_idx = (uint32_t*)take(nqz * pad * sizeof(uint32_t));
+    }
+    w.d_part = (uint64_t*)take(nqz * gz * kprime * sizeof(uint64_t));
+    w.d_heads = (uint64_t*)take(nqz * gz * sizeof(uint64_t));
+    return at;
+}
+
+extern "C" int ivf_search_device_noalloc(ivf_index* ix, const float* q_dev, int32_t nq, int32_t nprobe,
+                                         int32_t k, int64_t* ids_dev, float* dists_dev) {
+    int rc = check_query_args(ix, q_dev, nq, nprobe);
+    if (rc) return rc;
+    if (!ids_dev || !dists_dev) return fail(IVF_EINVAL, "output pointer is NULL");
+    if (k < 1) return fail(IVF_EINVAL, "k must be at least 1 (got %d)", k);
+    if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
+    if (ix->placement != IVF_PLACE_DEVICE)
+        return fail(IVF_ESTATE, "ivf_search_device_noalloc needs a device-resident index");
+    for (auto& l : ix->lanes)
+        if (l.pending.on) return fail(IVF_ESTATE, "a list-major batch is unfinished: call ivf_synchronize() first");
+    nprobe = std::min(nprobe, ix->nlist);
+    const int kprime = kprime_for(k);
+    const int grid = scan_grid_for(ix, nprobe, kprime);
+    const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
+    Workspace w{};
+    const size_t need = carve_search_buffers(w, nullptr, ix, nq, nprobe, kprime, grid, pad);
+    if (need > kScratchBytes)
+        return fail(IVF_ELIMIT, "this search needs %zu bytes of workspace, the fixed scratch area holds %zu "
+                    "(nq %d, nprobe %d, k %d): use ivf_search_device", need, kScratchBytes, nq, nprobe, k);
+    unsigned char* sp = nullptr;
+    if ((rc = scratch_for_device(ix->device, &sp))) return rc;
+    carve_search_buffers(w, sp, ix, nq, nprobe, kprime, grid, pad);
+    w.nq = nq; w.nprobe = nprobe; w.k = k; w.kprime = kprime; w.pad = pad; w.grid = grid;
+    // the kernels of one call only ever read what an earlier kernel of the same call wrote, so
+    // nothing in the area has to start at zero
+    hipStream_t cs = ix->cs; Workspace* cw = ix->cw;
+    ix->cs = ix->compute; ix->cw = &w;
+    rc = enqueue_probe(ix, q_dev, nq, nprobe, grid, true, true);
+    if (!rc) rc = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid);
+    if (!rc) rc = enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+    ix->cs = cs; ix->cw = cw;
     return rc;
 }
 
