@@ -21,4 +21,9 @@ from .generators import (  # noqa: F401
     zipf_sizes,
     config1_tiny,
     config2_single_query,
+    config3_mid_fp16,
+    config4_lookahead,
+    config5_large_bf16,
+    paper_shape_fp32,
+    pinned_rows,
 )

@@ -195,3 +195,65 @@ def shared_batch_queries(ds, nq, n_groups, seed, noise=0.5):
     base = _normalize(ds.centres[pick][which])
     q = _normalize(base + noise * (d ** -0.5) * torch.randn(nq, d, generator=g, device=device))
     return q.contiguous()
+
+
+def config3_mid_fp16(device="cuda", scale=1.0, groups=24, n_sets=8, batch=32, d=768):
+    """configs[2]: 10,000,000 x 768 fp16 rows generated cluster-major, nlist 4096 with Zipf(1.1)
+    sizes; batches of 32 queries drawn around `groups` mixture centres (24: measured sharing of the
+    probed clusters 0.40 at nprobe 128).  Searched with inner product, nprobe 128, k 10.
+    Returns (datastore, list of n_sets query batches)."""
+    n = int(10_000_000 * scale)
+    sizes = zipf_sizes(n, 4096, 1.1, 20975)
+    ds = cluster_major_datastore(sizes, d, 0.3, 20976, dtype="f16", device=device, chunk=1 << 20)
+    return ds, [shared_batch_queries(ds, batch, groups, 20980 + i) for i in range(n_sets)]
+
+
+def config5_large_bf16(device="cuda", scale=1.0, n_sets=8, batch=256, d=1024, groups=None):
+    """configs[4]: 30,000,000 x 1024 bf16 rows generated cluster-major, nlist 8192 with Zipf(1.2)
+    sizes; batches of 256 queries from 256 distinct mixture components.  Searched with inner
+    product, nprobe 512, k 100.  Returns (datastore, list of n_sets query batches)."""
+    n = int(30_000_000 * scale)
+    sizes = zipf_sizes(n, 8192, 1.2, 20977)
+    ds = cluster_major_datastore(sizes, d, 0.3, 20978, dtype="bf16", device=device, chunk=1 << 20)
+    return ds, [shared_batch_queries(ds, batch, groups or batch, 20980 + i) for i in range(n_sets)]
+
+
+def config4_lookahead(pinned_out, nlist, pairs, device="cuda"):
+    """configs[3]: fp16 rows generated on `device` chunk by chunk into `pinned_out` (a pinned host
+    tensor [n, 768]; 60,000,000 rows at full size), nlist near-uniform lists (16384 at full size),
+    `pairs` query pairs with alpha 0.3.  Searched with inner product, nprobe 256 at full size, k 10.
+    Returns (datastore, q_in, q_out); the queries are host tensors."""
+    n, d = pinned_out.shape
+    sizes = zipf_sizes(n, nlist, 0.1, 20972)
+    ds = cluster_major_datastore(sizes, d, 0.3, 20973, dtype="f16", device=device, out=pinned_out, chunk=1 << 20)
+    q_in, q_out = query_pairs(pinned_out, pairs, 0.3, 20974)
+    return ds, q_in, q_out
+
+
+def paper_shape_fp32(device="cuda", scale=1.0, nq=64):
+    """The shape the paper evaluates on (Sec. 5 set-up): 21,000,000 x 768 fp32 rows, 4096 clusters,
+    here generated cluster-major with Zipf(1.1) sizes; nq queries = perturbed stored rows.
+    Searched with nprobe 64 .. 1024, k 3, batches of 1 to 8.  Returns (datastore, q_out)."""
+    n = int(21_000_000 * scale)
+    sizes = zipf_sizes(n, 4096, 1.1, 20985)
+    ds = cluster_major_datastore(sizes, 768, 0.3, 20986, dtype="f32", device=device, chunk=1 << 20)
+    pick = torch.randint(0, n, (4096,), generator=torch.Generator().manual_seed(20987)).to(device)
+    _, q_out = query_pairs(ds.rows[pick], nq, 0.3, 20988)
+    return ds, q_out
+
+
+def pinned_rows(n_full, d, dtype, min_scale=0.01):
+    """A pinned host tensor [n, d] for a host-placed datastore of n_full rows; when the host
+    refuses to pin that much, the row count is halved until it does.  Returns (tensor, scale,
+    note) with n = n_full * scale and note = the refusal message of the first failed attempt."""
+    scale, note = 1.0, None
+    while True:
+        n = int(n_full * scale)
+        try:
+            return torch.empty((n, d), dtype=TORCH_DTYPE[dtype], pin_memory=True), scale, note
+        except RuntimeError as e:
+            if note is None:
+                note = str(e).splitlines()[0]
+            scale /= 2
+            if scale < min_scale:
+                raise
