@@ -61,7 +61,8 @@ constexpr int kMaxD = 4096;             // coarse kernel stages 4 queries x d fl
 constexpr int kProfileRing = 2048;      // searches whose events are kept before a drain
 
 struct Workspace {
-    int nq = 0, nprobe = 0, k = 0, kprime = 0, grid = 0;
+    int nq = 0, nprobe = 0, k = 0, kprime = 0;
+    size_t wg_cap = 0;               // scan workgroups (all queries of a call together) the tables below hold
     uint32_t pad = 0;
     float* d_q = nullptr;
     double* d_scores = nullptr;
@@ -70,8 +71,8 @@ struct Workspace {
     uint64_t* d_sort_keys = nullptr;
     uint32_t* d_sort_idx = nullptr;
     WgDesc* d_desc = nullptr;
-    uint64_t* d_part = nullptr;      // packed candidates of the scan workgroups
-    uint64_t* d_heads = nullptr;     // their first entries, densely
+    uint64_t* d_part = nullptr;      // packed candidates: one list per scan wavefront
+    uint64_t* d_heads = nullptr;     // the lists' best entries, densely
     int64_t* d_out_ids = nullptr;
     float* d_out_dists = nullptr;
     // pinned host staging
@@ -216,10 +217,11 @@ void free_workspace(Workspace& w) {
     w = Workspace{};
 }
 
-// Number of scan workgroups for a search of `nprobe` clusters with `kprime` candidates: all of
-// them must be resident at once (the rows are split evenly and statically), and there is no
-// point in more wavefronts than the largest possible scan has batches.
-int scan_grid_for(ivf_index* ix, int nprobe, int kprime) {
+// Number of scan workgroups per query for a call of `nq` searches of `nprobe` clusters with
+// `kprime` candidates.  One query: as many as are resident at once (the rows are split statically),
+// and no more wavefronts than the largest possible scan has batches.  Several queries share the
+// GPU: together they get about four rounds of resident workgroups, at least one per query.
+int scan_grid_for(ivf_index* ix, int nprobe, int kprime, int nq) {
     const int cls = kprime > 64 ? 1 : 0;
     if (ix->resident_grid[cls] == 0)
         ix->resident_grid[cls] = scan_resident_grid(ix->shape, ix->dtype, ix->metric, cls ? 128 : 64, ix->d, ix->n_cu);
@@ -228,9 +230,13 @@ int scan_grid_for(ivf_index* ix, int nprobe, int kprime) {
     uint64_t g = (batches + kScanWaves - 1) / kScanWaves;
     uint64_t cap = (uint64_t)ix->resident_grid[cls];
     if (g > cap) g = cap;
+    const uint64_t shared = (4 * cap + (uint64_t)nq - 1) / (uint64_t)nq;
+    if (g > shared) g = shared;
     if (g < 1) g = 1;
     return (int)g;
 }
+// scan workgroups of all queries of a call together: an upper bound of nq * scan_grid_for(.., nq') for nq' <= nq
+size_t scan_workgroup_bound(const ivf_index* ix, int nq) { return (size_t)4 * ix->n_cu * kScanMaxWgPerCu + (size_t)nq; }
 
 void use_lane(ivf_index* ix, size_t i) {
     ix->cs = ix->lanes[i].stream;
@@ -281,7 +287,6 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     Workspace& w = *ix->cw;
     const int kprime = kprime_for(k);
     const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
-    const int grid_cap = ix->n_cu * kScanMaxWgPerCu;
     if (nq <= w.nq && nprobe <= w.nprobe && k <= w.k && pad <= w.pad) return IVF_OK;
     const int nq2 = std::max(nq, w.nq), np2 = std::max(nprobe, w.nprobe), k2 = std::max(k, w.k);
     const uint32_t pad2 = std::max(pad, w.pad);
@@ -296,13 +301,14 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     HIP_TRY(hipMalloc(&w.slots.grow, nqz * npz * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&w.slots.nrows, nqz * npz * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&w.slots.rprefix, nqz * (npz + 1) * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&w.d_desc, nqz * grid_cap * sizeof(WgDesc)));
+    const size_t wgs = scan_workgroup_bound(ix, nq2);
+    HIP_TRY(hipMalloc(&w.d_desc, wgs * sizeof(WgDesc)));
     if (pad2 > (uint32_t)kSortLdsCap) {
         HIP_TRY(hipMalloc(&w.d_sort_keys, nqz * pad2 * sizeof(uint64_t)));
         HIP_TRY(hipMalloc(&w.d_sort_idx, nqz * pad2 * sizeof(uint32_t)));
     }
-    HIP_TRY(hipMalloc(&w.d_part, nqz * grid_cap * kp2 * sizeof(uint64_t)));
-    HIP_TRY(hipMalloc(&w.d_heads, nqz * grid_cap * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&w.d_part, wgs * kScanWaves * cand_slots(kp2) * sizeof(uint64_t)));
+    HIP_TRY(hipMalloc(&w.d_heads, wgs * kScanWaves * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&w.d_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipMalloc(&w.d_out_dists, nqz * k2 * sizeof(float)));
     HIP_TRY(hipHostMalloc(&w.h_q, nqz * ix->d * sizeof(float)));
@@ -318,7 +324,7 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     HIP_TRY(hipHostMalloc(&w.h_cand, nqz * kp2 * sizeof(HostCand)));
     HIP_TRY(hipHostMalloc(&w.h_cand_count, nqz * sizeof(int32_t)));
     memset(w.h_cand_count, 0, nqz * sizeof(int32_t));
-    w.nq = nq2; w.nprobe = np2; w.k = k2; w.kprime = kp2; w.pad = pad2; w.grid = grid_cap;
+    w.nq = nq2; w.nprobe = np2; w.k = k2; w.kprime = kp2; w.pad = pad2; w.wg_cap = wgs;
     return IVF_OK;
 }
 
@@ -386,8 +392,9 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
                   bool is_search = false) {
     Workspace& w = *ix->cw;
     int rc;
-    // the per-workgroup tables of the workspace were sized for w.grid workgroups and w.nq queries
-    if (grid > w.grid || nq > w.nq) return fail(IVF_ESTATE, "workspace holds %d scan workgroups x %d queries, asked for %d x %d", w.grid, w.nq, grid, nq);
+    // the per-workgroup tables of the workspace were sized for w.wg_cap workgroups and w.nq queries
+    if ((size_t)grid * nq > w.wg_cap || nq > w.nq)
+        return fail(IVF_ESTATE, "workspace holds %zu scan workgroups and %d queries, asked for %d x %d", w.wg_cap, w.nq, grid, nq);
     hipEvent_t e0, e1;
     if ((rc = prof_events(ix, 0, &e0, &e1))) return rc;
     CoarseArgs ca{ix->d_centroids, q_dev, w.d_scores, ix->nlist, ix->d, nq, ix->metric};
@@ -430,7 +437,7 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     ma.host_count = with_host ? w.h_cand_count : nullptr;
     ma.out_ids = out_ids; ma.out_dists = out_dists;
     ma.d = ix->d; ma.dtype = ix->dtype; ma.metric = ix->metric; ma.nprobe = nprobe; ma.nq = nq;
-    ma.k = k; ma.kprime = kprime; ma.nparts = grid;
+    ma.k = k; ma.kprime = kprime; ma.nparts = grid * kScanWaves; ma.list_len = cand_slots(kprime);
     ma.identity = ix->placement == IVF_PLACE_DEVICE;
     if (signal_done) { ma.done = w.hd_done; ma.done_value = ++w.done_seq; }
     hipEvent_t e0, e1;
@@ -846,7 +853,7 @@ static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int npro
     int r;
     if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
     const int kprime = kprime_for(k);
-    const int grid = scan_grid_for(ix, nprobe, kprime);
+    const int grid = scan_grid_for(ix, nprobe, kprime, nq);
     if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid, true, true))) return r;
     if ((r = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return r;
     return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
@@ -916,8 +923,8 @@ static size_t carve_search_buffers(Workspace& w, unsigned char* base, const ivf_
         w.d_sort_keys = (uint64_t*)take(nqz * pad * sizeof(uint64_t));
         w.d_sort_idx = (uint32_t*)take(nqz * pad * sizeof(uint32_t));
     }
-    w.d_part = (uint64_t*)take(nqz * gz * kprime * sizeof(uint64_t));
-    w.d_heads = (uint64_t*)take(nqz * gz * sizeof(uint64_t));
+    w.d_part = (uint64_t*)take(nqz * gz * kScanWaves * cand_slots(kprime) * sizeof(uint64_t));
+    w.d_heads = (uint64_t*)take(nqz * gz * kScanWaves * sizeof(uint64_t));
     return at;
 }
 
@@ -934,7 +941,7 @@ extern "C" int ivf_search_device_noalloc(ivf_index* ix, const float* q_dev, int3
         if (l.pending.on) return fail(IVF_ESTATE, "a list-major batch is unfinished: call ivf_synchronize() first");
     nprobe = std::min(nprobe, ix->nlist);
     const int kprime = kprime_for(k);
-    const int grid = scan_grid_for(ix, nprobe, kprime);
+    const int grid = scan_grid_for(ix, nprobe, kprime, nq);
     const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
     Workspace w{};
     const size_t need = carve_search_buffers(w, nullptr, ix, nq, nprobe, kprime, grid, pad);
@@ -944,7 +951,7 @@ extern "C" int ivf_search_device_noalloc(ivf_index* ix, const float* q_dev, int3
     unsigned char* sp = nullptr;
     if ((rc = scratch_for_device(ix->device, &sp))) return rc;
     carve_search_buffers(w, sp, ix, nq, nprobe, kprime, grid, pad);
-    w.nq = nq; w.nprobe = nprobe; w.k = k; w.kprime = kprime; w.pad = pad; w.grid = grid;
+    w.nq = nq; w.nprobe = nprobe; w.k = k; w.kprime = kprime; w.pad = pad; w.wg_cap = (size_t)grid * nq;
     // the kernels of one call only ever read what an earlier kernel of the same call wrote, so
     // nothing in the area has to start at zero
     hipStream_t cs = ix->cs; Workspace* cw = ix->cw;
@@ -970,7 +977,7 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
     if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
     Workspace& w = *ix->cw;
     const int kprime = kprime_for(k);
-    const int grid = scan_grid_for(ix, nprobe, kprime);
+    const int grid = scan_grid_for(ix, nprobe, kprime, nq);
     const bool hybrid = ix->placement == IVF_PLACE_HOST;
     ivf_search_stats st{};
 

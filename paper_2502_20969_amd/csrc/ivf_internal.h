@@ -21,6 +21,9 @@ constexpr int kPrefixLdsCap = 8192;        // select: row-prefix table kept in L
 
 // candidates re-scored in fp64 per query: the requested k plus a margin that absorbs the
 // rounding of the fp32 scan
+// entries of one wavefront's candidate list: its loose candidates (up to 64) or its sorted list
+inline int cand_slots(int kprime) { return kprime > 64 ? 128 : 64; }
+
 inline int kprime_for(int k) {
     int slack = k / 8 > 8 ? k / 8 : 8;
     int kp = k + slack;
@@ -84,9 +87,9 @@ struct ScanArgs {
     const uint32_t* idrank;  // [n] global row -> rank of its id among all ids, or nullptr (rank = global row)
     SlotTables slots;
     const WgDesc* desc;      // [nq x grid]
-    uint64_t* part;          // [nq x grid x kprime] out: workgroup lists of packed candidates
-                             // (fp32 key image << 32 | ~rank), best first, 0 = empty
-    uint64_t* heads;         // [nq x grid] out: entry 0 of every list again, packed densely for the merge
+    uint64_t* part;          // [nq x (grid x kScanWaves) x cand_slots(kprime)] out: one list of packed candidates
+                             // (fp32 key image << 32 | ~rank) per wavefront, unordered, 0 = empty
+    uint64_t* heads;         // [nq x (grid x kScanWaves)] out: the best entry of every list, packed densely for the merge
     int d, dtype, metric, nprobe, nq, kprime, grid;
     ScanShape shape;
 };
@@ -99,12 +102,12 @@ struct MergeArgs {
     const int64_t* ids;          // [n] global row -> id, or nullptr (id = global row)
     const uint32_t* rowof;       // [n] id rank -> global row, or nullptr (row = rank)
     SlotTables slots;
-    const uint64_t* part;        // [nq x nparts x kprime] packed candidates written by the scan
-    const uint64_t* heads;       // [nq x nparts] the lists' first entries
+    const uint64_t* part;        // [nq x nparts x slots] packed candidates written by the scan, lists unordered
+    const uint64_t* heads;       // [nq x nparts] the lists' best entries
     const HostCand* host_cand;   // [nq x kprime] device-visible, or nullptr
     const int32_t* host_count;   // [nq] valid entries in host_cand
     int64_t* out_ids; float* out_dists;   // [nq x k]
-    int d, dtype, metric, nprobe, nq, k, kprime, nparts;
+    int d, dtype, metric, nprobe, nq, k, kprime, nparts, list_len;   // list_len: entries per list
     int identity;            // 1: buffer row == global row (device placement)
     // Completion word in pinned host memory (device address) or nullptr: set to done_value after
     // the results are visible to the host.  Only for nq == 1 (one workgroup writes it).

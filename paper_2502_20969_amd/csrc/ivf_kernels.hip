@@ -441,18 +441,26 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
 
 // =============================================================================================
 // List scan (App. B, second step): d(x, y) for every row y of every selected, resident list,
-// reduced in the kernel to the kprime best rows per group of workgroups.  HBM-bound: each row
-// is read once with 16-byte streaming loads; only candidate lists are written.
+// reduced in the kernel to the best rows each wavefront saw.  HBM-bound: each row is read once
+// with 16-byte streaming loads; only candidate lists are written.
 //
 // A row is covered by LPR lanes with SEG 16-byte loads each, so one wavefront instruction
 // covers 64/LPR rows; a batch is U such row groups; each wavefront keeps two batches in
 // flight (the next one is requested before the current one is reduced).  The resident rows of
-// a query's clusters form one sequence that is split evenly over the workgroups and, inside a
-// workgroup, over its four wavefronts.
+// a query's clusters form one sequence.  With up to kLaneTableSlots selected clusters the
+// sequence is cut into windows of one batch and wavefront w of all W takes the windows
+// w, w + W, ...: every wavefront then reads the same mix of addresses.  With more clusters the
+// sequence is split evenly over the workgroups (the select kernel wrote where each share begins)
+// and inside a workgroup over its wavefronts.
+//
+// Every wavefront writes its own candidate list (kCandSlots per list, unordered, 0 = empty) and
+// the list's best entry again into a dense array of heads: no LDS, no barrier.
 // =============================================================================================
 // Position of a wavefront in the row sequence of its query.
 struct Cursor {
-    uint32_t r, r_end;           // next row and end of this wavefront's range
+    uint32_t r, r_end;           // next row and end of the current range (a window, or the wavefront's share)
+    uint32_t win, win_step;      // windows: start of the current one, distance to the next (0: one contiguous range)
+    uint32_t total;              // rows in the sequence (windows only)
     uint32_t slot, s_rb, s_re;   // current slot and its row range
     uint32_t s_grow;
     int64_t s_base;
@@ -500,7 +508,13 @@ struct LaneTable {
 __device__ __forceinline__ Batch next_batch(Cursor& c, const ScanArgs& p, int qi, int rows_per_batch,
                                             size_t row_bytes, const LaneTable& tab) {
     Batch b{nullptr, 0, 0};
-    if (c.r >= c.r_end) return b;
+    if (c.r >= c.r_end) {
+        if (c.win_step == 0) return b;
+        if (c.total - c.win <= c.win_step) { c.win_step = 0; return b; }
+        c.win += c.win_step;                 // the wavefront's next window
+        c.r = c.win;
+        c.r_end = c.total - c.win < (uint32_t)rows_per_batch ? c.total : c.win + (uint32_t)rows_per_batch;
+    }
     if (tab.on) {
         if (c.r >= c.s_re) tab.seek(c);
     } else {
@@ -514,100 +528,27 @@ __device__ __forceinline__ Batch next_batch(Cursor& c, const ScanArgs& p, int qi
         }
     }
     const uint32_t in_slot = c.r - c.s_rb;
-    b.nr = min((uint32_t)rows_per_batch, min(c.r_end, c.s_re) - c.r);
+    b.nr = min((uint32_t)rows_per_batch, min(c.r_end, c.s_re) - c.r);      // a window that crosses into the next slot comes in two batches
     b.rows = (const unsigned char*)p.buf + ((size_t)c.s_base + in_slot) * row_bytes;
     b.grow = c.s_grow + in_slot;
     c.r += b.nr;
     return b;
 }
 
-// LDS of the scan epilogue: a pool of loose candidates (one 64-entry chunk per wavefront at
-// most) and one sorted list of kprime entries per wavefront.
-struct ScanLds {
-    Cand* pool;                             // [kScanWaves * 64]
-    Cand* list;                             // [kScanWaves * kprime]
-    uint32_t* ctl;                          // [0] pool count, [1] bit mask of wavefronts with a list
-};
-__host__ __device__ inline size_t scan_epilogue_bytes(int kprime) {
-    return (size_t)kScanWaves * 64 * 8 + (size_t)kScanWaves * kprime * 8 + 16;
-}
-__device__ __forceinline__ ScanLds scan_lds(unsigned char* smem, int kprime) {
-    ScanLds l;
-    l.pool = (Cand*)smem;
-    l.list = l.pool + kScanWaves * 64;
-    l.ctl = (uint32_t*)(l.list + kScanWaves * kprime);
-    return l;
-}
-
-// Workgroup epilogue.  Every wavefront puts its loose (pending) candidates into the pool and,
-// when it has one, its sorted list into its list slot.  The pool is sorted in chunks of 64 by
-// as many wavefronts as there are chunks; wavefront 0 then merges all sorted runs into the
-// workgroup's list and writes it out.
-template <int KL>
-__device__ __forceinline__ void finish_workgroup(WaveTopK<KL, false>& top, const ScanArgs& p, const ScanLds& l, int qi) {
-    const int lane = lane_id(), wave = wave_id();
-    const int kp = p.kprime;
-    // ctl was zeroed at kernel start (before a barrier every wavefront has passed)
-    if (top.pcount > 0) {
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(&l.ctl[0], (uint32_t)top.pcount);
-        base = read_lane(base, 0);
-        if (lane < top.pcount) l.pool[base + lane] = top.pend;
-    }
-    const bool has_list = read_lane(top.top[0], 0) != 0;
-    if (has_list) {
-#pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            int e = j * 64 + lane;
-            if (e < kp) l.list[wave * kp + e] = top.top[j];
-        }
-        if (lane == 0) atomicOr(&l.ctl[1], 1u << wave);
-    }
-    __syncthreads();
-    const uint32_t pool = l.ctl[0];
-    const int nchunks = (int)((pool + 63) / 64);
-    if (wave < nchunks) {
-        uint32_t e = wave * 64 + lane;
-        l.pool[e] = bitonic_sort64<false>(e < pool ? l.pool[e] : (Cand)0);
-    }
-    __syncthreads();
-    if (wave != 0) return;
-    int nchunks_done = 0;
-    const uint32_t lists = l.ctl[1];
-    top.init();
-    if (KL == 1 && lists == 0 && nchunks == 1) { top.top[0] = l.pool[lane]; nchunks_done = 1; }
-    for (int w = 0; w < kScanWaves; ++w) {
-        if (!((lists >> w) & 1u)) continue;
-#pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            int e = j * 64 + lane;
-            top.merge_run_if_useful(e < kp ? l.list[w * kp + e] : (Cand)0, kp);
-        }
-    }
-    for (int c = nchunks_done; c < nchunks; ++c) top.merge_run_if_useful(l.pool[c * 64 + lane], kp);
-    size_t o = ((size_t)qi * p.grid + blockIdx.x) * kp;
-#pragma unroll
-    for (int j = 0; j < KL; ++j) {
-        int e = j * 64 + lane;
-        if (e < kp) p.part[o + e] = top.top[j];
-    }
-    if (lane == 0) p.heads[(size_t)qi * p.grid + blockIdx.x] = top.top[0];
-}
-
-__device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi, const LaneTable& tab) {
+__device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi, const LaneTable& tab, int rows_per_batch) {
     const int wave = wave_id();
     Cursor c;
+    c.win = 0; c.win_step = 0; c.total = 0;
     if (tab.on) {
-        // the workgroup's share of the rows, as the select kernel would have described it: rows
-        // split evenly over the workgroups, the first `extra` shares one row longer
-        const uint32_t R = tab.total(), g = (uint32_t)p.grid, b = blockIdx.x;
-        const uint32_t per = R / g, extra = R % g;
-        const uint32_t r_begin = per * b + min(b, extra), r_end = per * (b + 1) + min(b + 1, extra);
-        const uint32_t cnt = r_end - r_begin;
-        c.r = r_begin + (uint32_t)((uint64_t)cnt * wave / kScanWaves);
-        c.r_end = r_begin + (uint32_t)((uint64_t)cnt * (wave + 1) / kScanWaves);
+        const uint32_t R = tab.total();
+        const uint32_t w = blockIdx.x * kScanWaves + (uint32_t)wave;
+        c.total = R;
+        c.win = w * (uint32_t)rows_per_batch;
+        c.win_step = (uint32_t)p.grid * kScanWaves * (uint32_t)rows_per_batch;
+        c.r = min(c.win, R);
+        c.r_end = R - c.r < (uint32_t)rows_per_batch ? R : c.r + (uint32_t)rows_per_batch;
         c.slot = 0; c.s_rb = 0; c.s_re = 0; c.s_grow = 0; c.s_base = 0;
-        if (c.r < c.r_end) tab.seek(c);
+        if (c.r >= c.r_end) c.win_step = 0;        // beyond the last window: nothing to do
         return c;
     }
     const WgDesc ds = p.desc[(size_t)qi * p.grid + blockIdx.x];
@@ -619,32 +560,71 @@ __device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi, const 
     return c;
 }
 
+// The largest candidate word held by any lane (0 when all are empty); every lane gets it.
+__device__ __forceinline__ Cand wave_max(Cand c) {
+    Cand o;
+    o = xor_lane<1>(c); c = o > c ? o : c;
+    o = xor_lane<2>(c); c = o > c ? o : c;
+    o = xor_lane<4>(c); c = o > c ? o : c;
+    o = xor_lane<8>(c); c = o > c ? o : c;
+    o = xor_lane<16>(c); c = o > c ? o : c;
+    o = xor_lane<32>(c); c = o > c ? o : c;
+    return c;
+}
+
+// What a wavefront leaves behind: its candidates as a list of 64 * KL entries (the sorted list when it has one,
+// else the loose candidates as they stand) and the best of them as the list's head.
+template <int KL>
+__device__ __forceinline__ void write_wave_list(WaveTopK<KL, false>& top, const ScanArgs& p, int qi) {
+    const int lane = lane_id();
+    const size_t list = ((size_t)qi * p.grid + blockIdx.x) * kScanWaves + (size_t)wave_id();
+    Cand* out = p.part + list * (size_t)(64 * KL);
+    const bool has_list = read_lane(top.top[0], 0) != 0;
+    Cand head;
+    if (KL == 1 && !has_list) {
+        const Cand c = lane < top.pcount ? top.pend : (Cand)0;
+        out[lane] = c;
+        head = wave_max(c);
+    } else {
+        top.flush(p.kprime);
+#pragma unroll
+        for (int j = 0; j < KL; ++j) {
+            const int e = j * 64 + lane;
+            out[e] = e < p.kprime ? top.top[j] : (Cand)0;
+        }
+        head = read_lane(top.top[0], 0);
+    }
+    if (lane == 0) p.heads[list] = head;
+}
+
 template <typename T, int LPR, int SEG, int U, int METRIC, int KL>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     constexpr int EPL = T::kPerLoad;
     constexpr int RPI = 64 / LPR;
     constexpr int RPB = U * RPI;
-    extern __shared__ unsigned char smem[];
     const int lane = lane_id();
     const int sub = lane % LPR, rsel = lane / LPR;
     const int qi = blockIdx.y;
-    const ScanLds lds = scan_lds(smem, p.kprime);
-    if (threadIdx.x < 2) lds.ctl[threadIdx.x] = 0;
     const size_t row_bytes = (size_t)p.d * T::kBytes;
 
-    LaneTable tab;
-    tab.load(p, qi);
-    Cursor cur = start_cursor(p, qi, tab);
-
-    // this lane's slice of the query
+    // this lane's slice of the query, requested before anything else: it travels while the
+    // tables do (rows of this kernel are whole 16-byte chunks, so d is a multiple of EPL)
     float qv[SEG][EPL];
     const float* q = p.q + (size_t)qi * p.d;
 #pragma unroll
     for (int sg = 0; sg < SEG; ++sg) {
-        int col = (sg * LPR + sub) * EPL;
+        const int col = (sg * LPR + sub) * EPL;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) qv[sg][e] = col + e < p.d ? q[col + e] : 0.f;
+        for (int e = 0; e < EPL; e += 4) {
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (col < p.d) t = *(const float4*)(q + col + e);
+            qv[sg][e] = t.x; qv[sg][e + 1] = t.y; qv[sg][e + 2] = t.z; qv[sg][e + 3] = t.w;
+        }
     }
+
+    LaneTable tab;
+    tab.load(p, qi);
+    Cursor cur = start_cursor(p, qi, tab, RPB);
 
     WaveTopK<KL, false> top;
     top.init();
@@ -715,8 +695,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
         if (ba.nr) issue(ba, va, ta);
         consume(bb, vb, tb);
     }
-    __syncthreads();          // orders the zeroing of lds.ctl before its use
-    finish_workgroup<KL>(top, p, lds, qi);
+    write_wave_list<KL>(top, p, qi);
 }
 
 // Fallback for any d and any row alignment: element-wise loads, query in LDS, 4 rows per batch.
@@ -725,16 +704,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
     extern __shared__ unsigned char smem[];
     const int lane = lane_id();
     const int qi = blockIdx.y;
-    const ScanLds lds = scan_lds(smem, p.kprime);
-    if (threadIdx.x < 2) lds.ctl[threadIdx.x] = 0;
-    float* ql = (float*)(smem + scan_epilogue_bytes(p.kprime));
+    float* ql = (float*)smem;
     for (int i = threadIdx.x; i < p.d; i += blockDim.x) ql[i] = p.q[(size_t)qi * p.d + i];
     __syncthreads();
     const int esz = p.dtype == 0 ? 4 : 2;
     const size_t row_bytes = (size_t)p.d * esz;
     LaneTable tab;
     tab.load(p, qi);
-    Cursor cur = start_cursor(p, qi, tab);
+    Cursor cur = start_cursor(p, qi, tab, 4);
     WaveTopK<KL, false> top;
     top.init();
     for (Batch b = next_batch(cur, p, qi, 4, row_bytes, tab); b.nr; b = next_batch(cur, p, qi, 4, row_bytes, tab)) {
@@ -759,7 +736,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
             }
         }
     }
-    finish_workgroup<KL>(top, p, lds, qi);
+    write_wave_list<KL>(top, p, qi);
 }
 
 // ---- shape selection ---------------------------------------------------------------------
@@ -815,8 +792,8 @@ static ScanFn scan_fn(const ScanShape& sh, int dtype, int metric, int kprime) {
     return scan_fn_dtype<BF16>(sh, metric, big);
 }
 
-static size_t scan_lds_bytes(const ScanShape& sh, int kprime, int d) {
-    return scan_epilogue_bytes(kprime) + (sh.lanes_per_row == 0 ? (size_t)d * 4 : 0);
+static size_t scan_lds_bytes(const ScanShape& sh, int d) {
+    return sh.lanes_per_row == 0 ? (size_t)d * 4 : 0;      // only the fallback kernel stages the query
 }
 
 int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime, int d, int n_cu) {
@@ -824,7 +801,7 @@ int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime
     if (!fn) return n_cu;
     int per_cu = 0;
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)fn, kScanThreads,
-                                                                scan_lds_bytes(shape, kprime, d));
+                                                                scan_lds_bytes(shape, d));
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (per_cu > kScanMaxWgPerCu) per_cu = kScanMaxWgPerCu;
     return per_cu * n_cu;
@@ -834,7 +811,7 @@ hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t e0, hipEvent
     ScanFn fn = scan_fn(a.shape, a.dtype, a.metric, a.kprime);
     if (!fn) return hipErrorInvalidValue;
     dim3 grid(a.grid, a.nq);
-    IVF_LAUNCH(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.kprime, a.d), s, e0, e1, a);
+    IVF_LAUNCH(fn, grid, dim3(kScanThreads), scan_lds_bytes(a.shape, a.d), s, e0, e1, a);
     return hipGetLastError();
 }
 
@@ -844,7 +821,8 @@ hipError_t launch_scan(const ScanArgs& a, hipStream_t s, hipEvent_t e0, hipEvent
 // all workgroup lists, re-scores those rows in fp64 from the stored rows, adds the host's
 // candidates (already fp64), orders everything by (score, id) and writes the k nearest.
 // =============================================================================================
-constexpr int kMergeCandCap = 4096;    // kprime^2 for the largest kprime of the fast path
+constexpr int kMergeCandCap = 4096;    // candidates the fast path can pool
+constexpr int kMergeQlistCap = 1024;   // lists the fast path can visit
 constexpr int kMergeFastThreads = 1024;
 
 struct MergeLds {
@@ -855,25 +833,31 @@ struct MergeLds {
     int64_t f_id[2 * kMaxKPrime];
 };
 
-// Fast path (kprime <= 64).  Every list is sorted and candidates are distinct, so with T0 = the
-// kprime-th best list head, only entries >= T0 of the (at most kprime) lists whose head is
-// >= T0 can be among the kprime best.  Those are gathered, sorted in chunks of 64 and merged.
-// `pool` holds kMergeCandCap candidates, `qlist` 64 list numbers.
-__device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part, const Cand* heads, MergeLds& L,
+// Fast path (kprime <= 64).  The scan left one unordered list of `slots` candidates per wavefront
+// and each list's best entry in `heads` (0: empty list).  Candidates are distinct.  Every thread
+// folds the heads l = tid, tid + nt, ... into their maximum; T0 is the kprime-th best of those
+// maxima (the kprime-th best head when there are no more heads than threads).  At least kprime
+// candidates reach T0, so the kprime best overall are among the entries >= T0 of the lists whose
+// head reaches T0.  Those are gathered, sorted in chunks of 64 and merged.  Returns false (for
+// the whole workgroup) when they did not fit `pool` (kMergeCandCap) or `qlist` (kMergeQlistCap).
+__device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part, const Cand* heads, MergeLds& L,
                                             Cand* pool, uint32_t* qlist) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id(), nw = nt >> 6;
-    const int kp = a.kprime, np = a.nparts;
+    const int kp = a.kprime, np = a.nparts, slots = a.list_len;
     // 1. T0 from the list heads
     if (tid == 0) { L.sh[4] = 0; L.sh[5] = 0; }
-    Cand best = 0, first_head = 0;
+    Cand h0 = 0, h1 = 0, mine = 0;
+    {
+        int j = 0;
 #pragma unroll 1
-    for (int c0 = wave * 64; c0 < np; c0 += nw * 64) {
-        const int l = c0 + lane;
-        const Cand h = l < np ? heads[l] : (Cand)0;
-        if (c0 == wave * 64) first_head = h;
-        best = merge_best64<true>(best, bitonic_sort64<true>(h));
+        for (int l = tid; l < np; l += nt, ++j) {
+            const Cand h = heads[l];
+            if (j == 0) h0 = h; else if (j == 1) h1 = h;
+            mine = h > mine ? h : mine;
+        }
     }
-    const int busy = min(nw, (np + 63) / 64);       // wavefronts that hold heads
+    const int busy = min(nw, (min(np, nt) + 63) / 64);       // wavefronts that hold heads
+    Cand best = wave < busy ? bitonic_sort64<true>(mine) : (Cand)0;
 #pragma unroll 1
     for (int stride = 1; stride < busy; stride <<= 1) {
         const bool sender = (wave % (2 * stride)) == stride && wave < busy;
@@ -888,32 +872,49 @@ __device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part
         if (lane == 0) { L.sh[6] = (uint32_t)t; L.sh[7] = (uint32_t)(t >> 32); }
     }
     __syncthreads();
-    const Cand t0 = ((uint64_t)L.sh[7] << 32) | L.sh[6];     // 0 when fewer than kprime lists have entries
+    const Cand t0 = ((uint64_t)L.sh[7] << 32) | L.sh[6];     // 0 when fewer than kprime threads hold a head
     // 2. the lists whose head reaches T0 ...
+    {
+        int j = 0;
 #pragma unroll 1
-    for (int l = tid; l < np; l += nt) {
-        const Cand h = l == tid ? first_head : heads[l];
-        if (h != 0 && h >= t0) qlist[atomicAdd(&L.sh[5], 1u)] = (uint32_t)l;
+        for (int l = tid; l < np; l += nt, ++j) {
+            const Cand h = j == 0 ? h0 : (j == 1 ? h1 : heads[l]);
+            if (h != 0 && h >= t0) {
+                const uint32_t pos = atomicAdd(&L.sh[5], 1u);
+                if (pos < (uint32_t)kMergeQlistCap) qlist[pos] = (uint32_t)l;
+            }
+        }
     }
     __syncthreads();
     const int nql = (int)L.sh[5];
-    // ... and their entries that reach it, one entry per thread
+    if (nql > kMergeQlistCap) return false;
+    // ... and their entries that reach it: four entries per thread and pass, all requested before
+    // the first is looked at
+    const int total = nql * slots;
 #pragma unroll 1
-    for (int e0 = 0; e0 < nql * kp; e0 += nt) {
-        const int e = e0 + tid;
-        Cand c = 0;
-        if (e < nql * kp) c = part[(size_t)qlist[e / kp] * kp + e % kp];
-        const bool ok = c != 0 && c >= t0;
-        const uint64_t b = __ballot(ok);
-        if (b) {
-            uint32_t base = 0;
-            if (lane == 0) base = atomicAdd(&L.sh[4], (uint32_t)__popcll(b));
-            base = read_lane(base, 0);
-            if (ok) pool[base + __popcll(b & ((1ull << lane) - 1ull))] = c;
+    for (int e0 = 0; e0 < total; e0 += 4 * nt) {
+        Cand c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * nt + tid;
+            c[u] = e < total ? part[(size_t)qlist[e / slots] * slots + e % slots] : (Cand)0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool ok = c[u] != 0 && c[u] >= t0;
+            const uint64_t b = __ballot(ok);
+            if (b) {
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&L.sh[4], (uint32_t)__popcll(b));
+                base = read_lane(base, 0);
+                const uint32_t pos = base + __popcll(b & ((1ull << lane) - 1ull));
+                if (ok && pos < (uint32_t)kMergeCandCap) pool[pos] = c[u];
+            }
         }
     }
     __syncthreads();
     const uint32_t cnt = L.sh[4];
+    if (cnt > (uint32_t)kMergeCandCap) return false;
     // 3. sort the gathered candidates in chunks of 64, merge the chunks
     const int nchunks = (int)((cnt + 63) / 64);
 #pragma unroll 1
@@ -932,13 +933,14 @@ __device__ __forceinline__ void gather_fast(const MergeArgs& a, const Cand* part
         if (lane == 0) L.sh[4] = m;
     }
     __syncthreads();
+    return true;
 }
 
 // General path: radix select over all entries of all lists (candidates are distinct, so the
 // selection ends with exactly kprime of them).
 __device__ __forceinline__ void gather_radix(const MergeArgs& a, const Cand* part, MergeLds& L) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
-    const uint32_t n = (uint32_t)a.nparts * a.kprime, kp = a.kprime;
+    const uint32_t n = (uint32_t)a.nparts * (uint32_t)a.list_len, kp = a.kprime;
     auto key_at = [&](uint32_t i) { return ~part[i]; };      // ascending = best first; all ones = empty
     uint32_t my_valid = 0;
     for (uint32_t i = tid; i < n; i += nt) my_valid += part[i] != 0;
@@ -973,15 +975,18 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     __shared__ MergeLds L;
     const int tid = threadIdx.x, nt = blockDim.x;
     const int qi = blockIdx.x;
-    const uint32_t n = (uint32_t)a.nparts * a.kprime;
+    const uint32_t n = (uint32_t)a.nparts * (uint32_t)a.list_len;
     const Cand* part = a.part + (size_t)qi * n;
     const uint32_t kp = a.kprime;
 
     // 1. the kprime best fp32 candidates
+    bool gathered = false;
     if (fast) {
         Cand* pool = (Cand*)m_dyn;
-        gather_fast(a, part, a.heads + (size_t)qi * a.nparts, L, pool, (uint32_t*)(pool + kMergeCandCap));
-    } else {
+        gathered = gather_fast(a, part, a.heads + (size_t)qi * a.nparts, L, pool, (uint32_t*)(pool + kMergeCandCap));
+    }
+    if (!gathered) {
+        __syncthreads();
         gather_radix(a, part, L);
     }
     const uint32_t m = min(L.sh[4], (uint32_t)kMaxKPrime);
@@ -1089,10 +1094,10 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     if (a.done && a.nq != 1) return hipErrorInvalidValue;
-    const size_t n = (size_t)a.nparts * a.kprime;
+    const size_t n = (size_t)a.nparts * a.list_len;
     const int fast = a.kprime <= 64;
     const int threads = fast ? kMergeFastThreads : (n <= 8192 ? 256 : kSelectThreads);
-    const size_t lds = fast ? (size_t)kMergeCandCap * 8 + 64 * 4 : 0;
+    const size_t lds = fast ? (size_t)kMergeCandCap * 8 + (size_t)kMergeQlistCap * 4 : 0;
     IVF_LAUNCH(merge_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, fast);
     return hipGetLastError();
 }

@@ -61,7 +61,7 @@ def test_noalloc_refuses_what_does_not_fit():
     st, odt, cent, assign, ids, rng = _problem(78, n, d, nlist, "f32")
     index = P.ivf_build_layout(st, "f32", cent, assign, metric=P.IVF_IP,
                                compute_stream=torch.cuda.Stream(), copy_stream=torch.cuda.Stream())
-    nq, k = 128, 100                     # 128 queries x ~170 workgroups x 112 candidates x 8 bytes > 8 MiB
+    nq, k = 4096, 100                    # 4096 queries x 4 wavefront lists x 128 candidates x 8 bytes = 16 MiB
     q = torch.zeros(nq, d, device="cuda")
     ids_dev = torch.empty(nq, k, dtype=torch.int64, device="cuda")
     dists_dev = torch.empty(nq, k, dtype=torch.float32, device="cuda")
