@@ -32,8 +32,14 @@
  *     +INF (L2).
  *   - Arithmetic: coarse scores are accumulated in fp64.  The list scan
  *     accumulates in fp32 over rows stored as fp32 / fp16 / bf16 with the fp32
- *     query; the k + slack best rows are then re-scored in fp64 and ordered by
- *     that score, and the fp64 value rounded to fp32 is what is returned.
+ *     query; the k' = k + max(8, k / 8) best rows are then re-scored in fp64 and
+ *     ordered by that score, and the fp64 value rounded to fp32 is what is
+ *     returned.  The k nearest are exact with respect to the fp64 scores: when
+ *     the k-th fp64 score found is not above the last fp32 score kept by more
+ *     than a bound of the scan's rounding, a row that was dropped could belong
+ *     to the result, and the query gets an exact second pass (every selected
+ *     row scored in fp64) on the device, and likewise on the host for the host
+ *     part of a hybrid search.
  */
 #ifndef IVF_H
 #define IVF_H
@@ -87,6 +93,8 @@ typedef struct ivf_search_stats {
     float ms_total;        /* wall time of the call */
     float ms_probe;        /* until the selected clusters were known to the host (host placement) */
     float ms_host_scan;    /* host scan of C_miss */
+    int32_t n_exact_gpu;   /* queries whose GPU part needed the exact second pass (see "Arithmetic" above) */
+    int32_t n_exact_host;  /* queries whose host part needed it */
 } ivf_search_stats;
 
 typedef struct ivf_profile {
@@ -167,7 +175,8 @@ int ivf_search(ivf_index* index, const float* q_out, int32_t nq, int32_t nprobe,
  * The same search with device-resident queries and outputs (all device pointers), enqueued
  * on compute_stream without waiting: outputs are complete once that stream has reached
  * this point (with a pipeline depth above 1: see ivf_set_pipeline_depth; searched list-major:
- * see ivf_set_batch_mode, after ivf_synchronize()).  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
+ * see ivf_set_batch_mode, after ivf_synchronize()).  q_dev must be 16-byte aligned; q_dev, ids_dev
+ * and dists_dev must stay valid until the outputs are complete.  IVF_PLACE_DEVICE only.  nq, nprobe and k must not exceed what
  * ivf_reserve() or an earlier search has sized the workspace for, else the call sizes it
  * itself, which synchronises the device.
  */
@@ -200,7 +209,8 @@ int ivf_search_device_noalloc(ivf_index* index, const float* q_dev, int32_t nq, 
  * merge run on a few compute units while another query's scan streams its lists).  With depth
  * n > 1, successive ivf_search_device calls rotate over n internal streams (the first is
  * compute_stream), each with its own workspace; inputs must be complete when the call is made,
- * and outputs are complete after ivf_synchronize().  List-major batches overlap in the same way
+ * and outputs are complete after ivf_synchronize() (which also runs the exact second pass for
+ * the queries that need it; with depth 1 that pass follows every search on the stream).  List-major batches overlap in the same way
  * (the kernels that prepare one batch run beside the scan of the one before).  Depth 1 (the
  * default) keeps everything on compute_stream.  Changing the depth synchronises the device.  IVF_PLACE_DEVICE only; depth
  * in [1, 16].

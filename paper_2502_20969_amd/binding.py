@@ -4,6 +4,7 @@ Host arguments are numpy arrays (or CPU torch tensors); device arguments are tor
 tensors.  Nothing here computes: every step of the search runs in the HIP library, and the
 module raises at import of the library if it has not been built.
 """
+import collections
 import ctypes as C
 import os
 
@@ -43,7 +44,8 @@ class PrefetchStats(C.Structure):
 class SearchStats(C.Structure):
     _fields_ = [("n_probed", C.c_int32), ("n_overlap", C.c_int32), ("n_miss", C.c_int32),
                 ("hit_rate", C.c_float), ("bytes_gpu", C.c_uint64), ("bytes_host", C.c_uint64),
-                ("ms_total", C.c_float), ("ms_probe", C.c_float), ("ms_host_scan", C.c_float)]
+                ("ms_total", C.c_float), ("ms_probe", C.c_float), ("ms_host_scan", C.c_float),
+                ("n_exact_gpu", C.c_int32), ("n_exact_host", C.c_int32)]
 
 
 class Profile(C.Structure):
@@ -105,6 +107,17 @@ def load():
     return L
 
 
+_torch_mod = None
+
+
+def _torch():
+    global _torch_mod
+    if _torch_mod is None:
+        import torch
+        _torch_mod = torch
+    return _torch_mod
+
+
 def _check(status):
     if status != 0:
         L = load()
@@ -158,6 +171,9 @@ class Index:
         self._h = handle
         self.d, self.nlist, self.n = d, nlist, n
         self._keep = keep      # arrays the index adopted and that must outlive it
+        # device tensors of searches the library may still touch (a pipelined or list-major call is
+        # finished when its stream is next needed or in ivf_synchronize): one entry per stream at most
+        self._inflight = collections.deque(maxlen=32)
 
     def close(self):
         if self._h is not None:
@@ -194,17 +210,22 @@ class Index:
         return (ids, dists, st) if with_stats else (ids, dists)
 
     def ivf_search_device(self, q_dev, nprobe, k, ids_dev, dists_dev):
-        """q_dev [nq, d] float32, ids_dev [nq, k] int64, dists_dev [nq, k] float32: CUDA tensors."""
+        """q_dev [nq, d] float32, ids_dev [nq, k] int64, dists_dev [nq, k] float32: CUDA tensors.
+        The three tensors are kept referenced until ivf_synchronize (the library may read the queries
+        and rewrite the outputs until then)."""
         assert q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda
         assert q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()
+        assert q_dev.dtype == _torch().float32 and ids_dev.dtype == _torch().int64 and dists_dev.dtype == _torch().float32
         nq = q_dev.numel() // self.d
         assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
+        self._inflight.append((q_dev, ids_dev, dists_dev))
         _check(load().ivf_search_device(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
 
     def ivf_search_device_noalloc(self, q_dev, nprobe, k, ids_dev, dists_dev):
         """ivf_search_device on the library's fixed scratch area: allocates nothing."""
         assert q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda
         assert q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()
+        assert q_dev.dtype == _torch().float32 and ids_dev.dtype == _torch().int64 and dists_dev.dtype == _torch().float32
         nq = q_dev.numel() // self.d
         assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
         _check(load().ivf_search_device_noalloc(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
@@ -280,6 +301,7 @@ class Index:
 
     def ivf_synchronize(self):
         _check(load().ivf_synchronize(self._h))
+        self._inflight.clear()
 
     def ivf_set_batch_mode(self, mode):
         _check(load().ivf_set_batch_mode(self._h, mode))

@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <functional>
 
 namespace ivf {
 
@@ -179,9 +180,66 @@ ScanFn pick_scan(int dtype, int metric) {
     return metric == 0 ? scan_rows<bf16_t, 0> : scan_rows<bf16_t, 1>;
 }
 
+template <typename T>
+float norm_sq_max_rows(const T* base, int64_t r0, int64_t r1, int d) {
+    float best = 0.f;
+    for (int64_t r = r0; r < r1; ++r) {
+        const T* y = base + (size_t)r * d;
+        float acc[kLanes];
+        for (int j = 0; j < kLanes; ++j) acc[j] = 0.f;
+        int t = 0;
+        for (; t + kLanes <= d; t += kLanes)
+            for (int j = 0; j < kLanes; ++j) { const float x = load_elem(y, t + j); acc[j] += x * x; }
+        float s = 0.f;
+        for (; t < d; ++t) { const float x = load_elem(y, t); s += x * x; }
+        for (int j = 0; j < kLanes; ++j) s += acc[j];
+        best = std::max(best, s);
+    }
+    return best;
+}
+
+float norm_sq_max(const void* lists, int dtype, int64_t r0, int64_t r1, int d) {
+    if (dtype == 0) return norm_sq_max_rows((const float*)lists, r0, r1, d);
+    if (dtype == 1) return norm_sq_max_rows((const _Float16*)lists, r0, r1, d);
+    return norm_sq_max_rows((const bf16_t*)lists, r0, r1, d);
+}
+
+double key_f64(const HostScanArgs& a, int64_t row) {
+    if (a.dtype == 0) return row_key_f64(a.q, (const float*)a.lists + (size_t)row * a.d, a.d, a.metric);
+    if (a.dtype == 1) return row_key_f64(a.q, (const _Float16*)a.lists + (size_t)row * a.d, a.d, a.metric);
+    return row_key_f64(a.q, (const bf16_t*)a.lists + (size_t)row * a.d, a.d, a.metric);
+}
+
+// the kprime best seen so far by (fp64 key, id), best first
+struct ExactTop {
+    struct E { double key; int64_t id; };
+    std::vector<E> v;
+    int cap = 0;
+    static bool better(const E& x, const E& y) { return x.key > y.key || (x.key == y.key && x.id < y.id); }
+    void init(int kprime) { cap = kprime; v.clear(); v.reserve(kprime + 1); }
+    void offer(const E& e) {
+        if ((int)v.size() == cap && !better(e, v.back())) return;
+        v.insert(std::upper_bound(v.begin(), v.end(), e, better), e);
+        if ((int)v.size() > cap) v.pop_back();
+    }
+};
+
 }  // namespace
 
-int host_scan_query(const HostScanArgs& a, ThreadPool& pool, HostCand* out, uint64_t* rows_scanned) {
+float host_row_norm_max(const void* lists, int dtype, int64_t n, int d, ThreadPool& pool) {
+    if (n <= 0) return 0.f;
+    constexpr int64_t kChunk = 4096;
+    const int64_t items = (n + kChunk - 1) / kChunk;
+    std::vector<float> best(pool.size(), 0.f);
+    pool.run(items, [&](int worker, int64_t i) {
+        best[worker] = std::max(best[worker], norm_sq_max(lists, dtype, i * kChunk, std::min(n, (i + 1) * kChunk), d));
+    });
+    float b = 0.f;
+    for (float x : best) b = std::max(b, x);
+    return std::sqrt(b);
+}
+
+int host_scan_query(const HostScanArgs& a, ThreadPool& pool, HostCand* out, uint64_t* rows_scanned, bool* exact_pass) {
     // work items: row chunks of the listed clusters
     constexpr int64_t kChunk = 512;
     struct Item { int64_t r0, r1; };
@@ -193,6 +251,7 @@ int host_scan_query(const HostScanArgs& a, ThreadPool& pool, HostCand* out, uint
         for (int64_t r = lo; r < hi; r += kChunk) items.push_back(Item{r, std::min(hi, r + kChunk)});
     }
     if (rows_scanned) *rows_scanned = rows;
+    if (exact_pass) *exact_pass = false;
     if (items.empty()) return 0;
     std::vector<LocalTop> tops(pool.size());
     for (auto& t : tops) t.init(a.kprime);
@@ -206,13 +265,58 @@ int host_scan_query(const HostScanArgs& a, ThreadPool& pool, HostCand* out, uint
         for (auto& c : t.v) all.offer(c);
     int m = 0;
     for (auto& c : all.v) {
-        double key;
-        if (a.dtype == 0) key = row_key_f64(a.q, (const float*)a.lists + (size_t)c.row * a.d, a.d, a.metric);
-        else if (a.dtype == 1) key = row_key_f64(a.q, (const _Float16*)a.lists + (size_t)c.row * a.d, a.d, a.metric);
-        else key = row_key_f64(a.q, (const bf16_t*)a.lists + (size_t)c.row * a.d, a.d, a.metric);
-        out[m].key = key;
+        out[m].key = key_f64(a, c.row);
         out[m].id = c.id;
         ++m;
+    }
+    // Is every row of the k nearest among the kprime kept?  A row that was not kept has an fp32 key
+    // of at most f_last (the last one kept) and so an exact score of at most f_last + E, E bounding
+    // the rounding of the fp32 sums above (inner product: g |q| |y|; squared distance: g times the
+    // sum); the k-th best exact score found is a lower bound of the true one.
+    if (m == a.kprime && a.k >= 1 && a.k <= m) {
+        std::vector<double> keys(m);
+        for (int i = 0; i < m; ++i) keys[i] = out[i].key;
+        std::nth_element(keys.begin(), keys.begin() + (a.k - 1), keys.end(), std::greater<double>());
+        const double s_k = keys[a.k - 1];
+        const double f_last = (double)all.v.back().key;
+        // roundings on the longest path of a row's sum: a product and an addition per element of a
+        // partial sum, then the partial sums and the tail
+        const double terms = 2.0 * (a.d / kLanes + 1) + kLanes + 2.0 * (a.d % kLanes) + 4.0;
+        const double g = 1.05 * terms * 0x1p-24;
+        double e;
+        if (a.metric == 0) {
+            double qq = 0.0;
+            for (int t = 0; t < a.d; ++t) qq += (double)a.q[t] * (double)a.q[t];
+            float ymax = a.row_norm_max;
+            if (!(ymax > 0.f)) {
+                std::vector<float> best(pool.size(), 0.f);
+                pool.run((int64_t)items.size(), [&](int worker, int64_t i) {
+                    best[worker] = std::max(best[worker], norm_sq_max(a.lists, a.dtype, items[i].r0, items[i].r1, a.d));
+                });
+                float b = 0.f;
+                for (float x : best) b = std::max(b, x);
+                ymax = std::sqrt(b) * 1.0001f;
+            }
+            e = g * std::sqrt(qq) * (double)ymax;
+        } else {
+            e = g * std::fabs(f_last);
+        }
+        if (!(s_k > f_last + e)) {
+            // exact pass: every row scored in fp64, the kprime best by (score, id) kept
+            std::vector<ExactTop> ex(pool.size());
+            for (auto& t : ex) t.init(a.kprime);
+            pool.run((int64_t)items.size(), [&](int worker, int64_t i) {
+                for (int64_t r = items[i].r0; r < items[i].r1; ++r)
+                    ex[worker].offer(ExactTop::E{key_f64(a, r), a.ids ? a.ids[r] : r});
+            });
+            ExactTop fin;
+            fin.init(a.kprime);
+            for (auto& t : ex)
+                for (auto& c : t.v) fin.offer(c);
+            m = 0;
+            for (auto& c : fin.v) { out[m].key = c.key; out[m].id = c.id; ++m; }
+            if (exact_pass) *exact_pass = true;
+        }
     }
     return m;
 }

@@ -46,11 +46,20 @@ struct HostScanArgs {
     const int32_t* clusters;  // lists to scan
     int n_clusters;
     int kprime;
+    int k;                  // results wanted (k <= kprime)
+    float row_norm_max;     // an upper bound of the Euclidean norm of the rows; <= 0: measured over the listed clusters
 };
 
 // Scans the listed clusters for one query: fp32 accumulation over all rows, the kprime best kept
-// per thread, their union cut to kprime and re-scored in fp64.  Writes up to kprime candidates
-// (unordered) to out and returns how many.  *rows_scanned receives the number of rows covered.
-int host_scan_query(const HostScanArgs& a, ThreadPool& pool, HostCand* out, uint64_t* rows_scanned);
+// per thread, their union cut to kprime and re-scored in fp64.  When the fp32 rounding could have
+// kept a row of the k nearest out of those kprime (the k-th fp64 score found is within the rounding
+// bound of the last fp32 score kept), the clusters are scanned again in fp64 and the exact kprime
+// best by (score, id) are returned instead (*exact_pass, nullable, tells).  Writes up to kprime
+// candidates (unordered) to out and returns how many.  *rows_scanned receives the rows covered.
+int host_scan_query(const HostScanArgs& a, ThreadPool& pool, HostCand* out, uint64_t* rows_scanned,
+                    bool* exact_pass = nullptr);
+
+// The largest Euclidean norm over n stored rows (fp32 sums), with the pool's threads.
+float host_row_norm_max(const void* lists, int dtype, int64_t n, int d, ThreadPool& pool);
 
 }  // namespace ivf

@@ -75,6 +75,14 @@ struct Workspace {
     uint64_t* d_heads = nullptr;     // the lists' best entries, densely
     int64_t* d_out_ids = nullptr;
     float* d_out_dists = nullptr;
+    // exact second pass: per query a flag, the k-th best score found and a counter; its wavefronts' lists
+    uint32_t* d_redo_flag = nullptr;
+    double* d_redo_thr = nullptr;
+    uint32_t* d_redo_ticket = nullptr;
+    unsigned long long* d_redo_key = nullptr;
+    long long* d_redo_id = nullptr;
+    uint32_t* h_flag = nullptr;      // pinned copy of the flags for searches with host outputs
+    uint32_t* hd_flag = nullptr;     // ... as the device addresses it
     // pinned host staging
     float* h_q = nullptr;
     float* hd_q = nullptr;           // h_q as the device addresses it
@@ -120,8 +128,8 @@ struct ivf_index {
     float* d_centroids = nullptr;
     int64_t* d_off = nullptr;
     int64_t* d_ids = nullptr;
-    uint32_t* d_idrank = nullptr;    // row -> rank of its id among all ids; null when rank == row
-    uint32_t* d_rowof = nullptr;     // the inverse map
+    float row_norm_max = 0.f;        // largest Euclidean norm of a stored row
+    float err_coef = 0.f;            // rounding bound of the scan kernel (scan_error_coef)
     // cluster cache (host placement): hotness per cluster (< 0 = not cached), use marks of the round
     bool cache_on = false;
     float cache_fraction = 0.5f, cache_h_init = 1.f, cache_decay = 2.f, cache_h_inc = 1.f;
@@ -153,10 +161,11 @@ struct ivf_index {
     ScanShape shape{0, 0, 0, 4};
     // Searches through ivf_search_device rotate over `lanes` (stream + workspace each) so that
     // independent queries overlap; lane 0 runs on compute_stream.  cs / cw: lane in use.
-    // A list-major batch whose candidate-overflow flags have not been looked at yet: the queries
-    // that overflowed still have to be searched again one by one (settle_lane).
-    struct Pending { bool on = false; const float* q = nullptr; int nq = 0, nprobe = 0, k = 0;
-                     int64_t* ids = nullptr; float* dists = nullptr; };
+    // What a lane still owes for its last call (settle_lane).  A list-major batch: the queries whose
+    // candidate lists overflowed have to be searched again one by one.  A query-by-query call of a
+    // pipelined index: the queries whose result the merge could not prove get the exact second pass.
+    struct Pending { bool on = false; bool list_major = false; const float* q = nullptr; int nq = 0, nprobe = 0, k = 0;
+                     int64_t* ids = nullptr; float* dists = nullptr; unsigned long long done_seq = 0; };
     struct Lane { hipStream_t stream = nullptr; bool own = false; Workspace ws; Pending pending; };
     std::vector<Lane> lanes;
     size_t next_lane = 0;
@@ -172,7 +181,8 @@ struct ivf_index {
 };
 
 static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
-                             int64_t* ids_dev, float* dists_dev);
+                             int64_t* ids_dev, float* dists_dev, bool lazy = false);
+static bool wait_done_word(const unsigned long long* word, unsigned long long want);
 
 // ---- workspace for callers that cannot allocate (ivf_search_device_noalloc) -----------------------
 // One fixed array per GPU, held until the process ends.  In host code the array's name is only a
@@ -208,6 +218,8 @@ void free_workspace(Workspace& w) {
     dfree(w.d_sort_keys); dfree(w.d_sort_idx); dfree(w.d_part); dfree(w.d_heads);
     dfree(w.d_desc);
     dfree(w.d_out_ids); dfree(w.d_out_dists);
+    dfree(w.d_redo_flag); dfree(w.d_redo_thr); dfree(w.d_redo_ticket);
+    dfree(w.d_redo_id); dfree(w.d_redo_key); hfree(w.h_flag);
     hfree(w.h_q); hfree(w.h_done); hfree(w.h_probe); hfree(w.h_out_ids); hfree(w.h_out_dists);
     hfree(w.h_cand); hfree(w.h_cand_count); hfree(w.h_scores);
     dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row);
@@ -237,6 +249,13 @@ int scan_grid_for(ivf_index* ix, int nprobe, int kprime, int nq) {
 }
 // scan workgroups of all queries of a call together: an upper bound of nq * scan_grid_for(.., nq') for nq' <= nq
 size_t scan_workgroup_bound(const ivf_index* ix, int nq) { return (size_t)4 * ix->n_cu * kScanMaxWgPerCu + (size_t)nq; }
+// workgroups per query of the exact second pass: 64 for one query, fewer when a call has many
+int redo_grid_for(int nq) { return std::max(1, 64 / std::max(nq, 1)); }
+// entries of the lists it leaves behind, all queries of a call together (a bound for every nq' <= nq)
+size_t redo_entries_bound(int nq, int k) { return (size_t)std::max(64, nq) * kRedoListsPerWg * (size_t)k; }
+
+int enqueue_redo(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, bool with_host,
+                 int64_t* out_ids, float* out_dists);
 
 void use_lane(ivf_index* ix, size_t i) {
     ix->cs = ix->lanes[i].stream;
@@ -254,17 +273,24 @@ int settle_lane(ivf_index* ix, size_t i) {
     l.pending.on = false;
     const ivf_index::Pending pd = l.pending;
     int r = IVF_OK;
-    hipError_t e = hipStreamSynchronize(l.stream);
+    hipError_t e = hipSuccess;
+    // one query: its merge kernel set a completion word behind the flags; otherwise wait for the stream
+    if (pd.list_major || pd.nq != 1 || !wait_done_word(l.ws.h_done, pd.done_seq)) e = hipStreamSynchronize(l.stream);
     if (e != hipSuccess) r = fail(IVF_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
     const bool was_profiling = ix->profiling;
     ix->profiling = false;
     bool redone = false;
-    for (int qi = 0; qi < pd.nq && r == IVF_OK; ++qi)
-        if (l.ws.h_overflow[qi]) {
-            r = enqueue_per_query(ix, pd.q + (size_t)qi * ix->d, 1, pd.nprobe, pd.k, pd.ids + (size_t)qi * pd.k,
-                                  pd.dists + (size_t)qi * pd.k);
-            redone = true;
-        }
+    if (pd.list_major) {
+        for (int qi = 0; qi < pd.nq && r == IVF_OK; ++qi)
+            if (l.ws.h_overflow[qi]) {
+                r = enqueue_per_query(ix, pd.q + (size_t)qi * ix->d, 1, pd.nprobe, pd.k, pd.ids + (size_t)qi * pd.k,
+                                      pd.dists + (size_t)qi * pd.k);
+                redone = true;
+            }
+    } else if (r == IVF_OK) {
+        for (int qi = 0; qi < pd.nq; ++qi) redone = redone || l.ws.h_flag[qi] != 0;
+        if (redone) r = enqueue_redo(ix, pd.q, pd.nq, pd.nprobe, pd.k, kprime_for(pd.k), false, pd.ids, pd.dists);
+    }
     ix->profiling = was_profiling;
     if (r == IVF_OK && redone) {
         e = hipStreamSynchronize(l.stream);
@@ -311,6 +337,14 @@ int ensure_workspace(ivf_index* ix, int nq, int nprobe, int k) {
     HIP_TRY(hipMalloc(&w.d_heads, wgs * kScanWaves * sizeof(uint64_t)));
     HIP_TRY(hipMalloc(&w.d_out_ids, nqz * k2 * sizeof(int64_t)));
     HIP_TRY(hipMalloc(&w.d_out_dists, nqz * k2 * sizeof(float)));
+    HIP_TRY(hipMalloc(&w.d_redo_flag, nqz * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_redo_thr, nqz * sizeof(double)));
+    HIP_TRY(hipMalloc(&w.d_redo_ticket, nqz * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_redo_key, redo_entries_bound(nq2, k2) * sizeof(unsigned long long)));
+    HIP_TRY(hipMalloc(&w.d_redo_id, redo_entries_bound(nq2, k2) * sizeof(long long)));
+    HIP_TRY(hipHostMalloc(&w.h_flag, nqz * sizeof(uint32_t)));
+    HIP_TRY(hipHostGetDevicePointer((void**)&w.hd_flag, w.h_flag, 0));
+    memset(w.h_flag, 0, nqz * sizeof(uint32_t));
     HIP_TRY(hipHostMalloc(&w.h_q, nqz * ix->d * sizeof(float)));
     HIP_TRY(hipHostGetDevicePointer((void**)&w.hd_q, w.h_q, 0));
     HIP_TRY(hipHostMalloc(&w.h_done, sizeof(unsigned long long)));
@@ -415,7 +449,7 @@ int enqueue_probe(ivf_index* ix, const float* q_dev, int nq, int nprobe, int gri
 int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kprime, int grid) {
     Workspace& w = *ix->cw;
     ScanArgs sc{};
-    sc.buf = ix->d_buf; sc.q = q_dev; sc.idrank = ix->d_idrank; sc.slots = w.slots;
+    sc.buf = ix->d_buf; sc.q = q_dev; sc.slots = w.slots;
     sc.part = w.d_part; sc.heads = w.d_heads;
     sc.desc = w.d_desc;
     sc.d = ix->d; sc.dtype = ix->dtype; sc.metric = ix->metric; sc.nprobe = nprobe; sc.nq = nq;
@@ -427,11 +461,15 @@ int enqueue_scan(ivf_index* ix, const float* q_dev, int nq, int nprobe, int kpri
     return IVF_OK;
 }
 
+// host_flags: the proof flags also go to the pinned array (searches whose caller waits on the host)
 int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, int grid,
-                  bool with_host, int64_t* out_ids, float* out_dists, bool signal_done = false) {
+                  bool with_host, int64_t* out_ids, float* out_dists, bool signal_done = false, bool host_flags = false) {
     Workspace& w = *ix->cw;
     MergeArgs ma{};
-    ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.rowof = ix->d_rowof; ma.slots = w.slots;
+    ma.buf = ix->d_buf; ma.q = q_dev; ma.ids = ix->d_ids; ma.slots = w.slots;
+    ma.err_coef = ix->err_coef; ma.row_norm_max = ix->row_norm_max;
+    ma.redo_flag = w.d_redo_flag; ma.redo_thr = w.d_redo_thr; ma.redo_ticket = w.d_redo_ticket;
+    ma.host_flag = host_flags ? w.hd_flag : nullptr;
     ma.part = w.d_part; ma.heads = w.d_heads;
     ma.host_cand = with_host ? w.h_cand : nullptr;
     ma.host_count = with_host ? w.h_cand_count : nullptr;
@@ -444,6 +482,24 @@ int enqueue_merge(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, 
     int rc = prof_events(ix, 3, &e0, &e1);
     if (rc) return rc;
     HIP_TRY(launch_merge(ma, ix->cs, e0, e1));
+    return IVF_OK;
+}
+
+// The exact second pass for the queries whose merge could not prove its result; queries that were
+// proven cost one workgroup round that leaves at once.
+int enqueue_redo(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int kprime, bool with_host,
+                 int64_t* out_ids, float* out_dists) {
+    Workspace& w = *ix->cw;
+    RedoArgs ra{};
+    ra.buf = ix->d_buf; ra.q = q_dev; ra.ids = ix->d_ids; ra.slots = w.slots;
+    ra.redo_flag = w.d_redo_flag; ra.redo_thr = w.d_redo_thr; ra.redo_ticket = w.d_redo_ticket;
+    ra.list_key = w.d_redo_key; ra.list_id = w.d_redo_id;
+    ra.host_cand = with_host ? w.h_cand : nullptr;
+    ra.host_count = with_host ? w.h_cand_count : nullptr;
+    ra.out_ids = out_ids; ra.out_dists = out_dists;
+    ra.d = ix->d; ra.dtype = ix->dtype; ra.metric = ix->metric; ra.nprobe = nprobe; ra.nq = nq; ra.k = k;
+    ra.kprime = kprime;
+    HIP_TRY(launch_redo(ra, redo_grid_for(nq), ix->cs));
     return IVF_OK;
 }
 
@@ -551,49 +607,13 @@ int init_common(ivf_index* ix, int64_t n, int32_t d, int dtype, const float* cen
     HIP_TRY(hipMemset(ix->d_prof_rows, 0, sizeof(unsigned long long)));
     HIP_TRY(hipDeviceSynchronize());
     ix->shape = pick_scan_shape(d, dtype);
+    ix->err_coef = scan_error_coef(ix->shape, d, dtype, metric);
     // looked up here so that the entry point that must not allocate does no first-use work
     unsigned char* sp = nullptr;
     int rc = scratch_for_device(ix->device, &sp);
     if (rc) return rc;
     for (int cls = 0; cls < 2; ++cls)
         ix->resident_grid[cls] = scan_resident_grid(ix->shape, dtype, metric, cls ? 128 : 64, d, ix->n_cu);
-    return IVF_OK;
-}
-
-// Equal keys are ordered by smaller id.  The kernels carry, instead of the 64-bit id, the rank of
-// the id among all ids (ties between equal ids by row), which fits the low half of a packed
-// candidate; this builds row -> rank and rank -> row.  Nothing is needed when ids already grow
-// with the row position.
-int upload_id_ranks(ivf_index* ix) {
-    const int64_t n = ix->n;
-    const int64_t* ids = ix->h_ids.data();
-    bool increasing = true;
-    for (int64_t i = 1; i < n && increasing; ++i) increasing = ids[i - 1] < ids[i];
-    if (increasing) return IVF_OK;
-    std::vector<uint32_t> rank((size_t)n), rowof((size_t)n);
-    // the usual case, ids = positions in the caller's input: a permutation of 0..n-1 is its own rank
-    bool permutation = true;
-    {
-        std::vector<bool> seen((size_t)n, false);
-        for (int64_t i = 0; i < n && permutation; ++i) {
-            const int64_t v = ids[i];
-            if (v < 0 || v >= n || seen[(size_t)v]) permutation = false;
-            else seen[(size_t)v] = true;
-        }
-    }
-    if (permutation) {
-        for (int64_t i = 0; i < n; ++i) { rank[(size_t)i] = (uint32_t)ids[i]; rowof[(size_t)ids[i]] = (uint32_t)i; }
-    } else {
-        for (int64_t i = 0; i < n; ++i) rowof[(size_t)i] = (uint32_t)i;
-        std::sort(rowof.begin(), rowof.end(), [ids](uint32_t x, uint32_t y) {
-            return ids[x] < ids[y] || (ids[x] == ids[y] && x < y);
-        });
-        for (int64_t r = 0; r < n; ++r) rank[rowof[(size_t)r]] = (uint32_t)r;
-    }
-    HIP_TRY(hipMalloc(&ix->d_idrank, (size_t)n * sizeof(uint32_t)));
-    HIP_TRY(hipMalloc(&ix->d_rowof, (size_t)n * sizeof(uint32_t)));
-    HIP_TRY(hipMemcpy(ix->d_idrank, rank.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(ix->d_rowof, rowof.data(), (size_t)n * sizeof(uint32_t), hipMemcpyHostToDevice));
     return IVF_OK;
 }
 
@@ -604,8 +624,6 @@ int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
     if (!ix->h_ids.empty()) {
         HIP_TRY(hipMalloc(&ix->d_ids, (size_t)ix->n * sizeof(int64_t)));
         HIP_TRY(hipMemcpy(ix->d_ids, ix->h_ids.data(), (size_t)ix->n * sizeof(int64_t), hipMemcpyHostToDevice));
-        int rc = upload_id_ranks(ix);
-        if (rc != IVF_OK) return rc;
     }
     ix->h_res_off.assign(nlist, -1);
     if (ix->placement == IVF_PLACE_DEVICE) {
@@ -620,12 +638,20 @@ int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
         ix->pool.reset(new ThreadPool(nt));
     }
     HIP_TRY(hipMemcpy(ix->d_res_off, ix->h_res_off.data(), (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice));
-    if (ix->placement == IVF_PLACE_DEVICE && ix->dtype != IVF_F32) {
+    // the largest row norm: part of the rounding bounds of the scans
+    if (ix->placement == IVF_PLACE_DEVICE) {
         HIP_TRY(hipMalloc(&ix->d_row_norm_max, sizeof(unsigned int)));
         HIP_TRY(hipMemset(ix->d_row_norm_max, 0, sizeof(unsigned int)));
         HIP_TRY(hipDeviceSynchronize());
         HIP_TRY(launch_row_norm_max(ix->d_buf, ix->dtype, ix->n, ix->d, ix->d_row_norm_max, ix->compute));
         HIP_TRY(hipStreamSynchronize(ix->compute));
+        unsigned int bits = 0;
+        HIP_TRY(hipMemcpy(&bits, ix->d_row_norm_max, sizeof bits, hipMemcpyDeviceToHost));
+        float sq;
+        memcpy(&sq, &bits, sizeof sq);
+        ix->row_norm_max = sqrtf(sq) * 1.0001f;         // the kernel sums in fp32
+    } else {
+        ix->row_norm_max = host_row_norm_max(ix->h_lists, ix->dtype, ix->n, ix->d, *ix->pool) * 1.0001f;
     }
     std::vector<uint64_t> sizes(nlist);
     for (int c = 0; c < nlist; ++c) sizes[c] = (uint64_t)(ix->h_off[c + 1] - ix->h_off[c]);
@@ -656,10 +682,11 @@ int check_build_args(const void* data, int64_t n, int32_t d, int dtype, const fl
 
 extern "C" void ivf_free(ivf_index* ix) {
     if (!ix) return;
+    for (size_t i = 0; i < ix->lanes.size(); ++i) (void)settle_lane(ix, i);     // what the lanes still owe their callers
     (void)hipDeviceSynchronize();
     for (auto& l : ix->lanes) { free_workspace(l.ws); if (l.own) (void)hipStreamDestroy(l.stream); }
     for (auto& s : ix->prof_sets) for (auto& e : s.e) (void)hipEventDestroy(e);
-    dfree(ix->d_centroids); dfree(ix->d_off); dfree(ix->d_ids); dfree(ix->d_idrank); dfree(ix->d_rowof);
+    dfree(ix->d_centroids); dfree(ix->d_off); dfree(ix->d_ids);
     dfree(ix->d_hot); dfree(ix->d_used); dfree(ix->d_move_tmp);
     for (auto& e : ix->ev_cache) if (e) (void)hipEventDestroy(e);
     dfree(ix->d_res_off);
@@ -837,6 +864,7 @@ static double now_ms() {
 // Watches a completion word for up to two milliseconds; false when it did not arrive in that time
 // (the caller then waits for the stream, which also brings any launch error to light).
 static bool wait_done_word(const unsigned long long* word, unsigned long long want) {
+    if (__atomic_load_n(word, __ATOMIC_ACQUIRE) == want) return true;
     const double t_end = now_ms() + 2.0;
     for (;;) {
         for (int i = 0; i < 256; ++i) {
@@ -848,15 +876,19 @@ static bool wait_done_word(const unsigned long long* word, unsigned long long wa
 }
 
 // Device-pointer search of nq queries, query by query in one launch sequence (grid.y = nq).
+// lazy: no second pass is enqueued; the proof flags go to the pinned array (and, for one query, a
+// completion word follows them) and the caller looks at them later (settle_lane)
 static int enqueue_per_query(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k,
-                             int64_t* ids_dev, float* dists_dev) {
+                             int64_t* ids_dev, float* dists_dev, bool lazy) {
     int r;
     if ((r = ensure_workspace(ix, nq, nprobe, k))) return r;
     const int kprime = kprime_for(k);
     const int grid = scan_grid_for(ix, nprobe, kprime, nq);
     if ((r = enqueue_probe(ix, q_dev, nq, nprobe, grid, true, true))) return r;
     if ((r = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid))) return r;
-    return enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+    if ((r = enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev, lazy && nq == 1, lazy))) return r;
+    if (lazy) return IVF_OK;
+    return enqueue_redo(ix, q_dev, nq, nprobe, k, kprime, false, ids_dev, dists_dev);
 }
 
 // List-major batched search into device outputs.  Synchronises the stream to read the overflow
@@ -868,7 +900,7 @@ static int run_batched(ivf_index* ix, size_t lane, const float* q_dev, int nq, i
     if ((r = ensure_batched_workspace(ix, nq, nprobe))) return r;
     if ((r = enqueue_batched(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev))) return r;
     ivf_index::Pending& pd = ix->lanes[lane].pending;
-    pd.on = true; pd.q = q_dev; pd.nq = nq; pd.nprobe = nprobe; pd.k = k; pd.ids = ids_dev; pd.dists = dists_dev;
+    pd.on = true; pd.list_major = true; pd.q = q_dev; pd.nq = nq; pd.nprobe = nprobe; pd.k = k; pd.ids = ids_dev; pd.dists = dists_dev;
     // the overflow flags are looked at when the lane is next needed (or at ivf_synchronize), so that
     // the first kernels of the next batch, on another lane, run beside this batch's scan
     return defer ? IVF_OK : settle_lane(ix, lane);
@@ -890,13 +922,24 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
     if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
     if (ix->placement != IVF_PLACE_DEVICE)
         return fail(IVF_ESTATE, "ivf_search_device needs a device-resident index");
+    if (((uintptr_t)q_dev & 15u) != 0) return fail(IVF_EINVAL, "q_dev must be 16-byte aligned");
     nprobe = std::min(nprobe, ix->nlist);
     const size_t lane = ix->next_lane;
     if ((rc = settle_lane(ix, lane))) return rc;
     use_lane(ix, lane);
     ix->next_lane = (ix->next_lane + 1) % ix->lanes.size();
     if (batched_eligible(ix, nq)) rc = run_batched(ix, lane, q_dev, nq, nprobe, k, ids_dev, dists_dev, true);
-    else rc = enqueue_per_query(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev);
+    else {
+        // one stream: the exact second pass follows every merge on the stream, outputs are complete in
+        // stream order.  Several: it is decided when the lane is next needed or in ivf_synchronize.
+        const bool lazy = ix->lanes.size() > 1;
+        rc = enqueue_per_query(ix, q_dev, nq, nprobe, k, ids_dev, dists_dev, lazy);
+        if (rc == IVF_OK && lazy) {
+            ivf_index::Pending& pd = ix->lanes[lane].pending;
+            pd.on = true; pd.list_major = false; pd.q = q_dev; pd.nq = nq; pd.nprobe = nprobe; pd.k = k;
+            pd.ids = ids_dev; pd.dists = dists_dev; pd.done_seq = ix->lanes[lane].ws.done_seq;
+        }
+    }
     use_lane(ix, 0);
     return rc;
 }
@@ -904,7 +947,7 @@ extern "C" int ivf_search_device(ivf_index* ix, const float* q_dev, int32_t nq, 
 // Carves the device buffers of a query-by-query search out of `base` (256-byte aligned pieces) and
 // returns the bytes needed; with base == nullptr only the size is computed.
 static size_t carve_search_buffers(Workspace& w, unsigned char* base, const ivf_index* ix, int nq, int nprobe,
-                                   int kprime, int grid, uint32_t pad) {
+                                   int k, int kprime, int grid, uint32_t pad) {
     size_t at = 0;
     auto take = [&](size_t bytes) -> void* {
         void* p = base ? base + at : nullptr;
@@ -925,6 +968,12 @@ static size_t carve_search_buffers(Workspace& w, unsigned char* base, const ivf_
     }
     w.d_part = (uint64_t*)take(nqz * gz * kScanWaves * cand_slots(kprime) * sizeof(uint64_t));
     w.d_heads = (uint64_t*)take(nqz * gz * kScanWaves * sizeof(uint64_t));
+    w.d_redo_flag = (uint32_t*)take(nqz * sizeof(uint32_t));
+    w.d_redo_thr = (double*)take(nqz * sizeof(double));
+    w.d_redo_ticket = (uint32_t*)take(nqz * sizeof(uint32_t));
+    const size_t redo_entries = nqz * redo_grid_for(nq) * kRedoListsPerWg * (size_t)k;
+    w.d_redo_key = (unsigned long long*)take(redo_entries * sizeof(unsigned long long));
+    w.d_redo_id = (long long*)take(redo_entries * sizeof(long long));
     return at;
 }
 
@@ -937,6 +986,7 @@ extern "C" int ivf_search_device_noalloc(ivf_index* ix, const float* q_dev, int3
     if (k > IVF_MAX_K) return fail(IVF_ELIMIT, "k = %d is above IVF_MAX_K = %d", k, IVF_MAX_K);
     if (ix->placement != IVF_PLACE_DEVICE)
         return fail(IVF_ESTATE, "ivf_search_device_noalloc needs a device-resident index");
+    if (((uintptr_t)q_dev & 15u) != 0) return fail(IVF_EINVAL, "q_dev must be 16-byte aligned");
     for (auto& l : ix->lanes)
         if (l.pending.on) return fail(IVF_ESTATE, "a list-major batch is unfinished: call ivf_synchronize() first");
     nprobe = std::min(nprobe, ix->nlist);
@@ -944,13 +994,13 @@ extern "C" int ivf_search_device_noalloc(ivf_index* ix, const float* q_dev, int3
     const int grid = scan_grid_for(ix, nprobe, kprime, nq);
     const uint32_t pad = select_sort_pad(ix->nlist, nprobe);
     Workspace w{};
-    const size_t need = carve_search_buffers(w, nullptr, ix, nq, nprobe, kprime, grid, pad);
+    const size_t need = carve_search_buffers(w, nullptr, ix, nq, nprobe, k, kprime, grid, pad);
     if (need > kScratchBytes)
         return fail(IVF_ELIMIT, "this search needs %zu bytes of workspace, the fixed scratch area holds %zu "
                     "(nq %d, nprobe %d, k %d): use ivf_search_device", need, kScratchBytes, nq, nprobe, k);
     unsigned char* sp = nullptr;
     if ((rc = scratch_for_device(ix->device, &sp))) return rc;
-    carve_search_buffers(w, sp, ix, nq, nprobe, kprime, grid, pad);
+    carve_search_buffers(w, sp, ix, nq, nprobe, k, kprime, grid, pad);
     w.nq = nq; w.nprobe = nprobe; w.k = k; w.kprime = kprime; w.pad = pad; w.wg_cap = (size_t)grid * nq;
     // the kernels of one call only ever read what an earlier kernel of the same call wrote, so
     // nothing in the area has to start at zero
@@ -959,6 +1009,7 @@ extern "C" int ivf_search_device_noalloc(ivf_index* ix, const float* q_dev, int3
     rc = enqueue_probe(ix, q_dev, nq, nprobe, grid, true, true);
     if (!rc) rc = enqueue_scan(ix, q_dev, nq, nprobe, kprime, grid);
     if (!rc) rc = enqueue_merge(ix, q_dev, nq, nprobe, k, kprime, grid, false, ids_dev, dists_dev);
+    if (!rc) rc = enqueue_redo(ix, q_dev, nq, nprobe, k, kprime, false, ids_dev, dists_dev);
     ix->cs = cs; ix->cw = cw;
     return rc;
 }
@@ -1029,8 +1080,10 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
             if (hybrid) {
                 HostScanArgs ha{ix->h_lists, ix->h_off.data(), ix->h_ids.empty() ? nullptr : ix->h_ids.data(),
                                 ix->d, ix->dtype, ix->metric, q_out + (size_t)qi * ix->d,
-                                miss.data(), (int)miss.size(), kprime};
-                w.h_cand_count[qi] = host_scan_query(ha, *ix->pool, w.h_cand + (size_t)qi * kprime, nullptr);
+                                miss.data(), (int)miss.size(), kprime, k, ix->row_norm_max};
+                bool exact_pass = false;
+                w.h_cand_count[qi] = host_scan_query(ha, *ix->pool, w.h_cand + (size_t)qi * kprime, nullptr, &exact_pass);
+                st.n_exact_host += exact_pass ? 1 : 0;
             }
         }
         st.ms_host_scan = (float)(now_ms() - ts);
@@ -1040,8 +1093,15 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
     // One query: the kernel also sets a completion word after the results; the host watches that
     // word instead of waiting for the stream to drain (the stream keeps its order for later calls).
     const bool watch = nq == 1;
-    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.hd_out_ids, w.hd_out_dists, watch))) return rc;
+    if ((rc = enqueue_merge(ix, w.d_q, nq, nprobe, k, kprime, grid, hybrid, w.hd_out_ids, w.hd_out_dists, watch, true))) return rc;
     if (!watch || !wait_done_word(w.h_done, w.done_seq)) HIP_TRY(hipStreamSynchronize(ix->cs));
+    // a query whose result the merge could not prove gets the exact second pass (rare)
+    bool redo = false;
+    for (int qi = 0; qi < nq; ++qi) { redo = redo || w.h_flag[qi] != 0; st.n_exact_gpu += w.h_flag[qi] != 0 ? 1 : 0; }
+    if (redo) {
+        if ((rc = enqueue_redo(ix, w.d_q, nq, nprobe, k, kprime, hybrid, w.hd_out_ids, w.hd_out_dists))) return rc;
+        HIP_TRY(hipStreamSynchronize(ix->cs));
+    }
     memcpy(ids, w.h_out_ids, (size_t)nq * k * sizeof(int64_t));
     memcpy(dists, w.h_out_dists, (size_t)nq * k * sizeof(float));
     st.ms_total = (float)(now_ms() - t0);
@@ -1454,7 +1514,7 @@ extern "C" int ivf_host_scan(const void* lists, const int64_t* offsets, const in
     const int kprime = kprime_for(k);
     ThreadPool pool(threads);
     std::vector<HostCand> cand((size_t)kprime);
-    HostScanArgs ha{lists, offsets, ids, d, dtype, metric, q, clusters, n_clusters, kprime};
+    HostScanArgs ha{lists, offsets, ids, d, dtype, metric, q, clusters, n_clusters, kprime, k, 0.f};
     const int n = host_scan_query(ha, pool, cand.data(), nullptr);
     for (int i = 0; i < n; ++i) {
         out_ids[i] = cand[i].id;

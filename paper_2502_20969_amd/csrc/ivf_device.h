@@ -297,6 +297,119 @@ __device__ void block_radix_select(KeyAt key_at, uint32_t n, uint32_t want, uint
     }
 }
 
+// ---- block-wide bucket cut ----------------------------------------------------------------------
+// A coarse cut for "the `want` largest of n 32-bit values" in one pass over a 256-bucket
+// histogram (three barriers; the sorting networks cost several times that in a kernel of one
+// workgroup).  The bucket of a value is a monotone function of it over the range [lo, hi] of the
+// values present; `cut` is the highest bucket such that at least `want` values fall into buckets
+// >= cut.  Values below the range are not counted (they would all land on one counter); when
+// fewer than `want` values lie in the range, everything passes.  Every one of the `want` largest
+// values passes, and so does anything, also from outside the set, that is not smaller than one
+// of them.
+struct BucketCut {
+    uint32_t lo;             // lower end of the range (0 when everything passes)
+    float scale;
+    uint32_t cut;
+    uint32_t passing;        // values of the set that pass; all ones when everything passes (not counted then)
+    __device__ __forceinline__ uint32_t bucket(uint32_t v) const {      // v >= lo
+        const uint32_t b = (uint32_t)((float)(v - lo) * scale);
+        return b > 255u ? 255u : b;
+    }
+    __device__ __forceinline__ bool pass(uint32_t v) const { return v >= lo && bucket(v) >= cut; }
+};
+
+// val_at(i), i < n: the values (0 = no value, ignored).  hist: 256 words of LDS; red: 96 words of
+// LDS.  Must be called by all threads of the block (64 to 1024, a multiple of 64).
+//
+// The lower end of the range decides how fine the buckets are where it matters.  The threads
+// are taken in 64 groups and every group folds its values into a maximum: when at least `want`
+// groups hold a value, the smallest of those maxima has `want` values at or above it and is
+// used as the lower end (values below it all fall into bucket 0); otherwise the smallest value
+// is.  If the cut still lets more than about twice `want` values pass, the range is narrowed to
+// the buckets from the cut upwards and the histogram is taken again (at most twice).
+template <typename ValAt>
+__device__ __forceinline__ BucketCut block_bucket_cut(ValAt val_at, uint32_t n, uint32_t want, uint32_t* hist, uint32_t* red) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id();
+    const int per_group = nt >> 6;                      // lanes per group: a power of two up to 16, inside one wavefront
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+    for (uint32_t i = tid; i < n; i += nt) {
+        const uint32_t v = val_at(i);
+        if (v) { lo = min(lo, v); hi = max(hi, v); }
+    }
+    uint32_t gmax = hi;
+    for (int m = 1; m < per_group; m <<= 1) gmax = max(gmax, (uint32_t)__shfl_xor((int)gmax, m));
+    if ((lane & (per_group - 1)) == 0) red[8 + tid / per_group] = gmax;        // red[8 .. 71]: the group maxima
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) lo = min(lo, (uint32_t)__shfl_xor((int)lo, m));
+    if (lane == 0) red[72 + wave] = lo;                 // red[72 .. 87]: the wavefronts' smallest values
+    for (int i = tid; i < 256; i += nt) hist[i] = 0;
+    __syncthreads();
+    {
+        // all threads fold the 64 group maxima (lane l of every wavefront reads group l)
+        const uint32_t g = red[8 + lane];
+        uint32_t g_lo = g ? g : 0xFFFFFFFFu, g_hi = g;
+        const uint32_t groups = (uint32_t)__popcll(__ballot(g != 0));
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            g_lo = min(g_lo, (uint32_t)__shfl_xor((int)g_lo, m));
+            g_hi = max(g_hi, (uint32_t)__shfl_xor((int)g_hi, m));
+        }
+        uint32_t w_lo = lane < (nt >> 6) ? red[72 + lane] : 0xFFFFFFFFu;
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) w_lo = min(w_lo, (uint32_t)__shfl_xor((int)w_lo, m));
+        w_lo = (uint32_t)__shfl((int)w_lo, 0);
+        hi = g_hi;
+        lo = groups >= want ? g_lo : w_lo;
+    }
+    BucketCut bc;
+    bc.lo = lo;
+    bc.scale = hi > lo ? 255.5f / (float)(hi - lo) : 0.f;
+    bc.cut = 0; bc.passing = 0;
+#pragma unroll 1
+    for (int round = 0; round < 3; ++round) {
+        for (uint32_t i = tid; i < n; i += nt) {
+            const uint32_t v = val_at(i);
+            if (v != 0 && v >= bc.lo) atomicAdd(&hist[bc.bucket(v)], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t c[4], s4 = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) { c[b] = hist[4 * lane + b]; s4 += c[b]; }
+            uint32_t from_top = s4;                    // values in the buckets of this lane and of all higher lanes
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t dn = __shfl_down(from_top, o);
+                if (lane + o < 64) from_top += dn;
+            }
+            const uint32_t above = from_top - s4;
+            if (lane == 0 && from_top < want) { red[2] = 0xFFFFFFFFu; red[3] = 0xFFFFFFFFu; }
+            if (above < want && want <= from_top) {
+                uint32_t run = above;
+#pragma unroll
+                for (int b = 3; b >= 0; --b) {
+                    if (run < want && want <= run + c[b]) { red[2] = (uint32_t)(4 * lane + b); red[3] = run + c[b]; }
+                    run += c[b];
+                }
+            }
+        }
+        __syncthreads();
+        bc.cut = red[2];
+        bc.passing = red[3];
+        if (bc.cut == 0xFFFFFFFFu) { bc.lo = 0u; bc.scale = 0.f; bc.cut = 0u; break; }      // fewer than `want` in the range: all pass
+        if (round == 2 || bc.cut < 2 || bc.passing <= 2 * want + 16 || bc.scale == 0.f) break;
+        // narrow the range to the buckets from one below the cut upwards (the edge is rounded down, so
+        // nothing that passed is lost; what now falls below the range lands in bucket 0)
+        const uint32_t edge = bc.lo + (uint32_t)((float)(bc.cut - 1) / bc.scale);
+        bc.lo = min(max(edge, bc.lo), hi);
+        bc.scale = hi > bc.lo ? 255.5f / (float)(hi - bc.lo) : 0.f;
+        bc.cut = 0;
+        for (int i = tid; i < 256; i += nt) hist[i] = 0;
+        __syncthreads();                                // the histogram is clear, and red[2], red[3] were read, before the next round
+    }
+    return bc;
+}
+
 // ---- block-wide bitonic sort of (key, idx) pairs, ascending by key then idx --------------------
 // n must be a power of two.  keys/idx may point to LDS or to global memory.
 __device__ inline void block_bitonic_sort(uint64_t* keys, uint32_t* idx, uint32_t n) {

@@ -84,11 +84,10 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t start = 
 struct ScanArgs {
     const void* buf;         // device buffer holding resident lists, row-major
     const float* q;          // [nq x d]
-    const uint32_t* idrank;  // [n] global row -> rank of its id among all ids, or nullptr (rank = global row)
     SlotTables slots;
     const WgDesc* desc;      // [nq x grid]
     uint64_t* part;          // [nq x (grid x kScanWaves) x cand_slots(kprime)] out: one list of packed candidates
-                             // (fp32 key image << 32 | ~rank) per wavefront, unordered, 0 = empty
+                             // (fp32 key image << 32 | ~global row) per wavefront, unordered, 0 = empty
     uint64_t* heads;         // [nq x (grid x kScanWaves)] out: the best entry of every list, packed densely for the merge
     int d, dtype, metric, nprobe, nq, kprime, grid;
     ScanShape shape;
@@ -100,7 +99,6 @@ int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime
 struct MergeArgs {
     const void* buf; const float* q;
     const int64_t* ids;          // [n] global row -> id, or nullptr (id = global row)
-    const uint32_t* rowof;       // [n] id rank -> global row, or nullptr (row = rank)
     SlotTables slots;
     const uint64_t* part;        // [nq x nparts x slots] packed candidates written by the scan, lists unordered
     const uint64_t* heads;       // [nq x nparts] the lists' best entries
@@ -112,8 +110,34 @@ struct MergeArgs {
     // Completion word in pinned host memory (device address) or nullptr: set to done_value after
     // the results are visible to the host.  Only for nq == 1 (one workgroup writes it).
     unsigned long long* done; unsigned long long done_value;
+    // The proof that no dropped row belongs to the k nearest (merge_kernel, step 5): bound of the
+    // scan's fp32 rounding and the largest row norm of the lists; redo_flag[qi] (nullable) receives 1
+    // when the proof fails, with the k-th best score found in redo_thr[qi] and the counter of the
+    // exact second pass zeroed; host_flag (nullable, pinned) receives the same flag for the host.
+    float err_coef, row_norm_max;
+    uint32_t* redo_flag; double* redo_thr; uint32_t* redo_ticket;
+    uint32_t* host_flag;
 };
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+
+// The exact second pass (exact_redo_kernel) for the queries merge_kernel flagged: `grid` workgroups of
+// kRedoListsPerWg wavefronts per query, each wavefront leaving a list of k entries.
+constexpr int kRedoListsPerWg = 4;
+struct RedoArgs {
+    const void* buf; const float* q;
+    const int64_t* ids;          // [n] global row -> id, or nullptr
+    SlotTables slots;
+    const uint32_t* redo_flag; const double* redo_thr; uint32_t* redo_ticket;
+    unsigned long long* list_key;    // [nq x grid x kRedoListsPerWg x k] scores as ascending-order keys, 0 = empty
+    long long* list_id;              // [same] the rows' ids
+    const HostCand* host_cand; const int32_t* host_count;
+    int64_t* out_ids; float* out_dists;
+    unsigned long long* done; unsigned long long done_value;
+    int d, dtype, metric, nprobe, nq, k, kprime;
+};
+hipError_t launch_redo(const RedoArgs& a, int grid, hipStream_t s);
+// bound coefficient of the scan's fp32 rounding for (shape, d, metric): see result_is_safe
+float scan_error_coef(const ScanShape& shape, int d, int dtype, int metric);
 
 // cluster cache bookkeeping: hot[c] < 0 = not cached
 hipError_t launch_cache_admit(float* hot, uint32_t* used, const int64_t* res_off, int nlist, float h_init, int reset,

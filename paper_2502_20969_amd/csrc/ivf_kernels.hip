@@ -3,6 +3,7 @@
 // The operations are those of TeleRAG (arxiv 2502.20969) App. B: coarse search over the
 // centroids, fine search over the rows of the selected clusters, k nearest by a sort.
 #include "ivf_device.h"
+#include "../../include/ivf.h"
 #include <hip/hip_ext.h>
 #include <algorithm>
 
@@ -224,11 +225,57 @@ __device__ __forceinline__ void select_sorted(const SelectArgs& a, const double*
     block_bitonic_sort(keys, idx, pad);
 }
 
+// The nprobe nearest by a bucket cut (see block_bucket_cut) over the high halves of the keys: the
+// clusters that pass the cut (the nprobe nearest and a few more) are pooled with their full keys
+// and each counts the pooled clusters ahead of it by (key, index); the first nprobe take their
+// places in idx.  Exact, with no sorting network.  Returns false (for the whole workgroup) when
+// more clusters pass than the pool holds (masses of equal scores); idx is then untouched.
+constexpr int kSelectPoolCap = 1024;
+constexpr int kSelectCutMax = 512;          // largest nprobe this path takes
+__device__ __forceinline__ bool select_by_cut(const SelectArgs& a, const double* sc, uint32_t* idx, uint64_t* pool_key,
+                                              uint32_t* pool_idx, uint32_t* hist, uint32_t* red, uint32_t* sh) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const uint32_t nlist = a.nlist, nprobe = a.nprobe;
+    auto key_at = [&](uint32_t i) { return coarse_key(sc[i], a.metric); };
+    // larger = nearer; never 0, so that every cluster counts
+    auto near_at = [&](uint32_t i) -> uint32_t { const uint32_t v = (uint32_t)(~key_at(i) >> 32); return v ? v : 1u; };
+    if (tid == 0) sh[4] = 0;
+    const BucketCut bc = block_bucket_cut(near_at, nlist, nprobe, hist, red);
+    if (bc.passing > (uint32_t)kSelectPoolCap) return false;
+    for (uint32_t i = tid; i < nlist; i += nt) {
+        if (bc.pass(near_at(i))) {
+            const uint32_t p = atomicAdd(&sh[4], 1u);
+            pool_key[p] = key_at(i); pool_idx[p] = i;
+        }
+    }
+    __syncthreads();
+    const uint32_t cnt = sh[4];
+#pragma unroll 1
+    for (uint32_t t = tid; t < cnt; t += nt) {
+        const uint64_t mk = pool_key[t];
+        const uint32_t mi = pool_idx[t];
+        uint32_t rank = 0;
+        // eight others per pass, all read before any is compared
+#pragma unroll 1
+        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {
+            uint64_t ok[8]; uint32_t oi[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { const uint32_t j = min(j0 + u, cnt - 1); ok[u] = pool_key[j]; oi[u] = pool_idx[j]; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) rank += (uint32_t)(((ok[u] < mk) | ((ok[u] == mk) & (oi[u] < mi))) & (j0 + u < cnt));
+        }
+        if (rank < nprobe) idx[rank] = mi;
+    }
+    __syncthreads();
+    return true;
+}
+
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, uint32_t pad, int in_lds,
-                                                                int prefix_in_lds) {
+                                                                int prefix_in_lds, int by_cut) {
     extern __shared__ unsigned char smem_raw[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh[8];
+    __shared__ uint32_t red[96];
     __shared__ uint32_t scan_buf[kSelectThreads / 64 + 1];
     const int tid = threadIdx.x, nt = blockDim.x;
     const int qi = blockIdx.x;
@@ -304,7 +351,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
     } else if (in_lds) {
         uint64_t* keys = (uint64_t*)smem_raw;
         idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
-        select_sorted(a, sc, keys, idx, pad, hist, sh);
+        bool done = false;
+        if (by_cut) {
+            uint64_t* pool_key = (uint64_t*)(((uintptr_t)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4) + 15) & ~(uintptr_t)15);
+            done = select_by_cut(a, sc, idx, pool_key, (uint32_t*)(pool_key + kSelectPoolCap), hist, red, sh);
+        }
+        if (!done) {
+            __syncthreads();
+            select_sorted(a, sc, keys, idx, pad, hist, sh);
+        }
     } else {
         uint64_t* keys = a.sort_keys + (size_t)qi * pad;
         idx = a.sort_idx + (size_t)qi * pad;
@@ -434,8 +489,11 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
     // a workgroup with one wavefront per SIMD issues fastest when there is little work per thread
     const int threads = a.nlist <= 1024 && a.grid <= 1024 ? 256 : kSelectThreads;
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
-    if (in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax) lds += 16 + (size_t)(threads / 64) * 64 * 8;
-    IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds);
+    const bool wave_sort = in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax;
+    const int by_cut = in_lds && !wave_sort && a.nprobe <= kSelectCutMax;
+    if (wave_sort) lds += 16 + (size_t)(threads / 64) * 64 * 8;
+    if (by_cut) lds += 16 + (size_t)kSelectPoolCap * 12;
+    IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds, by_cut);
     return hipGetLastError();
 }
 
@@ -629,10 +687,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     WaveTopK<KL, false> top;
     top.init();
 
-    // `tie` receives the tie-break rank of batch row `lane` (lanes < RPB)
+    // `tie` receives the global row of batch row `lane` (lanes < RPB): equal keys come out by smaller row
     auto issue = [&](const Batch& b, uint4 (&v)[U][SEG], uint32_t& tie) {
-        const uint32_t tr = b.grow + min((uint32_t)lane, b.nr - 1);
-        tie = p.idrank ? p.idrank[tr] : tr;
+        tie = b.grow + min((uint32_t)lane, b.nr - 1);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             uint32_t r = min((uint32_t)(u * RPI + rsel), b.nr - 1);   // rows past the end re-read the last one
@@ -731,7 +788,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) 
             s = group_total_last_lane<64>(s);
             float ck = read_lane(METRIC == 0 ? s : -s, 63);
             if (ck >= top.thr) {
-                top.push(ck, p.idrank ? p.idrank[b.grow + r] : b.grow + r);
+                top.push(ck, b.grow + r);
                 if (top.pcount == 64) top.flush(p.kprime);
             }
         }
@@ -796,6 +853,19 @@ static size_t scan_lds_bytes(const ScanShape& sh, int d) {
     return sh.lanes_per_row == 0 ? (size_t)d * 4 : 0;      // only the fallback kernel stages the query
 }
 
+float scan_error_coef(const ScanShape& shape, int d, int dtype, int metric) {
+    // roundings on the longest path of one row's sum: the fused multiply-adds of a lane, then the tree over the lanes
+    int terms;
+    if (shape.lanes_per_row == 0) terms = (d + 63) / 64 + 6;
+    else {
+        int tree = 0;
+        for (int l = shape.lanes_per_row; l > 1; l >>= 1) ++tree;
+        terms = shape.segments * (dtype == 0 ? 4 : 8) + tree;
+    }
+    if (metric != 0) terms += 2;          // the difference is rounded before it is squared
+    return 1.05f * (float)(terms + 2) * 0x1p-24f;
+}
+
 int scan_resident_grid(const ScanShape& shape, int dtype, int metric, int kprime, int d, int n_cu) {
     ScanFn fn = scan_fn(shape, dtype, metric, kprime);
     if (!fn) return n_cu;
@@ -827,6 +897,7 @@ constexpr int kMergeFastThreads = 1024;
 
 struct MergeLds {
     uint32_t hist[256];
+    uint32_t red[96];
     uint32_t sh[8];
     Cand c_cand[kMaxKPrime];
     double f_key[2 * kMaxKPrime];
@@ -834,61 +905,37 @@ struct MergeLds {
 };
 
 // Fast path (kprime <= 64).  The scan left one unordered list of `slots` candidates per wavefront
-// and each list's best entry in `heads` (0: empty list).  Candidates are distinct.  Every thread
-// folds the heads l = tid, tid + nt, ... into their maximum; T0 is the kprime-th best of those
-// maxima (the kprime-th best head when there are no more heads than threads).  At least kprime
-// candidates reach T0, so the kprime best overall are among the entries >= T0 of the lists whose
-// head reaches T0.  Those are gathered, sorted in chunks of 64 and merged.  Returns false (for
-// the whole workgroup) when they did not fit `pool` (kMergeCandCap) or `qlist` (kMergeQlistCap).
+// and each list's best entry in `heads` (0: empty list).  Candidates are distinct.  A bucket cut
+// over the key halves of the heads finds a set of at least kprime heads that holds the kprime best
+// heads; the kprime best candidates overall are not smaller than the smallest of those, so they
+// pass the cut too, and they sit in lists whose head passes.  The passing entries of those lists
+// are pooled and ranked by counting (or, when there are many, sorted in chunks of 64 and merged).
+// Returns false (for the whole workgroup) when they did not fit `pool` (kMergeCandCap) or the
+// lists did not fit `qlist` (kMergeQlistCap).
 __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part, const Cand* heads, MergeLds& L,
                                             Cand* pool, uint32_t* qlist) {
     const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id(), nw = nt >> 6;
     const int kp = a.kprime, np = a.nparts, slots = a.list_len;
-    // 1. T0 from the list heads
+    // 1. the cut, from the list heads (the first two heads of a thread stay in registers)
     if (tid == 0) { L.sh[4] = 0; L.sh[5] = 0; }
-    Cand h0 = 0, h1 = 0, mine = 0;
-    {
-        int j = 0;
+    const Cand h0 = tid < np ? heads[tid] : (Cand)0;
+    const Cand h1 = tid + nt < np ? heads[tid + nt] : (Cand)0;
+    auto head_at = [&](uint32_t l) -> Cand { return l == (uint32_t)tid ? h0 : (l == (uint32_t)(tid + nt) ? h1 : heads[l]); };
+    auto key_half = [&](uint32_t l) -> uint32_t { return (uint32_t)(head_at(l) >> 32); };
+    const BucketCut bc = block_bucket_cut(key_half, (uint32_t)np, (uint32_t)kp, L.hist, L.red);
+    // 2. the lists whose head passes ...
 #pragma unroll 1
-        for (int l = tid; l < np; l += nt, ++j) {
-            const Cand h = heads[l];
-            if (j == 0) h0 = h; else if (j == 1) h1 = h;
-            mine = h > mine ? h : mine;
-        }
-    }
-    const int busy = min(nw, (min(np, nt) + 63) / 64);       // wavefronts that hold heads
-    Cand best = wave < busy ? bitonic_sort64<true>(mine) : (Cand)0;
-#pragma unroll 1
-    for (int stride = 1; stride < busy; stride <<= 1) {
-        const bool sender = (wave % (2 * stride)) == stride && wave < busy;
-        const bool receiver = (wave % (2 * stride)) == 0 && wave + stride < busy;
-        if (sender) pool[wave * 64 + lane] = best;
-        __syncthreads();
-        if (receiver) best = merge_best64<true>(best, pool[(wave + stride) * 64 + lane]);
-        __syncthreads();
-    }
-    if (wave == 0) {
-        const Cand t = read_lane(best, kp - 1);
-        if (lane == 0) { L.sh[6] = (uint32_t)t; L.sh[7] = (uint32_t)(t >> 32); }
-    }
-    __syncthreads();
-    const Cand t0 = ((uint64_t)L.sh[7] << 32) | L.sh[6];     // 0 when fewer than kprime threads hold a head
-    // 2. the lists whose head reaches T0 ...
-    {
-        int j = 0;
-#pragma unroll 1
-        for (int l = tid; l < np; l += nt, ++j) {
-            const Cand h = j == 0 ? h0 : (j == 1 ? h1 : heads[l]);
-            if (h != 0 && h >= t0) {
-                const uint32_t pos = atomicAdd(&L.sh[5], 1u);
-                if (pos < (uint32_t)kMergeQlistCap) qlist[pos] = (uint32_t)l;
-            }
+    for (int l = tid; l < np; l += nt) {
+        const Cand h = head_at((uint32_t)l);
+        if (h != 0 && bc.pass((uint32_t)(h >> 32))) {
+            const uint32_t pos = atomicAdd(&L.sh[5], 1u);
+            if (pos < (uint32_t)kMergeQlistCap) qlist[pos] = (uint32_t)l;
         }
     }
     __syncthreads();
     const int nql = (int)L.sh[5];
     if (nql > kMergeQlistCap) return false;
-    // ... and their entries that reach it: four entries per thread and pass, all requested before
+    // ... and their entries that pass: four entries per thread and pass, all requested before
     // the first is looked at
     const int total = nql * slots;
 #pragma unroll 1
@@ -901,7 +948,7 @@ __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const bool ok = c[u] != 0 && c[u] >= t0;
+            const bool ok = c[u] != 0 && bc.pass((uint32_t)(c[u] >> 32));
             const uint64_t b = __ballot(ok);
             if (b) {
                 uint32_t base = 0;
@@ -915,7 +962,26 @@ __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part
     __syncthreads();
     const uint32_t cnt = L.sh[4];
     if (cnt > (uint32_t)kMergeCandCap) return false;
-    // 3. sort the gathered candidates in chunks of 64, merge the chunks
+    if (cnt <= (uint32_t)nt) {
+        // 3a. few candidates: each counts the candidates ahead of it (eight per pass, all read
+        //     before any is compared) and the first kprime take their places
+        const Cand mine = (uint32_t)tid < cnt ? pool[tid] : (Cand)0;
+        uint32_t rank = 0;
+#pragma unroll 1
+        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {
+            Cand o[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) o[u] = pool[min(j0 + u, cnt - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) rank += (uint32_t)((o[u] > mine) & (j0 + u < cnt));
+        }
+        if ((uint32_t)tid < cnt && rank < (uint32_t)kp) L.c_cand[rank] = mine;
+        __syncthreads();
+        if (tid == 0) L.sh[4] = min(cnt, (uint32_t)kp);
+        __syncthreads();
+        return true;
+    }
+    // 3b. many: sort the pooled candidates in chunks of 64, merge the chunks
     const int nchunks = (int)((cnt + 63) / 64);
 #pragma unroll 1
     for (int c = wave; c < nchunks; c += nw) {
@@ -924,7 +990,7 @@ __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part
     }
     __syncthreads();
     if (wave == 0) {
-        Cand top = nchunks > 0 ? pool[lane] : (Cand)0;      // nothing gathered: the pool holds no candidates
+        Cand top = pool[lane];
 #pragma unroll 1
         for (int c = 1; c < nchunks; ++c) top = merge_best64<true>(top, pool[c * 64 + lane]);
         const bool ok = lane < kp && top != 0;          // valid entries form a prefix
@@ -970,14 +1036,68 @@ __device__ __forceinline__ void gather_radix(const MergeArgs& a, const Cand* par
     __syncthreads();
 }
 
+// fp64 score of the stored row `brow` of the buffer for the query q, computed by a group of
+// kRescoreLanes lanes (sub = lane in the group); every lane of the group gets the sum.  One fixed
+// order of operations (rescore_partial, then a butterfly over the lane distances 1 .. 16).
+__device__ __forceinline__ double rescore_row(const void* buf, const float* q, int d, int dtype, int metric,
+                                              size_t brow, int sub) {
+    constexpr int lpc = kRescoreLanes;
+    const size_t row_bytes = (size_t)d * (dtype == 0 ? 4 : 2);
+    const unsigned char* rp = (const unsigned char*)buf + brow * row_bytes;
+    double s = 0.0;
+    if (row_bytes % 16 == 0) {
+        if (dtype == 0) s = rescore_partial<F32>(rp, q, d, metric, sub, lpc);
+        else if (dtype == 1) s = rescore_partial<F16>(rp, q, d, metric, sub, lpc);
+        else s = rescore_partial<BF16>(rp, q, d, metric, sub, lpc);
+    } else {
+        const size_t e0 = brow * (size_t)d;
+#pragma unroll 1
+        for (int t = sub; t < d; t += lpc) {
+            const double x = (double)q[t], y = widen(buf, dtype, e0 + t);
+            if (metric == 0) s = fma(x, y, s);
+            else { const double df = x - y; s = fma(df, df, s); }
+        }
+    }
+#pragma unroll 1
+    for (int o = 1; o < lpc; o <<= 1) s += __shfl_xor(s, o);
+    return s;
+}
+
+// Can a row that the scan or the gathering dropped still belong to the k nearest?  Everything
+// dropped anywhere has an fp32 key of at most f_last, the key of the last candidate kept, so its
+// exact score is at most f_last + E, E bounding the rounding of the fp32 accumulation:
+//   inner product   |fl(sum) - sum| <= g |q| |y|        squared distance   |fl(sum) - sum| <= g sum
+// with g = err_coef (a little above (terms + 2) 2^-24 for sums whose terms pass through at most
+// `terms` roundings).  The k-th best exact score found, s_k, is a lower bound of the true one;
+// the result is exact when s_k > f_last + E.
+__device__ __forceinline__ bool result_is_safe(double s_k, float f_last, const MergeArgs& a, double qq) {
+    // single precision is enough for the bound itself: it is rounded upwards
+    const float e = a.metric == 0 ? a.err_coef * (sqrtf((float)qq) * 1.0001f) * a.row_norm_max * 1.0001f
+                                  : a.err_coef * fabsf(f_last) * 1.0001f;
+    return s_k > (double)f_last + (double)e;
+}
+
 __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int fast) {
     extern __shared__ unsigned char m_dyn[];
     __shared__ MergeLds L;
+    __shared__ double q_part[kSelectThreads / 64];
+    __shared__ double s_kth;
+    __shared__ uint32_t f_min;
     const int tid = threadIdx.x, nt = blockDim.x;
     const int qi = blockIdx.x;
     const uint32_t n = (uint32_t)a.nparts * (uint32_t)a.list_len;
     const Cand* part = a.part + (size_t)qi * n;
     const uint32_t kp = a.kprime;
+    const float* q = a.q + (size_t)qi * a.d;
+
+    // |q|^2 for the error bound, summed while the heads travel
+    {
+        double s = 0.0;
+        for (int t = tid; t < a.d; t += nt) { const double x = (double)q[t]; s = fma(x, x, s); }
+        s = wave_sum(s);
+        if (lane_id() == 0) q_part[wave_id()] = s;
+        if (tid == 0) { f_min = 0xFFFFFFFFu; s_kth = -INFINITY; }
+    }
 
     // 1. the kprime best fp32 candidates
     bool gathered = false;
@@ -992,17 +1112,15 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
     const uint32_t m = min(L.sh[4], (uint32_t)kMaxKPrime);
 
     // 2. fp64 re-score: a group of kRescoreLanes lanes per candidate, nt / kRescoreLanes
-    //    candidates at once.  The order of operations is fixed (see rescore_partial), so a row has
+    //    candidates at once.  The order of operations is fixed (see rescore_row), so a row has
     //    the same fp64 score whichever kernel, or the host, computes it.
-    const float* q = a.q + (size_t)qi * a.d;
     const int np = a.nprobe;
-    const size_t row_bytes = (size_t)a.d * (a.dtype == 0 ? 4 : 2);
     constexpr int lpc = kRescoreLanes;
     const int sub = tid % lpc;
 #pragma unroll 1
     for (uint32_t c = (uint32_t)(tid / lpc); c < m; c += (uint32_t)(nt / lpc)) {
-        const uint32_t rank = cand_tie(L.c_cand[c]);
-        const uint32_t row = a.rowof ? a.rowof[rank] : rank;
+        const Cand cand = L.c_cand[c];
+        const uint32_t row = cand_tie(cand);
         const int64_t id = a.ids ? a.ids[row] : (int64_t)row;
         size_t brow = row;
         bool found_row = true;
@@ -1020,26 +1138,11 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
             found_row = found >= 0;
             brow = found_row ? (size_t)(s_base[found] + (int64_t)(row - s_grow[found])) : 0;
         }
-        const unsigned char* rp = (const unsigned char*)a.buf + brow * row_bytes;
-        double s = 0.0;
-        if (row_bytes % 16 == 0) {
-            if (a.dtype == 0) s = rescore_partial<F32>(rp, q, a.d, a.metric, sub, lpc);
-            else if (a.dtype == 1) s = rescore_partial<F16>(rp, q, a.d, a.metric, sub, lpc);
-            else s = rescore_partial<BF16>(rp, q, a.d, a.metric, sub, lpc);
-        } else {
-            const size_t e0 = brow * (size_t)a.d;
-#pragma unroll 1
-            for (int t = sub; t < a.d; t += lpc) {
-                const double x = (double)q[t], y = widen(a.buf, a.dtype, e0 + t);
-                if (a.metric == 0) s = fma(x, y, s);
-                else { const double df = x - y; s = fma(df, df, s); }
-            }
-        }
-#pragma unroll 1
-        for (int o = 1; o < lpc; o <<= 1) s += __shfl_xor(s, o);
+        const double s = rescore_row(a.buf, q, a.d, a.dtype, a.metric, brow, sub);
         if (sub == 0) {
             L.f_key[c] = !found_row ? -INFINITY : (a.metric == 0 ? s : -s);
             L.f_id[c] = id;
+            atomicMin(&f_min, (uint32_t)(cand >> 32));        // key image of the last candidate kept
         }
     }
     // 3. host candidates
@@ -1078,18 +1181,185 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
             a.out_ids[(size_t)qi * k + rank] = mi;
             a.out_dists[(size_t)qi * k + rank] = (float)(a.metric == 0 ? mk : -mk);
         }
+        if (rank == (uint32_t)k - 1) s_kth = mk;
     }
     for (uint32_t i = tot + tid; i < (uint32_t)k; i += nt) {
         a.out_ids[(size_t)qi * k + i] = -1;
         a.out_dists[(size_t)qi * k + i] = a.metric == 0 ? -INFINITY : INFINITY;
     }
-    if (a.done) {       // uniform; every thread of the workgroup arrives here
+    __syncthreads();
+    // 5. is the result proven?  Rows were dropped only if kprime candidates were kept (a wavefront
+    //    drops nothing before it holds kprime, the gathering nothing before it has kprime).
+    if (tid == 0) {
+        uint32_t unsafe = 0;
+        if (m == kp) {
+            double qq = 0.0;
+            for (int w = 0; w < nt / 64; ++w) qq += q_part[w];
+            unsafe = result_is_safe(s_kth, unordered(f_min), a, qq) ? 0u : 1u;
+        }
+        if (a.redo_flag) {
+            a.redo_flag[qi] = unsafe;
+            if (unsafe) {
+                a.redo_thr[qi] = s_kth;
+                a.redo_ticket[qi] = 0u;
+            }
+        }
+        if (a.host_flag) a.host_flag[qi] = unsafe;       // pinned: stored before the completion word below
+        if (a.done) {
+            __threadfence_system();
+            __hip_atomic_store(a.done, a.done_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+}
+
+// =============================================================================================
+// Exact second pass for a query whose first result could not be proven (merge_kernel's step 5):
+// every selected resident row is scored in fp64, in the order of operations of the re-score.
+// Only rows that reach the k-th best score found so far can belong to the result; each wavefront
+// keeps the k best of those it meets, ordered by (score, id), in a small list in LDS (rows within
+// the rounding error of the scan are few unless the data holds masses of equal rows, and then
+// the lists still bound what is kept).  The workgroup that finishes last ranks the entries of all
+// lists, together with the host's candidates, and rewrites the query's results.  Launched after
+// every merge of the device path; all workgroups of a query whose result was proven leave at once.
+// =============================================================================================
+constexpr int kRedoThreads = 256;
+constexpr int kRedoWaves = kRedoThreads / 64;
+static_assert(kRedoWaves == kRedoListsPerWg, "the list buffers are sized by kRedoListsPerWg");
+
+__global__ __launch_bounds__(kRedoThreads) void exact_redo_kernel(RedoArgs a) {
+    __shared__ uint32_t s_last;
+    __shared__ unsigned long long w_key[kRedoWaves][IVF_MAX_K];     // ascending-order image of the score; 0 = empty
+    __shared__ long long w_id[kRedoWaves][IVF_MAX_K];
+    const int qi = blockIdx.y;
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    if (a.redo_flag[qi] == 0) {
+        if (a.done && blockIdx.x == 0 && tid == 0) {
+            __threadfence_system();
+            __hip_atomic_store(a.done, a.done_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        return;
+    }
+    const int np = a.nprobe, k = a.k;
+    const float* q = a.q + (size_t)qi * a.d;
+    const uint32_t* rp = a.slots.rprefix + (size_t)qi * (np + 1);
+    const int64_t* s_base = a.slots.base + (size_t)qi * np;
+    const uint32_t* s_grow = a.slots.grow + (size_t)qi * np;
+    const uint32_t R = rp[np];
+    const double thr = a.redo_thr[qi];
+    unsigned long long* mk = w_key[wave];
+    long long* mi = w_id[wave];
+    for (int i = lane; i < k; i += 64) { mk[i] = 0ull; mi[i] = 0; }
+    int count = 0;                                   // entries in this wavefront's list (uniform)
+    constexpr int lpc = kRescoreLanes;
+    constexpr int gpw = 64 / lpc;                    // rows a wavefront scores at a time
+    const int sub = lane % lpc;
+    const uint32_t group = (uint32_t)((blockIdx.x * kRedoWaves + wave) * gpw + lane / lpc);
+    const uint32_t ngroups = gridDim.x * kRedoWaves * gpw;
+    const uint32_t rounds = (R + ngroups - 1) / ngroups;
+#pragma unroll 1
+    for (uint32_t it = 0; it < rounds; ++it) {
+        const uint32_t r = it * ngroups + group;
+        double key = -INFINITY;
+        long long id = 0;
+        if (r < R) {
+            uint32_t lo = 0, hi = (uint32_t)np;            // rp[lo] <= r < rp[hi]
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (rp[mid] <= r) lo = mid; else hi = mid;
+            }
+            const uint32_t in_slot = r - rp[lo];
+            const size_t brow = (size_t)(s_base[lo] + (int64_t)in_slot);
+            const double s = rescore_row(a.buf, q, a.d, a.dtype, a.metric, brow, sub);
+            key = a.metric == 0 ? s : -s;
+            const uint32_t grow = s_grow[lo] + in_slot;
+            id = a.ids ? (long long)a.ids[grow] : (long long)grow;
+        }
+        // the rows of this round that reach the threshold go into the list one after the other
+        uint64_t want = __ballot(sub == 0 && r < R && key >= thr);
+        while (want) {
+            const int src = __ffsll((long long)want) - 1;
+            want &= want - 1;
+            const unsigned long long nk = ordered(__shfl(key, src));
+            const long long nid = __shfl(id, src);
+            // position: entries ahead of the new one (larger key, or equal key and smaller id)
+            int ahead = 0;
+            for (int i = lane; i < count; i += 64) ahead += (mk[i] > nk || (mk[i] == nk && mi[i] < nid)) ? 1 : 0;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) ahead += __shfl_xor(ahead, m);
+            if (ahead >= k) continue;                      // the list is full of better rows
+            const int last = min(count, k - 1);            // entries ahead .. last-1 move down by one
+            for (int base = ((last - 1) / 64) * 64; base >= 0 && last > ahead; base -= 64) {
+                const int i = base + lane;
+                const bool mv = i >= ahead && i < last;
+                const unsigned long long tk = mv ? mk[i] : 0ull;
+                const long long ti = mv ? mi[i] : 0;
+                if (mv) { mk[i + 1] = tk; mi[i + 1] = ti; }    // a wavefront's LDS operations complete in order
+            }
+            if (lane == 0) { mk[ahead] = nk; mi[ahead] = nid; }
+            count = min(count + 1, k);
+        }
+    }
+    // every wavefront leaves its k slots (0 = empty) in the query's list
+    {
+        const size_t o = ((size_t)qi * gridDim.x * kRedoWaves + (size_t)blockIdx.x * kRedoWaves + wave) * (size_t)k;
+        for (int i = lane; i < k; i += 64) {
+            __hip_atomic_store(&a.list_key[o + i], i < count ? mk[i] : 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.list_id[o + i], mi[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        s_last = atomicAdd(&a.redo_ticket[qi], 1u) == gridDim.x - 1 ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    // the last workgroup: rank the entries of all lists and the host's candidates by (score, id)
+    const uint32_t n = gridDim.x * kRedoWaves * (uint32_t)k;
+    const unsigned long long* l_key = a.list_key + (size_t)qi * n;
+    const long long* l_id = a.list_id + (size_t)qi * n;
+    const uint32_t nh = a.host_cand ? min((uint32_t)a.host_count[qi], (uint32_t)a.kprime) : 0u;
+    const uint32_t tot = n + nh;
+    auto key_of = [&](uint32_t j) -> unsigned long long {
+        if (j < n) return __hip_atomic_load(&l_key[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return (unsigned long long)ordered(a.host_cand[(size_t)qi * a.kprime + (j - n)].key);
+    };
+    auto id_of = [&](uint32_t j) -> long long {
+        if (j < n) return __hip_atomic_load(&l_id[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return (long long)a.host_cand[(size_t)qi * a.kprime + (j - n)].id;
+    };
+#pragma unroll 1
+    for (uint32_t e = tid; e < tot; e += kRedoThreads) {
+        const unsigned long long ek = key_of(e);
+        if (ek == 0ull) continue;
+        const long long ei = id_of(e);
+        uint32_t rank = 0;
+#pragma unroll 1
+        for (uint32_t j = 0; j < tot && rank < (uint32_t)k; ++j) {
+            const unsigned long long ok = key_of(j);
+            rank += (uint32_t)(ok > ek || (ok == ek && ok != 0ull && id_of(j) < ei));
+        }
+        if (rank < (uint32_t)k) {
+            const double key = unordered((uint64_t)ek);
+            a.out_ids[(size_t)qi * k + rank] = (int64_t)ei;
+            a.out_dists[(size_t)qi * k + rank] = (float)(a.metric == 0 ? key : -key);
+        }
+    }
+    if (a.done) {
         __syncthreads();
         if (tid == 0) {
             __threadfence_system();
             __hip_atomic_store(a.done, a.done_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
+}
+
+hipError_t launch_redo(const RedoArgs& a, int grid, hipStream_t s) {
+    if (a.done && a.nq != 1) return hipErrorInvalidValue;
+    if (a.k > IVF_MAX_K) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(exact_redo_kernel, dim3(grid, a.nq), dim3(kRedoThreads), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_merge(const MergeArgs& a, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
