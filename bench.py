@@ -445,7 +445,7 @@ def run_lookahead(args, full=True):
             index.ivf_prefetch(tq_in[0], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
             index.ivf_cache_configure(0.5 if cached else -1.0, 1.0, 2.0, 1.0)
             acc = {"hit": [], "ms_search": [], "bytes": [], "ms_update": [], "ms_compact": [], "moved": [], "evicted": [],
-                   "ms_round_call": []}
+                   "ms_round_call": [], "launches": []}
             for j in range(n_req):
                 ps = index.ivf_prefetch(tq_in[j], nprobe, budget, flags=0 if cached else P.IVF_PREFETCH_RESET)
                 decode(reps)
@@ -458,14 +458,14 @@ def run_lookahead(args, full=True):
                     cs = index.ivf_cache_end_round()
                     acc["ms_round_call"].append((time.perf_counter() - t) * 1e3)
                     acc["ms_update"].append(cs.ms_update); acc["ms_compact"].append(cs.ms_compact)
-                    acc["moved"].append(cs.bytes_moved); acc["evicted"].append(cs.n_evicted)
+                    acc["moved"].append(cs.bytes_moved); acc["evicted"].append(cs.n_evicted); acc["launches"].append(cs.n_launches)
             m = {k_: float(np.mean(v)) if v else 0.0 for k_, v in acc.items()}
             row = {"mode": mode, "requests": n_req, "topics": topics, "hit_rate": round(m["hit"], 4),
                    "prefetched_gb": round(m["bytes"] / 1e9, 3), "search_ms": round(m["ms_search"], 3)}
             if cached:
                 row.update({"end_round_ms": round(m["ms_round_call"], 3), "hotness_update_ms": round(m["ms_update"], 3),
                             "compact_ms": round(m["ms_compact"], 3), "moved_gb": round(m["moved"] / 1e9, 3),
-                            "evicted_clusters": round(m["evicted"], 1),
+                            "evicted_clusters": round(m["evicted"], 1), "move_launches": round(m["launches"], 1),
                             # a move reads and writes its bytes
                             "move_traffic_gbs": round((2 * m["moved"] / 1e9) / (m["ms_compact"] / 1e3), 1) if m["ms_compact"] > 0 else 0.0})
             cache_rows.append(row)

@@ -315,6 +315,8 @@ int ivf_profile_reset(ivf_index* index);
  * while the resident bytes exceed fraction * device_buffer_bytes, the cached cluster of lowest
  * hotness is evicted (equal hotness: the larger cluster index first); the survivors are moved
  * to the front of the device buffer, in their order, so that the freed space is contiguous.
+ * The moves run on copy_stream and the call returns when they are enqueued (the next prefetch and
+ * the next search are ordered behind them); passing `stats` waits for them, to report their time.
  * Call it between batches, with no ivf_prefetch reset in between that should keep the cache:
  * IVF_PREFETCH_RESET drops the cache too.  Hotness is single precision on the device.
  *   fraction in [0, 1]; h_init >= 0; decay >= 1; h_inc >= 0.  fraction < 0 switches the cache off.
@@ -327,7 +329,8 @@ typedef struct ivf_cache_stats {
     uint64_t bytes_kept;   /* payload bytes still cached afterwards (= device buffer in use) */
     uint64_t bytes_moved;  /* bytes moved inside the device buffer by the consolidation */
     float ms_update;       /* hotness kernel + read-back */
-    float ms_compact;      /* device-to-device moves */
+    float ms_compact;      /* the moves inside the device buffer */
+    int32_t n_launches;    /* kernels that carried them out (one per group of moves that do not disturb each other) */
 } ivf_cache_stats;
 int ivf_cache_configure(ivf_index* index, float fraction, float h_init, float decay, float h_inc);
 int ivf_cache_end_round(ivf_index* index, ivf_cache_stats* stats /* or NULL */);

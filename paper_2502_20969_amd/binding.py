@@ -33,7 +33,7 @@ EXPORTS = [
 class CacheStats(C.Structure):
     _fields_ = [("n_cached", C.c_int32), ("n_evicted", C.c_int32), ("bytes_cached", C.c_uint64),
                 ("bytes_kept", C.c_uint64), ("bytes_moved", C.c_uint64), ("ms_update", C.c_float),
-                ("ms_compact", C.c_float)]
+                ("ms_compact", C.c_float), ("n_launches", C.c_int32)]
 
 
 class PrefetchStats(C.Structure):

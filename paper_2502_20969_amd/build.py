@@ -10,9 +10,10 @@ OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libivf.so")
 
 HIP_SOURCES = ["ivf_kernels.hip", "ivf_batched.hip", "ivf_sched.hip", "ivf_api.hip"]
-HOST_SOURCES = ["host_scan.cpp"]
+HOST_SOURCES = ["host_scan.cpp", "host_plan.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+CLANG = os.environ.get("IVF_HOST_CLANG", "/opt/rocm/llvm/bin/clang")     # host compiler of the sanitizer builds (knows _Float16)
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result"]
 # packed-fp32 instructions are switched off for all device code.  The driver cannot forward
 # -Xclang through -Xarch_device, so the host pass sees the feature too and says it does not know
@@ -47,5 +48,31 @@ def build() -> str:
     return LIB
 
 
+def build_sanitized() -> list:
+    """CPU only: the host side of the library (host scan, planners) and the C oracle with a driver
+    that checks one against the other, once under the address + undefined-behaviour sanitizers and
+    once under the thread sanitizer.  Returns the two executables."""
+    root = os.path.dirname(HERE)
+    os.makedirs(OBJ, exist_ok=True)
+    cxx_src = [os.path.join(CSRC, "host_scan.cpp"), os.path.join(CSRC, "host_plan.cpp"),
+               os.path.join(root, "tests", "sanitize", "host_san_driver.cpp")]
+    out = []
+    for name, flags in (("asan", ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]),
+                        ("tsan", ["-fsanitize=thread"])):
+        oracle_obj = os.path.join(OBJ, f"oracle_{name}.o")
+        subprocess.run([CLANG, "-O1", "-g", "-std=c11", "-fno-omit-frame-pointer", *flags, "-c",
+                        os.path.join(root, "oracle", "ivf_oracle.c"), "-o", oracle_obj], check=True)
+        exe = os.path.join(OBJ, f"host_san_{name}")
+        subprocess.run([CLANG + "++", "-O1", "-g", "-std=c++17", "-fno-omit-frame-pointer", *HOST_SIMD, *flags, *cxx_src, oracle_obj,
+                        "-o", exe, "-lpthread", "-lm"], check=True)
+        out.append(exe)
+    return out
+
+
 if __name__ == "__main__":
-    print(build())
+    if "--sanitize" in sys.argv[1:]:
+        for exe in build_sanitized():
+            print(exe)
+            subprocess.run([exe], check=True)
+    else:
+        print(build())

@@ -14,6 +14,7 @@
 #include <string>
 #include <vector>
 
+#include "host_plan.h"
 #include "host_scan.h"
 #include "ivf_internal.h"
 
@@ -138,6 +139,11 @@ struct ivf_index {
     void* d_move_tmp = nullptr;      // staging for a cluster whose old and new place overlap
     size_t move_tmp_bytes = 0;
     hipEvent_t ev_cache[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev_round = nullptr;   // the searches of the round are done (recorded on the compute stream)
+    MoveDesc* h_moves = nullptr;     // pinned: the moves of a consolidation, uploaded to d_moves
+    MoveDesc* d_moves = nullptr;
+    size_t moves_cap = 0;
+    float* h_hot_stage = nullptr;    // pinned copy of the hotness values for their upload
     int64_t* d_res_off = nullptr;
     void* d_buf = nullptr;          // device lists (device placement) or the prefetch buffer
     size_t buf_bytes = 0;
@@ -689,6 +695,8 @@ extern "C" void ivf_free(ivf_index* ix) {
     dfree(ix->d_centroids); dfree(ix->d_off); dfree(ix->d_ids);
     dfree(ix->d_hot); dfree(ix->d_used); dfree(ix->d_move_tmp);
     for (auto& e : ix->ev_cache) if (e) (void)hipEventDestroy(e);
+    if (ix->ev_round) (void)hipEventDestroy(ix->ev_round);
+    hfree(ix->h_moves); hfree(ix->h_hot_stage); dfree(ix->d_moves);
     dfree(ix->d_res_off);
     dfree(ix->d_prof_rows); dfree(ix->d_row_norm_max);
     if (ix->own_buf) dfree(ix->d_buf);
@@ -1110,38 +1118,6 @@ extern "C" int ivf_search(ivf_index* ix, const float* q_out, int32_t nq, int32_t
 }
 
 // ---- lookahead prefetch --------------------------------------------------------------------------
-// The plan of one prefetch call (Sec. 4.3 "Prefetching target"; several queries: Sec. 4.2 "Batching"):
-// every query gets an equal share of the budget and walks its ranked clusters nearest first; a
-// cluster that is resident (also: taken for an earlier query of the call) costs nothing, one that
-// fits the query's remaining share and the remaining buffer is taken whole at the buffer's fill
-// mark, any other is skipped and the walk goes on.  Pure host arithmetic: res_off (row offset in
-// the buffer or -1) and buf_used are updated, `taken` lists the clusters to copy, in order.
-static void plan_prefetch(const int32_t* ranked, int nq, int nprobe, const int64_t* off, size_t row_bytes,
-                          size_t budget_bytes, size_t buf_bytes, size_t& buf_used, int64_t* res_off,
-                          std::vector<int32_t>& taken, ivf_prefetch_stats& st) {
-    const size_t per_query = budget_bytes / (size_t)nq;
-    for (int qi = 0; qi < nq; ++qi) {
-        size_t remaining = per_query;
-        for (int i = 0; i < nprobe; ++i) {
-            const int32_t c = ranked[(size_t)qi * nprobe + i];
-            st.n_ranked += 1;
-            if (res_off[c] >= 0) { st.n_resident += 1; continue; }
-            const size_t bytes = (size_t)(off[c + 1] - off[c]) * row_bytes;
-            if (bytes <= remaining && bytes <= buf_bytes - buf_used) {
-                res_off[c] = (int64_t)(buf_used / row_bytes);
-                buf_used += bytes;
-                remaining -= bytes;
-                st.bytes += bytes;
-                st.n_taken += 1;
-                taken.push_back(c);
-            } else {
-                st.n_skipped += 1;
-            }
-        }
-    }
-    st.buffer_used = buf_used;
-}
-
 extern "C" int ivf_prefetch_plan(const int32_t* ranked, int32_t nq, int32_t nprobe, const int64_t* offsets,
                                  int32_t nlist, size_t row_bytes, size_t budget_bytes, size_t buffer_bytes,
                                  int64_t* resident_off, size_t* buffer_used, int32_t* taken, int32_t* n_taken,
@@ -1257,6 +1233,8 @@ extern "C" int ivf_cache_configure(ivf_index* ix, float fraction, float h_init, 
         HIP_TRY(hipMalloc(&ix->d_hot, (size_t)ix->nlist * sizeof(float)));
         HIP_TRY(hipMalloc(&ix->d_used, (size_t)ix->nlist * sizeof(uint32_t)));
         for (auto& e : ix->ev_cache) HIP_TRY(hipEventCreate(&e));
+        HIP_TRY(hipEventCreateWithFlags(&ix->ev_round, hipEventDisableTiming));
+        HIP_TRY(hipHostMalloc(&ix->h_hot_stage, (size_t)ix->nlist * sizeof(float)));
     }
     ix->cache_fraction = fraction; ix->cache_h_init = h_init; ix->cache_decay = decay; ix->cache_h_inc = h_inc;
     // what is resident now becomes cached at h_init; nothing has been used yet
@@ -1276,55 +1254,6 @@ extern "C" int ivf_cache_hotness(ivf_index* ix, float* hotness) {
     HIP_TRY(hipStreamSynchronize(ix->cs));
     HIP_TRY(hipMemcpy(hotness, ix->d_hot, (size_t)ix->nlist * sizeof(float), hipMemcpyDeviceToHost));
     return IVF_OK;
-}
-
-// The host part of a cache round (Sec. 4.2 "Cache design"), after the hotness update.
-// Eviction: while the cached bytes exceed fraction x buffer, the cached cluster of lowest hotness
-// leaves (equal hotness: the larger index first); its hotness becomes -1.  Consolidation: the
-// survivors move to the front of the buffer in their current order.  A cluster only ever moves
-// towards lower addresses and never onto a later cluster's old place; it can overlap its own old
-// place, and then goes through a staging buffer (need_tmp: the largest such cluster).
-static void plan_cache_round(float* hot, const int64_t* off, int nlist, size_t rb, int64_t* res_off,
-                             size_t& buf_used, size_t buf_bytes, float fraction, std::vector<int32_t>& evicted,
-                             std::vector<ivf_cache_move>& moves, size_t& need_tmp, ivf_cache_stats& st) {
-    struct Item { float h; int32_t c; };
-    std::vector<Item> cached;
-    for (int c = 0; c < nlist; ++c)
-        if (res_off[c] >= 0) cached.push_back(Item{hot[c], (int32_t)c});
-    st.n_cached = (int32_t)cached.size();
-    st.bytes_cached = buf_used;
-    const uint64_t limit = (uint64_t)((double)fraction * (double)buf_bytes);
-    std::sort(cached.begin(), cached.end(), [](const Item& x, const Item& y) {
-        return x.h < y.h || (x.h == y.h && x.c > y.c);
-    });
-    uint64_t in_use = buf_used;
-    for (size_t i = 0; i < cached.size() && in_use > limit; ++i) {
-        const int c = cached[i].c;
-        in_use -= (uint64_t)(off[c + 1] - off[c]) * rb;
-        res_off[c] = -1;
-        hot[c] = -1.f;
-        st.n_evicted += 1;
-        evicted.push_back(c);
-    }
-    std::vector<std::pair<int64_t, int32_t>> order;
-    for (int c = 0; c < nlist; ++c)
-        if (res_off[c] >= 0) order.push_back({res_off[c], (int32_t)c});
-    std::sort(order.begin(), order.end());
-    need_tmp = 0;
-    uint64_t at = 0;
-    for (auto& oc : order) {
-        const int c = oc.second;
-        const uint64_t bytes = (uint64_t)(off[c + 1] - off[c]) * rb, old = (uint64_t)oc.first * rb;
-        if (old != at && bytes > 0) {
-            const bool overlap = old - at < bytes;
-            if (overlap) need_tmp = std::max<size_t>(need_tmp, bytes);
-            moves.push_back(ivf_cache_move{(int32_t)c, overlap ? 1 : 0, old, at, bytes});
-            st.bytes_moved += bytes;
-        }
-        res_off[c] = (int64_t)(at / rb);
-        at += bytes;
-    }
-    buf_used = at;
 }
 
 extern "C" int ivf_cache_plan(float* hotness, const int64_t* offsets, int32_t nlist, size_t row_bytes,
@@ -1362,7 +1291,12 @@ extern "C" int ivf_cache_end_round(ivf_index* ix, ivf_cache_stats* stats) {
     HIP_TRY(hipMemcpyAsync(hot.data(), ix->d_hot, (size_t)nlist * sizeof(float), hipMemcpyDeviceToHost, ix->cs));
     HIP_TRY(hipEventRecord(ix->ev_cache[1], ix->cs));
     HIP_TRY(hipStreamSynchronize(ix->cs));
-    // 2. eviction and 3. consolidation: planned on the host, then carried out by device copies
+    // 2. eviction and 3. consolidation: planned on the host, carried out on the copy stream by one
+    //    kernel per group of moves that do not disturb each other (no destination of the group
+    //    overlaps a source of the group; the moves all go towards lower addresses, so a group ends
+    //    where the next destination would reach the group's first source).  A cluster that overlaps
+    //    its own old place goes through the staging area.  The next prefetch and the next search
+    //    are ordered behind the moves by the copy stream and its event.
     std::vector<int32_t> evicted;
     std::vector<ivf_cache_move> moves;
     size_t need_tmp = 0;
@@ -1371,35 +1305,69 @@ extern "C" int ivf_cache_end_round(ivf_index* ix, ivf_cache_stats* stats) {
                      ix->cache_fraction, evicted, moves, need_tmp, st);
     const bool changed = before != ix->h_res_off;        // evictions and moves both show in the table
     if (need_tmp > ix->move_tmp_bytes) {
+        HIP_TRY(hipDeviceSynchronize());
         if (ix->d_move_tmp) HIP_TRY(hipFree(ix->d_move_tmp));
         ix->d_move_tmp = nullptr; ix->move_tmp_bytes = 0;
         HIP_TRY(hipMalloc(&ix->d_move_tmp, need_tmp));
         ix->move_tmp_bytes = need_tmp;
     }
-    HIP_TRY(hipEventRecord(ix->ev_cache[2], ix->cs));
-    for (const ivf_cache_move& m : moves) {
-        char* dst = (char*)ix->d_buf + m.to_byte;
-        const char* src = (const char*)ix->d_buf + m.from_byte;
-        if (!m.via_staging) {
-            HIP_TRY(hipMemcpyAsync(dst, src, m.bytes, hipMemcpyDeviceToDevice, ix->cs));
-        } else {
-            HIP_TRY(hipMemcpyAsync(ix->d_move_tmp, src, m.bytes, hipMemcpyDeviceToDevice, ix->cs));
-            HIP_TRY(hipMemcpyAsync(dst, ix->d_move_tmp, m.bytes, hipMemcpyDeviceToDevice, ix->cs));
+    if (moves.size() + 1 > ix->moves_cap) {
+        HIP_TRY(hipDeviceSynchronize());
+        hfree(ix->h_moves); dfree(ix->d_moves);
+        ix->h_moves = nullptr; ix->d_moves = nullptr; ix->moves_cap = 0;
+        const size_t cap = std::max<size_t>(moves.size() + 1, (size_t)nlist + 1);
+        HIP_TRY(hipHostMalloc(&ix->h_moves, cap * sizeof(MoveDesc)));
+        HIP_TRY(hipMalloc(&ix->d_moves, cap * sizeof(MoveDesc)));
+        ix->moves_cap = cap;
+    } else if (ix->pf_recorded) {
+        HIP_TRY(hipEventSynchronize(ix->ev_pf_done));     // the previous round's upload of the list is done
+    }
+    HIP_TRY(hipEventRecord(ix->ev_round, ix->cs));
+    HIP_TRY(hipStreamWaitEvent(ix->copy, ix->ev_round, 0));
+    HIP_TRY(hipEventRecord(ix->ev_cache[2], ix->copy));
+    const std::vector<MoveGroup> groups = group_moves(moves);
+    std::vector<uint32_t> group_chunks(groups.size(), 0u);
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+        if (groups[gi].through_staging) continue;
+        uint32_t chunks = 0;
+        for (size_t m = groups[gi].first; m < groups[gi].last; ++m) {
+            ix->h_moves[m] = MoveDesc{moves[m].from_byte, moves[m].to_byte, moves[m].bytes, chunks, 0u};
+            chunks += move_chunks(moves[m].bytes);
         }
+        group_chunks[gi] = chunks;
     }
-    HIP_TRY(hipEventRecord(ix->ev_cache[3], ix->cs));
+    if (!moves.empty())
+        HIP_TRY(hipMemcpyAsync(ix->d_moves, ix->h_moves, moves.size() * sizeof(MoveDesc), hipMemcpyHostToDevice, ix->copy));
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+        const MoveGroup& g = groups[gi];
+        if (g.through_staging) {
+            const ivf_cache_move& m = moves[g.first];
+            HIP_TRY(hipMemcpyAsync(ix->d_move_tmp, (const char*)ix->d_buf + m.from_byte, m.bytes, hipMemcpyDeviceToDevice, ix->copy));
+            HIP_TRY(hipMemcpyAsync((char*)ix->d_buf + m.to_byte, ix->d_move_tmp, m.bytes, hipMemcpyDeviceToDevice, ix->copy));
+        } else {
+            HIP_TRY(launch_gather_moves(ix->d_buf, ix->d_moves + g.first, (int)(g.last - g.first), group_chunks[gi], ix->n_cu, ix->copy));
+        }
+        st.n_launches += 1;
+    }
+    HIP_TRY(hipEventRecord(ix->ev_cache[3], ix->copy));
     if (changed) {
+        if (ix->pf_recorded) HIP_TRY(hipEventSynchronize(ix->ev_pf_table));    // the staging copy of the table is free again
         memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)nlist * sizeof(int64_t));
-        HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->cs));
-        HIP_TRY(hipMemcpyAsync(ix->d_hot, hot.data(), (size_t)nlist * sizeof(float), hipMemcpyHostToDevice, ix->cs));
+        memcpy(ix->h_hot_stage, hot.data(), (size_t)nlist * sizeof(float));
+        HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->copy));
+        HIP_TRY(hipMemcpyAsync(ix->d_hot, ix->h_hot_stage, (size_t)nlist * sizeof(float), hipMemcpyHostToDevice, ix->copy));
+        HIP_TRY(hipEventRecord(ix->ev_pf_table, ix->copy));
     }
-    HIP_TRY(hipStreamSynchronize(ix->cs));
-    // later prefetch copies (copy stream) must not start before the moves are done: they are, the
-    // compute stream was just drained
+    HIP_TRY(hipEventRecord(ix->ev_pf_done, ix->copy));
+    ix->pf_recorded = true;
     st.bytes_kept = ix->buf_used;
     HIP_TRY(hipEventElapsedTime(&st.ms_update, ix->ev_cache[0], ix->ev_cache[1]));
-    HIP_TRY(hipEventElapsedTime(&st.ms_compact, ix->ev_cache[2], ix->ev_cache[3]));
-    if (stats) *stats = st;
+    if (stats) {
+        // the time of the moves is known when they are done: asking for the numbers waits for them
+        HIP_TRY(hipEventSynchronize(ix->ev_cache[3]));
+        HIP_TRY(hipEventElapsedTime(&st.ms_compact, ix->ev_cache[2], ix->ev_cache[3]));
+        *stats = st;
+    }
     return IVF_OK;
 }
 

@@ -67,6 +67,11 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+__device__ __forceinline__ void store_stream16(void* p, const uint4& v) {
+    u4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, (u4_t*)p);
+}
+
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);

@@ -139,6 +139,13 @@ hipError_t launch_redo(const RedoArgs& a, int grid, hipStream_t s);
 // bound coefficient of the scan's fp32 rounding for (shape, d, metric): see result_is_safe
 float scan_error_coef(const ScanShape& shape, int d, int dtype, int metric);
 
+// One move of the buffer consolidation: bytes from from_byte to to_byte of the buffer; chunk0 = number of
+// the move's first chunk in its launch (move_chunks(bytes) chunks per move, numbered through the launch).
+struct MoveDesc { uint64_t from_byte, to_byte, bytes; uint32_t chunk0, pad; };
+uint32_t move_chunks(uint64_t bytes);
+// one launch for a group of moves that do not disturb each other; moves_dev holds n_moves entries
+hipError_t launch_gather_moves(void* buf, const MoveDesc* moves_dev, int n_moves, uint32_t n_chunks, int n_cu, hipStream_t s);
+
 // cluster cache bookkeeping: hot[c] < 0 = not cached
 hipError_t launch_cache_admit(float* hot, uint32_t* used, const int64_t* res_off, int nlist, float h_init, int reset,
                               hipStream_t s);

@@ -1403,6 +1403,61 @@ hipError_t launch_scatter_rows(const void* src, void* dst, const int64_t* pos, i
 }
 
 // =============================================================================================
+// Consolidation of the prefetch buffer (Sec. 4.2 "Cache design"; appendix: the GPU memory is
+// consolidated after each batch).  One launch carries out a group of moves that do not disturb
+// each other (no destination of the group overlaps a source of the group): the moves are cut
+// into chunks of kMoveChunk bytes and every workgroup copies chunks, 16 bytes per lane where the
+// addresses allow.  HBM-bound: every byte moved is read once and written once.
+// =============================================================================================
+constexpr uint32_t kMoveChunk = 64u << 10;
+
+__global__ __launch_bounds__(256) void gather_moves_kernel(unsigned char* buf, const MoveDesc* moves, int n_moves,
+                                                           uint32_t n_chunks) {
+    for (uint32_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+        int lo = 0, hi = n_moves;                  // moves[lo].chunk0 <= ch < moves[hi].chunk0 (a sentinel past the end)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (moves[mid].chunk0 <= ch) lo = mid; else hi = mid;
+        }
+        const MoveDesc m = moves[lo];
+        const uint64_t o = (uint64_t)(ch - m.chunk0) * kMoveChunk;
+        const uint64_t len = min((uint64_t)kMoveChunk, m.bytes - o);
+        const unsigned char* src = buf + m.from_byte + o;
+        unsigned char* dst = buf + m.to_byte + o;
+        if ((((uintptr_t)src | (uintptr_t)dst) & 15u) == 0) {
+            const uint32_t vec = (uint32_t)(len / 16);
+            // eight loads per lane in flight before the first store
+#pragma unroll 1
+            for (uint32_t i0 = 0; i0 < vec; i0 += 8 * 256) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t i = i0 + u * 256 + threadIdx.x;
+                    v[u] = load_stream16(src + (size_t)min(i, vec - 1) * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t i = i0 + u * 256 + threadIdx.x;
+                    if (i < vec) store_stream16(dst + (size_t)i * 16, v[u]);
+                }
+            }
+            for (uint64_t i = (uint64_t)vec * 16 + threadIdx.x; i < len; i += blockDim.x) dst[i] = src[i];
+        } else {
+            for (uint64_t i = threadIdx.x; i < len; i += blockDim.x) dst[i] = src[i];
+        }
+    }
+}
+
+uint32_t move_chunks(uint64_t bytes) { return (uint32_t)((bytes + kMoveChunk - 1) / kMoveChunk); }
+
+hipError_t launch_gather_moves(void* buf, const MoveDesc* moves_dev, int n_moves, uint32_t n_chunks, int n_cu, hipStream_t s) {
+    if (n_moves <= 0 || n_chunks == 0) return hipSuccess;
+    const uint32_t grid = std::min<uint32_t>(n_chunks, (uint32_t)n_cu * 8u);
+    hipLaunchKernelGGL(gather_moves_kernel, dim3(grid), dim3(256), 0, s, (unsigned char*)buf, moves_dev, n_moves, n_chunks);
+    return hipGetLastError();
+}
+
+// =============================================================================================
 // Queries handed over in host memory: a few KB that a kernel reads from the pinned buffer itself
 // (one dispatch on the search stream) instead of a copy engine transfer set up by the runtime.
 // =============================================================================================
