@@ -243,6 +243,15 @@ int ivf_set_batch_mode(ivf_index* index, int32_t mode);
 int ivf_coarse_scores(ivf_index* index, const float* q, int32_t nq, double* scores);
 /* the nprobe nearest clusters, nearest first: clusters (host, nq x min(nprobe, nlist)) */
 int ivf_probe(ivf_index* index, const float* q, int32_t nq, int32_t nprobe, int32_t* clusters);
+/*
+ * The scores the list-major scan filters with (Sec. 4.2 "Batching": the matrix-matrix product), for
+ * every row of one cluster against nq <= 32 queries: scores (host, nq x rows of the cluster, in row
+ * order) are the MFMA accumulators (query rounded to the storage type, fp32 accumulation), eps
+ * (host, nq) the bound the scan assumes for |score - exact inner product with the fp32 query|.
+ * Only for an index that has the list-major path (see ivf_set_batch_mode), clusters of at most
+ * 65536 rows.
+ */
+int ivf_batched_scores(ivf_index* index, const float* q, int32_t nq, int32_t cluster, float* scores, float* eps);
 /* resident clusters in ascending order; *n in: capacity of clusters, out: count */
 int ivf_resident(ivf_index* index, int32_t* clusters, int32_t* n);
 /* layout as built: offsets (host, nlist + 1) and/or ids (host, n); either may be NULL */

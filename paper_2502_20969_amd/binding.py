@@ -23,7 +23,7 @@ DTYPE_CODE = {"f32": IVF_F32, "f16": IVF_F16, "bf16": IVF_BF16}
 EXPORTS = [
     "ivf_build_layout", "ivf_adopt_layout", "ivf_free", "ivf_prefetch", "ivf_prefetch_wait",
     "ivf_search", "ivf_search_device", "ivf_search_device_noalloc", "ivf_reserve", "ivf_coarse_scores", "ivf_probe",
-    "ivf_resident", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
+    "ivf_resident", "ivf_batched_scores", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
     "ivf_schedule", "ivf_host_scan", "ivf_prefetch_plan", "ivf_cache_plan", "ivf_strerror", "ivf_last_error",
@@ -85,6 +85,7 @@ def load():
     L.ivf_coarse_scores.argtypes = [vp, vp, i32, vp]
     L.ivf_probe.argtypes = [vp, vp, i32, i32, vp]
     L.ivf_resident.argtypes = [vp, vp, C.POINTER(i32)]
+    L.ivf_batched_scores.argtypes = [vp, vp, i32, i32, vp, vp]
     L.ivf_get_layout.argtypes = [vp, vp, vp]
     L.ivf_profile_enable.argtypes = [vp, ci]
     L.ivf_profile_read.argtypes = [vp, C.POINTER(Profile)]
@@ -245,6 +246,14 @@ class Index:
         out = np.empty((q.shape[0], min(nprobe, self.nlist)), dtype=np.int32)
         _check(load().ivf_probe(self._h, _ptr(q), q.shape[0], nprobe, _ptr(out)))
         return out
+
+    def ivf_batched_scores(self, q, cluster, rows_in_cluster):
+        """MFMA filter scores [nq, rows] of one cluster and the error bound eps [nq] the scan assumes."""
+        q = _host(q, np.float32).reshape(-1, self.d)
+        scores = np.empty((q.shape[0], rows_in_cluster), dtype=np.float32)
+        eps = np.empty(q.shape[0], dtype=np.float32)
+        _check(load().ivf_batched_scores(self._h, _ptr(q), q.shape[0], int(cluster), _ptr(scores), _ptr(eps)))
+        return scores, eps
 
     def ivf_resident(self):
         n = C.c_int32(self.nlist)

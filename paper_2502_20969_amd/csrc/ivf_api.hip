@@ -844,7 +844,11 @@ extern "C" int ivf_set_pipeline_depth(ivf_index* ix, int32_t depth) {
     }
     while ((int)ix->lanes.size() < depth) {
         ivf_index::Lane l;
-        HIP_TRY(hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking));
+        const hipError_t e = hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking);
+        if (e != hipSuccess) {
+            use_lane(ix, 0);          // the lanes may have moved in memory: point at lane 0 again before leaving
+            return fail(IVF_EHIP, "hipStreamCreateWithFlags: %s", hipGetErrorString(e));
+        }
         l.own = true;
         ix->lanes.push_back(l);
     }
@@ -1155,33 +1159,53 @@ extern "C" int ivf_prefetch(ivf_index* ix, const float* q_in, int32_t nq, int32_
     HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
     HIP_TRY(hipStreamSynchronize(ix->cs));
 
+    // The plan is made on copies of the residency mirror: it becomes the index's state only when every
+    // copy and the table that describes them have been enqueued.
+    std::vector<int64_t> res_off(ix->h_res_off);
+    size_t buf_used = ix->buf_used;
     if (flags & IVF_PREFETCH_RESET) {
-        std::fill(ix->h_res_off.begin(), ix->h_res_off.end(), (int64_t)-1);
-        ix->buf_used = 0;
+        std::fill(res_off.begin(), res_off.end(), (int64_t)-1);
+        buf_used = 0;
     }
     ivf_prefetch_stats st{};
-    HIP_TRY(hipEventRecord(ix->ev_pf_begin, ix->copy));
     const size_t rb = ix->row_bytes;
     std::vector<int32_t> taken;
-    plan_prefetch(w.h_probe, nq, nprobe, ix->h_off.data(), rb, budget_bytes, ix->buf_bytes, ix->buf_used,
-                  ix->h_res_off.data(), taken, st);
-    for (int32_t c : taken) {
-        const size_t bytes = (size_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
-        if (bytes > 0)
-            HIP_TRY(hipMemcpyAsync((char*)ix->d_buf + (size_t)ix->h_res_off[c] * rb,
-                                   (const char*)ix->h_lists + (size_t)ix->h_off[c] * rb, bytes,
-                                   hipMemcpyHostToDevice, ix->copy));
+    plan_prefetch(w.h_probe, nq, nprobe, ix->h_off.data(), rb, budget_bytes, ix->buf_bytes, buf_used, res_off.data(), taken, st);
+    auto enqueue = [&]() -> int {
+        HIP_TRY(hipEventRecord(ix->ev_pf_begin, ix->copy));
+        for (int32_t c : taken) {
+            const size_t bytes = (size_t)(ix->h_off[c + 1] - ix->h_off[c]) * rb;
+            if (bytes > 0)
+                HIP_TRY(hipMemcpyAsync((char*)ix->d_buf + (size_t)res_off[c] * rb,
+                                       (const char*)ix->h_lists + (size_t)ix->h_off[c] * rb, bytes,
+                                       hipMemcpyHostToDevice, ix->copy));
+        }
+        // the residency table follows the data on the same stream; the pinned staging copy is reused,
+        // so the previous upload from it must have finished
+        if (ix->pf_recorded) HIP_TRY(hipEventSynchronize(ix->ev_pf_table));
+        memcpy(ix->h_res_stage, res_off.data(), (size_t)ix->nlist * sizeof(int64_t));
+        HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)ix->nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->copy));
+        HIP_TRY(hipEventRecord(ix->ev_pf_table, ix->copy));
+        if (ix->cache_on)     // clusters that arrived are cached from now on; a reset drops the cache
+            HIP_TRY(launch_cache_admit(ix->d_hot, ix->d_used, ix->d_res_off, ix->nlist, ix->cache_h_init,
+                                       (flags & IVF_PREFETCH_RESET) ? 1 : 0, ix->copy));
+        HIP_TRY(hipEventRecord(ix->ev_pf_done, ix->copy));
+        return IVF_OK;
+    };
+    rc = enqueue();
+    if (rc != IVF_OK) {
+        // Some copies may be on their way into places the device table does not know, or the table may
+        // be stale: nothing is resident any more, on either side (best effort for the device side).
+        const std::string why = g_last_error;
+        (void)hipStreamSynchronize(ix->copy);
+        std::fill(ix->h_res_off.begin(), ix->h_res_off.end(), (int64_t)-1);
+        ix->buf_used = 0;
+        (void)hipMemcpy(ix->d_res_off, ix->h_res_off.data(), (size_t)ix->nlist * sizeof(int64_t), hipMemcpyHostToDevice);
+        g_last_error = why + " (the residency was dropped)";
+        return rc;
     }
-    // the residency table follows the data on the same stream; the pinned staging copy is reused,
-    // so the previous upload from it must have finished
-    if (ix->pf_recorded) HIP_TRY(hipEventSynchronize(ix->ev_pf_table));
-    memcpy(ix->h_res_stage, ix->h_res_off.data(), (size_t)ix->nlist * sizeof(int64_t));
-    HIP_TRY(hipMemcpyAsync(ix->d_res_off, ix->h_res_stage, (size_t)ix->nlist * sizeof(int64_t), hipMemcpyHostToDevice, ix->copy));
-    HIP_TRY(hipEventRecord(ix->ev_pf_table, ix->copy));
-    if (ix->cache_on)     // clusters that arrived are cached from now on; a reset drops the cache
-        HIP_TRY(launch_cache_admit(ix->d_hot, ix->d_used, ix->d_res_off, ix->nlist, ix->cache_h_init,
-                                   (flags & IVF_PREFETCH_RESET) ? 1 : 0, ix->copy));
-    HIP_TRY(hipEventRecord(ix->ev_pf_done, ix->copy));
+    ix->h_res_off.swap(res_off);
+    ix->buf_used = buf_used;
     ix->pf_recorded = true;
     st.buffer_used = ix->buf_used;
     if (stats) *stats = st;
@@ -1414,6 +1438,53 @@ extern "C" int ivf_probe(ivf_index* ix, const float* q, int32_t nq, int32_t npro
     HIP_TRY(hipMemcpyAsync(w.h_probe, w.d_probe, (size_t)nq * nprobe * sizeof(int32_t), hipMemcpyDeviceToHost, ix->cs));
     HIP_TRY(hipStreamSynchronize(ix->cs));
     memcpy(clusters, w.h_probe, (size_t)nq * nprobe * sizeof(int32_t));
+    return IVF_OK;
+}
+
+extern "C" int ivf_batched_scores(ivf_index* ix, const float* q, int32_t nq, int32_t cluster, float* scores, float* eps) {
+    int rc = check_query_args(ix, q, nq, 1);
+    if (rc) return rc;
+    if (!scores || !eps) return fail(IVF_EINVAL, "scores or eps is NULL");
+    if (cluster < 0 || cluster >= ix->nlist) return fail(IVF_EINVAL, "cluster %d is outside [0, %d)", cluster, ix->nlist);
+    if (nq > 32) return fail(IVF_ELIMIT, "at most 32 queries (one group of the list-major scan)");
+    const int saved_mode = ix->batch_mode;
+    ix->batch_mode = 2;
+    const bool ok = batched_eligible(ix, 2);
+    ix->batch_mode = saved_mode;
+    if (!ok) return fail(IVF_ESTATE, "this index has no list-major scan (needs fp16 / bf16 rows in HBM, inner product, d a multiple of 64 that fits LDS)");
+    const int64_t n_c = ix->h_off[cluster + 1] - ix->h_off[cluster];
+    if (n_c > kCandCap) return fail(IVF_ELIMIT, "the cluster has %lld rows, at most %d can be returned", (long long)n_c, kCandCap);
+    if ((rc = settle_on_lane0(ix))) return rc;
+    if ((rc = ensure_workspace(ix, nq, 1, 1))) return rc;
+    if ((rc = ensure_batched_workspace(ix, nq, 1))) return rc;
+    Workspace& w = *ix->cw;
+    if ((rc = stage_queries(ix, q, nq))) return rc;
+    // every query "selects" the one cluster
+    std::vector<int32_t> probe((size_t)nq, cluster);
+    HIP_TRY(hipMemcpyAsync(w.d_probe, probe.data(), (size_t)nq * sizeof(int32_t), hipMemcpyHostToDevice, ix->cs));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->d, ix->n_cu);
+    BatchedArgs b{};
+    b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.q = w.d_q; b.probe = w.d_probe;
+    b.q_store = w.d_q_store; b.thr = w.d_thr; b.thr_part = w.d_thr_part; b.row_norm_max_bits = ix->d_row_norm_max;
+    b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
+    b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
+    b.cand_key = w.d_cand_key; b.cand_score = w.d_cand_score; b.eps = w.d_eps; b.surv_row = w.d_surv_row; b.overflow = w.d_overflow;
+    b.out_ids = w.d_out_ids; b.out_dists = w.d_out_dists;
+    b.nlist = ix->nlist; b.d = ix->d; b.dtype = ix->dtype; b.nq = nq; b.nprobe = 1; b.k = 1;
+    b.kprime = kprime_for(1); b.cand_cap = kCandCap; b.surv_cap = kSurvCap; b.keep_all = 1;
+    HIP_TRY(launch_batched(b, ix->batched_grid, ix->cs, nullptr, nullptr, false));
+    HIP_TRY(hipStreamSynchronize(ix->cs));
+    std::vector<uint32_t> count((size_t)nq), rows((size_t)n_c);
+    std::vector<float> sc((size_t)n_c);
+    HIP_TRY(hipMemcpy(count.data(), w.d_cand_count, (size_t)nq * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(eps, w.d_eps, (size_t)nq * sizeof(float), hipMemcpyDeviceToHost));
+    for (int qi = 0; qi < nq; ++qi) {
+        if ((int64_t)count[qi] != n_c) return fail(IVF_ESTATE, "query %d: %u of %lld rows came back", qi, count[qi], (long long)n_c);
+        HIP_TRY(hipMemcpy(rows.data(), w.d_cand_row + (size_t)qi * kCandCap, (size_t)n_c * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(sc.data(), w.d_cand_score + (size_t)qi * kCandCap, (size_t)n_c * sizeof(float), hipMemcpyDeviceToHost));
+        for (int64_t i = 0; i < n_c; ++i) scores[(size_t)qi * n_c + (rows[i] - (uint32_t)ix->h_off[cluster])] = sc[i];
+    }
     return IVF_OK;
 }
 

@@ -187,7 +187,7 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
         // covered by the same accumulation term.  A little slack absorbs the norms' own rounding.
         float ymax = sqrtf(__uint_as_float(*a.row_norm_max_bits));
         float eps = 1.01f * (sqrtf(res) + (float)a.d * 0x1p-22f * sqrtf(s)) * ymax;
-        a.thr[qi] = top.thr - eps;        // -inf (fewer than k sampled rows) stays -inf
+        a.thr[qi] = a.keep_all ? -INFINITY : top.thr - eps;        // -inf (fewer than k sampled rows) stays -inf
         a.eps[qi] = eps;
         a.cand_count[qi] = 0;
     }
@@ -584,7 +584,7 @@ int batched_resident_grid(int dtype, int d, int n_cu) {
     return per_cu * n_cu;
 }
 
-hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start, hipEvent_t scan_stop) {
+hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start, hipEvent_t scan_stop, bool with_merge) {
     const int pairs = a.nq * a.nprobe;
     if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
     else hipLaunchKernelGGL(thr_sample_kernel<BF16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
@@ -598,7 +598,7 @@ hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEven
         IVF_LAUNCH(batched_scan_kernel<F16>, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
     else
         IVF_LAUNCH(batched_scan_kernel<BF16>, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
-    hipLaunchKernelGGL(batched_merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
+    if (with_merge) hipLaunchKernelGGL(batched_merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
     return hipGetLastError();
 }
 

@@ -184,12 +184,14 @@ struct BatchedArgs {
     int64_t* out_ids; float* out_dists;      // [nq x k]
     unsigned long long* rows_counter;        // nullable: rows covered by the scan tasks (profiling)
     int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap, surv_cap;
+    int keep_all;                // 1: the threshold is -inf, every scanned row becomes a candidate (stage-level test entry)
 };
 // upper bound of the number of tasks for a batch of nq queries
 uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe);
 hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, hipStream_t s);
+// with_merge = false stops after the scan: the candidate lists hold what passed the filter
 hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start = nullptr,
-                          hipEvent_t scan_stop = nullptr);
+                          hipEvent_t scan_stop = nullptr, bool with_merge = true);
 int batched_resident_grid(int dtype, int d, int n_cu);
 size_t batched_thr_part_floats(int nq);
 size_t batched_scan_lds(int d);      // LDS bytes of the batched scan kernel (one group of queries)

@@ -147,3 +147,34 @@ def test_list_major_finds_every_row_by_its_own_query(streams, dtype, d, nq):
         gi, gd = index.ivf_search(q[lo:hi], nlist, 1)
         assert np.array_equal(gi[:, 0], ids[lo:hi]), f"rows {np.flatnonzero(gi[:, 0] != ids[lo:hi])[:8] + lo}"
     index.close()
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 1920), ("bf16", 1920), ("f16", 768), ("bf16", 1024)])
+def test_filter_scores_stay_within_the_assumed_bound(streams, dtype, d):
+    """The list-major scan prunes with MFMA scores and a bound eps of their error (query rounded to
+    the storage type, fp32 accumulation inside the matrix cores).  The scores of every row of a
+    cluster are read back and compared with fp64 inner products with the unrounded query, for sign
+    patterns that make the rounding add up: all-positive operands, alternating signs on both sides
+    (every product positive), and random signs.  d = 1920 is the longest row this path takes."""
+    rng = np.random.default_rng(21)
+    n = 3000
+    mag = np.abs(rng.standard_normal((n, d))) + 0.05
+    signs_alt = np.where(np.arange(d) % 2 == 0, 1.0, -1.0)
+    rows = np.concatenate([mag[:1000], mag[1000:2000] * signs_alt, mag[2000:] * rng.choice([-1.0, 1.0], (1000, d))])
+    rows /= np.linalg.norm(rows, axis=1, keepdims=True)
+    t = torch.from_numpy(rows.astype(np.float32)).to(torch.float16 if dtype == "f16" else torch.bfloat16).cuda()
+    off = np.array([0, n], dtype=np.int64)
+    cent = np.ones((1, d), dtype=np.float32)
+    index = P.ivf_adopt_layout(t, dtype, off, cent, metric=P.IVF_IP, compute_stream=streams[0], copy_stream=streams[1])
+    q = np.abs(rng.standard_normal((12, d))) + 0.05
+    q[4:8] *= signs_alt
+    q[8:] *= rng.choice([-1.0, 1.0], (4, d))
+    q = (q / np.linalg.norm(q, axis=1, keepdims=True)).astype(np.float32)
+    approx, eps = index.ivf_batched_scores(q, 0, n)
+    exact = q.astype(np.float64) @ t.to(torch.float64).cpu().numpy().T
+    err = np.abs(approx.astype(np.float64) - exact).max(axis=1)
+    print(f"{dtype} d {d}: largest |MFMA - exact| / eps per query: {np.round(err / eps, 3)}")
+    assert np.all(eps > 0) and np.all(err <= eps), (err, eps)
+    # the bound is not vacuous: it is within two orders of magnitude of the largest error seen
+    assert (err / eps).max() > 0.01
+    index.close()
