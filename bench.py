@@ -48,9 +48,11 @@ def med(xs):
 
 def free_gpu():
     import torch
+    import workloads as W
     gc.collect()
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
+    W.release_pinned_cache()
 
 
 def rates(units, seconds):
@@ -526,7 +528,8 @@ def run_lookahead(args, full=True):
                                   + ("" if scale == 1.0 else f" (rows and nlist scaled by {scale}; nprobe kept at {nprobe} rather than scaled with nlist, "
                                      "so that a query still scans and prefetches the named 1.4 GB)"),
                       "pinning": {"scale": scale, "first_refusal": note,
-                                  "host": "RLIMIT_MEMLOCK unlimited, 309 GB of RAM: hipHostMalloc itself refuses one region above ~64-70 GB"},
+                                  "host": "RLIMIT_MEMLOCK unlimited and 309 GB of RAM on the box, yet hipHostMalloc grants about 64 GB of "
+                                          "pinned memory per process in all (64 GB in one region succeeds, 70 GB does not, nor a second 40 GB beside a first)"},
                       "host_threads": threads, "decode_alone_ms": round(decode_alone_ms, 2), "decode_matmuls": reps},
            "budget_sweep": rows, "cluster_cache": cache_rows, "prefetch_scheduler": sched_rows, "parity_sample": parity,
            "setup_s": round(setup_s, 1)}

@@ -24,6 +24,7 @@ def _free():
     gc.collect()
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
+    W.release_pinned_cache()
 
 
 def _check_queries(gi, gd, rows_t, odt, off, cent, q_np, which, nprobe, k, metric, index=None):
@@ -123,7 +124,7 @@ def test_config3_lookahead_host_lists():
     t0 = time.time()
     pinned, scale, note = W.pinned_rows(60_000_000, 768, "f16")
     nlist = max(64, int(16384 * scale))
-    nprobe, k, pairs = 256, 10, 8
+    nprobe, k, pairs = 256, 10, 6
     ds, q_in, q_out = W.config4_lookahead(pinned, nlist, pairs)
     torch.cuda.synchronize()
     print(f"configs[3]: {pinned.shape[0]} rows pinned (scale {scale}; {note}), ready after {time.time() - t0:.1f} s")

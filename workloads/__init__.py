@@ -26,4 +26,5 @@ from .generators import (  # noqa: F401
     config5_large_bf16,
     paper_shape_fp32,
     pinned_rows,
+    release_pinned_cache,
 )

@@ -242,18 +242,24 @@ def paper_shape_fp32(device="cuda", scale=1.0, nq=64):
     return ds, q_out
 
 
-def pinned_rows(n_full, d, dtype, min_scale=0.01):
+def pinned_rows(n_full, d, dtype, scales=(1.0, 0.6875, 0.5, 0.25, 0.125, 0.0625)):
     """A pinned host tensor [n, d] for a host-placed datastore of n_full rows; when the host
-    refuses to pin that much, the row count is halved until it does.  Returns (tensor, scale,
-    note) with n = n_full * scale and note = the refusal message of the first failed attempt."""
-    scale, note = 1.0, None
-    while True:
+    refuses to pin that much, the next smaller scale is tried.  Returns (tensor, scale, note) with
+    n = n_full * scale and note = the refusal message of the first failed attempt."""
+    note = None
+    for scale in scales:
         n = int(n_full * scale)
         try:
             return torch.empty((n, d), dtype=TORCH_DTYPE[dtype], pin_memory=True), scale, note
         except RuntimeError as e:
             if note is None:
                 note = str(e).splitlines()[0]
-            scale /= 2
-            if scale < min_scale:
-                raise
+    raise RuntimeError(f"could not pin even {scales[-1]} of {n_full} x {d} {dtype}: {note}")
+
+
+def release_pinned_cache():
+    """Gives freed pinned host blocks back to the system (torch keeps them cached otherwise, and the
+    amount of pinned memory a process may hold is limited)."""
+    fn = getattr(torch._C, "_host_emptyCache", None)
+    if fn is not None:
+        fn()
