@@ -226,7 +226,11 @@ int ivf_synchronize(ivf_index* index);
  *      once per group of up to 32 queries that probe it, scores by MFMA); anything else query
  *      by query
  *   1  always query by query
- *   2  list-major whenever the index allows it (from 2 queries on)
+ *   2  list-major from 2 queries on; IVF_ESTATE (and the mode stays) when the index has no
+ *      list-major path
+ * An index has the list-major path when all its rows are in HBM (IVF_PLACE_DEVICE), there are
+ * fewer than 2^32 of them, and d is a multiple of 64 whose group of queries (32 of fp16 / bf16, 16
+ * of fp32) fits LDS; any storage type, both metrics.
  * The results are the same in every mode (the MFMA scores only filter rows; the ranking uses
  * fp64 re-scores with the fp32 query).  A list-major batch may leave a few queries to be
  * searched again one by one (their candidate lists overflowed): ivf_search does that before it
@@ -246,8 +250,10 @@ int ivf_probe(ivf_index* index, const float* q, int32_t nq, int32_t nprobe, int3
 /*
  * The scores the list-major scan filters with (Sec. 4.2 "Batching": the matrix-matrix product), for
  * every row of one cluster against nq <= 32 queries: scores (host, nq x rows of the cluster, in row
- * order) are the MFMA accumulators (query rounded to the storage type, fp32 accumulation), eps
- * (host, nq) the bound the scan assumes for |score - exact inner product with the fp32 query|.
+ * order) are the filter scores, larger is better: the MFMA accumulators (query rounded to the
+ * storage type, fp32 accumulation) for the inner product, 2 <q, y> - |y|^2 - |q|^2 from the same
+ * accumulators and the stored row norms for squared L2; eps (host, nq) is the bound the scan
+ * assumes for |score - exact value| (exact: <q, y>, or -|q - y|^2, with the fp32 query).
  * Only for an index that has the list-major path (see ivf_set_batch_mode), clusters of at most
  * 65536 rows.
  */

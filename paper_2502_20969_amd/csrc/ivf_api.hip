@@ -104,7 +104,7 @@ struct Workspace {
     void* d_q_store = nullptr;
     float* d_thr = nullptr;
     float* d_thr_part = nullptr;
-    float *d_cand_score = nullptr, *d_eps = nullptr;
+    float *d_cand_score = nullptr, *d_eps = nullptr, *d_qq = nullptr;
     uint32_t* d_surv_row = nullptr;
     uint32_t *d_list_count = nullptr, *d_cursor = nullptr, *d_qstart = nullptr, *d_tstart = nullptr, *d_qidx = nullptr;
     BatchTask* d_tasks = nullptr;
@@ -163,7 +163,8 @@ struct ivf_index {
     int resident_grid[2] = {0, 0};            // scan workgroups resident at once, for kprime <= 64 / > 64
     int batched_grid = 0;                     // resident workgroups of the batched scan kernel
     int batch_mode = 0;                       // 0 auto, 1 always query by query, 2 list-major when eligible
-    unsigned int* d_row_norm_max = nullptr;   // largest squared row norm (float bits); device placement, 2-byte rows
+    unsigned int* d_row_norm_max = nullptr;   // largest squared row norm (float bits); device placement
+    float* d_row_norm = nullptr;              // squared norm of every row; device placement with squared L2
     ScanShape shape{0, 0, 0, 4};
     // Searches through ivf_search_device rotate over `lanes` (stream + workspace each) so that
     // independent queries overlap; lane 0 runs on compute_stream.  cs / cw: lane in use.
@@ -228,7 +229,7 @@ void free_workspace(Workspace& w) {
     dfree(w.d_redo_id); dfree(w.d_redo_key); hfree(w.h_flag);
     hfree(w.h_q); hfree(w.h_done); hfree(w.h_probe); hfree(w.h_out_ids); hfree(w.h_out_dists);
     hfree(w.h_cand); hfree(w.h_cand_count); hfree(w.h_scores);
-    dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row);
+    dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row); dfree(w.d_qq);
     dfree(w.d_q_store); dfree(w.d_thr); dfree(w.d_list_count); dfree(w.d_cursor); dfree(w.d_qstart);
     dfree(w.d_tstart); dfree(w.d_qidx); dfree(w.d_tasks); dfree(w.d_cand_count); dfree(w.d_cand_row);
     dfree(w.d_cand_key); dfree(w.d_overflow); hfree(w.h_overflow);
@@ -515,9 +516,10 @@ constexpr int kSurvCap = 4096;           // of those, rows re-scored in fp64
 
 bool batched_eligible(const ivf_index* ix, int nq) {
     if (ix->batch_mode == 1 || nq < 2) return false;
-    if (ix->placement != IVF_PLACE_DEVICE || ix->metric != IVF_IP || ix->dtype == IVF_F32) return false;
-    if (ix->d % 64 != 0 || !ix->d_row_norm_max) return false;   // the MFMA kernel walks 64-element blocks
-    if (batched_scan_lds(ix->d) > ix->max_lds) return false;    // a group's queries must fit LDS
+    if (ix->placement != IVF_PLACE_DEVICE || !ix->d_row_norm_max || ix->n >= (int64_t)1 << 32) return false;
+    if (ix->metric != IVF_IP && !ix->d_row_norm) return false;
+    if (ix->d % 64 != 0) return false;                          // the MFMA kernels walk whole blocks of elements
+    if (batched_scan_lds(ix->d, ix->dtype) > ix->max_lds) return false;    // a group's queries must fit LDS
     return ix->batch_mode == 2 || nq >= 4;
 }
 
@@ -526,17 +528,18 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
     if (nq <= w.b_nq && nprobe <= w.b_nprobe) return IVF_OK;
     const int nq2 = std::max(nq, w.b_nq), np2 = std::max(nprobe, w.b_nprobe);
     HIP_TRY(hipDeviceSynchronize());
-    dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row);
+    dfree(w.d_thr_part); dfree(w.d_cand_score); dfree(w.d_eps); dfree(w.d_surv_row); dfree(w.d_qq);
     dfree(w.d_q_store); dfree(w.d_thr); dfree(w.d_list_count); dfree(w.d_cursor); dfree(w.d_qstart);
     dfree(w.d_tstart); dfree(w.d_qidx); dfree(w.d_tasks); dfree(w.d_cand_count); dfree(w.d_cand_row);
     dfree(w.d_cand_key); dfree(w.d_overflow); hfree(w.h_overflow);
-    w.d_thr_part = nullptr; w.d_cand_score = nullptr; w.d_eps = nullptr; w.d_surv_row = nullptr;
+    w.d_thr_part = nullptr; w.d_cand_score = nullptr; w.d_eps = nullptr; w.d_surv_row = nullptr; w.d_qq = nullptr;
     w.d_q_store = nullptr; w.d_thr = nullptr; w.d_list_count = w.d_cursor = w.d_qstart = w.d_tstart = w.d_qidx = nullptr;
     w.d_tasks = nullptr; w.d_cand_count = w.d_cand_row = nullptr; w.d_cand_key = nullptr; w.d_overflow = w.h_overflow = nullptr;
     w.b_nq = w.b_nprobe = 0;
     const size_t nqz = nq2, nl = ix->nlist;
-    const uint64_t task_cap = batched_task_bound(ix->h_off.data(), ix->nlist, nq2, np2);
+    const uint64_t task_cap = batched_task_bound(ix->h_off.data(), ix->nlist, nq2, ix->dtype);
     HIP_TRY(hipMalloc(&w.d_q_store, nqz * ix->d * 2));
+    HIP_TRY(hipMalloc(&w.d_qq, nqz * sizeof(float)));
     HIP_TRY(hipMalloc(&w.d_thr, nqz * sizeof(float)));
     HIP_TRY(hipMalloc(&w.d_thr_part, batched_thr_part_floats(nq2) * sizeof(float)));
     HIP_TRY(hipMalloc(&w.d_list_count, nl * sizeof(uint32_t)));
@@ -557,22 +560,33 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
     return IVF_OK;
 }
 
+// the parts of the batched scan's arguments that do not depend on the call
+static void fill_batched_args(const ivf_index* ix, const Workspace& w, BatchedArgs& b) {
+    b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.probe = w.d_probe;
+    b.q_store = w.d_q_store; b.thr = w.d_thr; b.thr_part = w.d_thr_part; b.row_norm_max_bits = ix->d_row_norm_max;
+    b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
+    b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
+    b.cand_key = w.d_cand_key; b.cand_score = w.d_cand_score; b.eps = w.d_eps; b.qq = w.d_qq; b.row_norm = ix->d_row_norm;
+    b.surv_row = w.d_surv_row; b.overflow = w.d_overflow;
+    b.nlist = ix->nlist; b.d = ix->d; b.dtype = ix->dtype; b.metric = ix->metric;
+    b.cand_cap = kCandCap; b.surv_cap = kSurvCap;
+    b.group_q = batched_group_q(ix->dtype);
+    b.acc_coef = (float)ix->d * 0x1p-23f;            // d products accumulated in fp32, in an order the hardware chooses
+    b.samp_coef = batched_sample_coef(ix->d, ix->dtype, ix->metric);
+}
+
 // coarse + select for the batch, then the list-major scan and the final ranking into (out_ids,
 // out_dists) (device pointers); the overflow flags land in the workspace
 int enqueue_batched(ivf_index* ix, const float* q_dev, int nq, int nprobe, int k, int64_t* out_ids, float* out_dists) {
     Workspace& w = *ix->cw;
     int rc;
     if ((rc = enqueue_probe(ix, q_dev, nq, nprobe, 1, false, true))) return rc;
-    if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->d, ix->n_cu);
+    if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->metric, ix->d, ix->n_cu);
     BatchedArgs b{};
-    b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.q = q_dev; b.probe = w.d_probe;
-    b.q_store = w.d_q_store; b.thr = w.d_thr; b.thr_part = w.d_thr_part; b.row_norm_max_bits = ix->d_row_norm_max;
-    b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
-    b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
-    b.cand_key = w.d_cand_key; b.cand_score = w.d_cand_score; b.eps = w.d_eps; b.surv_row = w.d_surv_row; b.overflow = w.d_overflow; b.out_ids = out_ids; b.out_dists = out_dists;
+    fill_batched_args(ix, w, b);
+    b.q = q_dev; b.out_ids = out_ids; b.out_dists = out_dists;
     b.rows_counter = ix->profiling ? ix->d_prof_rows : nullptr;
-    b.nlist = ix->nlist; b.d = ix->d; b.dtype = ix->dtype; b.nq = nq; b.nprobe = nprobe; b.k = k;
-    b.kprime = kprime_for(k); b.cand_cap = kCandCap; b.surv_cap = kSurvCap;
+    b.nq = nq; b.nprobe = nprobe; b.k = k; b.kprime = kprime_for(k);
     hipEvent_t e0, e1, m0, m1;
     if ((rc = prof_events(ix, 2, &e0, &e1))) return rc;
     if ((rc = prof_events(ix, 3, &m0, &m1))) return rc;
@@ -649,13 +663,15 @@ int finish_tables(ivf_index* ix, size_t device_buffer_bytes) {
         HIP_TRY(hipMalloc(&ix->d_row_norm_max, sizeof(unsigned int)));
         HIP_TRY(hipMemset(ix->d_row_norm_max, 0, sizeof(unsigned int)));
         HIP_TRY(hipDeviceSynchronize());
-        HIP_TRY(launch_row_norm_max(ix->d_buf, ix->dtype, ix->n, ix->d, ix->d_row_norm_max, ix->compute));
+        // squared L2 also keeps every row's norm: the list-major scan turns inner products into distances with them
+        if (ix->metric != IVF_IP && ix->n > 0) HIP_TRY(hipMalloc(&ix->d_row_norm, (size_t)ix->n * sizeof(float)));
+        HIP_TRY(launch_row_norms(ix->d_buf, ix->dtype, ix->n, ix->d, ix->d_row_norm_max, ix->d_row_norm, ix->compute));
         HIP_TRY(hipStreamSynchronize(ix->compute));
         unsigned int bits = 0;
         HIP_TRY(hipMemcpy(&bits, ix->d_row_norm_max, sizeof bits, hipMemcpyDeviceToHost));
         float sq;
         memcpy(&sq, &bits, sizeof sq);
-        ix->row_norm_max = sqrtf(sq) * 1.0001f;         // the kernel sums in fp32
+        ix->row_norm_max = sqrtf(sq) * 1.0001f;         // the squared norm was rounded to fp32, and so is the root
     } else {
         ix->row_norm_max = host_row_norm_max(ix->h_lists, ix->dtype, ix->n, ix->d, *ix->pool) * 1.0001f;
     }
@@ -698,7 +714,7 @@ extern "C" void ivf_free(ivf_index* ix) {
     if (ix->ev_round) (void)hipEventDestroy(ix->ev_round);
     hfree(ix->h_moves); hfree(ix->h_hot_stage); dfree(ix->d_moves);
     dfree(ix->d_res_off);
-    dfree(ix->d_prof_rows); dfree(ix->d_row_norm_max);
+    dfree(ix->d_prof_rows); dfree(ix->d_row_norm_max); dfree(ix->d_row_norm);
     if (ix->own_buf) dfree(ix->d_buf);
     if (ix->own_h_lists) hfree(ix->h_lists);
     hfree(ix->h_res_stage);
@@ -921,6 +937,13 @@ static int run_batched(ivf_index* ix, size_t lane, const float* q_dev, int nq, i
 extern "C" int ivf_set_batch_mode(ivf_index* ix, int32_t mode) {
     if (!ix) return fail(IVF_EINVAL, "index is NULL");
     if (mode < 0 || mode > 2) return fail(IVF_EINVAL, "batch mode must be 0, 1 or 2");
+    if (mode == 2) {
+        const int saved = ix->batch_mode;
+        ix->batch_mode = 2;
+        const bool ok = batched_eligible(ix, 2);
+        ix->batch_mode = saved;
+        if (!ok) return fail(IVF_ESTATE, "this index has no list-major scan (needs all rows in HBM, fewer than 2^32 of them, and d a multiple of 64 that fits LDS)");
+    }
     ix->batch_mode = mode;
     return IVF_OK;
 }
@@ -1451,7 +1474,7 @@ extern "C" int ivf_batched_scores(ivf_index* ix, const float* q, int32_t nq, int
     ix->batch_mode = 2;
     const bool ok = batched_eligible(ix, 2);
     ix->batch_mode = saved_mode;
-    if (!ok) return fail(IVF_ESTATE, "this index has no list-major scan (needs fp16 / bf16 rows in HBM, inner product, d a multiple of 64 that fits LDS)");
+    if (!ok) return fail(IVF_ESTATE, "this index has no list-major scan (needs all rows in HBM, fewer than 2^32 of them, and d a multiple of 64 that fits LDS)");
     const int64_t n_c = ix->h_off[cluster + 1] - ix->h_off[cluster];
     if (n_c > kCandCap) return fail(IVF_ELIMIT, "the cluster has %lld rows, at most %d can be returned", (long long)n_c, kCandCap);
     if ((rc = settle_on_lane0(ix))) return rc;
@@ -1463,16 +1486,11 @@ extern "C" int ivf_batched_scores(ivf_index* ix, const float* q, int32_t nq, int
     std::vector<int32_t> probe((size_t)nq, cluster);
     HIP_TRY(hipMemcpyAsync(w.d_probe, probe.data(), (size_t)nq * sizeof(int32_t), hipMemcpyHostToDevice, ix->cs));
     HIP_TRY(hipStreamSynchronize(ix->cs));
-    if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->d, ix->n_cu);
+    if (ix->batched_grid == 0) ix->batched_grid = batched_resident_grid(ix->dtype, ix->metric, ix->d, ix->n_cu);
     BatchedArgs b{};
-    b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.q = w.d_q; b.probe = w.d_probe;
-    b.q_store = w.d_q_store; b.thr = w.d_thr; b.thr_part = w.d_thr_part; b.row_norm_max_bits = ix->d_row_norm_max;
-    b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
-    b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
-    b.cand_key = w.d_cand_key; b.cand_score = w.d_cand_score; b.eps = w.d_eps; b.surv_row = w.d_surv_row; b.overflow = w.d_overflow;
-    b.out_ids = w.d_out_ids; b.out_dists = w.d_out_dists;
-    b.nlist = ix->nlist; b.d = ix->d; b.dtype = ix->dtype; b.nq = nq; b.nprobe = 1; b.k = 1;
-    b.kprime = kprime_for(1); b.cand_cap = kCandCap; b.surv_cap = kSurvCap; b.keep_all = 1;
+    fill_batched_args(ix, w, b);
+    b.q = w.d_q; b.out_ids = w.d_out_ids; b.out_dists = w.d_out_dists;
+    b.nq = nq; b.nprobe = 1; b.k = 1; b.kprime = kprime_for(1); b.keep_all = 1;
     HIP_TRY(launch_batched(b, ix->batched_grid, ix->cs, nullptr, nullptr, false));
     HIP_TRY(hipStreamSynchronize(ix->cs));
     std::vector<uint32_t> count((size_t)nq), rows((size_t)n_c);

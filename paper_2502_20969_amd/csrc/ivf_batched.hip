@@ -1,14 +1,19 @@
 // Batched list scan for query batches that share probed clusters (TeleRAG Sec. 4.2 "Batching":
 // the GPU part of the search becomes a matrix-matrix product).  Each selected list is read from
-// HBM once per group of up to 32 queries that probe it; scores come from MFMA
-// (v_mfma_f32_32x32x16 f16 / bf16, fp32 accumulate) and are only used to FILTER rows: a row whose
-// approximate score reaches the query's threshold becomes a candidate, and the final ranking is
-// done on fp64 re-scores with the fp32 query, exactly as in the single-query path.
+// HBM once per group of queries that probe it (up to 32 for fp16 / bf16 rows, up to 16 for fp32
+// rows); scores come from MFMA (v_mfma_f32_32x32x16 f16 / bf16 or v_mfma_f32_16x16x4 f32, fp32
+// accumulate) and are only used to FILTER rows: a row whose approximate score reaches the query's
+// threshold becomes a candidate, and the final ranking is done on fp64 re-scores with the fp32
+// query, exactly as in the single-query path.
+//
+// Scores are "larger is better": <q, y> for the inner product, -|q - y|^2 for squared L2.  The
+// MFMA always computes <q, y>; for L2 the filter score is 2 <q, y> - |y|^2 - |q|^2 with |y|^2
+// from a table of row norms made when the index is built.
 //
 // Threshold of a query: the k-th best fp32 score over a sample of its nearest cluster (a lower
-// bound of its k-th best score over all selected clusters), lowered by a bound eps on the MFMA
-// score error (query rounded to the storage type, fp32 accumulation).  Every true top-k row
-// passes this filter.
+// bound of its k-th best score over all selected clusters), lowered by a bound eps on the error
+// of the filter score (query rounded to the storage type, fp32 accumulation, rounded norms).
+// Every true top-k row passes this filter.
 #include "ivf_device.h"
 #include <hip/hip_ext.h>
 
@@ -25,35 +30,39 @@ constexpr int kTileRows = kBatchWaves * 32;     // rows per task: 32 per wavefro
 constexpr int kStageLd = 64 + 8;   // elements per row of a wavefront's staging area: 64 + padding
 constexpr int kGroupQ = 32;        // queries per task: one MFMA tile wide
 constexpr int kQPad = 8;           // padding (elements) of a staged query row in LDS
+constexpr int kStage16 = 2;        // 64-element blocks of a row per pipeline stage (fp16 / bf16 rows)
 
-// ---- largest row norm of the lists (one-time, at build) -------------------------------------------
-__global__ void row_norm_max_kernel(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits) {
+// ---- row norms of the lists (one-time, at build) ---------------------------------------------------
+// Squared norms summed in fp64 and rounded once to fp32; the largest goes to out_bits, all of
+// them to out_norm when that is not null.
+__global__ void row_norm_kernel(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, float* out_norm) {
     const int lane = threadIdx.x & 63;
     int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     float best = 0.f;
     for (int64_t r = wave; r < n; r += nwaves) {
-        float s = 0.f;
+        double s = 0.0;
         for (int t = lane; t < d; t += 64) {
-            float x = (float)widen(lists, dtype, (size_t)r * d + t);
-            s = fmaf(x, x, s);
+            const double x = widen(lists, dtype, (size_t)r * d + t);
+            s = fma(x, x, s);
         }
-        s = group_sum<64>(s);
-        best = fmaxf(best, s);
+        const float f = (float)wave_sum(s);
+        if (out_norm && lane == 0) out_norm[r] = f;
+        best = fmaxf(best, f);
     }
     if (lane == 0) atomicMax(out_bits, __float_as_uint(best));   // non-negative floats order as integers
 }
 
-hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, hipStream_t s) {
+hipError_t launch_row_norms(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, float* out_norm, hipStream_t s) {
     if (n <= 0) return hipSuccess;
     int64_t blocks = (n + 3) / 4;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(row_norm_max_kernel, dim3((unsigned)blocks), dim3(256), 0, s, lists, dtype, n, d, out_bits);
+    hipLaunchKernelGGL(row_norm_kernel, dim3((unsigned)blocks), dim3(256), 0, s, lists, dtype, n, d, out_bits, out_norm);
     return hipGetLastError();
 }
 
 // ---- threshold sample --------------------------------------------------------------------------------------
-// fp32 scores (fp32 query) of the first 2048 rows of each query's (at most 64 nearest) selected
+// fp32 scores (fp32 query; <q, y>, or -sum (q - y)^2 for L2) of the first 2048 rows of each query's (at most 64 nearest) selected
 // clusters, taken in probe order (usually all from the nearest cluster; more clusters when those
 // are small), reduced to the k-th best.  Any subset of the selected rows gives a valid lower bound of the k-th best
 // score over all of them.  The sample of a query is split over kSampleParts workgroups of 128 rows;
@@ -111,19 +120,23 @@ __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int64_t row = g[u] >= 0 ? g[u] : g[0];      // past the end: re-read a valid row
-                v[u] = *(const uint4*)((const unsigned char*)a.lists + (size_t)row * a.d * 2 + (size_t)ch * 16);
+                v[u] = *(const uint4*)((const unsigned char*)a.lists + (size_t)row * a.d * T::kBytes + (size_t)ch * 16);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 float x[EPL];
                 Unpack<T>::run(v[u], x);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) s[u] = fmaf(ql[ch * EPL + e], x[e], s[u]);
+                for (int e = 0; e < EPL; ++e) {
+                    if (a.metric == 0) s[u] = fmaf(ql[ch * EPL + e], x[e], s[u]);
+                    else { const float df = ql[ch * EPL + e] - x[e]; s[u] = fmaf(df, df, s[u]); }
+                }
             }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             float ck = read_lane(group_total_last_lane<64>(s[u]), 63);
+            if (a.metric != 0) ck = -ck;
             if (g[u] >= 0 && ck >= top.thr) top.push(ck, r0 + u);
         }
         if (top.pcount > 60) top.flush(a.k);
@@ -159,15 +172,18 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
     const int qi = blockIdx.x, lane = threadIdx.x & 63;
     const float* q = a.q + (size_t)qi * a.d;
     float s = 0.f, res = 0.f;          // |q~|^2 of the rounded query and |q~ - q|^2 of the rounding
+    double qq = 0.0;                   // |q|^2
     for (int t = threadIdx.x; t < a.d; t += 64) {
-        float x = q[t], xr;
+        float x = q[t], xr = x;
         if (a.dtype == 1) { _Float16 h = (_Float16)x; ((_Float16*)a.q_store)[(size_t)qi * a.d + t] = h; xr = (float)h; }
-        else { __bf16 h = (__bf16)x; ((__bf16*)a.q_store)[(size_t)qi * a.d + t] = h; xr = (float)h; }
+        else if (a.dtype == 2) { __bf16 h = (__bf16)x; ((__bf16*)a.q_store)[(size_t)qi * a.d + t] = h; xr = (float)h; }
         s = fmaf(xr, xr, s);
         res = fmaf(xr - x, xr - x, res);
+        qq = fma((double)x, (double)x, qq);
     }
     s = group_sum<64>(s);
     res = group_sum<64>(res);
+    qq = wave_sum(qq);
     // k-th best key over the sample parts
     WaveTopK<2, false> top;
     top.init();
@@ -181,14 +197,23 @@ __global__ void prep_queries_kernel(BatchedArgs a) {
         }
     }
     if (lane == 0) {
-        // Bound of |MFMA score - exact score| for any row y: the query rounding contributes
-        // |<q~ - q, y>| <= |q~ - q| |y| (Cauchy-Schwarz, with the residual norm measured above),
-        // fp32 accumulation of d products at most d 2^-23 |q~| |y|; the fp32 sample score is
-        // covered by the same accumulation term.  A little slack absorbs the norms' own rounding.
-        float ymax = sqrtf(__uint_as_float(*a.row_norm_max_bits));
-        float eps = 1.01f * (sqrtf(res) + (float)a.d * 0x1p-22f * sqrtf(s)) * ymax;
+        // Bound of |filter score - exact score| for any row y.  Inner product from the MFMA: the
+        // query rounding contributes |<q~ - q, y>| <= |q~ - q| |y| (Cauchy-Schwarz, with the
+        // residual norm measured above), the fp32 accumulation at most acc_coef |q~| |y|.  The
+        // fp32 sample score behind the threshold is off by at most samp_coef |q| |y| (inner
+        // product) or samp_coef |q - y|^2 (L2: every term of the sum is positive).  The L2
+        // filter score 2 <q, y> - |y|^2 - |q|^2 doubles the inner-product error and adds the
+        // rounding of the two norms and of its two operations, each at most 2^-24 (|q| + |y|)^2.
+        // A little slack absorbs the rounding of this arithmetic itself.
+        const float ymax = sqrtf(__uint_as_float(*a.row_norm_max_bits));
+        const float qn = sqrtf((float)qq);
+        const float ip_err = (sqrtf(res) + a.acc_coef * sqrtf(s)) * ymax;
+        float eps;
+        if (a.metric == 0) eps = 1.01f * (ip_err + a.samp_coef * qn * ymax);
+        else eps = 1.01f * (2.f * ip_err + (a.samp_coef + 0x1p-21f) * (qn + ymax) * (qn + ymax));
         a.thr[qi] = a.keep_all ? -INFINITY : top.thr - eps;        // -inf (fewer than k sampled rows) stays -inf
         a.eps[qi] = eps;
+        a.qq[qi] = (float)qq;
         a.cand_count[qi] = 0;
     }
 }
@@ -215,7 +240,7 @@ __global__ __launch_bounds__(1024) void scan_lists_kernel(BatchedArgs a) {
         if (c < a.nlist) {
             cq = a.list_count[c];
             uint32_t n = (uint32_t)(a.off[c + 1] - a.off[c]);
-            ct = cq ? ((n + kTileRows - 1) / kTileRows) * ((cq + kGroupQ - 1) / kGroupQ) : 0;
+            ct = cq ? ((n + kTileRows - 1) / kTileRows) * ((cq + a.group_q - 1) / a.group_q) : 0;
             a.cursor[c] = 0;
         }
         uint32_t iq = cq, it = ct;
@@ -292,12 +317,13 @@ template <> struct Mfma<BF16> {
 // row l % 32, eight elements per step) through a small LDS area of its own, and reads the B
 // fragments (lane l: query l % 32, the same elements) from the staged queries.  Scores that reach
 // the query's threshold are appended to the query's candidate list.
-template <typename T>
+template <typename T, int METRIC>
 __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs a) {
     typedef typename Mfma<T>::frag frag;
     extern __shared__ unsigned char smem[];
     __shared__ uint32_t s_q[kGroupQ];
     __shared__ float s_thr[kGroupQ];
+    __shared__ float s_qq[kGroupQ];
     const int lane = lane_id(), wave = wave_id();
     const int d = a.d, qstride = d + kQPad;
     uint16_t* qs = (uint16_t*)smem;                      // [kGroupQ][d + kQPad] storage-type queries
@@ -319,6 +345,7 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs
                 uint32_t qi = ok ? a.qidx[qbase + threadIdx.x] : 0;
                 s_q[threadIdx.x] = ok ? qi : 0xFFFFFFFFu;
                 s_thr[threadIdx.x] = ok ? a.thr[qi] : INFINITY;
+                s_qq[threadIdx.x] = ok ? a.qq[qi] : 0.f;
             }
             __syncthreads();
             const int chunks = d / 8;                     // 16-byte chunks per query row
@@ -351,19 +378,25 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs
         float16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-        // two blocks (128 elements, 8 MFMA steps) per stage, the next stage's rows in flight
-        uint4 av[2][8];
-        auto issue = [&](int k0, uint4 (&v)[8]) {
+        float yy[16];                  // L2: squared norms of the rows this lane will hold scores of
+        if (METRIC != 0) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
+            for (int i = 0; i < 16; ++i)
+                yy[i] = a.row_norm[(size_t)lo + min(r0 + (uint32_t)((i / 4) * 8 + khalf * 4 + (i % 4)), n - 1)];
+        }
+        // kStage16 blocks (of 64 elements, 4 MFMA steps) per stage, the next stage's rows in flight
+        uint4 av[2][4 * kStage16];
+        auto issue = [&](int k0, uint4 (&v)[4 * kStage16]) {
+#pragma unroll
+            for (int b = 0; b < kStage16; ++b) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     v[b * 4 + u] = k0 + b * 64 < d ? load_stream16(lptr[u] + k0 + b * 64) : make_uint4(0, 0, 0, 0);
             }
         };
-        auto consume = [&](int k0, const uint4 (&v)[8]) {
+        auto consume = [&](int k0, const uint4 (&v)[4 * kStage16]) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
+            for (int b = 0; b < kStage16; ++b) {
                 if (k0 + b * 64 < d) {
                     // through LDS: written in the loading layout, read back as fragments.  A
                     // wavefront's LDS operations complete in order, so no barrier is needed.
@@ -378,17 +411,23 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs
                 }
             }
         };
+        constexpr int kStep = kStage16 * 64;              // elements per stage
         issue(0, av[0]);
-        for (int k0 = 0; k0 < d; k0 += 256) {
-            if (k0 + 128 < d) issue(k0 + 128, av[1]);
+        for (int k0 = 0; k0 < d; k0 += 2 * kStep) {
+            if (k0 + kStep < d) issue(k0 + kStep, av[1]);
             consume(k0, av[0]);
-            if (k0 + 128 >= d) break;
-            if (k0 + 256 < d) issue(k0 + 256, av[0]);
-            consume(k0 + 128, av[1]);
+            if (k0 + kStep >= d) break;
+            if (k0 + 2 * kStep < d) issue(k0 + 2 * kStep, av[0]);
+            consume(k0 + kStep, av[1]);
         }
         // lane holds query `col`, rows (i / 4) * 8 + khalf * 4 + i % 4
         const float thr = s_thr[col];
         const uint32_t qi = s_q[col];
+        if (METRIC != 0) {
+            const float qq = s_qq[col];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = fmaf(2.f, acc[i], -yy[i]) - qq;
+        }
         uint32_t pass = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -404,6 +443,174 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs
                     if (pos < (uint32_t)a.cand_cap) {
                         a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r0 + (i / 4) * 8 + khalf * 4 + (i % 4));
                         a.cand_score[(size_t)qi * a.cand_cap + pos] = acc[i];
+                    }
+                    ++pos;
+                }
+            }
+        }
+    }
+}
+
+// fp32 rows: v_mfma_f32_16x16x4_f32 multiplies a 16 x 4 block of rows (lane l: row l % 16,
+// element l / 16) with a 4 x 16 block of queries (lane l: query l % 16, the same element).  The
+// order of the elements inside a dot product is free, so the MFMA lane (row i, part p) takes the
+// 16-byte chunk p of each 16-element block of its row and the four values of the chunk feed four
+// MFMA steps; the query operand is read the same way from the group's queries in LDS.  The rows
+// are LOADED in another lane order, eight consecutive lanes on one 128-byte line of a row (MFMA
+// lanes of one row are 16 lanes apart: loading in that order makes every group of four lanes touch
+// four different lines, and half lines per instruction, which costs a quarter of the bandwidth),
+// and register moves across lanes (a DPP row shift and a ds_bpermute per value: no LDS memory)
+// take each value to its MFMA lane.  A wavefront scores two blocks of 16 rows against up to 16
+// queries; four 32-element pieces of its 32 rows are in flight while the previous four are consumed
+// (16 KB per wavefront: the depth per wavefront matters more here than a second workgroup per CU).
+typedef float float4_t __attribute__((ext_vector_type(4)));
+constexpr int kGroupQ32 = 16;      // queries per task for fp32 rows: one MFMA tile wide
+constexpr int kQPad32 = 4;         // padding (floats) of a staged query row: consecutive queries start 4 banks apart
+constexpr int kStage32 = 4;        // 32-element pieces of a row per pipeline stage
+
+template <int METRIC>
+__global__ __launch_bounds__(kBatchThreads) void batched_scan_f32_kernel(BatchedArgs a) {
+    extern __shared__ unsigned char smem[];
+    __shared__ uint32_t s_q[kGroupQ32];
+    __shared__ float s_thr[kGroupQ32];
+    __shared__ float s_qq[kGroupQ32];
+    const int lane = lane_id(), wave = wave_id();
+    const int d = a.d, qstride = d + kQPad32;
+    float* qs = (float*)smem;                            // [kGroupQ32][d + kQPad32] queries
+    const uint32_t total = a.tstart[a.nlist];
+    const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
+    const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    uint32_t staged_cluster = 0xFFFFFFFFu, staged_group = 0xFFFFFFFFu;
+    const int col = lane & 15, kq = lane >> 4;
+    for (uint32_t t = t_begin; t < t_end; ++t) {
+        const BatchTask task = a.tasks[t];
+        const uint32_t c = task.cluster;
+        const uint32_t qbase = a.qstart[c] + task.group * kGroupQ32;
+        const uint32_t nqg = min((uint32_t)kGroupQ32, a.qstart[c + 1] - qbase);
+        if (c != staged_cluster || task.group != staged_group) {
+            __syncthreads();                              // everyone is done with the previous queries
+            if (threadIdx.x < kGroupQ32) {
+                bool ok = threadIdx.x < nqg;
+                uint32_t qi = ok ? a.qidx[qbase + threadIdx.x] : 0;
+                s_q[threadIdx.x] = ok ? qi : 0xFFFFFFFFu;
+                s_thr[threadIdx.x] = ok ? a.thr[qi] : INFINITY;
+                s_qq[threadIdx.x] = ok ? a.qq[qi] : 0.f;
+            }
+            __syncthreads();
+            const int chunks = d / 4;                     // 16-byte chunks per query row
+            for (int i = threadIdx.x; i < kGroupQ32 * chunks; i += blockDim.x) {
+                int qq = i / chunks, ch = i - qq * chunks;
+                uint32_t qi = s_q[qq];
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (qi != 0xFFFFFFFFu) v = *(const uint4*)(a.q + (size_t)qi * d + ch * 4);
+                *(uint4*)(qs + (size_t)qq * qstride + ch * 4) = v;
+            }
+            __syncthreads();
+            staged_cluster = c; staged_group = task.group;
+        }
+        const int64_t lo = a.off[c];
+        const uint32_t n = (uint32_t)(a.off[c + 1] - lo);
+        const uint32_t r0 = task.tile * kTileRows + wave * 32;     // first row of this wavefront
+        if (r0 >= n) continue;
+        // Loading role of a lane: 16-byte chunk lane % 8 of rows lane / 8 and lane / 8 + 8 of each row
+        // block, for every 32-element (128-byte) piece of the rows; rows past the end re-read the last one.
+        const float* lp[4];            // [row block][row half]
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            lp[j] = (const float*)a.lists + ((size_t)lo + min(r0 + 8u * j + (uint32_t)(lane >> 3), n - 1)) * d + (lane & 7) * 4;
+        // lane that holds, after the exchange below, what this MFMA lane (row col, part kq) needs
+        const int from = (((col & 7) << 3) | ((col >> 3) << 2) | kq) << 2;
+        const float* bq = qs + (size_t)col * qstride + kq * 4;
+        float4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        float yy[8];                   // L2: squared norms of the rows this lane will hold scores of
+        if (METRIC != 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                yy[i] = a.row_norm[(size_t)lo + min(r0 + (uint32_t)((i / 4) * 16 + kq * 4 + (i % 4)), n - 1)];
+        }
+        uint4 av[2][4 * kStage32];
+        auto issue = [&](int k0, uint4 (&v)[4 * kStage32]) {
+#pragma unroll
+            for (int b = 0; b < kStage32; ++b) {
+                const bool in = k0 + b * 32 < d;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[4 * b + j] = in ? load_stream16(lp[j] + k0 + b * 32) : make_uint4(0, 0, 0, 0);
+            }
+        };
+        // One loaded value to its MFMA lanes.  Lanes with chunk >= 4 hold the second 16-element
+        // block of the piece.  A move by four lanes inside each row of 16 lanes (DPP row shift,
+        // written only to the lanes of one chunk half) gathers the first block of both row halves
+        // in one register (lane (r, c): row r + 8 (c / 4), chunk c % 4) and the second block in
+        // another; one lane permutation each then puts them in MFMA order.
+        auto to_mfma = [&](uint32_t lo_half, uint32_t hi_half, float& first, float& second) {
+            const int f = __builtin_amdgcn_update_dpp((int)lo_half, (int)hi_half, 0x114, 0xF, 0xA, false);   // row_shr:4 into chunks 4..7
+            const int g = __builtin_amdgcn_update_dpp((int)hi_half, (int)lo_half, 0x104, 0xF, 0x5, false);   // row_shl:4 into chunks 0..3
+            first = __int_as_float(__builtin_amdgcn_ds_bpermute(from, f));
+            second = __int_as_float(__builtin_amdgcn_ds_bpermute(from, g));
+        };
+        auto consume = [&](int k0, const uint4 (&v)[4 * kStage32]) {
+#pragma unroll
+            for (int b = 0; b < kStage32; ++b) {
+                if (k0 + b * 32 < d) {
+                    const float4 bv0 = *(const float4*)(bq + k0 + b * 32);
+                    const float4 bv1 = *(const float4*)(bq + k0 + b * 32 + 16);
+                    float x[2][2][4];          // [row block][16-element block][value of the chunk]
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb) {
+                        const uint4 h0 = v[4 * b + 2 * rb], h1 = v[4 * b + 2 * rb + 1];
+                        to_mfma(h0.x, h1.x, x[rb][0][0], x[rb][1][0]);
+                        to_mfma(h0.y, h1.y, x[rb][0][1], x[rb][1][1]);
+                        to_mfma(h0.z, h1.z, x[rb][0][2], x[rb][1][2]);
+                        to_mfma(h0.w, h1.w, x[rb][0][3], x[rb][1][3]);
+                    }
+                    const float q0[4] = {bv0.x, bv0.y, bv0.z, bv0.w}, q1[4] = {bv1.x, bv1.y, bv1.z, bv1.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[0][0][e], q0[e], acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[1][0][e], q0[e], acc[1], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[0][1][e], q1[e], acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[1][1][e], q1[e], acc[1], 0, 0, 0);
+                    }
+                }
+            }
+        };
+        constexpr int kStep = kStage32 * 32;              // elements per stage
+        issue(0, av[0]);
+        for (int k0 = 0; k0 < d; k0 += 2 * kStep) {
+            if (k0 + kStep < d) issue(k0 + kStep, av[1]);
+            consume(k0, av[0]);
+            if (k0 + kStep >= d) break;
+            if (k0 + 2 * kStep < d) issue(k0 + 2 * kStep, av[0]);
+            consume(k0 + kStep, av[1]);
+        }
+        // lane holds query `col`, rows (i / 4) * 16 + kq * 4 + i % 4
+        const float thr = s_thr[col];
+        const uint32_t qi = s_q[col];
+        float sc[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { sc[i] = acc[0][i]; sc[4 + i] = acc[1][i]; }
+        if (METRIC != 0) {
+            const float qq = s_qq[col];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sc[i] = fmaf(2.f, sc[i], -yy[i]) - qq;
+        }
+        uint32_t pass = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t r = r0 + (i / 4) * 16 + kq * 4 + (i % 4);
+            if (sc[i] >= thr && r < n) pass |= 1u << i;
+        }
+        if (pass) {
+            uint32_t pos = atomicAdd(&a.cand_count[qi], (uint32_t)__popc(pass));
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if ((pass >> i) & 1u) {
+                    if (pos < (uint32_t)a.cand_cap) {
+                        a.cand_row[(size_t)qi * a.cand_cap + pos] = (uint32_t)(lo + r0 + (i / 4) * 16 + kq * 4 + (i % 4));
+                        a.cand_score[(size_t)qi * a.cand_cap + pos] = sc[i];
                     }
                     ++pos;
                 }
@@ -477,18 +684,14 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
     // 2. fp64 re-score of the survivors
     uint64_t* keys = a.cand_key + (size_t)qi * a.surv_cap;
     const float* q = a.q + (size_t)qi * a.d;
-    const size_t row_bytes = (size_t)a.d * 2;
-    // a group of lanes per survivor, 32 survivors per pass, so that their row loads overlap; the
-    // same order of operations as the query-by-query merge
+    // a group of lanes per survivor, so that their row loads overlap; the same order of operations
+    // as the query-by-query merge
     constexpr int kLpc = kRescoreLanes;
     const int sub = tid % kLpc;
 #pragma unroll 1
     for (uint32_t c = (uint32_t)(tid / kLpc); c < n; c += (uint32_t)(nt / kLpc)) {
-        const unsigned char* rp = (const unsigned char*)a.lists + (size_t)rows[c] * row_bytes;
-        double s = a.dtype == 1 ? rescore_partial<F16>(rp, q, a.d, 0, sub, kLpc) : rescore_partial<BF16>(rp, q, a.d, 0, sub, kLpc);
-#pragma unroll
-        for (int o = 1; o < kLpc; o <<= 1) s += __shfl_xor(s, o);
-        if (sub == 0) keys[c] = ~ordered(s);            // ascending key = best first
+        const double s = rescore_row(a.lists, q, a.d, a.dtype, a.metric, rows[c], sub);
+        if (sub == 0) keys[c] = ~ordered(a.metric == 0 ? s : -s);            // ascending key = best first
     }
     __syncthreads();
     const uint32_t want = min((uint32_t)k, n);
@@ -548,45 +751,62 @@ __global__ __launch_bounds__(kSelectThreads) void batched_merge_kernel(BatchedAr
         }
         if (rank < (uint32_t)k) {
             a.out_ids[(size_t)qi * k + rank] = mi;
-            a.out_dists[(size_t)qi * k + rank] = (float)mk;
+            a.out_dists[(size_t)qi * k + rank] = (float)(a.metric == 0 ? mk : -mk);
         }
     }
     for (uint32_t i = tot + tid; i < (uint32_t)k; i += nt) {
         a.out_ids[(size_t)qi * k + i] = -1;
-        a.out_dists[(size_t)qi * k + i] = -INFINITY;
+        a.out_dists[(size_t)qi * k + i] = a.metric == 0 ? -INFINITY : INFINITY;
     }
 }
 
 // ---- launch sequence ---------------------------------------------------------------------------------------
-size_t batched_scan_lds(int d) {
+int batched_group_q(int dtype) { return dtype == 0 ? kGroupQ32 : kGroupQ; }
+
+size_t batched_scan_lds(int d, int dtype) {
+    if (dtype == 0) return (size_t)kGroupQ32 * (d + kQPad32) * 4;
     return (size_t)kGroupQ * (d + kQPad) * 2 + (size_t)kBatchWaves * 32 * kStageLd * 2;
 }
 
-uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe) {
-    // a cluster has at most min(nq, ...) queries; every cluster may be probed
+uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int dtype) {
+    // every cluster may be probed, by every query
     uint64_t tiles = 0;
     for (int c = 0; c < nlist; ++c) tiles += (uint64_t)((off_host[c + 1] - off_host[c] + kTileRows - 1) / kTileRows);
-    uint64_t groups = (uint64_t)(nq + kGroupQ - 1) / kGroupQ;
-    // clusters with fewer than a full group of queries still cost one group each: bound by pairs too
-    uint64_t bound = tiles * groups;
-    (void)nprobe;
-    return bound + 1;
+    const uint64_t gq = (uint64_t)batched_group_q(dtype);
+    return tiles * (((uint64_t)nq + gq - 1) / gq) + 1;
 }
 
 size_t batched_thr_part_floats(int nq) { return (size_t)nq * kSampleParts * kMaxKPrime; }
 
-int batched_resident_grid(int dtype, int d, int n_cu) {
+typedef void (*BatchedScanFn)(BatchedArgs);
+static BatchedScanFn batched_scan_fn(int dtype, int metric) {
+    if (dtype == 0) return metric == 0 ? batched_scan_f32_kernel<0> : batched_scan_f32_kernel<1>;
+    if (dtype == 1) return metric == 0 ? batched_scan_kernel<F16, 0> : batched_scan_kernel<F16, 1>;
+    return metric == 0 ? batched_scan_kernel<BF16, 0> : batched_scan_kernel<BF16, 1>;
+}
+
+int batched_resident_grid(int dtype, int metric, int d, int n_cu) {
     int per_cu = 0;
-    const void* fn = dtype == 1 ? (const void*)batched_scan_kernel<F16> : (const void*)batched_scan_kernel<BF16>;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kBatchThreads, batched_scan_lds(d));
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)batched_scan_fn(dtype, metric), kBatchThreads,
+                                                                batched_scan_lds(d, dtype));
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (per_cu > 4) per_cu = 4;
     return per_cu * n_cu;
 }
 
+// rounding of an fp32 sum made like the threshold sample's: terms per lane, six additions across
+// the lanes, and for L2 the rounded difference and its square
+float batched_sample_coef(int d, int dtype, int metric) {
+    const int epl = dtype == 0 ? 4 : 8;
+    const int chunks = d / epl;
+    const int terms = epl * ((chunks + 63) / 64) + 6 + (metric != 0 ? 3 : 0);
+    return 1.05f * (float)(terms + 2) * 0x1p-24f;
+}
+
 hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start, hipEvent_t scan_stop, bool with_merge) {
     const int pairs = a.nq * a.nprobe;
-    if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
+    if (a.dtype == 0) hipLaunchKernelGGL(thr_sample_kernel<F32>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
+    else if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
     else hipLaunchKernelGGL(thr_sample_kernel<BF16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
     hipLaunchKernelGGL(prep_queries_kernel, dim3(a.nq), dim3(64), 0, s, a);
     hipLaunchKernelGGL(zero_u32_kernel, dim3((a.nlist + 255) / 256), dim3(256), 0, s, a.list_count, a.nlist);
@@ -594,10 +814,8 @@ hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEven
     hipLaunchKernelGGL(scan_lists_kernel, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(fill_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);
     hipLaunchKernelGGL(make_tasks_kernel, dim3(min(a.nlist, 4096)), dim3(256), 0, s, a);
-    if (a.dtype == 1)
-        IVF_LAUNCH(batched_scan_kernel<F16>, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
-    else
-        IVF_LAUNCH(batched_scan_kernel<BF16>, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d), s, scan_start, scan_stop, a);
+    const BatchedScanFn scan = batched_scan_fn(a.dtype, a.metric);
+    IVF_LAUNCH(scan, dim3(grid), dim3(kBatchThreads), batched_scan_lds(a.d, a.dtype), s, scan_start, scan_stop, a);
     if (with_merge) hipLaunchKernelGGL(batched_merge_kernel, dim3(a.nq), dim3(kSelectThreads), 0, s, a);
     return hipGetLastError();
 }

@@ -159,7 +159,7 @@ constexpr int kScheduleMaxQueries = 4096;
 struct BatchTask { uint32_t cluster, group, tile; };    // 128 rows of a cluster x up to 32 of its queries
 
 struct BatchedArgs {
-    const void* lists;           // device lists (device placement), fp16 or bf16
+    const void* lists;           // device lists (device placement)
     const int64_t* off;          // [nlist+1]
     const int64_t* ids;          // [n] or nullptr
     const float* q;              // [nq x d] fp32 queries
@@ -178,23 +178,31 @@ struct BatchedArgs {
     uint32_t* cand_row;          // [nq x cand_cap] global rows that passed the filter
     float* cand_score;           // [nq x cand_cap] their approximate (MFMA) scores
     float* eps;                  // [nq] bound of |approximate - exact| score
+    float* qq;                   // [nq] squared norms of the queries
+    const float* row_norm;       // [n] squared norms of the rows (L2 only)
     uint32_t* surv_row;          // [nq x surv_cap] rows that survive the pruning by approximate score
     uint64_t* cand_key;          // [nq x surv_cap] fp64 re-scores as ascending keys
     int32_t* overflow;           // [nq] 1 when a query had more candidates than cand_cap
     int64_t* out_ids; float* out_dists;      // [nq x k]
     unsigned long long* rows_counter;        // nullable: rows covered by the scan tasks (profiling)
-    int nlist, d, dtype, nq, nprobe, k, kprime, cand_cap, surv_cap;
+    int nlist, d, dtype, metric, nq, nprobe, k, kprime, cand_cap, surv_cap;
+    int group_q;                 // queries per task: batched_group_q(dtype)
+    float acc_coef;              // fp32 accumulation of the MFMA: |error| <= acc_coef |q| |y|
+    float samp_coef;             // batched_sample_coef(d, dtype, metric)
     int keep_all;                // 1: the threshold is -inf, every scanned row becomes a candidate (stage-level test entry)
 };
 // upper bound of the number of tasks for a batch of nq queries
-uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int nprobe);
-hipError_t launch_row_norm_max(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, hipStream_t s);
+uint64_t batched_task_bound(const int64_t* off_host, int nlist, int nq, int dtype);
+// squared row norms (fp64 sums rounded to fp32): the largest as float bits, all of them when out_norm is not null
+hipError_t launch_row_norms(const void* lists, int dtype, int64_t n, int d, unsigned int* out_bits, float* out_norm, hipStream_t s);
+int batched_group_q(int dtype);
+float batched_sample_coef(int d, int dtype, int metric);
 // with_merge = false stops after the scan: the candidate lists hold what passed the filter
 hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEvent_t scan_start = nullptr,
                           hipEvent_t scan_stop = nullptr, bool with_merge = true);
-int batched_resident_grid(int dtype, int d, int n_cu);
+int batched_resident_grid(int dtype, int metric, int d, int n_cu);
 size_t batched_thr_part_floats(int nq);
-size_t batched_scan_lds(int d);      // LDS bytes of the batched scan kernel (one group of queries)
+size_t batched_scan_lds(int d, int dtype);      // LDS bytes of the batched scan kernel (one group of queries)
 
 // scatters n rows to their cluster-major positions: dst[pos[i]] = src[i] (row_bytes each)
 // n floats from a pinned host buffer (its device address) to device memory, by a kernel

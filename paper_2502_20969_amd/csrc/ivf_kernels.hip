@@ -1036,33 +1036,6 @@ __device__ __forceinline__ void gather_radix(const MergeArgs& a, const Cand* par
     __syncthreads();
 }
 
-// fp64 score of the stored row `brow` of the buffer for the query q, computed by a group of
-// kRescoreLanes lanes (sub = lane in the group); every lane of the group gets the sum.  One fixed
-// order of operations (rescore_partial, then a butterfly over the lane distances 1 .. 16).
-__device__ __forceinline__ double rescore_row(const void* buf, const float* q, int d, int dtype, int metric,
-                                              size_t brow, int sub) {
-    constexpr int lpc = kRescoreLanes;
-    const size_t row_bytes = (size_t)d * (dtype == 0 ? 4 : 2);
-    const unsigned char* rp = (const unsigned char*)buf + brow * row_bytes;
-    double s = 0.0;
-    if (row_bytes % 16 == 0) {
-        if (dtype == 0) s = rescore_partial<F32>(rp, q, d, metric, sub, lpc);
-        else if (dtype == 1) s = rescore_partial<F16>(rp, q, d, metric, sub, lpc);
-        else s = rescore_partial<BF16>(rp, q, d, metric, sub, lpc);
-    } else {
-        const size_t e0 = brow * (size_t)d;
-#pragma unroll 1
-        for (int t = sub; t < d; t += lpc) {
-            const double x = (double)q[t], y = widen(buf, dtype, e0 + t);
-            if (metric == 0) s = fma(x, y, s);
-            else { const double df = x - y; s = fma(df, df, s); }
-        }
-    }
-#pragma unroll 1
-    for (int o = 1; o < lpc; o <<= 1) s += __shfl_xor(s, o);
-    return s;
-}
-
 // Can a row that the scan or the gathering dropped still belong to the k nearest?  Everything
 // dropped anywhere has an fp32 key of at most f_last, the key of the last candidate kept, so its
 // exact score is at most f_last + E, E bounding the rounding of the fp32 accumulation:

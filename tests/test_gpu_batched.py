@@ -19,15 +19,22 @@ def streams():
 
 
 def _stored_numpy(ds):
+    if ds.dtype == "f32":
+        return ds.rows.cpu().numpy(), O.F32
     if ds.dtype == "f16":
         return ds.rows.cpu().numpy(), O.F16
     return ds.rows.cpu().view(torch.int16).numpy().view(np.uint16), O.BF16
 
 
-@pytest.mark.parametrize("dtype,d,nq,k,nprobe", [
-    ("f16", 768, 32, 10, 24), ("bf16", 1024, 37, 10, 16), ("f16", 128, 5, 100, 40), ("bf16", 256, 64, 1, 7),
+@pytest.mark.parametrize("dtype,d,nq,k,nprobe,metric", [
+    ("f16", 768, 32, 10, 24, "ip"), ("bf16", 1024, 37, 10, 16, "ip"), ("f16", 128, 5, 100, 40, "ip"),
+    ("bf16", 256, 64, 1, 7, "ip"),
+    ("f32", 768, 8, 3, 24, "ip"), ("f32", 128, 37, 100, 40, "ip"), ("f32", 1024, 16, 10, 7, "l2"), ("f32", 64, 70, 1, 30, "l2"),
+    ("f16", 768, 32, 10, 24, "l2"), ("bf16", 256, 64, 5, 7, "l2"),
 ])
-def test_list_major_equals_oracle_and_per_query(streams, dtype, d, nq, k, nprobe):
+def test_list_major_equals_oracle_and_per_query(streams, dtype, d, nq, k, nprobe, metric):
+    pm, om = (P.IVF_IP, O.IP) if metric == "ip" else (P.IVF_L2, O.L2)
+    esz = 4 if dtype == "f32" else 2
     nlist = 96
     sizes = W.zipf_sizes(60000 if d <= 256 else 30000, nlist, 1.1, 3)
     sizes[5] += sizes[7]; sizes[7] = 0                  # an empty cluster
@@ -37,7 +44,7 @@ def test_list_major_equals_oracle_and_per_query(streams, dtype, d, nq, k, nprobe
     off = ds.offsets.numpy()
     cent = ds.centroids.cpu().numpy()
     ids = (np.random.default_rng(1).permutation(ds.n) * 2 + 3).astype(np.int64)
-    index = P.ivf_adopt_layout(ds.rows, dtype, off, cent, ids=ids, metric=P.IVF_IP,
+    index = P.ivf_adopt_layout(ds.rows, dtype, off, cent, ids=ids, metric=pm,
                                compute_stream=streams[0], copy_stream=streams[1])
     index.ivf_set_batch_mode(2)
     bi, bd, st = index.ivf_search(q, nprobe, k, with_stats=True)
@@ -46,13 +53,13 @@ def test_list_major_equals_oracle_and_per_query(streams, dtype, d, nq, k, nprobe
     assert np.array_equal(bi, pi) and np.array_equal(bd, pd)
     exempt = 0
     for b in range(nq):
-        exempt += check_topk(bi[b], bd[b], lists, odt, off, ids, cent, q[b], nprobe, k, O.IP)
+        exempt += check_topk(bi[b], bd[b], lists, odt, off, ids, cent, q[b], nprobe, k, om)
     assert exempt == 0
     # bytes reported: the union of the selected clusters, each once
     union = set()
     for b in range(nq):
-        union |= set(O.probe(cent, q[b], nprobe, O.IP))
-    assert st.bytes_gpu == sum(int(off[c + 1] - off[c]) for c in union) * d * 2
+        union |= set(O.probe(cent, q[b], nprobe, om))
+    assert st.bytes_gpu == sum(int(off[c + 1] - off[c]) for c in union) * d * esz
     # device-pointer entry point, automatic mode (nq >= 4 goes list-major)
     index.ivf_set_batch_mode(0)
     q_dev = torch.from_numpy(q).cuda()
@@ -120,7 +127,8 @@ def test_batches_in_flight_are_finished_by_synchronize(streams, depth):
     index.close()
 
 
-@pytest.mark.parametrize("dtype,d,nq", [("f16", 128, 256), ("bf16", 256, 200), ("f16", 768, 32), ("bf16", 64, 77)])
+@pytest.mark.parametrize("dtype,d,nq", [("f16", 128, 256), ("bf16", 256, 200), ("f16", 768, 32), ("bf16", 64, 77),
+                                        ("f32", 128, 200), ("f32", 768, 17), ("f32", 64, 77)])
 def test_list_major_finds_every_row_by_its_own_query(streams, dtype, d, nq):
     """Coverage of the batched scan: with every list selected, each stored row is the nearest
     neighbour of its own values (normalised, distinct rows), whichever tile of 256 rows and group of
@@ -149,32 +157,43 @@ def test_list_major_finds_every_row_by_its_own_query(streams, dtype, d, nq):
     index.close()
 
 
-@pytest.mark.parametrize("dtype,d", [("f16", 1920), ("bf16", 1920), ("f16", 768), ("bf16", 1024)])
-def test_filter_scores_stay_within_the_assumed_bound(streams, dtype, d):
+@pytest.mark.parametrize("dtype,d,metric", [("f16", 1920, "ip"), ("bf16", 1920, "ip"), ("f16", 768, "ip"), ("bf16", 1024, "ip"),
+                                            ("f32", 768, "ip"), ("f32", 1920, "ip"), ("f32", 1024, "l2"), ("f16", 1920, "l2"),
+                                            ("bf16", 768, "l2")])
+def test_filter_scores_stay_within_the_assumed_bound(streams, dtype, d, metric):
     """The list-major scan prunes with MFMA scores and a bound eps of their error (query rounded to
-    the storage type, fp32 accumulation inside the matrix cores).  The scores of every row of a
-    cluster are read back and compared with fp64 inner products with the unrounded query, for sign
-    patterns that make the rounding add up: all-positive operands, alternating signs on both sides
-    (every product positive), and random signs.  d = 1920 is the longest row this path takes."""
+    the storage type, fp32 accumulation inside the matrix cores; for squared L2 also the rounded
+    norms).  The scores of every row of a cluster are read back and compared with fp64 values from
+    the unrounded query, for sign patterns that make the rounding add up: all-positive operands,
+    alternating signs on both sides (every product positive), and random signs.  d = 1920 is the
+    longest row this path takes."""
     rng = np.random.default_rng(21)
     n = 3000
     mag = np.abs(rng.standard_normal((n, d))) + 0.05
     signs_alt = np.where(np.arange(d) % 2 == 0, 1.0, -1.0)
     rows = np.concatenate([mag[:1000], mag[1000:2000] * signs_alt, mag[2000:] * rng.choice([-1.0, 1.0], (1000, d))])
     rows /= np.linalg.norm(rows, axis=1, keepdims=True)
-    t = torch.from_numpy(rows.astype(np.float32)).to(torch.float16 if dtype == "f16" else torch.bfloat16).cuda()
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    t = torch.from_numpy(rows.astype(np.float32)).to(tdt).cuda()
     off = np.array([0, n], dtype=np.int64)
     cent = np.ones((1, d), dtype=np.float32)
-    index = P.ivf_adopt_layout(t, dtype, off, cent, metric=P.IVF_IP, compute_stream=streams[0], copy_stream=streams[1])
+    index = P.ivf_adopt_layout(t, dtype, off, cent, metric=P.IVF_IP if metric == "ip" else P.IVF_L2,
+                               compute_stream=streams[0], copy_stream=streams[1])
     q = np.abs(rng.standard_normal((12, d))) + 0.05
     q[4:8] *= signs_alt
     q[8:] *= rng.choice([-1.0, 1.0], (4, d))
     q = (q / np.linalg.norm(q, axis=1, keepdims=True)).astype(np.float32)
     approx, eps = index.ivf_batched_scores(q, 0, n)
-    exact = q.astype(np.float64) @ t.to(torch.float64).cpu().numpy().T
+    y = t.to(torch.float64).cpu().numpy()
+    q64 = q.astype(np.float64)
+    if metric == "ip":
+        exact = q64 @ y.T
+    else:
+        exact = -((q64[:, None, :] - y[None, :, :]) ** 2).sum(axis=2)
     err = np.abs(approx.astype(np.float64) - exact).max(axis=1)
-    print(f"{dtype} d {d}: largest |MFMA - exact| / eps per query: {np.round(err / eps, 3)}")
+    print(f"{dtype} {metric} d {d}: largest |filter score - exact| / eps per query: {np.round(err / eps, 3)}")
     assert np.all(eps > 0) and np.all(err <= eps), (err, eps)
     # the bound is not vacuous: it is within two orders of magnitude of the largest error seen
-    assert (err / eps).max() > 0.01
+    # (fp32 rows: within three, the accumulation order inside the matrix cores is not known)
+    assert (err / eps).max() > (0.001 if dtype == "f32" else 0.01)
     index.close()

@@ -75,11 +75,19 @@ def test_random_search_case(streams, seed):
     index.close()
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_batched_case(streams, seed):
-    """List-major batched search: equal to the oracle and, bit for bit, to the query-by-query path."""
+    """List-major batched search: equal to the oracle and, bit for bit, to the query-by-query path.
+    The first 24 seeds are 2-byte rows with the inner product; the later ones draw fp32 rows and
+    squared L2 as well."""
     rng = np.random.default_rng(9500 + seed)
     dtype = str(rng.choice(["f16", "bf16"]))
+    metric = "ip"
+    if seed >= 24:
+        rng2 = np.random.default_rng(9700 + seed)
+        dtype = str(rng2.choice(["f32", "f32", "f16", "bf16"]))
+        metric = str(rng2.choice(["ip", "l2"])) if dtype != "f32" else str(rng2.choice(["ip", "l2", "l2"]))
+    pm, om = (P.IVF_IP, O.IP) if metric == "ip" else (P.IVF_L2, O.L2)
     d = int(rng.choice([64, 128, 192, 256, 768, 1024]))
     nlist = int(rng.choice([3, 16, 64, 200, 1000]))
     n = int(rng.integers(nlist, 40000))
@@ -98,14 +106,18 @@ def test_random_batched_case(streams, seed):
     t = torch.from_numpy(st.view(np.int16) if dtype == "bf16" else st).cuda()
     if dtype == "bf16":
         t = t.view(torch.bfloat16)
-    index = P.ivf_adopt_layout(t, dtype, off, cent, ids=ids, metric=P.IVF_IP, compute_stream=streams[0],
+    index = P.ivf_adopt_layout(t, dtype, off, cent, ids=ids, metric=pm, compute_stream=streams[0],
                                copy_stream=streams[1])
     q = (cent[rng.integers(0, nlist, nq)] + 0.3 * rng.standard_normal((nq, d))).astype(np.float32)
     index.ivf_set_batch_mode(2)
-    gi, gd = index.ivf_search(q, nprobe, k)
+    gi, gd, stats = index.ivf_search(q, nprobe, k, with_stats=True)
+    union = set()
+    for b in range(nq):
+        union |= set(O.probe(cent, q[b], nprobe, om))
+    assert stats.bytes_gpu == sum(int(off[c + 1] - off[c]) for c in union) * d * st.itemsize   # each list read once
     exempt = 0
     for b in range(nq):
-        exempt += check_topk(gi[b], gd[b], st, odt, off, ids, cent, q[b], nprobe, k, O.IP)
+        exempt += check_topk(gi[b], gd[b], st, odt, off, ids, cent, q[b], nprobe, k, om)
     assert exempt == 0
     index.ivf_set_batch_mode(1)
     hi, hd = index.ivf_search(q, nprobe, k)
