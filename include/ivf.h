@@ -305,7 +305,7 @@ int ivf_cache_plan(float* hotness, const int64_t* offsets, int32_t nlist, size_t
  *   offsets   host, enough entries for every listed cluster (c + 1 is read)
  *   ids       host, row -> id, or NULL (id = row)
  *   q         host, d float32         clusters  host, n_clusters lists to scan
- *   out_ids / out_scores   host, room for k + max(8, k / 8) entries: the candidates the merge step
+ *   out_ids / out_scores   host, room for ivf_host_scan_capacity(k) entries: the candidates the merge step
  *             would receive, unordered, with their float64 scores (inner product, or squared L2)
  *   *n_out    number of candidates written; the k best by (score, id) are among them
  * threads: host threads to use (at least 1).  Caller keeps every array.
@@ -313,6 +313,9 @@ int ivf_cache_plan(float* hotness, const int64_t* offsets, int32_t nlist, size_t
 int ivf_host_scan(const void* lists, const int64_t* offsets, const int64_t* ids, int32_t d, int dtype,
                   int metric, const float* q, const int32_t* clusters, int32_t n_clusters, int32_t k,
                   int32_t threads, int64_t* out_ids, double* out_scores, int32_t* n_out);
+/* Entries ivf_host_scan may write for a search of k results (k' of "Arithmetic" above); 0 when k is
+ * outside 1 .. IVF_MAX_K. */
+int32_t ivf_host_scan_capacity(int32_t k);
 
 /* Kernel timing with HIP events on compute_stream around each kernel of every search while
  * enabled (adds event records to the stream; leave off when timing throughput). */

@@ -26,7 +26,7 @@ EXPORTS = [
     "ivf_resident", "ivf_batched_scores", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
-    "ivf_schedule", "ivf_host_scan", "ivf_prefetch_plan", "ivf_cache_plan", "ivf_strerror", "ivf_last_error",
+    "ivf_schedule", "ivf_host_scan", "ivf_host_scan_capacity", "ivf_prefetch_plan", "ivf_cache_plan", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -364,11 +364,11 @@ def ivf_host_scan(lists, dtype, offsets, q, clusters, k, ids=None, metric=IVF_IP
     cl = _host(clusters, np.int32).reshape(-1)
     d = rows.shape[1]
     assert qv.shape[0] == d
-    cap = k + max(8, k // 8)
+    L = load()
+    cap = max(1, int(L.ivf_host_scan_capacity(int(k))))      # 0 for a k the library will refuse below
     out_ids = np.empty(cap, dtype=np.int64)
     out_scores = np.empty(cap, dtype=np.float64)
     n_out = C.c_int32(0)
-    L = load()
     _check(L.ivf_host_scan(_ptr(rows), _ptr(off), _ptr(idv), d, DTYPE_CODE[dtype], metric, _ptr(qv), _ptr(cl),
                            cl.shape[0], k, threads, _ptr(out_ids), _ptr(out_scores), C.byref(n_out)))
     return out_ids[:n_out.value], out_scores[:n_out.value]

@@ -1558,6 +1558,10 @@ extern "C" int ivf_profile_reset(ivf_index* ix) {
     return IVF_OK;
 }
 
+extern "C" int32_t ivf_host_scan_capacity(int32_t k) {
+    return k >= 1 && k <= IVF_MAX_K ? kprime_for(k) : 0;
+}
+
 extern "C" int ivf_host_scan(const void* lists, const int64_t* offsets, const int64_t* ids, int32_t d, int dtype,
                              int metric, const float* q, const int32_t* clusters, int32_t n_clusters, int32_t k,
                              int32_t threads, int64_t* out_ids, double* out_scores, int32_t* n_out) {
