@@ -520,6 +520,18 @@ __device__ __forceinline__ Cand mirror(Cand c) {
     return ((uint64_t)mirror_lane_u32((uint32_t)(c >> 32)) << 32) | mirror_lane_u32((uint32_t)c);
 }
 
+// The largest candidate word held by any lane (0 when all are empty); every lane gets it.
+__device__ __forceinline__ Cand wave_max(Cand c) {
+    Cand o;
+    o = xor_lane<1>(c); c = o > c ? o : c;
+    o = xor_lane<2>(c); c = o > c ? o : c;
+    o = xor_lane<4>(c); c = o > c ? o : c;
+    o = xor_lane<8>(c); c = o > c ? o : c;
+    o = xor_lane<16>(c); c = o > c ? o : c;
+    o = xor_lane<32>(c); c = o > c ? o : c;
+    return c;
+}
+
 // One compare-exchange step between lane and lane ^ STRIDE.  keep_first: this lane keeps the
 // candidate that comes first (the larger word), else the other one.
 template <int STRIDE>

@@ -286,68 +286,129 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, ui
     if (in_lds && nprobe <= 64 && a.nlist <= kSelectWaveSortMax) {
         // Few clusters wanted from a small index.  Each score is cut down to a packed candidate:
         // the top 40 bits of its descending key image, then the complement of the cluster index
-        // (larger = nearer; equal prefixes by smaller index).  Every wavefront sorts chunks of 64
-        // in registers and keeps its best 64; a pairwise tree merges the wavefronts' runs.  The
-        // order of the prefixes is the order of the scores wherever prefixes differ, so the
-        // result is exact unless two prefixes tie among the selected clusters or across the
-        // cut; then the exact general path below redoes the selection.
+        // (larger = nearer; equal prefixes by smaller index).  The candidates are dealt to 64 or
+        // 128 groups (a thread's go to the group of its lane); the nprobe-th largest group maximum
+        // is not above the nprobe-th largest candidate, so the nprobe nearest are among the
+        // candidates that reach its prefix: about nprobe (1 + nprobe / 128) of them when the
+        // groups are unrelated to the scores.  Those are pooled; up to 64 are ordered by one
+        // sort of wavefront 0, more by counting.  The order of the prefixes is the order of the
+        // scores wherever prefixes differ, so the result is exact unless two prefixes tie among
+        // the selected clusters or across the cut; then the exact general path below redoes the
+        // selection, as it does when the pool overflows.
         uint64_t* keys = (uint64_t*)smem_raw;
         idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
         const int lane = lane_id(), wave = wave_id(), nw = nt >> 6;
-        if (tid == 0) { sh[6] = 0; sh[7] = 0; }
-        Cand best = 0;
-        bool tie_cut = false;     // a dropped candidate shared its prefix with the last one kept
-        auto fold = [&](Cand run) {
-            Cand dropped;
-            best = merge_best64<true>(best, run, dropped);
-            const uint64_t low = read_lane(best, 63) >> 24;
-            tie_cut |= __ballot(dropped != 0 && (dropped >> 24) == low) != 0;
-        };
+        Cand* pool = (Cand*)(((uintptr_t)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4) + 15) & ~(uintptr_t)15);   // [nt]
+        Cand* sel = pool + nt;                                  // [65] the nprobe best and the one after, when counted
+        uint32_t* gmax = (uint32_t*)(sel + 66);                 // [2 * nt] halves of every thread's best candidate
+        if (tid == 0) { sh[4] = 0; sh[6] = 0; }
+        if (tid < 65) sel[tid] = 0;
         auto packed = [&](int i, double s) {
             return (~coarse_key(s, a.metric) & ~0xFFFFFFull) | (uint64_t)(0xFFFFFFu - (uint32_t)i);
         };
-        // the first four chunks of a wavefront are requested together
-        double s4[4];
+        // the first four scores of a thread are requested together and stay in registers
+        Cand c4[4];
+        {
+            double s4[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int i = (wave + j * nw) * 64 + lane;
-            s4[j] = i < a.nlist ? sc[i] : 0.0;
-        }
+            for (int j = 0; j < 4; ++j) { const int i = tid + j * nt; s4[j] = i < a.nlist ? sc[i] : 0.0; }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int i = (wave + j * nw) * 64 + lane;
-            if ((wave + j * nw) * 64 < a.nlist) fold(bitonic_sort64<true>(i < a.nlist ? packed(i, s4[j]) : (Cand)0));
+            for (int j = 0; j < 4; ++j) { const int i = tid + j * nt; c4[j] = i < a.nlist ? packed(i, s4[j]) : (Cand)0; }
         }
+        Cand mine = max(max(c4[0], c4[1]), max(c4[2], c4[3]));
 #pragma unroll 1
-        for (int c0 = (wave + 4 * nw) * 64; c0 < a.nlist; c0 += nw * 64) {
-            const int i = c0 + lane;
-            fold(bitonic_sort64<true>(i < a.nlist ? packed(i, sc[i]) : (Cand)0));
-        }
-        Cand* run = (Cand*)(((uintptr_t)(smem_raw + sort_bytes + (size_t)(nprobe + 1) * 4) + 15) & ~(uintptr_t)15);
-#pragma unroll 1
-        for (int stride = 1; stride < nw; stride <<= 1) {
-            const bool sender = (wave % (2 * stride)) == stride;
-            const bool receiver = (wave % (2 * stride)) == 0 && wave + stride < nw;
-            if (sender) run[wave * 64 + lane] = best;
-            __syncthreads();
-            if (receiver) fold(run[(wave + stride) * 64 + lane]);
-            __syncthreads();
-        }
-        if (tie_cut && lane == 0) atomicOr(&sh[7], 1u);
+        for (int i = tid + 4 * nt; i < a.nlist; i += nt) mine = max(mine, packed(i, sc[i]));
+        gmax[2 * tid] = (uint32_t)mine; gmax[2 * tid + 1] = (uint32_t)(mine >> 32);
         __syncthreads();
-        if (wave == 0) {
-            const uint64_t cut = read_lane(best, (int)nprobe - 1) >> 24;     // prefix of the last selected
-            const bool in_s = best != 0 && (best >> 24) >= cut;              // a prefix of the lanes
-            const int ns = __popcll(__ballot(in_s));
+        // more than 32 wanted: 128 groups, sorted by two wavefronts, keep the pool small
+        const int gw = nprobe > 32 ? 2 : 1;
+        Cand sorted = 0;
+        if (wave < gw) {
+            Cand g = 0;
+#pragma unroll 4
+            for (int w = wave; w < nw; w += gw) {
+                const Cand o = ((Cand)gmax[2 * (w * 64 + lane) + 1] << 32) | gmax[2 * (w * 64 + lane)];
+                g = max(g, o);
+            }
+            sorted = bitonic_sort64<true>(g);                                  // largest first
+            if (wave == 1) pool[lane] = sorted;
+        }
+        if (gw == 2) {
+            __syncthreads();
+            if (wave == 0) sorted = merge_best64<true>(sorted, pool[lane]);
+        }
+        if (wave == 0 && lane == (int)nprobe - 1) { gmax[0] = (uint32_t)(sorted >> 24); gmax[1] = (uint32_t)(sorted >> 56); }   // 0: all pass
+        __syncthreads();
+        const uint64_t cut = ((uint64_t)gmax[1] << 32) | gmax[0];              // 40-bit prefix
+        {
+            auto offer = [&](Cand c) {
+                const bool ok = c != 0 && (c >> 24) >= cut;
+                const uint64_t bal = __ballot(ok);
+                if (bal) {
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&sh[4], (uint32_t)__popcll(bal));
+                    base = read_lane(base, 0);
+                    const uint32_t pos = base + __popcll(bal & ((1ull << lane) - 1ull));
+                    if (ok && pos < (uint32_t)nt) pool[pos] = c;
+                }
+            };
+#pragma unroll
+            for (int j = 0; j < 4; ++j) offer(c4[j]);
+#pragma unroll 1
+            for (int i0 = 4 * nt; i0 < a.nlist; i0 += nt) { const int i = i0 + tid; offer(i < a.nlist ? packed(i, sc[i]) : (Cand)0); }
+        }
+        __syncthreads();
+        const uint32_t cnt = sh[4];
+        Cand half = 0;                       // 65 .. 128 pooled: the sorted half of wavefronts 0 and 1
+        Cand* run2 = (Cand*)gmax;            // the cut has been read: the area is free
+        if (__builtin_expect(cnt > (uint32_t)nt, 0)) {
+            if (tid == 0) sh[6] = 1;                                            // pool overflow: masses of equal prefixes
+        } else if (__builtin_expect(cnt > 128, 0)) {
+            // each pooled candidate counts those ahead of it; the first nprobe + 1 take their places
+            const Cand me = (uint32_t)tid < cnt ? pool[tid] : (Cand)0;
+            uint32_t rank = 0;
+#pragma unroll 1
+            for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {
+                Cand o[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) o[u] = pool[min(j0 + u, cnt - 1)];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += (uint32_t)((o[u] > me) & (j0 + u < cnt));
+            }
+            if ((uint32_t)tid < cnt && rank <= nprobe) sel[rank] = me;
+        } else if (cnt > 64) {
+            if (wave < 2) {
+                half = bitonic_sort64<true>((uint32_t)tid < cnt ? pool[tid] : (Cand)0);
+                if (wave == 1) run2[lane] = half;
+            }
+        }
+        __syncthreads();
+        if (wave == 0 && sh[6] == 0) {
+            Cand best, after;
+            if (cnt <= 64) {
+                const Cand sorted = bitonic_sort64<true>((uint32_t)lane < cnt ? pool[lane] : (Cand)0);
+                after = nprobe < 64 ? read_lane(sorted, (int)(nprobe & 63)) : (Cand)0;
+                best = lane < (int)nprobe ? sorted : (Cand)0;
+            } else if (cnt <= 128) {
+                Cand dropped;
+                const Cand merged = merge_best64<true>(half, run2[lane], dropped);
+                after = nprobe < 64 ? read_lane(merged, (int)(nprobe & 63)) : wave_max(dropped);
+                best = lane < (int)nprobe ? merged : (Cand)0;
+            } else {
+                best = lane < (int)nprobe ? sel[lane] : (Cand)0;
+                after = sel[nprobe];
+            }
+            const int ns = __popcll(__ballot(best != 0));                     // a prefix of the lanes
             const uint64_t next = ((uint64_t)(uint32_t)__shfl_down((int)(uint32_t)(best >> 32), 1) << 32) |
                                   (uint32_t)__shfl_down((int)(uint32_t)best, 1);
             const bool adjacent = lane + 1 < ns && (best >> 24) == (next >> 24);
-            const bool redo = __ballot(adjacent) != 0 || (ns == 64 && sh[7] != 0);
+            const bool cut_tie = ns > 0 && after != 0 && (after >> 24) == (read_lane(best, max(ns - 1, 0)) >> 24);
+            const bool redo = __ballot(adjacent) != 0 || cut_tie;
             if (lane == 0) sh[6] = redo;
             if (!redo && lane < (int)pad) idx[lane] = best != 0 ? 0xFFFFFFu - (uint32_t)(best & 0xFFFFFFull) : 0xFFFFFFFFu;
         }
         __syncthreads();
-        if (sh[6]) select_sorted(a, sc, keys, idx, pad, hist, sh);
+        if (__builtin_expect(sh[6] != 0, 0)) select_sorted(a, sc, keys, idx, pad, hist, sh);
     } else if (in_lds) {
         uint64_t* keys = (uint64_t*)smem_raw;
         idx = (uint32_t*)(smem_raw + sizeof(uint64_t) * pad);
@@ -491,7 +552,7 @@ hipError_t launch_select(const SelectArgs& a, hipStream_t s, hipEvent_t e0, hipE
     size_t lds = (in_lds ? (size_t)pad * 12 : 0) + (prefix_in_lds ? (size_t)(a.nprobe + 1) * 4 : 0);
     const bool wave_sort = in_lds && a.nprobe <= 64 && a.nlist <= kSelectWaveSortMax;
     const int by_cut = in_lds && !wave_sort && a.nprobe <= kSelectCutMax;
-    if (wave_sort) lds += 16 + (size_t)(threads / 64) * 64 * 8;
+    if (wave_sort) lds += 16 + (size_t)threads * 8 + 66 * 8 + (size_t)threads * 8;      // pool, the ranked few, the threads' best
     if (by_cut) lds += 16 + (size_t)kSelectPoolCap * 12;
     IVF_LAUNCH(select_kernel, dim3(a.nq), dim3(threads), lds, s, e0, e1, a, pad, in_lds, prefix_in_lds, by_cut);
     return hipGetLastError();
@@ -615,18 +676,6 @@ __device__ __forceinline__ Cursor start_cursor(const ScanArgs& p, int qi, const 
     c.r_end = ds.r_begin + (uint32_t)((uint64_t)cnt * (wave + 1) / kScanWaves);
     c.slot = ds.slot; c.s_rb = ds.slot_rbegin; c.s_re = ds.slot_rend;
     c.s_grow = ds.slot_grow; c.s_base = ds.slot_base;
-    return c;
-}
-
-// The largest candidate word held by any lane (0 when all are empty); every lane gets it.
-__device__ __forceinline__ Cand wave_max(Cand c) {
-    Cand o;
-    o = xor_lane<1>(c); c = o > c ? o : c;
-    o = xor_lane<2>(c); c = o > c ? o : c;
-    o = xor_lane<4>(c); c = o > c ? o : c;
-    o = xor_lane<8>(c); c = o > c ? o : c;
-    o = xor_lane<16>(c); c = o > c ? o : c;
-    o = xor_lane<32>(c); c = o > c ? o : c;
     return c;
 }
 
@@ -896,6 +945,7 @@ constexpr int kMergeQlistCap = 1024;   // lists the fast path can visit
 constexpr int kMergeFastThreads = 1024;
 
 struct MergeLds {
+    uint32_t gmax[kMergeFastThreads];      // fast path: the largest head key of every thread's share
     uint32_t hist[256];
     uint32_t red[96];
     uint32_t sh[8];
@@ -904,12 +954,56 @@ struct MergeLds {
     int64_t f_id[2 * kMaxKPrime];
 };
 
+// The kprime best of `cnt` pooled candidates (cnt above 64) into L.c_cand, their number into
+// L.sh[4].  The usual search pools fewer than 64 and never comes here.
+__device__ __forceinline__ void rank_pool(Cand* pool, uint32_t cnt, int kp, MergeLds& L) {
+    const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id(), wave = wave_id(), nw = nt >> 6;
+    if (cnt <= (uint32_t)nt) {
+        // each counts the candidates ahead of it (eight per pass, all read before any is
+        // compared) and the first kprime take their places
+        const Cand mine = (uint32_t)tid < cnt ? pool[tid] : (Cand)0;
+        uint32_t rank = 0;
+#pragma unroll 1
+        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {
+            Cand o[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) o[u] = pool[min(j0 + u, cnt - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) rank += (uint32_t)((o[u] > mine) & (j0 + u < cnt));
+        }
+        if ((uint32_t)tid < cnt && rank < (uint32_t)kp) L.c_cand[rank] = mine;
+        __syncthreads();
+        if (tid == 0) L.sh[4] = min(cnt, (uint32_t)kp);
+        __syncthreads();
+        return;
+    }
+    // many: sort the pooled candidates in chunks of 64, merge the chunks
+    const int nchunks = (int)((cnt + 63) / 64);
+#pragma unroll 1
+    for (int c = wave; c < nchunks; c += nw) {
+        const uint32_t e = c * 64 + lane;
+        pool[e] = bitonic_sort64<true>(e < cnt ? pool[e] : (Cand)0);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        Cand top = pool[lane];
+#pragma unroll 1
+        for (int c = 1; c < nchunks; ++c) top = merge_best64<true>(top, pool[c * 64 + lane]);
+        const bool ok = lane < kp && top != 0;          // valid entries form a prefix
+        if (ok) L.c_cand[lane] = top;
+        const uint32_t m = (uint32_t)__popcll(__ballot(ok));
+        if (lane == 0) L.sh[4] = m;
+    }
+    __syncthreads();
+}
+
 // Fast path (kprime <= 64).  The scan left one unordered list of `slots` candidates per wavefront
-// and each list's best entry in `heads` (0: empty list).  Candidates are distinct.  A bucket cut
-// over the key halves of the heads finds a set of at least kprime heads that holds the kprime best
-// heads; the kprime best candidates overall are not smaller than the smallest of those, so they
-// pass the cut too, and they sit in lists whose head passes.  The passing entries of those lists
-// are pooled and ranked by counting (or, when there are many, sorted in chunks of 64 and merged).
+// and each list's best entry in `heads` (0: empty list).  Candidates are distinct.  The heads are
+// dealt to 64 groups (a thread's heads go to the group of its lane); the kprime-th largest group
+// maximum T is not above the kprime-th largest head, so at least kprime candidates reach T and the
+// kprime best overall are among those that do, in lists whose head does.  With heads spread at
+// random over the groups, about kprime (1 + kprime / 128) heads reach T.  The passing entries of
+// those lists are pooled; up to 64 are ordered by one sort of wavefront 0, more by rank_pool.
 // Returns false (for the whole workgroup) when they did not fit `pool` (kMergeCandCap) or the
 // lists did not fit `qlist` (kMergeQlistCap).
 __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part, const Cand* heads, MergeLds& L,
@@ -921,13 +1015,25 @@ __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part
     const Cand h0 = tid < np ? heads[tid] : (Cand)0;
     const Cand h1 = tid + nt < np ? heads[tid + nt] : (Cand)0;
     auto head_at = [&](uint32_t l) -> Cand { return l == (uint32_t)tid ? h0 : (l == (uint32_t)(tid + nt) ? h1 : heads[l]); };
-    auto key_half = [&](uint32_t l) -> uint32_t { return (uint32_t)(head_at(l) >> 32); };
-    const BucketCut bc = block_bucket_cut(key_half, (uint32_t)np, (uint32_t)kp, L.hist, L.red);
+    uint32_t best = max((uint32_t)(h0 >> 32), (uint32_t)(h1 >> 32));
+#pragma unroll 1
+    for (int l = tid + 2 * nt; l < np; l += nt) best = max(best, (uint32_t)(heads[l] >> 32));
+    L.gmax[wave * 64 + lane] = best;
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t g = 0;
+#pragma unroll 4
+        for (int w = 0; w < nw; ++w) g = max(g, L.gmax[w * 64 + lane]);
+        const Cand sorted = bitonic_sort64<true>((Cand)g << 32);          // largest first
+        if (lane == kp - 1) L.sh[6] = (uint32_t)(sorted >> 32);            // 0: fewer than kprime groups hold anything, all pass
+    }
+    __syncthreads();
+    const uint32_t cut = L.sh[6];
     // 2. the lists whose head passes ...
 #pragma unroll 1
     for (int l = tid; l < np; l += nt) {
         const Cand h = head_at((uint32_t)l);
-        if (h != 0 && bc.pass((uint32_t)(h >> 32))) {
+        if (h != 0 && (uint32_t)(h >> 32) >= cut) {
             const uint32_t pos = atomicAdd(&L.sh[5], 1u);
             if (pos < (uint32_t)kMergeQlistCap) qlist[pos] = (uint32_t)l;
         }
@@ -948,7 +1054,7 @@ __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const bool ok = c[u] != 0 && bc.pass((uint32_t)(c[u] >> 32));
+            const bool ok = c[u] != 0 && (uint32_t)(c[u] >> 32) >= cut;
             const uint64_t b = __ballot(ok);
             if (b) {
                 uint32_t base = 0;
@@ -962,41 +1068,12 @@ __device__ __forceinline__ bool gather_fast(const MergeArgs& a, const Cand* part
     __syncthreads();
     const uint32_t cnt = L.sh[4];
     if (cnt > (uint32_t)kMergeCandCap) return false;
-    if (cnt <= (uint32_t)nt) {
-        // 3a. few candidates: each counts the candidates ahead of it (eight per pass, all read
-        //     before any is compared) and the first kprime take their places
-        const Cand mine = (uint32_t)tid < cnt ? pool[tid] : (Cand)0;
-        uint32_t rank = 0;
-#pragma unroll 1
-        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {
-            Cand o[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) o[u] = pool[min(j0 + u, cnt - 1)];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) rank += (uint32_t)((o[u] > mine) & (j0 + u < cnt));
-        }
-        if ((uint32_t)tid < cnt && rank < (uint32_t)kp) L.c_cand[rank] = mine;
-        __syncthreads();
-        if (tid == 0) L.sh[4] = min(cnt, (uint32_t)kp);
-        __syncthreads();
-        return true;
-    }
-    // 3b. many: sort the pooled candidates in chunks of 64, merge the chunks
-    const int nchunks = (int)((cnt + 63) / 64);
-#pragma unroll 1
-    for (int c = wave; c < nchunks; c += nw) {
-        const uint32_t e = c * 64 + lane;
-        pool[e] = bitonic_sort64<true>(e < cnt ? pool[e] : (Cand)0);
-    }
-    __syncthreads();
+    if (__builtin_expect(cnt > 64, 0)) { rank_pool(pool, cnt, kp, L); return true; }
+    // 3. at most 64 candidates: one sort
     if (wave == 0) {
-        Cand top = pool[lane];
-#pragma unroll 1
-        for (int c = 1; c < nchunks; ++c) top = merge_best64<true>(top, pool[c * 64 + lane]);
-        const bool ok = lane < kp && top != 0;          // valid entries form a prefix
-        if (ok) L.c_cand[lane] = top;
-        const uint32_t m = (uint32_t)__popcll(__ballot(ok));
-        if (lane == 0) L.sh[4] = m;
+        const Cand sorted = bitonic_sort64<true>((uint32_t)lane < cnt ? pool[lane] : (Cand)0);
+        if ((uint32_t)lane < cnt && lane < kp) L.c_cand[lane] = sorted;
+        if (lane == 0) L.sh[4] = min(cnt, (uint32_t)kp);
     }
     __syncthreads();
     return true;
@@ -1078,7 +1155,7 @@ __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int 
         Cand* pool = (Cand*)m_dyn;
         gathered = gather_fast(a, part, a.heads + (size_t)qi * a.nparts, L, pool, (uint32_t*)(pool + kMergeCandCap));
     }
-    if (!gathered) {
+    if (__builtin_expect(!gathered, 0)) {
         __syncthreads();
         gather_radix(a, part, L);
     }
