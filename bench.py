@@ -23,9 +23,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes one scan launch moves, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a 1 GiB
 # copy (profiles/scan_kernel_c2_single_query.md, profiles/batched_scan_kernel_c3_c5.md)
-C2_SCAN_TRAFFIC_BYTES = 89207 * 1024 + 96 * 1024
-C3_SCAN_TRAFFIC_BYTES = 5027107 * 2048
-C5_SCAN_TRAFFIC_BYTES = 30003315 * 2048
+C2_SCAN_TRAFFIC_BYTES = 88649 * 1024 + 1040 * 1024
+C3_SCAN_TRAFFIC_BYTES = 5007648 * 2048
+C5_SCAN_TRAFFIC_BYTES = 30003314 * 2048
 # MFMA utilisation of the batched scan, rocprofv3 --pmc MfmaUtil (profiles/batched_scan_kernel_c3_c5.md)
 C3_MFMA_UTIL, C5_MFMA_UTIL = 0.093, 0.095
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
@@ -717,13 +717,13 @@ def run_paper_shape(args, full=True):
                 "scan_gbs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
 
     depth = args.depth if args.depth > 0 else 6
-    head = run(256, 1, depth, REPEATS)
+    head = run(256, 1, depth, REPEATS if args.batch == 0 else 1)
     log(f"n1: head {head}")
     sweep = []
     if not args.no_sweep:
-        for B in (2, 4, 8):
+        for B in ((args.batch,) if args.batch > 0 else (2, 4, 8)):
             sweep.append(run(256, B, 1, 3))
-        if full:
+        if full and args.batch == 0:
             for nprobe in (64, 128, 512, 1024):
                 sweep.append(run(nprobe, 1, depth, 3))
             sweep.append(run(256, 1, 1, 3))
@@ -809,7 +809,7 @@ def main():
                          "with host-resident lists; c3 / c5: batched retrieval over fp16 / bf16 lists; n1: the paper's resident shape")
     ap.add_argument("--scale", type=float, default=1.0, help="c3, c4, c5, n1: fraction of the named datastore to build")
     ap.add_argument("--dim", type=int, default=0, help="c3, c5: row dimension instead of the named one (a multiple of 64)")
-    ap.add_argument("--batch", type=int, default=0, help="c3, c5: queries per batch instead of the named number")
+    ap.add_argument("--batch", type=int, default=0, help="c3, c5: queries per batch instead of the named number; n1: only this batch size in the batch rows")
     ap.add_argument("--topk", type=int, default=0, help="c3, c5: k instead of the named one")
     ap.add_argument("--groups", type=int, default=0, help="c3, c5: mixture components the batch's queries are drawn around")
     ap.add_argument("--pairs", type=int, default=16, help="c4: (q_in, q_out) pairs per budget")
