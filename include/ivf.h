@@ -190,11 +190,14 @@ int ivf_reserve(ivf_index* index, int32_t nq, int32_t nprobe, int32_t k);
  * ivf_search_device for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as a
  * query-by-query ivf_search_device, enqueued on compute_stream, but the workspace (coarse scores,
- * selected clusters and their tables, the scan workgroups' candidate lists) lives in one fixed
+ * selected clusters and their tables, the scan wavefronts' candidate lists, the flags and lists of
+ * the exact second pass) lives in one fixed
  * device array of IVF_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it runs on until
  * the process ends.  The call allocates and frees nothing, on the host side of HIP or on the device.
- *   - A search whose workspace does not fit (roughly nq x (8 nlist + 8 grid k' + 32 nprobe) bytes,
- *     grid <= 2 x compute units, k' = k + max(8, k / 8)) is refused with IVF_ELIMIT and nothing is enqueued.
+ *   - A search whose workspace does not fit (roughly nq x (8 nlist + 32 nprobe) + 2100 x grid x nq
+ *     bytes for k <= 56, twice the second term above that, grid <= 2 x compute units per query and
+ *     fewer per query when nq is large: one query of a 1024-list index needs 1.1 MB) is refused with
+ *     IVF_ELIMIT and nothing is enqueued.
  *   - Always query by query (the batch mode and the pipeline depth are ignored).  IVF_PLACE_DEVICE only.
  *   - Every call on a GPU shares that GPU's array, also across indexes: calls whose kernels could
  *     overlap on one GPU (other streams, other threads) race.  Calls on one compute_stream are
