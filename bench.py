@@ -331,6 +331,33 @@ def run_single_query(args):
         leg["roofline"] = {"bound": "hbm", "kernel": "scan_kernel", "achieved": round(pr["scan_gbs"], 1),
                            "frac": round(pr["scan_gbs"] / HBM_PEAK_GBS, 4), "us_per_launch": round(pr["us_scan"], 2),
                            "bytes_per_launch": round(pr["scan_bytes_per_call"], 1)}
+        # the same searches 32 queries per call: list-major over fp32 rows with the L2 filter score
+        per_query_ids, per_query_dists = ids_dev.clone(), dists_dev.clone()
+        ix2.ivf_reserve(32, 1024, k)
+
+        def batched_pass(count):
+            t = time.perf_counter()
+            for _ in range(count):
+                for j in range(0, nq, 32):
+                    ix2.ivf_search_device(q_dev[j:j + 32], args.nprobe, k, ids_dev[j:j + 32], dists_dev[j:j + 32])
+            ix2.ivf_synchronize()
+            return time.perf_counter() - t
+        batched_pass(2)
+        cnt = max(2, int(MIN_REGION_S / max(batched_pass(2) / 2, 1e-6)) + 1)
+        rb = rates(cnt * nq, [batched_pass(cnt) for _ in range(3)])
+        same = bool(torch.equal(ids_dev, per_query_ids) and torch.equal(dists_dev, per_query_dists))
+        leg["batch32_list_major"] = {"qps": rb["median"], "qps_min": rb["min"], "qps_max": rb["max"],
+                                     "equal_to_query_by_query": same}
+        if not NO_EVENTS:
+            ix2.ivf_profile_enable(True); ix2.ivf_profile_reset()
+            batched_pass(2)
+            pb = ix2.ivf_profile_read(); ix2.ivf_profile_enable(False)
+            calls = max(int(pb.calls), 1)
+            us = pb.ms_scan / calls * 1e3
+            leg["batch32_list_major"].update({"kernel": "batched_scan_f32_kernel", "us_per_launch": round(us, 1),
+                                              "union_mb_per_call": round(pb.scan_bytes / calls / 1e6, 1),
+                                              "achieved": round(pb.scan_bytes / calls / 1e3 / us, 1) if us > 0 else 0.0,
+                                              "frac": round(pb.scan_bytes / calls / 1e3 / us / HBM_PEAK_GBS, 4) if us > 0 else 0.0})
         ix2.close()
         del ix2
         out["legs"] = {"l2": leg}
@@ -346,7 +373,7 @@ def run_single_query(args):
 def run_lookahead(args, full=True):
     """Lists in pinned host memory, an 8 GB device prefetch buffer, ivf_prefetch(q_in) overlapped with
     a synthetic ~20 ms decode, then ivf_search(q_out) with the resident clusters on the GPU and the
-    others on the host.  full: budget sweep, cluster cache and scheduler rows; else the 1.28 GB row,
+    others on the host.  full: budget sweep and scheduler rows as well; else the cluster cache rows, the 1.28 GB row,
     the row whose copy fits under the decode, and the parity sample."""
     import numpy as np
     import torch
@@ -431,7 +458,8 @@ def run_lookahead(args, full=True):
     log(f"c4: budget rows done ({head})")
     cache_rows, sched_rows = [], []
     budget = int(1.28e9)
-    if full:
+    cache_leg = True          # also in the compact leg of the default run: the consolidation is measured there
+    if cache_leg:
         # Cluster cache (Sec. 4.2 "Cache design"): a stream of requests around a few topics, each
         # request = prefetch(q_in) under the 1.28 GB budget, decode, search(q_out); once with a cold
         # buffer per request, once with the cache keeping at most half of the buffer between requests.
@@ -472,36 +500,37 @@ def run_lookahead(args, full=True):
                             "move_traffic_gbs": round((2 * m["moved"] / 1e9) / (m["ms_compact"] / 1e3), 1) if m["ms_compact"] > 0 else 0.0})
             cache_rows.append(row)
         index.ivf_cache_configure(-1.0, 1.0, 2.0, 1.0)
-        # Prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching"): a global batch of
-        # requests around many topics, served in micro-batches that share one prefetch budget; once in
-        # arrival order, once grouped by ivf_schedule.
-        gB, micro, g_topics = 8 * args.pairs, 8, 2 * args.pairs
-        gq_in = W.shared_batch_queries(ds, gB, g_topics, 20983)
-        gq_out = W.perturbed(gq_in, 0.3, 20984)
-        perm = torch.randperm(gB, generator=torch.Generator().manual_seed(20985))
-        gq_in, gq_out = gq_in.cpu()[perm].numpy(), gq_out.cpu()[perm].numpy()       # topics arrive interleaved
-        index.ivf_schedule(gq_in, micro)                                             # untimed first call
-        t = time.perf_counter()
-        order, ms_sched = index.ivf_schedule(gq_in, micro, with_time=True)
-        ms_sched_call = (time.perf_counter() - t) * 1e3
-        index.ivf_reserve(micro, nprobe, k)
-        for j in range(0, gB, micro):            # untimed first touch
-            index.ivf_prefetch(gq_in[j:j + micro], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
-            index.ivf_search(gq_out[j:j + micro], nprobe, k)
-        for mode, seq in (("arrival order", np.arange(gB)), ("grouped by ivf_schedule", order)):
-            hits, ms_s, copied = [], [], []
-            for j in range(0, gB, micro):
-                g = seq[j:j + micro]
-                ps = index.ivf_prefetch(gq_in[g], nprobe, budget, flags=P.IVF_PREFETCH_RESET)
-                decode(reps)
-                torch.cuda.synchronize()
-                index.ivf_prefetch_wait()
-                ids, dists, st = index.ivf_search(gq_out[g], nprobe, k, with_stats=True)
-                hits.append(st.hit_rate); ms_s.append(st.ms_total); copied.append(ps.bytes)
-            sched_rows.append({"mode": mode, "global_batch": gB, "micro_batch": micro, "topics": g_topics,
-                               "hit_rate": round(float(np.mean(hits)), 4), "search_ms_per_micro_batch": round(float(np.mean(ms_s)), 3),
-                               "prefetched_gb": round(float(np.mean(copied)) / 1e9, 3)})
-        sched_rows.append({"ivf_schedule_gpu_ms": round(ms_sched, 3), "ivf_schedule_call_ms": round(ms_sched_call, 3)})
+        if full:
+            # Prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching"): a global batch of
+            # requests around many topics, served in micro-batches that share one prefetch budget; once in
+            # arrival order, once grouped by ivf_schedule.
+            gB, micro, g_topics = 8 * args.pairs, 8, 2 * args.pairs
+            gq_in = W.shared_batch_queries(ds, gB, g_topics, 20983)
+            gq_out = W.perturbed(gq_in, 0.3, 20984)
+            perm = torch.randperm(gB, generator=torch.Generator().manual_seed(20985))
+            gq_in, gq_out = gq_in.cpu()[perm].numpy(), gq_out.cpu()[perm].numpy()       # topics arrive interleaved
+            index.ivf_schedule(gq_in, micro)                                             # untimed first call
+            t = time.perf_counter()
+            order, ms_sched = index.ivf_schedule(gq_in, micro, with_time=True)
+            ms_sched_call = (time.perf_counter() - t) * 1e3
+            index.ivf_reserve(micro, nprobe, k)
+            for j in range(0, gB, micro):            # untimed first touch
+                index.ivf_prefetch(gq_in[j:j + micro], nprobe, 0, flags=P.IVF_PREFETCH_RESET)
+                index.ivf_search(gq_out[j:j + micro], nprobe, k)
+            for mode, seq in (("arrival order", np.arange(gB)), ("grouped by ivf_schedule", order)):
+                hits, ms_s, copied = [], [], []
+                for j in range(0, gB, micro):
+                    g = seq[j:j + micro]
+                    ps = index.ivf_prefetch(gq_in[g], nprobe, budget, flags=P.IVF_PREFETCH_RESET)
+                    decode(reps)
+                    torch.cuda.synchronize()
+                    index.ivf_prefetch_wait()
+                    ids, dists, st = index.ivf_search(gq_out[g], nprobe, k, with_stats=True)
+                    hits.append(st.hit_rate); ms_s.append(st.ms_total); copied.append(ps.bytes)
+                sched_rows.append({"mode": mode, "global_batch": gB, "micro_batch": micro, "topics": g_topics,
+                                   "hit_rate": round(float(np.mean(hits)), 4), "search_ms_per_micro_batch": round(float(np.mean(ms_s)), 3),
+                                   "prefetched_gb": round(float(np.mean(copied)) / 1e9, 3)})
+            sched_rows.append({"ivf_schedule_gpu_ms": round(ms_sched, 3), "ivf_schedule_call_ms": round(ms_sched_call, 3)})
     # sampled parity at this size: hybrid searches against the oracle reading the same pinned lists
     parity, cpu = None, None
     if not args.no_cpu:
@@ -776,6 +805,8 @@ def compact(leg):
         out["qps_min"], out["qps_max"] = leg["head"]["qps_min"], leg["head"]["qps_max"]
     if "budget_sweep" in leg:
         out["budget_rows"] = leg["budget_sweep"]
+    if leg.get("cluster_cache"):
+        out["cluster_cache"] = leg["cluster_cache"]
     if "sweep" in leg:
         out["rows"] = leg["sweep"]
     return out

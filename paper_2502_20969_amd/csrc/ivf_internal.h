@@ -14,6 +14,7 @@ constexpr int kMaxKPrime = 128;            // candidates kept per list: k + slac
 constexpr int kScanWaves = 4;              // scan workgroup: 4 wavefronts, two workgroups per compute unit
 constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kLaneTableSlots = 64;        // up to this many selected clusters the scan keeps the slot table in its lanes
+constexpr int kScanBatches = 2;           // batches of rows a scan wavefront has in flight
 constexpr int kScanMaxWgPerCu = 2;        // scan workgroups per compute unit at most (sizes the per-workgroup tables)
 constexpr int kSelectThreads = 1024;       // select / merge workgroup: 16 wavefronts
 constexpr int kSortLdsCap = 2048;          // select: pairs sorted in LDS up to this many

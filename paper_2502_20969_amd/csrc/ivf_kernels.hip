@@ -788,18 +788,25 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
         }
     };
 
-    uint4 va[U][SEG], vb[U][SEG];
-    uint32_t ta = 0, tb = 0;
-    Batch ba = next_batch(cur, p, qi, RPB, row_bytes, tab);
-    if (ba.nr) issue(ba, va, ta);
-    while (ba.nr) {
-        Batch bb = next_batch(cur, p, qi, RPB, row_bytes, tab);
-        if (bb.nr) issue(bb, vb, tb);
-        consume(ba, va, ta);
-        if (!bb.nr) break;
-        ba = next_batch(cur, p, qi, RPB, row_bytes, tab);
-        if (ba.nr) issue(ba, va, ta);
-        consume(bb, vb, tb);
+    // kScanBatches batches in flight: the oldest is consumed, its buffer takes the next one
+    uint4 v[kScanBatches][U][SEG];
+    uint32_t tie[kScanBatches];
+    Batch bt[kScanBatches];
+#pragma unroll
+    for (int i = 0; i < kScanBatches; ++i) {
+        tie[i] = 0;
+        bt[i] = next_batch(cur, p, qi, RPB, row_bytes, tab);
+        if (bt[i].nr) issue(bt[i], v[i], tie[i]);
+    }
+    bool more = true;
+    while (more) {
+#pragma unroll
+        for (int i = 0; i < kScanBatches; ++i) {
+            if (bt[i].nr == 0) { more = false; break; }     // batches arrive in order: an empty buffer ends the walk
+            consume(bt[i], v[i], tie[i]);
+            bt[i] = next_batch(cur, p, qi, RPB, row_bytes, tab);
+            if (bt[i].nr) issue(bt[i], v[i], tie[i]);
+        }
     }
     write_wave_list<KL>(top, p, qi);
 }
