@@ -953,8 +953,7 @@ constexpr int kMergeFastThreads = 1024;
 
 struct MergeLds {
     uint32_t gmax[kMergeFastThreads];      // fast path: the largest head key of every thread's share
-    uint32_t hist[256];
-    uint32_t red[96];
+    uint32_t hist[256];                    // general path: digit counts of the radix select
     uint32_t sh[8];
     Cand c_cand[kMaxKPrime];
     double f_key[2 * kMaxKPrime];
