@@ -79,6 +79,51 @@ def test_select_redoes_prefix_ties_exactly(streams, nprobe):
     index.close()
 
 
+@pytest.mark.parametrize("nlist", [1024, 4096])
+@pytest.mark.parametrize("nprobe,layout", [(20, "spread"), (20, "few_groups"), (32, "few_groups"), (64, "spread"),
+                                            (64, "few_groups"), (64, "most_in_63_groups"), (33, "most_in_63_groups")])
+def test_select_cut_by_group_maxima_on_adversarial_layouts(streams, nlist, nprobe, layout):
+    """The selection deals the scores to 64 or 128 groups by cluster index (index mod 64 / mod 128)
+    and cuts at the nprobe-th largest group maximum; how many scores pass depends on how the large
+    ones fall into the groups.  Large scores spread evenly: a few more than nprobe pass (one sort,
+    or two sorts and a merge).  All large scores in 8 groups: hundreds pass (ranked by counting).
+    Large scores in 63 groups and none elsewhere: the cut falls among the small ones and more pass
+    than the pool holds (the exact general path takes over).  The result must be the oracle's
+    every time."""
+    rng = np.random.default_rng(77)
+    d = 8
+    small = 0.1 + 0.3 * rng.random(nlist)
+    large = 1.0 + rng.permutation(nlist) * 1e-4           # distinct, far apart in the 40-bit prefixes
+    idx = np.arange(nlist)
+    if layout == "spread":
+        is_large = rng.random(nlist) < 0.08
+    elif layout == "few_groups":
+        is_large = (idx % 128) < 8
+    else:
+        is_large = ((idx % 128) < 63) & (rng.random(nlist) < 0.75)
+    score = np.where(is_large, large, small)
+    cent = np.zeros((nlist, d), dtype=np.float32)
+    cent[:, 0] = score.astype(np.float32)
+    cent[:, 1:] = 0.01 * rng.standard_normal((nlist, d - 1)).astype(np.float32)
+    index = _index(streams, cent, d, P.IVF_IP)
+    q = np.zeros((3, d), dtype=np.float32)
+    q[:, 0] = [1.0, 0.7, 2.5]
+    q[:, 1:] = 0.01 * rng.standard_normal((3, d - 1)).astype(np.float32)
+    pr = index.ivf_probe(q, nprobe)
+    for b in range(3):
+        assert list(pr[b]) == list(O.probe(cent, q[b], nprobe, O.IP))
+    # and a whole search over the same index
+    gi, gd = index.ivf_search(q, nprobe, 5)
+    n = 2 * nlist
+    rows_assign = (np.arange(n) % nlist).astype(np.int32)
+    off, perm = O.build_layout(rows_assign, nlist)
+    rows = np.random.default_rng(0).standard_normal((n, d)).astype(np.float32)
+    for b in range(3):
+        oi, osc = O.search(rows[perm], O.F32, off, perm.astype(np.int64), cent, q[b], nprobe, 5, O.IP)
+        assert list(gi[b]) == list(oi)
+    index.close()
+
+
 @pytest.mark.parametrize("kind", ["increasing", "permutation", "sparse"])
 def test_id_rank_tables(streams, kind):
     """Adopted layouts whose ids grow with the row (no rank table), are a permutation of the row
