@@ -154,3 +154,40 @@ def test_dense_band_split_between_host_and_gpu(dtype):
     if dtype == "f32":
         assert exact_gpu >= 1 and exact_host >= 1
     index.close()
+
+
+@pytest.mark.parametrize("k", [10, 40])
+def test_best_rows_concentrated_in_few_scan_wavefronts(k):
+    """The merge cuts at the k'-th largest of 64 group maxima of the scan wavefronts' best
+    candidates (a wavefront's list goes to the group of its number mod 64).  Here the good rows sit
+    only in windows that go to wavefronts whose number is a multiple of 64 (one list, rows dealt to
+    the 2048 wavefronts in windows of four), so one group holds every good candidate, the cut
+    falls among the poor ones, and hundreds of candidates are pooled instead of a handful: the
+    pooled candidates are then ranked by counting.  The result must still be the oracle's."""
+    rng = np.random.default_rng(31)
+    d, n = 768, 40000
+    q = np.zeros(d, dtype=np.float32)
+    q[0] = 1.0
+    window = np.arange(n) // 4
+    good = (window % 64) == 0
+    x0 = np.where(good, 0.9, 0.1) + rng.permutation(n) * 1e-6
+    rows = (0.01 * rng.standard_normal((n, d))).astype(np.float32)
+    rows[:, 0] = x0.astype(np.float32)
+    cent = np.zeros((1, d), dtype=np.float32)
+    cent[0, 0] = 1.0
+    off = np.array([0, n], dtype=np.int64)
+    ids = rng.permutation(n).astype(np.int64) * 3 + 1
+    index = P.ivf_adopt_layout(torch.from_numpy(rows).cuda(), "f32", off, cent, ids=ids, metric=P.IVF_IP,
+                               compute_stream=torch.cuda.Stream(), copy_stream=torch.cuda.Stream())
+    gi, gd, ss = index.ivf_search(q, 1, k, with_stats=True)
+    oi, osc = O.search(rows, O.F32, off, ids, cent, q, 1, k + 8, O.IP)
+    assert compare_topk(gi[0], gd[0], oi, osc, k, O.F32, O.IP) == 0
+    # the same through the device entry point
+    q_dev = torch.from_numpy(q).cuda()
+    ids_dev = torch.empty(1, k, dtype=torch.int64, device="cuda")
+    d_dev = torch.empty(1, k, device="cuda")
+    torch.cuda.synchronize()
+    index.ivf_search_device(q_dev, 1, k, ids_dev, d_dev)
+    index.ivf_synchronize()
+    assert np.array_equal(ids_dev.cpu().numpy(), gi) and np.array_equal(d_dev.cpu().numpy(), gd)
+    index.close()
