@@ -40,6 +40,8 @@ def lib():
             "orc_schedule": [vp, i32, i32, i32, vp],
             "orc_cache_round": [vp, vp, vp, vp, i32, i32, ci, C.c_float, C.c_float, C.c_double, u64, vp, vp],
         }
+        L.orc_prefetch_amount.restype = C.c_double
+        L.orc_prefetch_amount.argtypes = [C.c_double, C.c_double, i32, C.c_double, vp, vp, i32, C.c_double, vp]
         L.orc_cache_admit.restype = None
         L.orc_cache_admit.argtypes = [vp, vp, i32, C.c_float]
         for name, args in sigs.items():
@@ -184,6 +186,18 @@ def cache_round(hot, used_flags, res, off, d, dtype, decay, h_inc, fraction):
                               C.byref(res.used), _p(evicted))
     assert n >= 0
     return evicted[:n]
+
+
+def prefetch_amount(bandwidth, t_llm, nprobe, t_cc, budgets, miss_rates, step):
+    """App. C: the prefetch amount (bytes) that minimises t_1 + t_2, tried on a grid of `step` bytes,
+    and that time.  budgets / miss_rates: the measured miss-rate curve."""
+    bs = np.ascontiguousarray(budgets, dtype=np.float64)
+    rs = np.ascontiguousarray(miss_rates, dtype=np.float64)
+    assert bs.ndim == 1 and bs.shape == rs.shape and bs.shape[0] >= 1 and np.all(np.diff(bs) > 0)
+    t = C.c_double(0.0)
+    b = lib().orc_prefetch_amount(float(bandwidth), float(t_llm), int(nprobe), float(t_cc), _p(bs), _p(rs),
+                                  bs.shape[0], float(step), C.byref(t))
+    return b, t.value
 
 
 def schedule(q, micro):

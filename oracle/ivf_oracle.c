@@ -37,7 +37,9 @@
  * Parity status: every exported function below is pinned by tests that do not
  * call it to produce their expected values (hand-worked dyadic example,
  * brute-force kNN through a library matmul + argsort, set identities of the
- * lookahead split, closed-form budget cases).  None is "parity unpinned".
+ * lookahead split, closed-form budget cases; the prefetch amount of App. C by
+ * its closed forms for a linear and an exponential miss-rate curve).  None is
+ * "parity unpinned".
  */
 #include <math.h>
 #ifdef _OPENMP
@@ -437,6 +439,48 @@ int32_t orc_schedule(const float *q, int32_t B, int32_t d, int32_t m, int32_t *o
     }
     free(taken);
     return B;
+}
+
+/* ---- prefetch amount (App. C "Finding Prefetching Amount") ------------------------ */
+
+/* Miss rate after prefetching b bytes, from n measured points (bs[i], rs[i]) with
+ * bs increasing: linear between neighbouring points, constant before the first
+ * and after the last. */
+static double miss_rate_at(double b, const double *bs, const double *rs, int32_t n)
+{
+    if (b <= bs[0]) return rs[0];
+    for (int32_t i = 1; i < n; ++i)
+        if (b <= bs[i]) {
+            const double x = (b - bs[i - 1]) / (bs[i] - bs[i - 1]);      /* 1 exactly at the measured point */
+            return x >= 1.0 ? rs[i] : rs[i - 1] + (rs[i] - rs[i - 1]) * x;
+        }
+    return rs[n - 1];
+}
+
+/* The amount b_p that minimises t_1 + t_2 of App. C, by trying every amount on a
+ * grid: t_1 = t_LLM up to b_p = B * t_LLM and b_p / B beyond (generation and
+ * prefetch overlap), t_2 =
+ * r_miss(b_p) * nprobe * t_cc (the CPU searches the missed clusters one after the
+ * other).  Amounts tried: 0, step, 2 step, ... up to the larger of B * t_LLM and
+ * the last measured point, and B * t_LLM itself (the boundary of App. C's case 1).
+ * Of several amounts with the same smallest time the one nearest to B * t_LLM is
+ * returned (case 1: "pushing b_p to the boundary").  *t_total receives the time. */
+double orc_prefetch_amount(double B, double t_llm, int32_t nprobe, double t_cc,
+                           const double *bs, const double *rs, int32_t n, double step, double *t_total)
+{
+    const double b1 = B * t_llm;
+    const double hi = b1 > bs[n - 1] ? b1 : bs[n - 1];
+    double best_b = b1;
+    double best_t = t_llm + miss_rate_at(b1, bs, rs, n) * (double)nprobe * t_cc;
+    for (int64_t g = 0; (double)g * step <= hi; ++g) {
+        const double b = (double)g * step;
+        const double t1 = b <= b1 ? t_llm : b / B;           /* App. C's piecewise t_1 */
+        const double t = t1 + miss_rate_at(b, bs, rs, n) * (double)nprobe * t_cc;
+        const double gap = b > b1 ? b - b1 : b1 - b, best_gap = best_b > b1 ? best_b - b1 : b1 - best_b;
+        if (t < best_t || (t == best_t && gap < best_gap)) { best_t = t; best_b = b; }
+    }
+    if (t_total) *t_total = best_t;
+    return best_b;
 }
 
 /* Number of OpenMP threads the scoring loop will use (for the baseline report). */

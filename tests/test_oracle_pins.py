@@ -524,3 +524,66 @@ def test_schedule_recovers_separated_groups():
     order = O.schedule(q, m)
     for g0 in range(0, centres * m, m):
         assert len(set(label[order[g0:g0 + m]])) == 1
+
+
+# ---- prefetch amount (App. C "Finding Prefetching Amount") ------------------------------------
+
+def test_prefetch_amount_is_the_generation_window_on_a_pcie_class_link():
+    """App. C, case 1: with a miss rate that falls linearly until everything is fetched and a link
+    whose transfer time per byte exceeds what a fetched byte saves the CPU, the best amount is what
+    the link moves during generation, B * t_LLM, and the time is t_LLM plus the CPU's share."""
+    B, t_llm, nprobe, t_cc = 50e9, 0.020, 256, 20e-6
+    b_full = 4e9                                           # the miss rate reaches 0 here
+    bs = np.array([0.0, b_full])
+    rs = np.array([1.0, 0.0])
+    assert nprobe * t_cc / b_full < 1.0 / B               # a byte costs more to move than it saves
+    b, t = O.prefetch_amount(B, t_llm, nprobe, t_cc, bs, rs, step=1e6)
+    assert b == B * t_llm
+    assert t == pytest.approx(t_llm + (1.0 - B * t_llm / b_full) * nprobe * t_cc, rel=1e-12)
+
+
+def test_prefetch_amount_goes_beyond_the_window_when_cpu_search_is_slow():
+    """App. C, case 2 with a linear miss rate: when a fetched byte saves more CPU time than it costs
+    to move (nprobe * t_cc / b_full > 1 / B), every further byte pays and the best amount is
+    everything (the derivative never reaches zero before the miss rate does)."""
+    B, t_llm, nprobe, t_cc = 50e9, 0.005, 256, 2e-3
+    b_full = 2e9
+    assert nprobe * t_cc / b_full > 1.0 / B and b_full > B * t_llm
+    b, t = O.prefetch_amount(B, t_llm, nprobe, t_cc, np.array([0.0, b_full]), np.array([1.0, 0.0]), step=1e6)
+    assert b == b_full and t == pytest.approx(b_full / B, rel=1e-12)
+
+
+def test_prefetch_amount_stationary_point_of_a_convex_miss_curve():
+    """App. C, case 2: for r_miss(b) = exp(-b / s), sampled finely, the derivative condition
+    1 / B + r'(b) nprobe t_cc = 0 gives b* = s ln(B nprobe t_cc / s) when that lies beyond
+    B * t_LLM; otherwise the answer is B * t_LLM."""
+    B, nprobe, t_cc, s = 50e9, 256, 1e-3, 1e9
+    bs = np.arange(0.0, 12e9 + 1, 1e6)
+    rs = np.exp(-bs / s)
+    b_star = s * np.log(B * nprobe * t_cc / s)
+    assert b_star > 1e9
+    b, t = O.prefetch_amount(B, 0.010, nprobe, t_cc, bs, rs, step=1e6)          # window 0.5 GB < b*
+    assert abs(b - b_star) <= 2e6
+    assert t == pytest.approx(b_star / B + np.exp(-b_star / s) * nprobe * t_cc, rel=1e-6)
+    b, t = O.prefetch_amount(B, 0.100, nprobe, t_cc, bs, rs, step=1e6)          # window 5 GB > b*
+    assert b == B * 0.100
+
+
+def test_prefetch_amount_brute_force_on_random_convex_curves():
+    """The grid search against numpy's own argmin of the same objective on random convex,
+    non-increasing curves, and: the result never lies below the generation window."""
+    rng = np.random.default_rng(12)
+    for _ in range(50):
+        n = int(rng.integers(2, 12))
+        bs = np.concatenate([[0.0], np.cumsum(rng.integers(1, 40, n - 1)) * 1e8])
+        slopes = -np.sort(rng.random(n - 1))[::-1]                        # rising towards 0: convex
+        rs = np.concatenate([[0.0], np.cumsum(slopes * np.diff(bs))])
+        rs = (rs - rs.min()) / max(rs.max() - rs.min(), 1e-30)           # from 1 down to 0
+        B = float(rng.choice([16e9, 50e9, 400e9]))
+        t_llm, nprobe, t_cc = float(rng.uniform(0.001, 0.05)), int(rng.integers(1, 512)), float(rng.uniform(1e-6, 1e-3))
+        step = 1e7
+        b, t = O.prefetch_amount(B, t_llm, nprobe, t_cc, bs, rs, step)
+        grid = np.append(np.arange(0.0, max(B * t_llm, bs[-1]) + 0.5, step), B * t_llm)
+        obj = np.where(grid <= B * t_llm, t_llm, grid / B) + np.interp(grid, bs, rs) * nprobe * t_cc
+        assert t == pytest.approx(obj.min(), rel=1e-12, abs=1e-15)
+        assert b >= B * t_llm - 1e-3
