@@ -453,9 +453,29 @@ def run_lookahead(args, full=True):
     # bandwidth this machine's copies reach
     fit_budget = int(head["pcie_gbs"] * 1e9 * decode_alone_ms / 1e3 * 0.97) if head["pcie_gbs"] > 0 else int(0.9e9)
     rows = [budget_row(fit_budget, "measured copy GB/s x decode ms"), head]
-    if full:
-        rows = [budget_row(int(g * 1e9)) for g in (0.0, 0.25, 0.5)] + rows + [budget_row(int(g * 1e9)) for g in (2.0, 8.0)]
+    rows = [budget_row(int(g * 1e9)) for g in ((0.0, 0.25, 0.5) if full else (0.0, 0.5))] + rows + \
+           [budget_row(int(g * 1e9)) for g in ((2.0, 8.0) if full else (2.0,))]
     log(f"c4: budget rows done ({head})")
+    # App. C: the amount the model picks from what was just measured (link rate, generation time, host
+    # time per missed cluster, miss-rate curve), beside the row that was fastest in fact
+    model = None
+    with_copy = [r for r in rows if r["pcie_gbs"] > 0]
+    with_miss = [r for r in rows if r["hit_rate"] < 1.0 and r["host_scan_ms"] > 0]
+    if with_copy and with_miss:
+        bw = float(np.median([r["pcie_gbs"] for r in with_copy])) * 1e9
+        t_cc = float(np.median([r["host_scan_ms"] / 1e3 / (nprobe * (1.0 - r["hit_rate"])) for r in with_miss]))
+        curve = {}
+        for r in sorted(rows, key=lambda r_: r_["prefetched_gb"]):
+            curve.setdefault(r["prefetched_gb"] * 1e9, 1.0 - r["hit_rate"])
+        bs = np.array(sorted(curve))
+        rs = np.minimum.accumulate(np.array([curve[b_] for b_ in bs]))
+        amount, seconds, which = P.ivf_prefetch_amount(bw, decode_alone_ms / 1e3, nprobe, t_cc, bs, rs)
+        measured = [(max(r["decode_ms"], r["copy_ms"]) + r["search_ms"], r["budget_gb"]) for r in rows]
+        model = {"bandwidth_gbs": round(bw / 1e9, 1), "t_llm_ms": round(decode_alone_ms, 2), "t_cc_us": round(t_cc * 1e6, 2),
+                 "amount_gb": round(amount / 1e9, 3), "case": which, "model_t1_plus_t2_ms": round(seconds * 1e3, 3),
+                 "measured_t1_plus_t2_ms": {f"{g}": round(t, 3) for t, g in measured},
+                 "fastest_measured_budget_gb": min(measured)[1]}
+        log(f"c4: prefetch amount model {model}")
     cache_rows, sched_rows = [], []
     budget = int(1.28e9)
     cache_leg = True          # also in the compact leg of the default run: the consolidation is measured there
@@ -560,7 +580,8 @@ def run_lookahead(args, full=True):
                                   "host": "RLIMIT_MEMLOCK unlimited and 309 GB of RAM on the box, yet hipHostMalloc grants about 64 GB of "
                                           "pinned memory per process in all (64 GB in one region succeeds, 70 GB does not, nor a second 40 GB beside a first)"},
                       "host_threads": threads, "decode_alone_ms": round(decode_alone_ms, 2), "decode_matmuls": reps},
-           "budget_sweep": rows, "cluster_cache": cache_rows, "prefetch_scheduler": sched_rows, "parity_sample": parity,
+           "budget_sweep": rows, "prefetch_amount_model": model, "cluster_cache": cache_rows,
+           "prefetch_scheduler": sched_rows, "parity_sample": parity,
            "setup_s": round(setup_s, 1)}
     if cpu:
         out["cpu_baseline"] = cpu
@@ -807,6 +828,8 @@ def compact(leg):
         out["budget_rows"] = leg["budget_sweep"]
     if leg.get("cluster_cache"):
         out["cluster_cache"] = leg["cluster_cache"]
+    if leg.get("prefetch_amount_model"):
+        out["prefetch_amount_model"] = leg["prefetch_amount_model"]
     if "sweep" in leg:
         out["rows"] = leg["sweep"]
     return out

@@ -302,6 +302,27 @@ int ivf_cache_plan(float* hotness, const int64_t* offsets, int32_t nlist, size_t
                    int32_t* evicted, int32_t* n_evicted, ivf_cache_move* moves, int32_t* n_moves);
 
 /*
+ * How much to prefetch (App. C "Finding Prefetching Amount"; Sec. 4.1 "Prefetching amount"): the byte
+ * budget b_p that minimises t_1 + t_2, where t_1 = t_llm while b_p <= bandwidth * t_llm and
+ * b_p / bandwidth beyond it (the copy overlaps the generation that precedes the retrieval) and
+ * t_2 = r_miss(b_p) * nprobe * t_cc (the host searches the missed clusters one after the other).
+ *   bandwidth   host-to-device bytes per second, > 0        t_llm   seconds of generation, >= 0
+ *   nprobe      clusters a search selects, >= 1             t_cc    host seconds per missed cluster, >= 0
+ *   budgets, miss_rates   host, n >= 1 measured points of the miss-rate curve: budgets (bytes) strictly
+ *               increasing, miss rates in [0, 1] and not rising; the curve is taken as linear between
+ *               the points and constant outside them
+ *   *amount     out: the best budget in bytes: bandwidth * t_llm (App. C's case 1) unless a measured
+ *               point beyond it gives a strictly smaller time (case 2; of equal ones the smallest)
+ *   *seconds    out, or NULL: the model's t_1 + t_2 at that budget
+ *   *which      out, or NULL: 1 or 2, the case
+ * t_1 + t_2 is piecewise linear in b_p, so no other amount can be better.  IVF_EINVAL for arguments
+ * outside the stated ranges.  Needs no index and no GPU.  Caller keeps every array.
+ */
+int ivf_prefetch_amount(double bandwidth, double t_llm, int32_t nprobe, double t_cc,
+                        const double* budgets, const double* miss_rates, int32_t n,
+                        double* amount, double* seconds, int32_t* which);
+
+/*
  * The host part of the hybrid search on its own (Sec. 4.1 step 3: the clusters of q_out that were
  * not prefetched are searched by CPU threads).  Needs no index and no GPU.
  *   lists     host, cluster-major rows of `dtype`, list c = rows offsets[c] .. offsets[c+1]

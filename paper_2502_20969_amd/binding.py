@@ -26,7 +26,7 @@ EXPORTS = [
     "ivf_resident", "ivf_batched_scores", "ivf_get_layout", "ivf_profile_enable", "ivf_profile_read",
     "ivf_profile_reset", "ivf_set_host_threads", "ivf_set_pipeline_depth", "ivf_synchronize",
     "ivf_set_batch_mode", "ivf_cache_configure", "ivf_cache_end_round", "ivf_cache_hotness",
-    "ivf_schedule", "ivf_host_scan", "ivf_host_scan_capacity", "ivf_prefetch_plan", "ivf_cache_plan", "ivf_strerror", "ivf_last_error",
+    "ivf_schedule", "ivf_host_scan", "ivf_host_scan_capacity", "ivf_prefetch_amount", "ivf_prefetch_plan", "ivf_cache_plan", "ivf_strerror", "ivf_last_error",
 ]
 
 
@@ -372,6 +372,20 @@ def ivf_host_scan(lists, dtype, offsets, q, clusters, k, ids=None, metric=IVF_IP
     _check(L.ivf_host_scan(_ptr(rows), _ptr(off), _ptr(idv), d, DTYPE_CODE[dtype], metric, _ptr(qv), _ptr(cl),
                            cl.shape[0], k, threads, _ptr(out_ids), _ptr(out_scores), C.byref(n_out)))
     return out_ids[:n_out.value], out_scores[:n_out.value]
+
+
+def ivf_prefetch_amount(bandwidth, t_llm, nprobe, t_cc, budgets, miss_rates):
+    """The prefetch budget of App. C for a measured miss-rate curve: (bytes, seconds of t_1 + t_2, case)."""
+    bs = _host(budgets, np.float64).reshape(-1)
+    rs = _host(miss_rates, np.float64).reshape(-1)
+    assert bs.shape == rs.shape
+    L = load()
+    L.ivf_prefetch_amount.argtypes = [C.c_double, C.c_double, C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_int32,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
+    amount, seconds, which = C.c_double(0.0), C.c_double(0.0), C.c_int32(0)
+    _check(L.ivf_prefetch_amount(float(bandwidth), float(t_llm), int(nprobe), float(t_cc), _ptr(bs), _ptr(rs), bs.shape[0],
+                                 C.byref(amount), C.byref(seconds), C.byref(which)))
+    return amount.value, seconds.value, which.value
 
 
 def ivf_prefetch_plan(ranked, offsets, row_bytes, budget_bytes, buffer_bytes, resident_off, buffer_used):

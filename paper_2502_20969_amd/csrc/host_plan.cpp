@@ -101,4 +101,29 @@ std::vector<MoveGroup> group_moves(const std::vector<ivf_cache_move>& moves) {
     return groups;
 }
 
+PrefetchAmount plan_prefetch_amount(double bandwidth, double t_llm, int nprobe, double t_cc,
+                                    const double* budgets, const double* miss_rates, int n) {
+    const double window = bandwidth * t_llm;            // what the link moves while the generation runs
+    const double per_miss = (double)nprobe * t_cc;      // host seconds if every selected cluster were missed
+    // miss rate at the window: between two measured points, or the first / last one outside them
+    double r = miss_rates[n - 1];
+    if (window <= budgets[0]) r = miss_rates[0];
+    else {
+        for (int i = 1; i < n; ++i) {
+            if (window <= budgets[i]) {
+                const double x = (window - budgets[i - 1]) / (budgets[i] - budgets[i - 1]);
+                r = x >= 1.0 ? miss_rates[i] : miss_rates[i - 1] + (miss_rates[i] - miss_rates[i - 1]) * x;
+                break;
+            }
+        }
+    }
+    PrefetchAmount best{window, t_llm + r * per_miss, 1};
+    for (int i = 0; i < n; ++i) {
+        if (budgets[i] <= window) continue;
+        const double t = budgets[i] / bandwidth + miss_rates[i] * per_miss;
+        if (t < best.seconds) best = PrefetchAmount{budgets[i], t, 2};       // of equal points the first, nearest to the window
+    }
+    return best;
+}
+
 }  // namespace ivf

@@ -18,6 +18,15 @@ void plan_prefetch(const int32_t* ranked, int nq, int nprobe, const int64_t* off
                    size_t budget_bytes, size_t buf_bytes, size_t& buf_used, int64_t* res_off,
                    std::vector<int32_t>& taken, ivf_prefetch_stats& st);
 
+// How much to prefetch (App. C "Finding Prefetching Amount"): the byte budget that minimises
+// t_1 + t_2 for a measured miss-rate curve (n points, budgets increasing, linear between the points,
+// constant outside).  t_1 + t_2 is piecewise linear in the budget, with corners at bandwidth * t_llm
+// and at the measured points, and cannot fall below bandwidth * t_llm while the miss rate does not
+// rise: only that amount (case 1) and the measured points beyond it (case 2) are looked at.
+struct PrefetchAmount { double amount, seconds; int which; };
+PrefetchAmount plan_prefetch_amount(double bandwidth, double t_llm, int nprobe, double t_cc,
+                                    const double* budgets, const double* miss_rates, int n);
+
 // Eviction and consolidation of a cache round (Sec. 4.2 "Cache design"), after the hotness update.
 void plan_cache_round(float* hot, const int64_t* off, int nlist, size_t rb, int64_t* res_off,
                       size_t& buf_used, size_t buf_bytes, float fraction, std::vector<int32_t>& evicted,

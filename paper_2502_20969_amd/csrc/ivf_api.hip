@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <chrono>
 #include <memory>
 #include <new>
@@ -1160,6 +1161,26 @@ extern "C" int ivf_prefetch_plan(const int32_t* ranked, int32_t nq, int32_t npro
     std::copy(t.begin(), t.end(), taken);
     *n_taken = (int32_t)t.size();
     if (stats) *stats = st;
+    return IVF_OK;
+}
+
+extern "C" int ivf_prefetch_amount(double bandwidth, double t_llm, int32_t nprobe, double t_cc,
+                                   const double* budgets, const double* miss_rates, int32_t n,
+                                   double* amount, double* seconds, int32_t* which) {
+    if (!budgets || !miss_rates || !amount) return fail(IVF_EINVAL, "NULL argument");
+    if (!(bandwidth > 0.0) || !(t_llm >= 0.0) || !(t_cc >= 0.0) || nprobe < 1 || n < 1 ||
+        !std::isfinite(bandwidth) || !std::isfinite(t_llm) || !std::isfinite(t_cc))
+        return fail(IVF_EINVAL, "bandwidth must be positive, t_llm and t_cc not negative, nprobe and n at least 1");
+    for (int32_t i = 0; i < n; ++i) {
+        if (!(budgets[i] >= 0.0) || !std::isfinite(budgets[i]) || !(miss_rates[i] >= 0.0) || !(miss_rates[i] <= 1.0))
+            return fail(IVF_EINVAL, "point %d of the miss-rate curve is not a budget >= 0 with a rate in [0, 1]", i);
+        if (i > 0 && !(budgets[i] > budgets[i - 1])) return fail(IVF_EINVAL, "budgets must increase (point %d)", i);
+        if (i > 0 && miss_rates[i] > miss_rates[i - 1]) return fail(IVF_EINVAL, "miss rates must not rise with the budget (point %d)", i);
+    }
+    const PrefetchAmount r = plan_prefetch_amount(bandwidth, t_llm, nprobe, t_cc, budgets, miss_rates, n);
+    *amount = r.amount;
+    if (seconds) *seconds = r.seconds;
+    if (which) *which = r.which;
     return IVF_OK;
 }
 

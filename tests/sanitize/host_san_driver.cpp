@@ -1,6 +1,6 @@
 // CPU-only driver for the sanitizer builds (address + undefined behaviour, and thread): runs the
-// host scan of the missed clusters, the prefetch and cache planners and the grouping of the
-// consolidation moves on seeded inputs and checks them against the CPU oracle, so that every line
+// host scan of the missed clusters, the prefetch and cache planners, the prefetch-amount model and
+// the grouping of the consolidation moves on seeded inputs and checks them against the CPU oracle, so that every line
 // of the host side executes under the sanitizers.  Built by paper_2502_20969_amd/build.py --sanitize.
 #include <math.h>
 #include <stdint.h>
@@ -23,6 +23,8 @@ int32_t orc_probe(const float* centroids, int32_t nlist, int32_t d, int metric, 
 int32_t orc_prefetch(const float* centroids, int32_t nlist, int32_t d, int metric, const int64_t* off, int dtype,
                      const float* x_in, int32_t L, uint64_t budget, uint64_t cap, uint8_t* resident, uint64_t* used,
                      int32_t* chosen, int32_t* n_skipped, uint64_t* bytes_taken);
+double orc_prefetch_amount(double B, double t_llm, int32_t nprobe, double t_cc, const double* bs, const double* rs,
+                           int32_t n, double step, double* t_total);
 }
 
 using namespace ivf;
@@ -189,6 +191,29 @@ static void check_cache_rounds(uint32_t seed) {
     }
 }
 
+// the prefetch amount on random non-increasing miss-rate curves whose points lie on the oracle's grid
+static void check_prefetch_amount(uint32_t seed) {
+    std::mt19937 rng(seed);
+    std::uniform_real_distribution<double> u(0.0, 1.0);
+    for (int trial = 0; trial < 40; ++trial) {
+        const int n = 1 + (int)(rng() % 12);
+        std::vector<double> bs(n), rs(n);
+        double b = (double)(rng() % 3) * 1e8, r = 0.3 + 0.7 * u(rng);
+        for (int i = 0; i < n; ++i) {
+            bs[i] = b; rs[i] = r;
+            b += (double)(1 + rng() % 30) * 1e8;
+            r *= u(rng) < 0.3 ? 1.0 : u(rng);
+        }
+        const double bw = (rng() % 2) ? 52e9 : 400e9, t_llm = 0.05 * u(rng), t_cc = 2e-3 * u(rng) * u(rng);
+        const int nprobe = 1 + (int)(rng() % 400);
+        const PrefetchAmount got = plan_prefetch_amount(bw, t_llm, nprobe, t_cc, bs.data(), rs.data(), n);
+        double ot = 0.0;
+        const double ob = orc_prefetch_amount(bw, t_llm, nprobe, t_cc, bs.data(), rs.data(), n, 1e7, &ot);
+        CHECK(got.amount == ob, "prefetch amount: seed %u trial %d: %.17g, oracle %.17g", seed, trial, got.amount, ob);
+        CHECK(fabs(got.seconds - ot) <= 1e-12 * fabs(ot), "prefetch amount: time %.17g, oracle %.17g", got.seconds, ot);
+    }
+}
+
 int main() {
     int exact = 0;
     {
@@ -217,6 +242,7 @@ int main() {
         for (int i = 0; i < 10; ++i) CHECK(out[i].id == oi[i], "identical rows: result %d", i);
     }
     for (uint32_t seed = 1; seed <= 8; ++seed) check_cache_rounds(seed);
+    for (uint32_t seed = 1; seed <= 4; ++seed) check_prefetch_amount(seed);
     printf("%s (%d exact passes of the host scan)\n", g_failed ? "FAILED" : "host sanitizer driver ok", exact);
     return g_failed;
 }

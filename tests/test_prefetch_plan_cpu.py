@@ -83,3 +83,62 @@ def test_plan_rejects_bad_arguments():
     with pytest.raises(P.binding.IvfError) as e:
         P.ivf_prefetch_plan(np.array([[0, 1]], dtype=np.int32), off, 8, 100, 10, res_off, 11)
     assert e.value.status == -1
+
+
+# ---- how much to prefetch (App. C "Finding Prefetching Amount") ------------------------------
+
+def test_prefetch_amount_equals_the_oracle_on_random_curves():
+    """ivf_prefetch_amount looks only at bandwidth * t_llm and the measured points beyond it; the
+    oracle tries every amount on a grid that contains those points.  Both must name the same amount
+    and the same time, on convex curves (the paper's assumption) and on curves that are merely
+    non-increasing."""
+    rng = np.random.default_rng(44)
+    cases = {1: 0, 2: 0}
+    for trial in range(300):
+        n = int(rng.integers(1, 14))
+        bs = np.concatenate([[float(rng.integers(0, 3)) * 1e8], np.zeros(n - 1)])
+        bs[1:] = bs[0] + np.cumsum(rng.integers(1, 40, n - 1)) * 1e8
+        if trial % 2 == 0:
+            slopes = -np.sort(rng.random(n - 1))[::-1]                    # convex
+        else:
+            slopes = -rng.random(n - 1) * (rng.random(n - 1) < 0.7)       # any non-increasing curve, with flat pieces
+        rs = np.concatenate([[0.0], np.cumsum(slopes * np.diff(bs))]) if n > 1 else np.zeros(1)
+        span = rs.max() - rs.min()
+        rs = (rs - rs.min()) / span * rng.uniform(0.3, 1.0) if span > 0 else np.full(n, rng.uniform(0, 1))
+        B = float(rng.choice([16e9, 52e9, 64e9, 400e9]))
+        t_llm = float(rng.choice([0.0, rng.uniform(0.001, 0.05)]))
+        nprobe, t_cc = int(rng.integers(1, 512)), float(rng.choice([0.0, rng.uniform(1e-6, 3e-3)]))
+        amount, seconds, which = P.ivf_prefetch_amount(B, t_llm, nprobe, t_cc, bs, rs)
+        ob, ot = O.prefetch_amount(B, t_llm, nprobe, t_cc, bs, rs, step=1e7)
+        assert amount == ob, (trial, amount, ob)
+        assert seconds == pytest.approx(ot, rel=1e-12, abs=1e-18)
+        assert which == (1 if amount == B * t_llm else 2)
+        cases[which] += 1
+    assert cases[1] > 30 and cases[2] > 30              # both cases of App. C were met
+
+
+def test_prefetch_amount_of_a_measured_sweep():
+    """Numbers of the kind the lookahead benchmark measures: 52 GB/s, 18 ms of generation, nprobe 256,
+    5 us of host time per missed cluster: a byte costs more to move than it saves, so the answer is
+    the generation window, 0.936 GB, with the miss rate read off the line between the measured points."""
+    bs = np.array([0.0, 0.25e9, 0.5e9, 0.9e9, 1.28e9, 2.0e9])
+    rs = np.array([1.0, 0.83, 0.67, 0.47, 0.32, 0.27])
+    amount, seconds, which = P.ivf_prefetch_amount(52e9, 0.018, 256, 5e-6, bs, rs)
+    assert which == 1 and amount == 52e9 * 0.018
+    r = 0.47 + (0.32 - 0.47) * (0.936e9 - 0.9e9) / (1.28e9 - 0.9e9)
+    assert seconds == pytest.approx(0.018 + r * 256 * 5e-6, rel=1e-12)
+    # a host that needs 1 ms per missed cluster changes the answer: every measured point pays until the curve flattens
+    amount, seconds, which = P.ivf_prefetch_amount(52e9, 0.018, 256, 1e-3, bs, rs)
+    assert which == 2 and amount == 1.28e9
+    assert seconds == pytest.approx(1.28e9 / 52e9 + 0.32 * 256 * 1e-3, rel=1e-12)
+
+
+def test_prefetch_amount_rejects_bad_arguments():
+    bs, rs = np.array([0.0, 1e9]), np.array([1.0, 0.5])
+    for args in ((0.0, 0.01, 8, 1e-5, bs, rs), (1e9, -1.0, 8, 1e-5, bs, rs), (1e9, 0.01, 0, 1e-5, bs, rs),
+                 (1e9, 0.01, 8, -1e-5, bs, rs), (1e9, 0.01, 8, 1e-5, bs[::-1].copy(), rs),
+                 (1e9, 0.01, 8, 1e-5, bs, rs[::-1].copy()), (1e9, 0.01, 8, 1e-5, bs, np.array([1.5, 0.5])),
+                 (float("nan"), 0.01, 8, 1e-5, bs, rs)):
+        with pytest.raises(P.binding.IvfError) as e:
+            P.ivf_prefetch_amount(*args)
+        assert e.value.status == -1
