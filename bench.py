@@ -483,7 +483,7 @@ def run_lookahead(args, full=True):
         # Cluster cache (Sec. 4.2 "Cache design"): a stream of requests around a few topics, each
         # request = prefetch(q_in) under the 1.28 GB budget, decode, search(q_out); once with a cold
         # buffer per request, once with the cache keeping at most half of the buffer between requests.
-        n_req, topics = 3 * args.pairs, 6
+        n_req, topics = 48, 6
         tq_in = W.shared_batch_queries(ds, n_req, topics, 20981)
         tq_out = W.perturbed(tq_in, 0.3, 20982)
         tq_in, tq_out = tq_in.cpu().numpy(), tq_out.cpu().numpy()
@@ -524,7 +524,7 @@ def run_lookahead(args, full=True):
             # Prefetching scheduler (Sec. 4.2 "Scheduling optimization for prefetching"): a global batch of
             # requests around many topics, served in micro-batches that share one prefetch budget; once in
             # arrival order, once grouped by ivf_schedule.
-            gB, micro, g_topics = 8 * args.pairs, 8, 2 * args.pairs
+            gB, micro, g_topics = 128, 8, 32
             gq_in = W.shared_batch_queries(ds, gB, g_topics, 20983)
             gq_out = W.perturbed(gq_in, 0.3, 20984)
             perm = torch.randperm(gB, generator=torch.Generator().manual_seed(20985))
@@ -866,7 +866,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="c3, c5: queries per batch instead of the named number; n1: only this batch size in the batch rows")
     ap.add_argument("--topk", type=int, default=0, help="c3, c5: k instead of the named one")
     ap.add_argument("--groups", type=int, default=0, help="c3, c5: mixture components the batch's queries are drawn around")
-    ap.add_argument("--pairs", type=int, default=16, help="c4: (q_in, q_out) pairs per budget")
+    ap.add_argument("--pairs", type=int, default=64, help="c4: (q_in, q_out) pairs per budget")
     args = ap.parse_args()
     global NO_EVENTS, REPEATS
     NO_EVENTS = args.no_events
