@@ -27,7 +27,7 @@ C2_SCAN_TRAFFIC_BYTES = 88649 * 1024 + 1040 * 1024
 C3_SCAN_TRAFFIC_BYTES = 5007648 * 2048
 C5_SCAN_TRAFFIC_BYTES = 30003314 * 2048
 # MFMA utilisation of the batched scan, rocprofv3 --pmc MfmaUtil (profiles/batched_scan_kernel_c3_c5.md)
-C3_MFMA_UTIL, C5_MFMA_UTIL = 0.093, 0.095
+C3_MFMA_UTIL, C5_MFMA_UTIL = 0.088, 0.103
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
 NO_EVENTS = False
 REPEATS = 5
