@@ -14,7 +14,7 @@ constexpr int kMaxKPrime = 128;            // candidates kept per list: k + slac
 constexpr int kScanWaves = 4;              // scan workgroup: 4 wavefronts, two workgroups per compute unit
 constexpr int kScanThreads = kScanWaves * 64;
 constexpr int kLaneTableSlots = 64;        // up to this many selected clusters the scan keeps the slot table in its lanes
-constexpr int kScanBatches = 2;           // batches of rows a scan wavefront has in flight
+constexpr int kScanBatches = 1;           // batches of rows a scan wavefront has in flight (measured: one small batch beats two larger ones)
 constexpr int kScanMaxWgPerCu = 2;        // scan workgroups per compute unit at most (sizes the per-workgroup tables)
 constexpr int kSelectThreads = 1024;       // select / merge workgroup: 16 wavefronts
 constexpr int kSortLdsCap = 2048;          // select: pairs sorted in LDS up to this many
@@ -32,7 +32,7 @@ inline int kprime_for(int k) {
 }
 
 // How one scan kernel variant walks rows: a batch is up to `rows_per_batch` consecutive rows
-// of one list; two batches are in flight per wavefront.
+// of one list; kScanBatches batches are in flight per wavefront.
 struct ScanShape {
     int lanes_per_row;   // 16, 32 or 64; 0 selects the any-d fallback kernel
     int segments;        // 16-byte loads per lane per row
