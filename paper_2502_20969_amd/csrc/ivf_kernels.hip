@@ -714,23 +714,29 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
     const int qi = blockIdx.y;
     const size_t row_bytes = (size_t)p.d * T::kBytes;
 
-    // this lane's slice of the query, requested before anything else: it travels while the
-    // tables do (rows of this kernel are whole 16-byte chunks, so d is a multiple of EPL)
+    // This lane's slice of the query (rows of this kernel are whole 16-byte chunks, so d is a
+    // multiple of EPL).  It is requested right AFTER the tables: loads return in order, and the
+    // tables decide where the rows are, so nothing should arrive before them; the query is needed
+    // only when the first rows are there.  (Measured: query first 16.8 us, tables first 16.5,
+    // query after the first rows 16.6 - 16.9.)
     float qv[SEG][EPL];
     const float* q = p.q + (size_t)qi * p.d;
+    auto load_query = [&]() {
 #pragma unroll
-    for (int sg = 0; sg < SEG; ++sg) {
-        const int col = (sg * LPR + sub) * EPL;
+        for (int sg = 0; sg < SEG; ++sg) {
+            const int col = (sg * LPR + sub) * EPL;
 #pragma unroll
-        for (int e = 0; e < EPL; e += 4) {
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (col < p.d) t = *(const float4*)(q + col + e);
-            qv[sg][e] = t.x; qv[sg][e + 1] = t.y; qv[sg][e + 2] = t.z; qv[sg][e + 3] = t.w;
+            for (int e = 0; e < EPL; e += 4) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (col < p.d) t = *(const float4*)(q + col + e);
+                qv[sg][e] = t.x; qv[sg][e + 1] = t.y; qv[sg][e + 2] = t.z; qv[sg][e + 3] = t.w;
+            }
         }
-    }
+    };
 
     LaneTable tab;
     tab.load(p, qi);
+    load_query();
     Cursor cur = start_cursor(p, qi, tab, RPB);
 
     WaveTopK<KL, false> top;
