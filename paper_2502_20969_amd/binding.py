@@ -175,6 +175,23 @@ class Index:
         # device tensors of searches the library may still touch (a pipelined or list-major call is
         # finished when its stream is next needed or in ivf_synchronize): one entry per stream at most
         self._inflight = collections.deque(maxlen=32)
+        self._search_device = load().ivf_search_device
+        t = _torch()
+        self._f32, self._i64 = t.float32, t.int64
+
+    def _device_triple(self, q_dev, k, ids_dev, dists_dev):
+        """Checks the three device tensors of a device-side search (this runs once per search: kept short);
+        returns the number of queries."""
+        if q_dev.dtype is not self._f32 or ids_dev.dtype is not self._i64 or dists_dev.dtype is not self._f32:
+            raise TypeError("queries and distances must be float32, ids int64")
+        if not (q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda):
+            raise ValueError("expected CUDA tensors")
+        if not (q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()):
+            raise ValueError("expected contiguous tensors")
+        nq = q_dev.numel() // self.d
+        if ids_dev.numel() < nq * k or dists_dev.numel() < nq * k:
+            raise ValueError("ids / dists hold fewer than nq * k entries")
+        return nq
 
     def close(self):
         if self._h is not None:
@@ -214,21 +231,15 @@ class Index:
         """q_dev [nq, d] float32, ids_dev [nq, k] int64, dists_dev [nq, k] float32: CUDA tensors.
         The three tensors are kept referenced until ivf_synchronize (the library may read the queries
         and rewrite the outputs until then)."""
-        assert q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda
-        assert q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()
-        assert q_dev.dtype == _torch().float32 and ids_dev.dtype == _torch().int64 and dists_dev.dtype == _torch().float32
-        nq = q_dev.numel() // self.d
-        assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
+        nq = self._device_triple(q_dev, k, ids_dev, dists_dev)
         self._inflight.append((q_dev, ids_dev, dists_dev))
-        _check(load().ivf_search_device(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
+        status = self._search_device(self._h, q_dev.data_ptr(), nq, nprobe, k, ids_dev.data_ptr(), dists_dev.data_ptr())
+        if status != 0:
+            _check(status)
 
     def ivf_search_device_noalloc(self, q_dev, nprobe, k, ids_dev, dists_dev):
         """ivf_search_device on the library's fixed scratch area: allocates nothing."""
-        assert q_dev.is_cuda and ids_dev.is_cuda and dists_dev.is_cuda
-        assert q_dev.is_contiguous() and ids_dev.is_contiguous() and dists_dev.is_contiguous()
-        assert q_dev.dtype == _torch().float32 and ids_dev.dtype == _torch().int64 and dists_dev.dtype == _torch().float32
-        nq = q_dev.numel() // self.d
-        assert ids_dev.numel() >= nq * k and dists_dev.numel() >= nq * k
+        nq = self._device_triple(q_dev, k, ids_dev, dists_dev)
         _check(load().ivf_search_device_noalloc(self._h, _ptr(q_dev), nq, nprobe, k, _ptr(ids_dev), _ptr(dists_dev)))
 
     def ivf_reserve(self, nq, nprobe, k):
