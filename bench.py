@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes one scan launch moves, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a 1 GiB
 # copy (profiles/scan_kernel_c2_single_query.md, profiles/batched_scan_kernel_c3_c5.md)
-C2_SCAN_TRAFFIC_BYTES = 88547 * 1024 + 1040 * 1024
+C2_SCAN_TRAFFIC_BYTES = 88561 * 1024 + 1040 * 1024
 C3_SCAN_TRAFFIC_BYTES = 5007648 * 2048
 C5_SCAN_TRAFFIC_BYTES = 30003314 * 2048
 # MFMA utilisation of the batched scan, rocprofv3 --pmc MfmaUtil (profiles/batched_scan_kernel_c3_c5.md)
