@@ -157,7 +157,7 @@ hipError_t launch_schedule(const float* q_dev, int B, int d, int m, double* dist
 constexpr int kScheduleMaxQueries = 4096;
 
 // ---- batched (list-major) search: ivf_batched.hip ------------------------------------------------
-struct BatchTask { uint32_t cluster, group, tile; };    // 128 rows of a cluster x up to 32 of its queries
+struct BatchTask { uint32_t cluster, group, tile; };    // tile: 256 rows of the cluster; group: up to 32 (fp32 rows: 16) of the queries probing it
 
 struct BatchedArgs {
     const void* lists;           // device lists (device placement)
