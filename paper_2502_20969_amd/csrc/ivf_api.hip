@@ -543,7 +543,7 @@ int ensure_batched_workspace(ivf_index* ix, int nq, int nprobe) {
     HIP_TRY(hipMalloc(&w.d_qq, nqz * sizeof(float)));
     HIP_TRY(hipMalloc(&w.d_thr, nqz * sizeof(float)));
     HIP_TRY(hipMalloc(&w.d_thr_part, batched_thr_part_floats(nq2) * sizeof(float)));
-    HIP_TRY(hipMalloc(&w.d_list_count, nl * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&w.d_list_count, (nl + 1) * sizeof(uint32_t)));      // + the scan's task counter
     HIP_TRY(hipMalloc(&w.d_cursor, nl * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&w.d_qstart, (nl + 1) * sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&w.d_tstart, (nl + 1) * sizeof(uint32_t)));
@@ -566,6 +566,7 @@ static void fill_batched_args(const ivf_index* ix, const Workspace& w, BatchedAr
     b.lists = ix->d_buf; b.off = ix->d_off; b.ids = ix->d_ids; b.probe = w.d_probe;
     b.q_store = w.d_q_store; b.thr = w.d_thr; b.thr_part = w.d_thr_part; b.row_norm_max_bits = ix->d_row_norm_max;
     b.list_count = w.d_list_count; b.cursor = w.d_cursor; b.qstart = w.d_qstart; b.tstart = w.d_tstart;
+    b.ticket = w.d_list_count + ix->nlist;
     b.qidx = w.d_qidx; b.tasks = w.d_tasks; b.cand_count = w.d_cand_count; b.cand_row = w.d_cand_row;
     b.cand_key = w.d_cand_key; b.cand_score = w.d_cand_score; b.eps = w.d_eps; b.qq = w.d_qq; b.row_norm = ix->d_row_norm;
     b.surv_row = w.d_surv_row; b.overflow = w.d_overflow;

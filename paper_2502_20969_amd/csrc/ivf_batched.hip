@@ -295,6 +295,54 @@ __global__ void make_tasks_kernel(BatchedArgs a) {
     }
 }
 
+// ---- how the scan workgroups get their tasks ---------------------------------------------------------------
+// The workgroups resident on the GPU draw runs of consecutive tasks from one counter (a.ticket,
+// zero at launch) until the list is used up: compute units, and whole XCDs, differ by several
+// per cent in how fast they stream from HBM, and with equal shares the slowest one sets the
+// kernel's time.  A run has up to kRunMax tasks (tasks that follow each other mostly share their
+// cluster and group of queries, which are staged once) and shrinks towards the end of the list
+// (remaining / (4 x workgroups), at least one), so that all workgroups finish within about a task
+// of each other.  Every workgroup leaves once a run starts past the end of the list.
+constexpr uint32_t kRunMax = 8;
+struct TaskFeed {
+    uint32_t t, t_stop, total;      // same in all threads: next task, end of the run, end of the list
+    uint32_t ahead_t0, ahead_n;     // thread 0: the run reserved ahead
+    __device__ __forceinline__ uint32_t run_length(uint32_t counter_seen) const {
+        const uint32_t left = total - min(total, counter_seen);
+        return max(1u, min(kRunMax, left / (4u * gridDim.x)));
+    }
+    __device__ __forceinline__ void reserve(const BatchedArgs& a, uint32_t counter_seen) {
+        ahead_n = run_length(counter_seen);
+        ahead_t0 = atomicAdd(a.ticket, ahead_n);
+    }
+    __device__ __forceinline__ void start(const BatchedArgs& a) {
+        total = (uint32_t)__builtin_amdgcn_readfirstlane((int)a.tstart[a.nlist]);
+        t = t_stop = 0;
+        ahead_t0 = ahead_n = 0;
+        if (threadIdx.x == 0) reserve(a, 0);
+    }
+    // the next task's index, or false when the list is used up; all threads of the workgroup call it together.
+    // s_run: four words of LDS (16 bytes, so that the dynamic LDS area behind the static one stays 16-byte aligned)
+    __device__ __forceinline__ bool next(const BatchedArgs& a, uint32_t* s_run, uint32_t& index) {
+        if (t == t_stop) {
+            __syncthreads();                              // s_run of the previous run has been read by everyone
+            if (threadIdx.x == 0) {
+                s_run[0] = ahead_t0;
+                s_run[1] = min(ahead_t0 + ahead_n, total);
+                if (ahead_t0 < total) reserve(a, ahead_t0 + ahead_n);
+            }
+            __syncthreads();
+            // (read from LDS: the compiler is told that the values are the same in every lane, so
+            // that the task and everything derived from it stay in scalar registers)
+            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_run[0]);
+            t_stop = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_run[1]);
+            if (t >= total) return false;
+        }
+        index = t++;
+        return true;
+    }
+};
+
 // ---- the MFMA scan -------------------------------------------------------------------------------------
 template <typename T> struct Mfma;
 template <> struct Mfma<F16> {
@@ -328,12 +376,12 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs
     const int d = a.d, qstride = d + kQPad;
     uint16_t* qs = (uint16_t*)smem;                      // [kGroupQ][d + kQPad] storage-type queries
     uint16_t* stage = qs + (size_t)kGroupQ * qstride + (size_t)wave * 32 * kStageLd;   // [32][kStageLd], this wavefront's
-    const uint32_t total = a.tstart[a.nlist];
-    const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
-    const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    __shared__ __align__(16) uint32_t s_run[4];
+    TaskFeed feed;
+    feed.start(a);
     uint32_t staged_cluster = 0xFFFFFFFFu, staged_group = 0xFFFFFFFFu;
     const int col = lane & 31, khalf = lane >> 5;
-    for (uint32_t t = t_begin; t < t_end; ++t) {
+    for (uint32_t t = 0; feed.next(a, s_run, t);) {
         const BatchTask task = a.tasks[t];
         const uint32_t c = task.cluster;
         const uint32_t qbase = a.qstart[c] + task.group * kGroupQ;
@@ -477,12 +525,12 @@ __global__ __launch_bounds__(kBatchThreads) void batched_scan_f32_kernel(Batched
     const int lane = lane_id(), wave = wave_id();
     const int d = a.d, qstride = d + kQPad32;
     float* qs = (float*)smem;                            // [kGroupQ32][d + kQPad32] queries
-    const uint32_t total = a.tstart[a.nlist];
-    const uint32_t t_begin = (uint32_t)((uint64_t)total * blockIdx.x / gridDim.x);
-    const uint32_t t_end = (uint32_t)((uint64_t)total * (blockIdx.x + 1) / gridDim.x);
+    __shared__ __align__(16) uint32_t s_run[4];
+    TaskFeed feed;
+    feed.start(a);
     uint32_t staged_cluster = 0xFFFFFFFFu, staged_group = 0xFFFFFFFFu;
     const int col = lane & 15, kq = lane >> 4;
-    for (uint32_t t = t_begin; t < t_end; ++t) {
+    for (uint32_t t = 0; feed.next(a, s_run, t);) {
         const BatchTask task = a.tasks[t];
         const uint32_t c = task.cluster;
         const uint32_t qbase = a.qstart[c] + task.group * kGroupQ32;
@@ -809,7 +857,7 @@ hipError_t launch_batched(const BatchedArgs& a, int grid, hipStream_t s, hipEven
     else if (a.dtype == 1) hipLaunchKernelGGL(thr_sample_kernel<F16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
     else hipLaunchKernelGGL(thr_sample_kernel<BF16>, dim3(a.nq, kSampleParts), dim3(256), (size_t)a.d * 4, s, a);
     hipLaunchKernelGGL(prep_queries_kernel, dim3(a.nq), dim3(64), 0, s, a);
-    hipLaunchKernelGGL(zero_u32_kernel, dim3((a.nlist + 255) / 256), dim3(256), 0, s, a.list_count, a.nlist);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3((a.nlist + 1 + 255) / 256), dim3(256), 0, s, a.list_count, a.nlist + 1);   // and the ticket behind them
     hipLaunchKernelGGL(count_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);
     hipLaunchKernelGGL(scan_lists_kernel, dim3(1), dim3(1024), 0, s, a);
     hipLaunchKernelGGL(fill_pairs_kernel, dim3((pairs + 255) / 256), dim3(256), 0, s, a);

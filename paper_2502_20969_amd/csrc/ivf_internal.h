@@ -175,6 +175,7 @@ struct BatchedArgs {
     uint32_t* tstart;            // [nlist+1] prefix of tasks per cluster
     uint32_t* qidx;              // [nq x nprobe] queries grouped by cluster
     BatchTask* tasks;            // [task capacity]
+    uint32_t* ticket;            // one counter, zero when the scan starts: the tasks handed out so far
     uint32_t* cand_count;        // [nq]
     uint32_t* cand_row;          // [nq x cand_cap] global rows that passed the filter
     float* cand_score;           // [nq x cand_cap] their approximate (MFMA) scores
