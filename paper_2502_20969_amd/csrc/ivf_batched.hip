@@ -329,7 +329,6 @@ struct TaskFeed {
             if (threadIdx.x == 0) {
                 s_run[0] = ahead_t0;
                 s_run[1] = min(ahead_t0 + ahead_n, total);
-                if (ahead_t0 < total) reserve(a, ahead_t0 + ahead_n);
             }
             __syncthreads();
             // (read from LDS: the compiler is told that the values are the same in every lane, so
@@ -337,6 +336,9 @@ struct TaskFeed {
             t = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_run[0]);
             t_stop = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_run[1]);
             if (t >= total) return false;
+            // the run after this one: asked for behind the barrier, so that only this wavefront
+            // waits for the counter while the others are already at work
+            if (threadIdx.x == 0) reserve(a, ahead_t0 + ahead_n);
         }
         index = t++;
         return true;
