@@ -72,7 +72,7 @@ constexpr int kSamplePartRows = 128;
 
 template <typename T>
 __global__ __launch_bounds__(256) void thr_sample_kernel(BatchedArgs a) {
-    extern __shared__ unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];
     __shared__ Cand m_cand[3 * kMaxKPrime];
     constexpr int EPL = T::kPerLoad;
     const int qi = blockIdx.x, part = blockIdx.y, lane = lane_id(), wave = wave_id();
@@ -370,7 +370,7 @@ template <> struct Mfma<BF16> {
 template <typename T, int METRIC>
 __global__ __launch_bounds__(kBatchThreads) void batched_scan_kernel(BatchedArgs a) {
     typedef typename Mfma<T>::frag frag;
-    extern __shared__ unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t s_q[kGroupQ];
     __shared__ float s_thr[kGroupQ];
     __shared__ float s_qq[kGroupQ];
@@ -520,7 +520,7 @@ constexpr int kStage32 = 4;        // 32-element pieces of a row per pipeline st
 
 template <int METRIC>
 __global__ __launch_bounds__(kBatchThreads) void batched_scan_f32_kernel(BatchedArgs a) {
-    extern __shared__ unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t s_q[kGroupQ32];
     __shared__ float s_thr[kGroupQ32];
     __shared__ float s_qq[kGroupQ32];

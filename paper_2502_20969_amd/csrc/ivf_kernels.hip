@@ -272,7 +272,7 @@ __device__ __forceinline__ bool select_by_cut(const SelectArgs& a, const double*
 
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a, uint32_t pad, int in_lds,
                                                                 int prefix_in_lds, int by_cut) {
-    extern __shared__ unsigned char smem_raw[];
+    extern __shared__ __align__(16) unsigned char smem_raw[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sh[8];
     __shared__ uint32_t red[96];
@@ -820,7 +820,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs p) {
 // Fallback for any d and any row alignment: element-wise loads, query in LDS, 4 rows per batch.
 template <int METRIC, int KL>
 __global__ __launch_bounds__(kScanThreads) void scan_generic_kernel(ScanArgs p) {
-    extern __shared__ unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];
     const int lane = lane_id();
     const int qi = blockIdx.y;
     float* ql = (float*)smem;
@@ -1143,7 +1143,7 @@ __device__ __forceinline__ bool result_is_safe(double s_k, float f_last, const M
 }
 
 __global__ __launch_bounds__(kSelectThreads) void merge_kernel(MergeArgs a, int fast) {
-    extern __shared__ unsigned char m_dyn[];
+    extern __shared__ __align__(16) unsigned char m_dyn[];
     __shared__ MergeLds L;
     __shared__ double q_part[kSelectThreads / 64];
     __shared__ double s_kth;
