@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes one scan launch moves, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a 1 GiB
 # copy (profiles/scan_kernel_c2_single_query.md, profiles/batched_scan_kernel_c3_c5.md)
 C2_SCAN_TRAFFIC_BYTES = 88561 * 1024 + 1040 * 1024
-C3_SCAN_TRAFFIC_BYTES = 5007648 * 2048
-C5_SCAN_TRAFFIC_BYTES = 30003314 * 2048
+C3_SCAN_TRAFFIC_BYTES = 5007893 * 2048
+C5_SCAN_TRAFFIC_BYTES = 30004499 * 2048
 # MFMA utilisation of the batched scan, rocprofv3 --pmc MfmaUtil (profiles/batched_scan_kernel_c3_c5.md)
 C3_MFMA_UTIL, C5_MFMA_UTIL = 0.088, 0.103
 METRIC = "IVF search queries/sec + achieved HBM GB/s (% of peak) at nprobe sweep, 1 GPU"
